@@ -1,0 +1,130 @@
+/*
+ * ckpt.h - C ABI of the MI355X (gfx950) checkpoint-selection library.
+ *
+ * Problem (paper, Section 3.1 "Problem Definition"): a chain of n layers is the
+ * sequence of n+1 positive data sizes d_0..d_n (bytes); d_0 is the input, d_n
+ * the output, and both are always checkpoints.  A checkpoint set C is a byte
+ * mask over positions 0..n with mask[0] = mask[n] = 1.
+ *
+ * Memory and ownership.  Every pointer below, except the ckpt_layout itself,
+ * is a DEVICE pointer owned by the caller.  The library allocates nothing,
+ * keeps nothing between calls and never synchronises: each call validates its
+ * arguments on the host, enqueues its kernels on `hip_stream` (a hipStream_t
+ * passed as void*, NULL = the null stream) and returns.  Outputs are valid
+ * once the stream has reached the end of the call's work.  `ws` is scratch of
+ * at least ckpt_workspace_bytes() bytes, 256-byte aligned, private to the call
+ * until it has finished on the stream; its contents need no initialisation.
+ *
+ * Layout.  A batch holds `batch` independent chains of the same n.  Element k
+ * of chain c of an int64 array `a` is a[c*chain_stride + k*pos_stride]
+ * (strides in elements, both > 0).  The fast layout is position-major
+ * ("structure of arrays"): chain_stride = 1, pos_stride = batch, which makes
+ * the 64 lanes of a wavefront read 512 contiguous bytes per position.  Masks
+ * (input and output) use the same two strides in bytes.  Chain-major
+ * (chain_stride = n+1, pos_stride = 1) is accepted and slower.
+ *
+ * Errors.  Host-detectable errors (null pointer, bad shape or stride, too
+ * small a workspace) are returned and nothing is launched.  Data-dependent
+ * errors are reported per chain in status_out[c] (may be NULL) as one of the
+ * ckpt_status values; such a chain gets peak -1 and an all-zero mask, the
+ * other chains are unaffected:
+ *   CKPT_ERR_SIZE      some d_k <= 0 (Lemma 1 of Section 4.2 needs d > 0),
+ *   CKPT_ERR_OVERFLOW  sum(d) + max(d) does not fit in a signed 64-bit value,
+ *   CKPT_ERR_MASK      mask[0] or mask[n] is 0 (ckpt_eval_peak only).
+ *
+ * Results are exact integers.  Where several optimal sets exist the library
+ * returns a canonical one, defined on the value functions (see each call).
+ */
+#ifndef CKPT_H
+#define CKPT_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    CKPT_OK = 0,
+    CKPT_ERR_NULL = 1,
+    CKPT_ERR_SHAPE = 2,
+    CKPT_ERR_SIZE = 3,
+    CKPT_ERR_OVERFLOW = 4,
+    CKPT_ERR_MASK = 5,
+    CKPT_ERR_WORKSPACE = 6,
+    CKPT_ERR_DEVICE = 7
+} ckpt_status;
+
+typedef enum {
+    CKPT_OBJ_STATIC = 0,  /* Equation (cost), Section 3.1: all checkpoints + largest segment */
+    CKPT_OBJ_DYNAMIC = 1  /* Equation (memory), Section 4: early release + output-gradient buffer */
+} ckpt_objective;
+
+typedef enum { CKPT_CALL_EVAL_PEAK = 0, CKPT_CALL_SOLVE_CUBIC = 1, CKPT_CALL_SOLVE_LINEAR = 2 } ckpt_call;
+
+/* Largest n accepted by ckpt_eval_peak and ckpt_solve_linear, and by
+ * ckpt_solve_cubic (whose work grows as n^3). */
+#define CKPT_MAX_LAYERS 65535
+#define CKPT_CUBIC_MAX_LAYERS 8191
+
+typedef struct {
+    int64_t batch;        /* number of chains, >= 0 (0: the call does nothing) */
+    int32_t n_layers;     /* n >= 1; every chain has n+1 sizes */
+    int64_t chain_stride; /* elements between the same position of consecutive chains */
+    int64_t pos_stride;   /* elements between consecutive positions of one chain */
+} ckpt_layout;
+
+/* Bytes of scratch the call `which` (a ckpt_call) needs for this layout;
+ * 0 if the layout is invalid.  Host-only, launches nothing. */
+size_t ckpt_workspace_bytes(int which, const ckpt_layout *layout);
+
+/* Peak memory of a given checkpoint set, per chain.
+ *   CKPT_OBJ_STATIC : Equation (cost), the model of Algorithm 2 -
+ *       sum_{i in C} d_i + max over segments of the segment's sum.
+ *   CKPT_OBJ_DYNAMIC: Equation (memory), the model of Algorithm 3 - the
+ *       largest, over checkpoints i with previous checkpoint h, of
+ *       sum_{c in C, c <= i} d_c + sum_{h<k<i} d_k + max_{h<=k<i} d_k.
+ * d [in] sizes, mask [in] checkpoint bytes (non-zero = checkpoint), both in
+ * `layout`; peak_out [out] `batch` int64; status_out [out] `batch` int32 or
+ * NULL. */
+int ckpt_eval_peak(const int64_t *d, const uint8_t *mask, const ckpt_layout *layout,
+                   int objective, int64_t *peak_out, int32_t *status_out,
+                   void *ws, size_t ws_bytes, void *hip_stream);
+
+/* Optimal checkpoint set under Equation (cost) by the two-step scheme of
+ * Section 3.2 (Algorithm 4, Theorem 1): for every candidate segment budget s
+ * (0 and every sum of a contiguous range inside d_1..d_{n-1}) the least
+ * checkpoint memory c_s whose segments all fit in s, by the recurrence of
+ * Equation (T); the answer is min_s (s + c_s) with d_0 and d_n checkpoints.
+ * n <= CKPT_CUBIC_MAX_LAYERS.
+ * Canonical result: budget_out[c] is the smallest optimal budget value s*;
+ * the set is built from position n by taking, each time, the smallest
+ * feasible predecessor of minimal value.
+ * mask_out [out] bytes 0/1 in `layout`; peak_out [out] `batch` int64;
+ * budget_out [out] `batch` int64 or NULL; status_out as above. */
+int ckpt_solve_cubic(const int64_t *d, const ckpt_layout *layout, uint8_t *mask_out,
+                     int64_t *peak_out, int64_t *budget_out, int32_t *status_out,
+                     void *ws, size_t ws_bytes, void *hip_stream);
+
+/* Optimal checkpoint set under Equation (memory) by the linear-time method of
+ * Section 4.2 (Equation (TU), Lemmas 1-4, Algorithm 6, Theorem 3):
+ *   M(n) = d_n,  M(i) = d_i + min_{i<j<=n} max(M(j), U(i,j)),
+ *   U(i,j) = sum_{k=i+1}^{j} d_k + max_{i<=k<j} d_k ;  peak_out[c] = M(0).
+ * Canonical result: from i = 0 the set follows the smallest j attaining M(i).
+ * Arguments as for ckpt_solve_cubic (no budget). */
+int ckpt_solve_linear(const int64_t *d, const ckpt_layout *layout, uint8_t *mask_out,
+                      int64_t *peak_out, int32_t *status_out,
+                      void *ws, size_t ws_bytes, void *hip_stream);
+
+/* Number of recurrence cells one ckpt_solve_cubic call evaluates per chain:
+ * (n(n-1)/2 + 1) budgets times n positions.  Host-only. */
+int64_t ckpt_cubic_cells(int32_t n_layers);
+
+/* Static, human-readable name of a ckpt_status value. */
+const char *ckpt_status_string(int status);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* CKPT_H */

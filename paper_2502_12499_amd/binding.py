@@ -1,0 +1,162 @@
+"""Python binding of the C ABI in include/ckpt.h: argument marshalling only.
+
+Each function takes torch tensors that already live on the GPU, passes their
+device pointers, the layout and the current HIP stream to the library call of
+the same name, and returns the output tensors.  No step of the computation runs
+here, and there is no fallback: if libckpt_hip.so has not been built the import
+of the library fails loudly.
+
+Tensor convention: ``d`` is int64 of shape (n+1, batch) ("position-major",
+contiguous: the fast layout) or (batch, n+1) with ``chain_major=True``; masks
+have the same shape, uint8.
+"""
+import ctypes
+import os
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libckpt_hip.so")
+
+CKPT_OK = 0
+OBJ_STATIC, OBJ_DYNAMIC = 0, 1
+CALL_EVAL_PEAK, CALL_SOLVE_CUBIC, CALL_SOLVE_LINEAR = 0, 1, 2
+
+EXPORTS = ("ckpt_workspace_bytes", "ckpt_eval_peak", "ckpt_solve_cubic", "ckpt_solve_linear",
+           "ckpt_cubic_cells", "ckpt_status_string")
+
+
+class Layout(ctypes.Structure):
+    _fields_ = [("batch", ctypes.c_int64), ("n_layers", ctypes.c_int32),
+                ("chain_stride", ctypes.c_int64), ("pos_stride", ctypes.c_int64)]
+
+
+_lib = None
+
+
+def load():
+    """dlopen the in-tree library; raises if it has not been built."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError(
+                f"{LIB_PATH} is missing: build it with `python -m paper_2502_12499_amd.build` "
+                "(there is no CPU fallback)")
+        lib = ctypes.CDLL(LIB_PATH)
+        vp, LP = ctypes.c_void_p, ctypes.POINTER(Layout)
+        lib.ckpt_workspace_bytes.restype = ctypes.c_size_t
+        lib.ckpt_workspace_bytes.argtypes = [ctypes.c_int, LP]
+        lib.ckpt_eval_peak.restype = ctypes.c_int
+        lib.ckpt_eval_peak.argtypes = [vp, vp, LP, ctypes.c_int, vp, vp, vp, ctypes.c_size_t, vp]
+        lib.ckpt_solve_cubic.restype = ctypes.c_int
+        lib.ckpt_solve_cubic.argtypes = [vp, LP, vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
+        lib.ckpt_solve_linear.restype = ctypes.c_int
+        lib.ckpt_solve_linear.argtypes = [vp, LP, vp, vp, vp, vp, ctypes.c_size_t, vp]
+        lib.ckpt_cubic_cells.restype = ctypes.c_int64
+        lib.ckpt_cubic_cells.argtypes = [ctypes.c_int32]
+        lib.ckpt_status_string.restype = ctypes.c_char_p
+        lib.ckpt_status_string.argtypes = [ctypes.c_int]
+        _lib = lib
+    return _lib
+
+
+class CkptError(RuntimeError):
+    def __init__(self, call, code):
+        self.code = code
+        super().__init__(f"{call} failed: {status_string(code)} ({code})")
+
+
+def status_string(code):
+    return load().ckpt_status_string(int(code)).decode()
+
+
+def cubic_cells(n_layers):
+    return int(load().ckpt_cubic_cells(int(n_layers)))
+
+
+def layout_of(t, chain_major=False):
+    """ckpt_layout for a 2-D tensor of sizes or masks (strides in elements)."""
+    if t.dim() != 2:
+        raise ValueError("expected a 2-D tensor")
+    if chain_major:
+        batch, n1 = t.shape
+        cs, ps = t.stride(0), t.stride(1)
+    else:
+        n1, batch = t.shape
+        ps, cs = t.stride(0), t.stride(1)
+    if batch == 1:      # a lone chain: any positive chain stride addresses it
+        cs = max(cs, 1)
+    return Layout(batch, n1 - 1, cs, ps)
+
+
+def workspace_bytes(which, layout):
+    return int(load().ckpt_workspace_bytes(int(which), ctypes.byref(layout)))
+
+
+def _workspace(which, layout, device, workspace):
+    need = workspace_bytes(which, layout)
+    if workspace is None:
+        workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=device)
+    return workspace, workspace.numel()
+
+
+def _stream():
+    return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def _ptr(t):
+    return ctypes.c_void_p(t.data_ptr()) if t is not None else None
+
+
+def _check_inputs(d, mask=None):
+    if d.dtype != torch.int64 or not d.is_cuda:
+        raise TypeError("d must be an int64 tensor on the GPU")
+    if mask is not None:
+        if mask.dtype != torch.uint8 or not mask.is_cuda:
+            raise TypeError("mask must be a uint8 tensor on the GPU")
+        if mask.shape != d.shape or mask.stride() != d.stride():
+            raise ValueError("mask must have the shape and strides of d")
+
+
+def ckpt_eval_peak(d, mask, objective, chain_major=False, want_status=True):
+    """Peak memory of each chain's checkpoint set.  Returns (peak, status)."""
+    _check_inputs(d, mask)
+    L = layout_of(d, chain_major)
+    peak = torch.empty(L.batch, dtype=torch.int64, device=d.device)
+    status = torch.empty(L.batch, dtype=torch.int32, device=d.device) if want_status else None
+    rc = load().ckpt_eval_peak(_ptr(d), _ptr(mask), ctypes.byref(L), int(objective), _ptr(peak), _ptr(status),
+                               None, 0, _stream())
+    if rc != CKPT_OK:
+        raise CkptError("ckpt_eval_peak", rc)
+    return peak, status
+
+
+def ckpt_solve_cubic(d, chain_major=False, workspace=None, want_status=True):
+    """Optimal set under the static objective.  Returns (mask, peak, budget, status)."""
+    _check_inputs(d)
+    L = layout_of(d, chain_major)
+    mask = torch.empty_strided(d.shape, d.stride(), dtype=torch.uint8, device=d.device)
+    peak = torch.empty(L.batch, dtype=torch.int64, device=d.device)
+    budget = torch.empty(L.batch, dtype=torch.int64, device=d.device)
+    status = torch.empty(L.batch, dtype=torch.int32, device=d.device) if want_status else None
+    ws, ws_bytes = _workspace(CALL_SOLVE_CUBIC, L, d.device, workspace)
+    rc = load().ckpt_solve_cubic(_ptr(d), ctypes.byref(L), _ptr(mask), _ptr(peak), _ptr(budget), _ptr(status),
+                                 _ptr(ws), ws_bytes, _stream())
+    if rc != CKPT_OK:
+        raise CkptError("ckpt_solve_cubic", rc)
+    return mask, peak, budget, status
+
+
+def ckpt_solve_linear(d, chain_major=False, workspace=None, want_status=True):
+    """Optimal set under the dynamic objective.  Returns (mask, peak, status)."""
+    _check_inputs(d)
+    L = layout_of(d, chain_major)
+    mask = torch.empty_strided(d.shape, d.stride(), dtype=torch.uint8, device=d.device)
+    peak = torch.empty(L.batch, dtype=torch.int64, device=d.device)
+    status = torch.empty(L.batch, dtype=torch.int32, device=d.device) if want_status else None
+    ws, ws_bytes = _workspace(CALL_SOLVE_LINEAR, L, d.device, workspace)
+    rc = load().ckpt_solve_linear(_ptr(d), ctypes.byref(L), _ptr(mask), _ptr(peak), _ptr(status),
+                                  _ptr(ws), ws_bytes, _stream())
+    if rc != CKPT_OK:
+        raise CkptError("ckpt_solve_linear", rc)
+    return mask, peak, status

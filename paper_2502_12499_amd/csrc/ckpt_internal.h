@@ -1,0 +1,39 @@
+// Internal launch interface between the C-ABI entry points (ckpt_api.hip) and
+// the kernel translation units.  Host code only validates and launches; every
+// step of the path runs in the kernels.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "../../include/ckpt.h"
+
+namespace ckpt {
+
+constexpr int kWave = 64;
+
+// Chain c, position k of an array laid out by a ckpt_layout.
+struct Strides {
+    int64_t chain;
+    int64_t pos;
+};
+
+inline size_t align_up(size_t x, size_t a = 256) { return (x + a - 1) / a * a; }
+
+// ---- eval_peak ---------------------------------------------------------------
+hipError_t launch_eval_peak(const int64_t *d, const uint8_t *mask, int64_t batch, int n, Strides st,
+                            int objective, int64_t *peak_out, int32_t *status_out, hipStream_t stream);
+
+// ---- solve_linear ------------------------------------------------------------
+size_t linear_workspace_bytes(int64_t batch, int n);
+hipError_t launch_solve_linear(const int64_t *d, int64_t batch, int n, Strides st, uint8_t *mask_out,
+                               int64_t *peak_out, int32_t *status_out, void *ws, hipStream_t stream);
+
+// ---- solve_cubic -------------------------------------------------------------
+size_t cubic_workspace_bytes(int64_t batch, int n);
+hipError_t launch_solve_cubic(const int64_t *d, int64_t batch, int n, Strides st, uint8_t *mask_out,
+                              int64_t *peak_out, int64_t *budget_out, int32_t *status_out, void *ws,
+                              hipStream_t stream);
+
+}  // namespace ckpt

@@ -1,0 +1,421 @@
+// Checkpoint selection under Equation (cost) by the two-step scheme of
+// Section 3.2 (Equation (T), Algorithm 4, Theorem 1).
+//
+// For a segment budget s let F_s(0) = d_0 and
+//     F_s(j) = d_j + min{ F_s(h) : h < j, P[j-1] - P[h] <= s },   P[k] = d_0+..+d_k,
+// i.e. F_s(j) = d_j + M(j-1,s) in the paper's notation; c_s = F_s(n) is the
+// least checkpoint memory whose segments all fit in s (d_0, d_n forced), and
+// the answer is min_s (s + c_s) over the budgets s = 0 and s = P[b] - P[a-1],
+// 1 <= a <= b <= n-1.
+//
+// Kernels, all on the caller's stream:
+//   prologue  one wave per chain: validates the sizes, builds P by a wave scan,
+//             divides everything by the largest common power of two and picks
+//             32-bit arithmetic when sum(d)+max(d) then fits (it does for
+//             aligned tensor sizes), else 64-bit.
+//   budgets   one LANE per budget, 64 budgets of equal range length and
+//             consecutive start per wave (the segment-length anti-diagonal), all
+//             lanes walking j = 1..n together so that d_j and P[j-1] are
+//             wave-uniform scalar loads.  The window minimum is Algorithm 4's
+//             monotone queue, kept per lane as a small ring in LDS laid out
+//             [slot][lane] (bank = lane, so lanes at different depths never
+//             conflict).  Expiry compares the stored key P[h] with P[j-1]-s, so
+//             l(i) is never computed.  Only values are needed here, so equal
+//             tails are dropped too and the queue stays strictly increasing.
+//             A lane whose queue outgrows the ring raises its bit in the wave's
+//             flag word and is recomputed by the next kernel.
+//   overflow  one WAVE per flagged budget: F_s kept in LDS, the window minimum
+//             taken by a wave reduction over the window.  Any queue depth, no
+//             scratch in HBM.
+//   epilogue  one wave per chain: lexicographic minimum of (s + c_s, s) over the
+//             per-wave partial results (the smallest optimal budget value s*),
+//             then F_{s*} again with the smallest minimal predecessor recorded
+//             for every j, and the walk back from n that writes the mask.
+#include "ckpt_internal.h"
+
+namespace ckpt {
+namespace {
+
+constexpr int kBlock = 256;       // budgets kernel: 4 waves
+constexpr int kRing = 16;         // queue ring slots per lane
+constexpr int64_t kInf = INT64_MAX;
+
+struct ChainMeta {
+    int32_t status;
+    int32_t mode32;   // 1: normalised values fit 32-bit arithmetic
+    int32_t shift;    // sizes were divided by 2^shift
+    int32_t pad;
+};
+
+struct Partial {
+    int64_t cost;     // s + c_s, normalised; kInf if none
+    int64_t s;
+};
+
+struct CubicWs {
+    ChainMeta *meta;      // [batch]
+    int64_t *dn;          // [batch][n+1] normalised sizes (int32 view when mode32)
+    int64_t *Pn;          // [batch][n+1] normalised prefix sums
+    Partial *partial;     // [batch][waves_per_chain]
+    uint64_t *flags;      // [batch][waves_per_chain] lanes to recompute
+    int32_t *pred;        // [batch][n+1]
+};
+
+__host__ __device__ inline int64_t num_budgets(int n) { return (int64_t)n * (n - 1) / 2 + 1; }
+__host__ __device__ inline int64_t waves_per_chain(int n) { return (num_budgets(n) + kWave - 1) / kWave; }
+
+__host__ CubicWs carve_cubic(void *ws, int64_t batch, int n)
+{
+    char *p = (char *)ws;
+    const size_t n1 = (size_t)n + 1, B = (size_t)batch, wpc = (size_t)waves_per_chain(n);
+    CubicWs w;
+    w.meta = (ChainMeta *)p;    p += align_up(B * sizeof(ChainMeta));
+    w.dn = (int64_t *)p;        p += align_up(B * n1 * 8);
+    w.Pn = (int64_t *)p;        p += align_up(B * n1 * 8);
+    w.partial = (Partial *)p;   p += align_up(B * wpc * sizeof(Partial));
+    w.flags = (uint64_t *)p;    p += align_up(B * wpc * 8);
+    w.pred = (int32_t *)p;
+    return w;
+}
+
+// ---- wave helpers -----------------------------------------------------------
+
+__device__ inline int64_t shfl_i64(int64_t v, int src) { return __shfl(v, src, kWave); }
+__device__ inline int64_t shfl_xor_i64(int64_t v, int m) { return __shfl_xor(v, m, kWave); }
+__device__ inline int64_t shfl_up_i64(int64_t v, int d) { return __shfl_up(v, d, kWave); }
+
+// Lexicographic minimum of (a, b) over the wave; every lane gets the result.
+__device__ inline void wave_min_pair(int64_t &a, int64_t &b)
+{
+#pragma unroll
+    for (int m = kWave / 2; m >= 1; m >>= 1) {
+        const int64_t oa = shfl_xor_i64(a, m);
+        const int64_t ob = shfl_xor_i64(b, m);
+        const bool take = oa < a || (oa == a && ob < b);
+        a = take ? oa : a;
+        b = take ? ob : b;
+    }
+}
+
+// ---- prologue ---------------------------------------------------------------
+
+__global__ __launch_bounds__(kWave) void cubic_prologue_kernel(const int64_t *__restrict__ d, int64_t batch,
+                                                               int n, int64_t cstride, int64_t pstride,
+                                                               CubicWs w)
+{
+    const int64_t c = blockIdx.x;
+    const int lane = threadIdx.x;
+    const int64_t *dp = d + c * cstride;
+    const int n1 = n + 1;
+    const int chunk = (n1 + kWave - 1) / kWave;
+    const int k0 = lane * chunk;
+    const int k1 = min(k0 + chunk, n1);
+
+    uint64_t sum = 0, bits = 0;
+    int64_t mx = 0;
+    bool bad = false, ovf = false;
+    for (int k = k0; k < k1; ++k) {
+        const int64_t x = dp[(int64_t)k * pstride];
+        bad |= x <= 0;
+        bits |= (uint64_t)x;
+        mx = x > mx ? x : mx;
+        sum += (uint64_t)x;
+        ovf |= sum > (uint64_t)INT64_MAX;
+    }
+    // inclusive scan of the lane sums (all terms positive: any wrap shows as > INT64_MAX first)
+    uint64_t incl = sum;
+#pragma unroll
+    for (int dlt = 1; dlt < kWave; dlt <<= 1) {
+        const uint64_t o = (uint64_t)shfl_up_i64((int64_t)incl, dlt);
+        const bool oo = __shfl_up((int)ovf, dlt, kWave);
+        if (lane >= dlt) {
+            incl += o;
+            ovf |= oo | (incl > (uint64_t)INT64_MAX);
+        }
+    }
+    const uint64_t total = (uint64_t)shfl_i64((int64_t)incl, kWave - 1);
+#pragma unroll
+    for (int m = kWave / 2; m >= 1; m >>= 1) {
+        bits |= (uint64_t)shfl_xor_i64((int64_t)bits, m);
+        const int64_t om = shfl_xor_i64(mx, m);
+        mx = om > mx ? om : mx;
+    }
+    const bool any_bad = __any(bad);
+    bool any_ovf = __any(ovf);
+    any_ovf |= (total + (uint64_t)mx) > (uint64_t)INT64_MAX;
+
+    ChainMeta meta;
+    meta.status = any_bad ? CKPT_ERR_SIZE : (any_ovf ? CKPT_ERR_OVERFLOW : CKPT_OK);
+    meta.shift = 0;
+    meta.mode32 = 0;
+    meta.pad = 0;
+    if (meta.status == CKPT_OK) {
+        meta.shift = __ffsll((unsigned long long)bits) - 1;
+        meta.mode32 = ((total + (uint64_t)mx) >> meta.shift) < (1ull << 30);
+    }
+    if (lane == 0) w.meta[c] = meta;
+    if (meta.status != CKPT_OK) return;
+
+    uint64_t run = incl - sum;  // exclusive prefix of this lane's chunk
+    int64_t *dn64 = w.dn + c * n1;
+    int64_t *Pn64 = w.Pn + c * n1;
+    int32_t *dn32 = (int32_t *)dn64;
+    int32_t *Pn32 = (int32_t *)Pn64;
+    for (int k = k0; k < k1; ++k) {
+        const uint64_t x = (uint64_t)dp[(int64_t)k * pstride];
+        run += x;
+        if (meta.mode32) {
+            dn32[k] = (int32_t)(x >> meta.shift);
+            Pn32[k] = (int32_t)(run >> meta.shift);
+        } else {
+            dn64[k] = (int64_t)(x >> meta.shift);
+            Pn64[k] = (int64_t)(run >> meta.shift);
+        }
+    }
+}
+
+// ---- budget index -> (range length, start) ------------------------------------
+
+// Budget 0 is s = 0.  Budget t+1, 0 <= t < m(m+1)/2 with m = n-1, is the range of
+// length len starting at a, ranges ordered by length, then start.  Counting t
+// from the far end turns the rows of sizes m, m-1, .., 1 into rows of sizes
+// 1, 2, .., m whose starts are the triangular numbers.
+__device__ inline void budget_range(int64_t idx, int n, int &a, int &len)
+{
+    const int64_t m = n - 1;
+    const int64_t tri = m * (m + 1) / 2;
+    const int64_t tr = tri - 1 - (idx - 1);
+    int64_t r = (int64_t)((1.0 + sqrt(1.0 + 8.0 * (double)tr)) * 0.5);
+    while (r * (r - 1) / 2 > tr) --r;
+    while (r * (r + 1) / 2 <= tr) ++r;
+    const int64_t off = tr - r * (r - 1) / 2;  // 0 .. r-1 from the far end of the row
+    len = (int)(m - r + 1);
+    a = (int)(r - off);
+}
+
+template <typename V>
+__device__ inline V budget_value(const V *__restrict__ Pn, int64_t idx, int n)
+{
+    if (idx == 0) return 0;
+    int a, len;
+    budget_range(idx, n, a, len);
+    return Pn[a + len - 1] - Pn[a - 1];
+}
+
+// ---- budgets kernel: one lane per budget -----------------------------------------
+
+template <typename V>
+__global__ __launch_bounds__(kBlock) void cubic_budgets_kernel(int n, int64_t blocks_per_chain, CubicWs w)
+{
+    __shared__ V ringF[kRing][kBlock];
+    __shared__ V ringK[kRing][kBlock];
+
+    const int64_t c = blockIdx.x / blocks_per_chain;
+    const int64_t tile = blockIdx.x % blocks_per_chain;
+    const ChainMeta meta = w.meta[c];
+    if (meta.status != CKPT_OK || (meta.mode32 != 0) != (sizeof(V) == 4)) return;
+
+    const int tid = threadIdx.x;
+    const int n1 = n + 1;
+    const V *__restrict__ dn = (const V *)(w.dn + c * n1);
+    const V *__restrict__ Pn = (const V *)(w.Pn + c * n1);
+    const int64_t K = num_budgets(n);
+    const int64_t idx = tile * kBlock + tid;
+    const int64_t wave_in_chain = idx / kWave;   // uniform per wave
+    if (wave_in_chain * kWave >= K) return;      // whole wave beyond the list
+    const bool live = idx < K;
+    const V s = live ? budget_value<V>(Pn, idx, n) : 0;
+
+    int hd = 0, tl = -1;  // queue occupies ring slots hd..tl (mod kRing)
+    bool over = false;
+    V Fprev = dn[0];      // F(0) = d_0
+    for (int j = 1; j <= n; ++j) {
+        const V Pj1 = Pn[j - 1];
+        const V dj = dn[j];
+        // insert h = j-1 behind every strictly smaller value
+        while (tl >= hd && ringF[tl & (kRing - 1)][tid] >= Fprev) --tl;
+        ++tl;
+        ringF[tl & (kRing - 1)][tid] = Fprev;
+        ringK[tl & (kRing - 1)][tid] = Pj1;
+        over |= (tl - hd) >= kRing;
+        // drop heads whose segment h+1..j-1 no longer fits in s
+        const V theta = Pj1 - s;
+        while (hd < tl && ringK[hd & (kRing - 1)][tid] < theta) ++hd;
+        Fprev = dj + ringF[hd & (kRing - 1)][tid];
+    }
+
+    const bool redo = live && over;
+    const uint64_t flag = __ballot(redo);
+    int64_t cost = (live && !over) ? (int64_t)s + (int64_t)Fprev : kInf;
+    int64_t sv = (int64_t)s;
+    wave_min_pair(cost, sv);
+    if ((tid & (kWave - 1)) == 0) {
+        const int64_t slot = c * waves_per_chain(n) + wave_in_chain;
+        w.partial[slot] = Partial{cost, sv};
+        w.flags[slot] = flag;
+    }
+}
+
+// ---- one budget per wave ---------------------------------------------------------
+
+// F_s(0..n) into LDS array F by a wave reduction over each window; returns
+// F_s(n).  With pred != nullptr also records, for every j, the smallest h in
+// the window with minimal F (lane 0 writes).  Must be called by a full wave
+// that is the whole workgroup.
+template <typename V>
+__device__ V wave_budget_table(const V *__restrict__ dn, const V *__restrict__ Pn, int n, V s, V *F,
+                               int32_t *pred)
+{
+    const int lane = threadIdx.x;
+    if (lane == 0) F[0] = dn[0];
+    __syncthreads();
+    int l = 0;  // window start, uniform
+    V last = dn[0];
+    for (int j = 1; j <= n; ++j) {
+        const V Pj1 = Pn[j - 1];
+        while (Pj1 - Pn[l] > s) ++l;
+        int64_t bv = kInf, bh = kInf;
+        for (int h = l + lane; h <= j - 1; h += kWave) {
+            const int64_t v = (int64_t)F[h];
+            if (v < bv) { bv = v; bh = h; }
+        }
+        wave_min_pair(bv, bh);
+        last = dn[j] + (V)bv;
+        if (lane == 0) {
+            F[j] = last;
+            if (pred) pred[j] = (int32_t)bh;
+        }
+        __syncthreads();
+    }
+    return last;
+}
+
+extern __shared__ __align__(16) unsigned char dyn_lds[];
+
+__global__ __launch_bounds__(kWave) void cubic_overflow_kernel(int n, int64_t n_words, CubicWs w)
+{
+    const int64_t wpc = waves_per_chain(n);
+    const int n1 = n + 1;
+    for (int64_t word = blockIdx.x; word < n_words; word += gridDim.x) {
+        const int64_t c = word / wpc;
+        const int64_t base = (word % wpc) * kWave;
+        const ChainMeta meta = w.meta[c];
+        if (meta.status != CKPT_OK) continue;  // its flag words were never written
+        uint64_t flag = w.flags[word];
+        if (flag == 0) continue;
+        Partial best = w.partial[word];
+        while (flag) {
+            const int bit = __ffsll((unsigned long long)flag) - 1;
+            flag &= flag - 1;
+            int64_t s64, cost;
+            if (meta.mode32) {
+                const int32_t *dn = (const int32_t *)(w.dn + c * n1);
+                const int32_t *Pn = (const int32_t *)(w.Pn + c * n1);
+                const int32_t s = budget_value<int32_t>(Pn, base + bit, n);
+                s64 = s;
+                cost = s64 + wave_budget_table<int32_t>(dn, Pn, n, s, (int32_t *)dyn_lds, nullptr);
+            } else {
+                const int64_t *dn = w.dn + c * n1;
+                const int64_t *Pn = w.Pn + c * n1;
+                s64 = budget_value<int64_t>(Pn, base + bit, n);
+                cost = s64 + wave_budget_table<int64_t>(dn, Pn, n, s64, (int64_t *)dyn_lds, nullptr);
+            }
+            if (cost < best.cost || (cost == best.cost && s64 < best.s)) best = Partial{cost, s64};
+            __syncthreads();
+        }
+        if (threadIdx.x == 0) w.partial[word] = best;
+    }
+}
+
+// ---- epilogue --------------------------------------------------------------------
+
+__global__ __launch_bounds__(kWave) void cubic_epilogue_kernel(int n, int64_t cstride, int64_t pstride,
+                                                               uint8_t *__restrict__ mask_out,
+                                                               int64_t *__restrict__ peak_out,
+                                                               int64_t *__restrict__ budget_out,
+                                                               int32_t *__restrict__ status_out, CubicWs w)
+{
+    const int64_t c = blockIdx.x;
+    const int lane = threadIdx.x;
+    const int n1 = n + 1;
+    const ChainMeta meta = w.meta[c];
+    uint8_t *mp = mask_out + c * cstride;
+    if (lane == 0 && status_out) status_out[c] = meta.status;
+    if (meta.status != CKPT_OK) {
+        for (int k = lane; k < n1; k += kWave) mp[(int64_t)k * pstride] = 0;
+        if (lane == 0) {
+            peak_out[c] = -1;
+            if (budget_out) budget_out[c] = -1;
+        }
+        return;
+    }
+    const int64_t wpc = waves_per_chain(n);
+    int64_t cost = kInf, s = kInf;
+    for (int64_t t = lane; t < wpc; t += kWave) {
+        const Partial p = w.partial[c * wpc + t];
+        if (p.cost < cost || (p.cost == cost && p.s < s)) { cost = p.cost; s = p.s; }
+    }
+    wave_min_pair(cost, s);
+
+    int32_t *pred = w.pred + c * n1;
+    if (meta.mode32)
+        wave_budget_table<int32_t>((const int32_t *)(w.dn + c * n1), (const int32_t *)(w.Pn + c * n1), n,
+                                   (int32_t)s, (int32_t *)dyn_lds, pred);
+    else
+        wave_budget_table<int64_t>(w.dn + c * n1, w.Pn + c * n1, n, s, (int64_t *)dyn_lds, pred);
+
+    // the table is no longer needed: reuse its LDS as the mark array
+    uint8_t *mark = dyn_lds;
+    __syncthreads();
+    for (int k = lane; k < n1; k += kWave) mark[k] = 0;
+    __syncthreads();
+    if (lane == 0) {
+        int j = n;
+        mark[n] = 1;
+        while (j > 0) {
+            j = pred[j];
+            mark[j] = 1;
+        }
+        peak_out[c] = cost << meta.shift;
+        if (budget_out) budget_out[c] = s << meta.shift;
+    }
+    __syncthreads();
+    for (int k = lane; k < n1; k += kWave) mp[(int64_t)k * pstride] = mark[k];
+}
+
+}  // namespace
+
+size_t cubic_workspace_bytes(int64_t batch, int n)
+{
+    const size_t n1 = (size_t)n + 1, B = (size_t)batch, wpc = (size_t)waves_per_chain(n);
+    return align_up(B * sizeof(ChainMeta)) + 2 * align_up(B * n1 * 8) + align_up(B * wpc * sizeof(Partial)) +
+           align_up(B * wpc * 8) + align_up(B * n1 * 4) + 256;
+}
+
+hipError_t launch_solve_cubic(const int64_t *d, int64_t batch, int n, Strides st, uint8_t *mask_out,
+                              int64_t *peak_out, int64_t *budget_out, int32_t *status_out, void *ws,
+                              hipStream_t stream)
+{
+    if (batch == 0) return hipSuccess;
+    CubicWs w = carve_cubic(ws, batch, n);
+    const int64_t K = num_budgets(n);
+    const int64_t blocks_per_chain = (K + kBlock - 1) / kBlock;
+    const int64_t total_blocks = blocks_per_chain * batch;
+    const int64_t n_words = waves_per_chain(n) * batch;
+    if (total_blocks > 0x7fffffffLL || batch > 0x7fffffffLL) return hipErrorInvalidConfiguration;
+    const size_t table_lds = ((size_t)n + 1) * 8;
+
+    hipLaunchKernelGGL(cubic_prologue_kernel, dim3((unsigned)batch), dim3(kWave), 0, stream, d, batch, n,
+                       st.chain, st.pos, w);
+    hipLaunchKernelGGL(cubic_budgets_kernel<int32_t>, dim3((unsigned)total_blocks), dim3(kBlock), 0, stream, n,
+                       blocks_per_chain, w);
+    hipLaunchKernelGGL(cubic_budgets_kernel<int64_t>, dim3((unsigned)total_blocks), dim3(kBlock), 0, stream, n,
+                       blocks_per_chain, w);
+    const unsigned over_grid = (unsigned)(n_words < 4096 ? n_words : 4096);
+    hipLaunchKernelGGL(cubic_overflow_kernel, dim3(over_grid), dim3(kWave), table_lds, stream, n, n_words, w);
+    hipLaunchKernelGGL(cubic_epilogue_kernel, dim3((unsigned)batch), dim3(kWave), table_lds, stream, n, st.chain,
+                       st.pos, mask_out, peak_out, budget_out, status_out, w);
+    return hipGetLastError();
+}
+
+}  // namespace ckpt

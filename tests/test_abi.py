@@ -1,0 +1,79 @@
+"""The C-ABI library loads and exports every symbol include/ckpt.h declares;
+host-only calls and host-side argument checks (nothing here launches a kernel)."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2502_12499_amd import binding as B
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def declared_functions():
+    text = open(os.path.join(ROOT, "include", "ckpt.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(ckpt_[a-z_]+)\s*\(", text)))
+
+
+def test_header_declares_the_three_calls():
+    names = declared_functions()
+    for want in ("ckpt_eval_peak", "ckpt_solve_cubic", "ckpt_solve_linear", "ckpt_workspace_bytes"):
+        assert want in names
+
+
+def test_library_exports_every_declared_symbol():
+    lib = B.load()
+    for name in declared_functions():
+        assert getattr(lib, name) is not None, name
+    assert set(B.EXPORTS) == set(declared_functions())
+
+
+def test_host_only_helpers():
+    assert B.cubic_cells(12) == (12 * 11 // 2 + 1) * 12 == 804
+    assert B.cubic_cells(1001) == 500501 * 1001
+    assert B.cubic_cells(4096) == 8386561 * 4096
+    assert B.status_string(0) == "ok"
+    assert "size" in B.status_string(3)
+
+
+def test_workspace_bytes_and_layout_checks():
+    good = B.Layout(1024, 64, 1, 1024)
+    for which in (B.CALL_EVAL_PEAK, B.CALL_SOLVE_CUBIC, B.CALL_SOLVE_LINEAR):
+        assert B.workspace_bytes(which, good) > 0
+    assert B.workspace_bytes(7, good) == 0
+    for bad in (B.Layout(-1, 64, 1, 1024), B.Layout(8, 0, 1, 8), B.Layout(8, 64, 0, 8),
+                B.Layout(8, 64, 1, 0), B.Layout(8, 70000, 1, 8)):
+        assert B.workspace_bytes(B.CALL_SOLVE_LINEAR, bad) == 0
+    # the cubic solver has its own, smaller limit on n
+    assert B.workspace_bytes(B.CALL_SOLVE_CUBIC, B.Layout(1, 8192, 1, 1)) == 0
+    assert B.workspace_bytes(B.CALL_SOLVE_CUBIC, B.Layout(1, 8191, 1, 1)) > 0
+    # grows with the problem
+    assert B.workspace_bytes(B.CALL_SOLVE_LINEAR, B.Layout(2048, 64, 1, 2048)) > \
+        B.workspace_bytes(B.CALL_SOLVE_LINEAR, good)
+
+
+def test_host_detectable_errors_return_without_launching():
+    lib = B.load()
+    L = B.Layout(4, 8, 1, 4)
+    fake = ctypes.c_void_p(4096)  # never dereferenced: every call below fails validation first
+    assert lib.ckpt_eval_peak(fake, fake, None, 0, fake, None, None, 0, None) == 1
+    assert lib.ckpt_eval_peak(None, fake, ctypes.byref(L), 0, fake, None, None, 0, None) == 1
+    assert lib.ckpt_eval_peak(fake, fake, ctypes.byref(L), 2, fake, None, None, 0, None) == 2
+    assert lib.ckpt_solve_linear(fake, ctypes.byref(B.Layout(4, 0, 1, 4)), fake, fake, None, fake, 1 << 20, None) == 2
+    assert lib.ckpt_solve_linear(fake, ctypes.byref(L), fake, fake, None, None, 0, None) == 1
+    assert lib.ckpt_solve_linear(fake, ctypes.byref(L), fake, fake, None, fake, 16, None) == 6      # too small
+    assert lib.ckpt_solve_cubic(fake, ctypes.byref(L), fake, fake, None, None, ctypes.c_void_p(4100), 1 << 30, None) == 6  # misaligned
+    assert lib.ckpt_solve_cubic(fake, ctypes.byref(L), None, fake, None, None, fake, 1 << 30, None) == 1
+    # an empty batch is a successful no-op
+    E = B.Layout(0, 8, 1, 1)
+    assert lib.ckpt_solve_cubic(None, ctypes.byref(E), None, None, None, None, None, 0, None) == 0
+    assert lib.ckpt_eval_peak(None, None, ctypes.byref(E), 1, None, None, None, 0, None) == 0
+
+
+def test_binding_refuses_cpu_tensors():
+    import torch
+    d = torch.ones(5, 3, dtype=torch.int64)
+    with pytest.raises(TypeError):
+        B.ckpt_solve_linear(d)

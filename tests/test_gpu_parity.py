@@ -1,0 +1,232 @@
+"""Parity of the HIP library (through the C ABI) with the CPU oracle, element
+by element, on seeded inputs.  All values are integers: the bar is bit-exact
+peaks, budgets, statuses and checkpoint masks (the canonical sets)."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2502_12499_amd import binding as B
+from paper_2502_12499_amd import inputs
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+
+def to_dev(x):
+    return torch.from_numpy(np.ascontiguousarray(x)).to(DEV)
+
+
+def np_(t):
+    return t.cpu().numpy()
+
+
+def say(msg):
+    print(msg, flush=True)
+
+
+# ---------------------------------------------------------------------------
+# helpers: run one call and compare with the oracle
+# ---------------------------------------------------------------------------
+
+def check_eval(d, m, chain_major=False):
+    """d, m: position-major numpy (n+1, batch)."""
+    dc, mc = inputs.chain_major(d), inputs.chain_major(m)
+    for obj in (B.OBJ_STATIC, B.OBJ_DYNAMIC):
+        if chain_major:
+            peak, status = B.ckpt_eval_peak(to_dev(dc), to_dev(mc), obj, chain_major=True)
+        else:
+            peak, status = B.ckpt_eval_peak(to_dev(d), to_dev(m), obj)
+        torch.cuda.synchronize()
+        want = oracle.batch_peak(dc, mc, obj)
+        assert (np_(status) == 0).all()
+        assert np.array_equal(np_(peak), want), f"objective {obj}"
+
+
+def check_linear(d, chain_major=False):
+    dc = inputs.chain_major(d)
+    if chain_major:
+        mask, peak, status = B.ckpt_solve_linear(to_dev(dc), chain_major=True)
+        got_mask = np_(mask)
+    else:
+        mask, peak, status = B.ckpt_solve_linear(to_dev(d))
+        got_mask = np_(mask).T
+    torch.cuda.synchronize()
+    want_peak, want_mask = oracle.batch_solve_dynamic(dc)
+    assert (np_(status) == 0).all()
+    assert np.array_equal(np_(peak), want_peak)
+    assert np.array_equal(got_mask, want_mask)
+
+
+def check_cubic(d, chain_major=False):
+    dc = inputs.chain_major(d)
+    if chain_major:
+        mask, peak, budget, status = B.ckpt_solve_cubic(to_dev(dc), chain_major=True)
+        got_mask = np_(mask)
+    else:
+        mask, peak, budget, status = B.ckpt_solve_cubic(to_dev(d))
+        got_mask = np_(mask).T
+    torch.cuda.synchronize()
+    want_peak, want_mask, want_s = oracle.batch_solve_static(dc)
+    assert (np_(status) == 0).all()
+    assert np.array_equal(np_(peak), want_peak)
+    assert np.array_equal(np_(budget), want_s)
+    assert np.array_equal(got_mask, want_mask)
+
+
+def special_chains():
+    """Degenerate and adversarial single chains, as (name, 1-D int64 array)."""
+    rng = np.random.default_rng(7)
+    out = [
+        ("n1", np.array([5, 9])),
+        ("n2", np.array([5, 1, 9])),
+        ("n3_ties", np.array([2, 2, 2, 2])),
+        ("uniform_50", np.ones(51, dtype=np.int64) * 4096),
+        ("increasing_80", np.arange(1, 82, dtype=np.int64) * 3),          # deep queues
+        ("decreasing_80", np.arange(81, 0, -1, dtype=np.int64) * 5),
+        ("huge_last", np.concatenate([np.ones(70, dtype=np.int64), [10 ** 12]])),
+        ("huge_first", np.concatenate([[10 ** 12], np.ones(70, dtype=np.int64)])),
+        ("sawtooth_97", np.tile(np.array([1, 50, 3, 40, 7], dtype=np.int64), 20)[:98]),
+        ("ties_200", rng.integers(1, 4, size=201)),
+        ("wide_130", rng.integers(1, 1 << 40, size=131)),                   # 64-bit arithmetic
+        ("odd_bytes_65", rng.integers(1, 1 << 20, size=66) * 2 + 1),        # no common factor
+        ("vgg19", inputs.vgg19_chain()[:, 0]),
+    ]
+    return [(k, np.asarray(v, dtype=np.int64)) for k, v in out]
+
+
+# ---------------------------------------------------------------------------
+# eval_peak
+# ---------------------------------------------------------------------------
+
+@pytest.mark.parametrize("batch,n", [(1, 12), (3, 1), (64, 64), (1000, 64), (777, 257), (4096, 256)])
+def test_eval_peak_batches(batch, n):
+    say(f"eval_peak batch={batch} n={n}")
+    d = inputs.log_uniform_chains(11, n, batch)
+    m = inputs.bernoulli_masks(11, n, batch)
+    check_eval(d, m)
+    check_eval(d, m, chain_major=True)
+
+
+def test_eval_peak_fixed_sets_and_paper_sets():
+    d = inputs.vgg19_chain()
+    for positions in ([3, 6, 24], [5, 10, 15, 20, 24], [2, 4, 6, 9, 11, 14, 16, 19, 21, 23, 24], [24],
+                      list(range(1, 25))):
+        m = np.zeros((25, 1), dtype=np.uint8)
+        m[0] = 1
+        m[positions] = 1
+        check_eval(d, m)
+
+
+def test_eval_peak_data_errors():
+    n, batch = 9, 6
+    d = inputs.uniform_aligned_chains(3, n, batch, 1, 100, unit=1)
+    m = np.ones((n + 1, batch), dtype=np.uint8)
+    d[4, 1] = 0                      # non-positive size
+    d[2, 2] = -5
+    d[:, 3] = (1 << 62)              # overflow of the sum
+    m[0, 4] = 0                      # open ends
+    m[n, 5] = 0
+    for obj in (0, 1):
+        peak, status = B.ckpt_eval_peak(to_dev(d), to_dev(m), obj)
+        torch.cuda.synchronize()
+        assert np_(status).tolist() == [0, 3, 3, 4, 5, 5]
+        assert np_(peak)[1:].tolist() == [-1] * 5
+        assert np_(peak)[0] == oracle.batch_peak(inputs.chain_major(d)[:1], inputs.chain_major(m)[:1], obj)[0]
+
+
+# ---------------------------------------------------------------------------
+# solve_linear
+# ---------------------------------------------------------------------------
+
+@pytest.mark.parametrize("name,d", special_chains())
+def test_solve_linear_special_chains(name, d):
+    say(f"solve_linear {name}")
+    check_linear(d.reshape(-1, 1))
+
+
+def test_solve_linear_single_chain_configs():
+    for name, d in (("config1", inputs.config1()), ("config2", inputs.config2()), ("config4", inputs.config4())):
+        say(f"solve_linear {name}")
+        check_linear(d)
+    say("solve_linear config5 single")
+    check_linear(inputs.config5_single(4096))
+
+
+@pytest.mark.parametrize("batch,n,kind", [(64, 64, "log"), (1000, 64, "log"), (333, 17, "ties"),
+                                          (4096, 64, "log"), (2048, 256, "aligned"), (130, 300, "ties")])
+def test_solve_linear_batches(batch, n, kind):
+    say(f"solve_linear batch={batch} n={n} {kind}")
+    if kind == "log":
+        d = inputs.log_uniform_chains(1, n, batch)
+    elif kind == "aligned":
+        d = inputs.uniform_aligned_chains(2, n, batch, 256, 32768)
+    else:
+        d = inputs.uniform_aligned_chains(5, n, batch, 1, 3, unit=1)
+    check_linear(d)
+    if batch <= 1000:
+        check_linear(d, chain_major=True)
+
+
+def test_solve_linear_data_errors():
+    n, batch = 12, 4
+    d = inputs.uniform_aligned_chains(3, n, batch, 1, 100, unit=1)
+    d[5, 1] = 0
+    d[:, 2] = (1 << 61)
+    mask, peak, status = B.ckpt_solve_linear(to_dev(d))
+    torch.cuda.synchronize()
+    assert np_(status).tolist() == [0, 3, 4, 0]
+    assert np_(peak)[1] == -1 and np_(peak)[2] == -1
+    assert (np_(mask)[:, 1] == 0).all() and (np_(mask)[:, 2] == 0).all()
+    for c in (0, 3):
+        v, mk, _ = oracle.solve_dynamic(d[:, c])
+        assert np_(peak)[c] == v and (np_(mask)[:, c] == mk).all()
+
+
+# ---------------------------------------------------------------------------
+# solve_cubic
+# ---------------------------------------------------------------------------
+
+@pytest.mark.parametrize("name,d", special_chains())
+def test_solve_cubic_special_chains(name, d):
+    say(f"solve_cubic {name}")
+    check_cubic(d.reshape(-1, 1))
+
+
+def test_solve_cubic_single_chain_configs():
+    for name, d in (("config1", inputs.config1()), ("config2", inputs.config2())):
+        say(f"solve_cubic {name}")
+        check_cubic(d)
+
+
+def test_solve_cubic_resnet1001():
+    say("solve_cubic config4 (n=1001)")
+    check_cubic(inputs.config4())
+
+
+@pytest.mark.parametrize("batch,n,kind", [(64, 64, "log"), (200, 33, "ties"), (16, 64, "aligned"), (5, 130, "log")])
+def test_solve_cubic_batches(batch, n, kind):
+    say(f"solve_cubic batch={batch} n={n} {kind}")
+    if kind == "log":
+        d = inputs.log_uniform_chains(1, n, batch)
+    elif kind == "aligned":
+        d = inputs.uniform_aligned_chains(2, n, batch, 256, 32768)
+    else:
+        d = inputs.uniform_aligned_chains(5, n, batch, 1, 3, unit=1)
+    check_cubic(d)
+    check_cubic(d, chain_major=True)
+
+
+def test_solve_cubic_data_errors():
+    n, batch = 12, 4
+    d = inputs.uniform_aligned_chains(3, n, batch, 1, 100, unit=1)
+    d[5, 1] = 0
+    d[:, 2] = (1 << 61)
+    mask, peak, budget, status = B.ckpt_solve_cubic(to_dev(d))
+    torch.cuda.synchronize()
+    assert np_(status).tolist() == [0, 3, 4, 0]
+    assert np_(peak)[1] == -1 and np_(peak)[2] == -1
+    assert (np_(mask)[:, 1] == 0).all() and (np_(mask)[:, 2] == 0).all()
+    for c in (0, 3):
+        v, mk, s = oracle.solve_static(d[:, c])
+        assert np_(peak)[c] == v and np_(budget)[c] == s and (np_(mask)[:, c] == mk).all()
