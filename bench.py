@@ -1,0 +1,205 @@
+#!/usr/bin/env python3
+"""Benchmark of the checkpoint-selection hot path on one MI355X.
+
+One step = one pass of the whole path over the stress workload:
+  ckpt_eval_peak (static, then dynamic objective) and ckpt_solve_linear on a
+  batch of 1,048,576 chains of n = 256 layers, and ckpt_solve_cubic on one chain
+  of n = 4096 layers; sizes are 4 KiB multiples in [1 MiB, 128 MiB], seed 2.
+Inputs are generated on the host once, copied to HBM, and stay there; the timed
+region contains only library calls.  Prints one JSON line.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+# 256 CUs x 4 SIMDs x 16 lanes x 2.4 GHz: one 32-bit integer lane-op per lane per clock
+INT32_PEAK_TOPS = 256 * 64 * 2.4e9 / 1e12
+CUBIC_OPS_PER_CELL = 3  # one add and two compare-selects (queue push / pop) per recurrence cell
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def cpu_baseline(d_batch_np, d_single_np, n_cubic, linear_cells, cubic_cells):
+    """The oracle, as it stands, on a bounded sample of the same workload."""
+    import oracle
+    from paper_2502_12499_amd import inputs
+    threads = oracle.max_threads()
+    # linear: Algorithm 5 on the first chains of the batch
+    sample_chains = min(d_batch_np.shape[1], 65536 * max(1, threads // 4))
+    dc = inputs.chain_major(d_batch_np[:, :sample_chains])
+    t0 = time.perf_counter()
+    oracle.batch_solve_dynamic(dc, want_mask=True)
+    t_lin = time.perf_counter() - t0
+    lin_rate = sample_chains * (dc.shape[1] - 1) / t_lin
+    # cubic: Algorithm 4's queue on slices of the budget list spread over all range lengths
+    K = oracle.num_budgets(n_cubic)
+    slices, per = 16, 16384 * max(1, threads // 4)
+    d1 = d_single_np[:, 0]
+    t0 = time.perf_counter()
+    done = 0
+    for i in range(slices):
+        first = (K // slices) * i
+        num = min(per, K - first)
+        oracle.solve_static_range(d1, first, num)
+        done += num
+    t_cub = time.perf_counter() - t0
+    cub_rate = done * n_cubic / t_cub
+    est_step_s = linear_cells / lin_rate + cubic_cells / cub_rate
+    return {
+        "value": (linear_cells + cubic_cells) / est_step_s,
+        "unit": "cells/s",
+        "cores": threads,
+        "kind": "oracle",
+        "sample": (f"Algorithm 5 on {sample_chains} chains of the batch ({t_lin:.2f} s, {lin_rate:.3e} cells/s); "
+                   f"Algorithm 4 on {done} of {K} budgets of the n={n_cubic} chain in {slices} slices "
+                   f"({t_cub:.2f} s, {cub_rate:.3e} cells/s); value = step cells / (cells/rate summed)"),
+        "linear_cells_per_s": lin_rate,
+        "cubic_cells_per_s": cub_rate,
+    }
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=5)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--batch", type=int, default=1048576, help="chains in the batched part")
+    ap.add_argument("--n-batch", type=int, default=256)
+    ap.add_argument("--n-cubic", type=int, default=4096)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this path runs on one GPU only (independent chains and budgets would be split "
+              "across GPUs without communication; no multi-GPU figure is produced). Use --gpus 1.",
+              file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2502_12499_amd import binding as B
+    from paper_2502_12499_amd import inputs
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    dev = torch.device("cuda:0")
+    B.load()
+
+    t0 = time.perf_counter()
+    d_np, m_np = inputs.config5_batch(batch=args.batch, n_layers=args.n_batch)
+    d1_np = inputs.config5_single(args.n_cubic)
+    log(f"inputs generated in {time.perf_counter() - t0:.1f} s")
+    d = torch.from_numpy(d_np).to(dev)
+    m = torch.from_numpy(m_np).to(dev)
+    d1 = torch.from_numpy(d1_np).to(dev)
+
+    L = B.layout_of(d)
+    L1 = B.layout_of(d1)
+    ws_lin = torch.empty(B.workspace_bytes(B.CALL_SOLVE_LINEAR, L), dtype=torch.uint8, device=dev)
+    ws_cub = torch.empty(B.workspace_bytes(B.CALL_SOLVE_CUBIC, L1), dtype=torch.uint8, device=dev)
+
+    names = ["eval_static", "eval_dynamic", "solve_linear", "solve_cubic"]
+
+    def step(events=None):
+        marks = []
+
+        def mark():
+            if events is not None:
+                e = torch.cuda.Event(enable_timing=True)
+                e.record()
+                marks.append(e)
+        mark()
+        r0 = B.ckpt_eval_peak(d, m, B.OBJ_STATIC, want_status=False)
+        mark()
+        r1 = B.ckpt_eval_peak(d, m, B.OBJ_DYNAMIC, want_status=False)
+        mark()
+        r2 = B.ckpt_solve_linear(d, workspace=ws_lin, want_status=False)
+        mark()
+        r3 = B.ckpt_solve_cubic(d1, workspace=ws_cub, want_status=False)
+        mark()
+        if events is not None:
+            events.append(marks)
+        return r0, r1, r2, r3
+
+    for _ in range(args.warmup):
+        out = step()
+    torch.cuda.synchronize()
+    events = []
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        out = step(events)
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+
+    per_call = {k: [] for k in names}
+    for marks in events:
+        for i, k in enumerate(names):
+            per_call[k].append(marks[i].elapsed_time(marks[i + 1]))
+    ms = {k: float(np.mean(v)) for k, v in per_call.items()}
+    ms_step = wall * 1e3 / args.steps
+
+    n, Bn, nc = args.n_batch, args.batch, args.n_cubic
+    linear_cells = Bn * n
+    cubic_cells = B.cubic_cells(nc)
+    chain_bytes = 9 * (n + 1) + 8  # sizes in (or out: the mask) + 8-byte peak
+    kernels = {
+        "eval_static": {"ms": ms["eval_static"], "instances_per_s": Bn / (ms["eval_static"] * 1e-3),
+                        "hbm_GBs": Bn * chain_bytes / (ms["eval_static"] * 1e-3) / 1e9},
+        "eval_dynamic": {"ms": ms["eval_dynamic"], "instances_per_s": Bn / (ms["eval_dynamic"] * 1e-3),
+                         "hbm_GBs": Bn * chain_bytes / (ms["eval_dynamic"] * 1e-3) / 1e9},
+        "solve_linear": {"ms": ms["solve_linear"], "instances_per_s": Bn / (ms["solve_linear"] * 1e-3),
+                         "cells_per_s": linear_cells / (ms["solve_linear"] * 1e-3),
+                         "hbm_GBs": Bn * chain_bytes / (ms["solve_linear"] * 1e-3) / 1e9},
+        "solve_cubic": {"ms": ms["solve_cubic"], "instances_per_s": 1.0 / (ms["solve_cubic"] * 1e-3),
+                        "cells_per_s": cubic_cells / (ms["solve_cubic"] * 1e-3),
+                        "cells_nominal_n3_per_s": float(nc) ** 3 / (ms["solve_cubic"] * 1e-3),
+                        "int32_TOPs": cubic_cells * CUBIC_OPS_PER_CELL / (ms["solve_cubic"] * 1e-3) / 1e12},
+    }
+    for k in ("eval_static", "eval_dynamic", "solve_linear"):
+        kernels[k]["hbm_frac"] = kernels[k]["hbm_GBs"] / HBM_PEAK_GBS
+    kernels["solve_cubic"]["int32_frac"] = kernels["solve_cubic"]["int32_TOPs"] / INT32_PEAK_TOPS
+
+    dominant = max(names, key=lambda k: ms[k])
+    if dominant == "solve_cubic":
+        roofline = {"kernel": "cubic_budgets_kernel (ckpt_solve_cubic)", "bound": "alu",
+                    "achieved": kernels["solve_cubic"]["int32_TOPs"], "peak": INT32_PEAK_TOPS, "unit": "TOP/s",
+                    "frac": kernels["solve_cubic"]["int32_frac"], "traffic": None}
+    else:
+        roofline = {"kernel": dominant, "bound": "hbm", "achieved": kernels[dominant]["hbm_GBs"],
+                    "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": kernels[dominant]["hbm_frac"], "traffic": None}
+    roofline_linear = {"kernel": "ckpt_solve_linear", "bound": "hbm", "achieved": kernels["solve_linear"]["hbm_GBs"],
+                       "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": kernels["solve_linear"]["hbm_frac"],
+                       "traffic": None}
+
+    rec = {
+        "metric": "DP cells/sec over one pass of the checkpoint-selection path (cubic + linear recurrence cells)",
+        "value": (linear_cells + cubic_cells) / (ms_step * 1e-3),
+        "unit": "cells/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "int64 in/out, int32 arithmetic after dividing by the common power of two",
+        "data": "synthetic",
+        "config": {"workload": f"stress: 1 chain n={nc} (cubic) + {Bn} chains n={n} (linear, eval_peak x2), "
+                               "sizes 4 KiB x U{256..32768}, seed 2",
+                   "layout": "position-major int64"},
+        "instances_per_sec": {k: kernels[k]["instances_per_s"] for k in names},
+        "kernels": kernels,
+        "roofline": roofline,
+        "roofline_linear": roofline_linear,
+        "paper_context": "Python on a Xeon Gold 6226R, VGG-19 (n=24): Algorithm 4 20 ms, Algorithm 6 1.1 ms per chain",
+    }
+    if not args.no_cpu_baseline:
+        rec["cpu_baseline"] = cpu_baseline(d_np, d1_np, nc, linear_cells, cubic_cells)
+    print(json.dumps(rec), flush=True)
+
+
+if __name__ == "__main__":
+    main()

@@ -232,14 +232,15 @@ i64 orc_num_budgets(int n) { return (i64)n * (n - 1) / 2 + 1; }
  * start. */
 void orc_budgets(const i64 *d, int n, i64 *out)
 {
+    i64 *P = (i64 *)malloc(sizeof(i64) * ((size_t)n + 1));   /* P[k] = d_0 + .. + d_k */
+    P[0] = d[0];
+    for (int k = 1; k <= n; k++) P[k] = P[k - 1] + d[k];
     i64 t = 0;
     out[t++] = 0;
     for (int len = 1; len <= n - 1; len++)
-        for (int a = 1; a + len - 1 <= n - 1; a++) {
-            i64 s = 0;
-            for (int k = a; k <= a + len - 1; k++) s += d[k];
-            out[t++] = s;
-        }
+        for (int a = 1; a + len - 1 <= n - 1; a++)
+            out[t++] = P[a + len - 1] - P[a - 1];            /* d_a + .. + d_{a+len-1} */
+    free(P);
 }
 
 /* The two-step scheme with the literal recurrence.  O(n^4); small n only.
