@@ -36,8 +36,6 @@
 namespace ckpt {
 namespace {
 
-constexpr int kBlock = 256;       // budgets kernel: 4 waves
-constexpr int kRing = 16;         // queue ring slots per lane
 constexpr int64_t kInf = INT64_MAX;
 
 struct ChainMeta {
@@ -205,10 +203,16 @@ __device__ inline V budget_value(const V *__restrict__ Pn, int64_t idx, int n)
 // ---- budgets kernel: one lane per budget -----------------------------------------
 
 template <typename V>
-__global__ __launch_bounds__(kBlock) void cubic_budgets_kernel(int n, int64_t blocks_per_chain, CubicWs w)
+struct QueueEntry {
+    V F;  // F_s(h)
+    V K;  // P[h], the key the expiry test compares with P[j-1] - s
+};
+
+// RING slots per lane, BLOCK lanes per workgroup: RING * BLOCK * sizeof(QueueEntry) bytes of LDS.
+template <typename V, int RING, int BLOCK>
+__global__ __launch_bounds__(BLOCK) void cubic_budgets_kernel(int n, int64_t blocks_per_chain, CubicWs w)
 {
-    __shared__ V ringF[kRing][kBlock];
-    __shared__ V ringK[kRing][kBlock];
+    __shared__ QueueEntry<V> ring[RING][BLOCK];
 
     const int64_t c = blockIdx.x / blocks_per_chain;
     const int64_t tile = blockIdx.x % blocks_per_chain;
@@ -220,28 +224,41 @@ __global__ __launch_bounds__(kBlock) void cubic_budgets_kernel(int n, int64_t bl
     const V *__restrict__ dn = (const V *)(w.dn + c * n1);
     const V *__restrict__ Pn = (const V *)(w.Pn + c * n1);
     const int64_t K = num_budgets(n);
-    const int64_t idx = tile * kBlock + tid;
+    const int64_t idx = tile * BLOCK + tid;
     const int64_t wave_in_chain = idx / kWave;   // uniform per wave
     if (wave_in_chain * kWave >= K) return;      // whole wave beyond the list
     const bool live = idx < K;
     const V s = live ? budget_value<V>(Pn, idx, n) : 0;
 
-    int hd = 0, tl = -1;  // queue occupies ring slots hd..tl (mod kRing)
+    // The queue occupies ring slots hd..tl (mod RING); its head entry and its
+    // tail value are mirrored in registers.  It starts as {h = 0}.
+    int hd = 0, tl = 0;
+    V hF = dn[0], hK = Pn[0], tF = hF;
+    ring[0][tid] = QueueEntry<V>{hF, hK};
     bool over = false;
-    V Fprev = dn[0];      // F(0) = d_0
-    for (int j = 1; j <= n; ++j) {
+    V Fprev = dn[1] + hF;  // F(1) = d_1 + F(0)
+    for (int j = 2; j <= n; ++j) {
         const V Pj1 = Pn[j - 1];
         const V dj = dn[j];
-        // insert h = j-1 behind every strictly smaller value
-        while (tl >= hd && ringF[tl & (kRing - 1)][tid] >= Fprev) --tl;
+        // insert h = j-1 behind every strictly smaller value; the head is
+        // smaller than F(j-1) = d_{j-1} + head, so it is never dropped here
+        while (tF >= Fprev && tl > hd) {
+            --tl;
+            tF = ring[tl & (RING - 1)][tid].F;
+        }
         ++tl;
-        ringF[tl & (kRing - 1)][tid] = Fprev;
-        ringK[tl & (kRing - 1)][tid] = Pj1;
-        over |= (tl - hd) >= kRing;
-        // drop heads whose segment h+1..j-1 no longer fits in s
+        ring[tl & (RING - 1)][tid] = QueueEntry<V>{Fprev, Pj1};
+        tF = Fprev;
+        over |= (tl - hd) >= RING;
+        // drop heads whose segment h+1..j-1 no longer fits in s (h = j-1 always fits)
         const V theta = Pj1 - s;
-        while (hd < tl && ringK[hd & (kRing - 1)][tid] < theta) ++hd;
-        Fprev = dj + ringF[hd & (kRing - 1)][tid];
+        while (hK < theta && hd < tl) {
+            ++hd;
+            const QueueEntry<V> e = ring[hd & (RING - 1)][tid];
+            hF = e.F;
+            hK = e.K;
+        }
+        Fprev = dj + hF;
     }
 
     const bool redo = live && over;
@@ -254,6 +271,14 @@ __global__ __launch_bounds__(kBlock) void cubic_budgets_kernel(int n, int64_t bl
         w.partial[slot] = Partial{cost, sv};
         w.flags[slot] = flag;
     }
+}
+
+template <typename V, int RING, int BLOCK>
+void launch_budgets(int n, int64_t batch, CubicWs w, hipStream_t stream)
+{
+    const int64_t blocks_per_chain = (num_budgets(n) + BLOCK - 1) / BLOCK;
+    hipLaunchKernelGGL((cubic_budgets_kernel<V, RING, BLOCK>), dim3((unsigned)(blocks_per_chain * batch)),
+                       dim3(BLOCK), 0, stream, n, blocks_per_chain, w);
 }
 
 // ---- one budget per wave ---------------------------------------------------------
@@ -399,18 +424,21 @@ hipError_t launch_solve_cubic(const int64_t *d, int64_t batch, int n, Strides st
     if (batch == 0) return hipSuccess;
     CubicWs w = carve_cubic(ws, batch, n);
     const int64_t K = num_budgets(n);
-    const int64_t blocks_per_chain = (K + kBlock - 1) / kBlock;
-    const int64_t total_blocks = blocks_per_chain * batch;
+    const int64_t total_blocks = (K + 127) / 128 * batch;
     const int64_t n_words = waves_per_chain(n) * batch;
     if (total_blocks > 0x7fffffffLL || batch > 0x7fffffffLL) return hipErrorInvalidConfiguration;
     const size_t table_lds = ((size_t)n + 1) * 8;
 
     hipLaunchKernelGGL(cubic_prologue_kernel, dim3((unsigned)batch), dim3(kWave), 0, stream, d, batch, n,
                        st.chain, st.pos, w);
-    hipLaunchKernelGGL(cubic_budgets_kernel<int32_t>, dim3((unsigned)total_blocks), dim3(kBlock), 0, stream, n,
-                       blocks_per_chain, w);
-    hipLaunchKernelGGL(cubic_budgets_kernel<int64_t>, dim3((unsigned)total_blocks), dim3(kBlock), 0, stream, n,
-                       blocks_per_chain, w);
+    // Queue depth grows like log(window length): 16 slots for short chains, 32 beyond.
+    if (n <= 512) {
+        launch_budgets<int32_t, 16, 256>(n, batch, w, stream);
+        launch_budgets<int64_t, 16, 256>(n, batch, w, stream);
+    } else {
+        launch_budgets<int32_t, 32, 256>(n, batch, w, stream);
+        launch_budgets<int64_t, 32, 128>(n, batch, w, stream);
+    }
     const unsigned over_grid = (unsigned)(n_words < 4096 ? n_words : 4096);
     hipLaunchKernelGGL(cubic_overflow_kernel, dim3(over_grid), dim3(kWave), table_lds, stream, n, n_words, w);
     hipLaunchKernelGGL(cubic_epilogue_kernel, dim3((unsigned)batch), dim3(kWave), table_lds, stream, n, st.chain,
