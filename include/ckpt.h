@@ -69,7 +69,7 @@ typedef enum { CKPT_CALL_EVAL_PEAK = 0, CKPT_CALL_SOLVE_CUBIC = 1, CKPT_CALL_SOL
 #define CKPT_CUBIC_MAX_LAYERS 8191
 
 typedef struct {
-    int64_t batch;        /* number of chains, >= 0 (0: the call does nothing) */
+    int64_t batch;        /* number of chains, 0 .. 2^31-1 (0: the call does nothing) */
     int32_t n_layers;     /* n >= 1; every chain has n+1 sizes */
     int64_t chain_stride; /* elements between the same position of consecutive chains */
     int64_t pos_stride;   /* elements between consecutive positions of one chain */

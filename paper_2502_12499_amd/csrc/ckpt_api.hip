@@ -9,7 +9,7 @@ using ckpt::Strides;
 int check_layout(const ckpt_layout *L, int max_layers)
 {
     if (!L) return CKPT_ERR_NULL;
-    if (L->batch < 0 || L->n_layers < 1 || L->n_layers > max_layers) return CKPT_ERR_SHAPE;
+    if (L->batch < 0 || L->batch > INT32_MAX || L->n_layers < 1 || L->n_layers > max_layers) return CKPT_ERR_SHAPE;
     if (L->chain_stride <= 0 || L->pos_stride <= 0) return CKPT_ERR_SHAPE;
     // the largest element offset must be addressable with 63 bits
     const __int128 last = (__int128)(L->batch > 0 ? L->batch - 1 : 0) * L->chain_stride +

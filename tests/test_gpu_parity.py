@@ -168,6 +168,26 @@ def test_solve_linear_batches(batch, n, kind):
         check_linear(d, chain_major=True)
 
 
+def test_solve_linear_mixed_alignment_and_deferred_chains():
+    # sizes whose common power of two shrinks as the chain is read, chains that
+    # need 64-bit values, deep queues and long steps, all in one batch
+    say("solve_linear mixed batch")
+    rng = np.random.default_rng(42)
+    n, batch = 300, 256
+    d = inputs.uniform_aligned_chains(9, n, batch, 256, 32768)
+    for c in range(0, batch, 3):
+        k = int(rng.integers(0, n + 1))
+        d[k, c] += int(rng.integers(1, 4096))              # one unaligned size somewhere
+    for c in range(1, batch, 16):
+        d[:, c] *= 1 << 20                                 # still 32-bit after the common shift
+    for c in range(2, batch, 16):
+        d[:, c] = rng.integers(1, 1 << 45, size=n + 1)     # needs 64-bit values
+    d[n, 5] = 10 ** 13                                     # every entry stays live: ring overflow
+    d[:, 7] = 1
+    d[n, 7] = 1000                                         # optimal steps longer than 255
+    check_linear(d)
+
+
 def test_solve_linear_data_errors():
     n, batch = 12, 4
     d = inputs.uniform_aligned_chains(3, n, batch, 1, 100, unit=1)
