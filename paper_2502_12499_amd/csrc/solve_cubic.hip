@@ -12,18 +12,28 @@
 //   prologue  one wave per chain: validates the sizes, builds P by a wave scan,
 //             divides everything by the largest common power of two and picks
 //             32-bit arithmetic when sum(d)+max(d) then fits (it does for
-//             aligned tensor sizes), else 64-bit.
+//             aligned tensor sizes), else 64-bit.  Writes the table
+//             pd[j] = (P[j-1], d_j), the pair every cell j consumes.
 //   budgets   one LANE per budget, 64 budgets of equal range length and
 //             consecutive start per wave (the segment-length anti-diagonal), all
-//             lanes walking j = 1..n together so that d_j and P[j-1] are
-//             wave-uniform scalar loads.  The window minimum is Algorithm 4's
-//             monotone queue, kept per lane as a small ring in LDS laid out
-//             [slot][lane] (bank = lane, so lanes at different depths never
-//             conflict).  Expiry compares the stored key P[h] with P[j-1]-s, so
-//             l(i) is never computed.  Only values are needed here, so equal
-//             tails are dropped too and the queue stays strictly increasing.
-//             A lane whose queue outgrows the ring raises its bit in the wave's
-//             flag word and is recomputed by the next kernel.
+//             lanes walking j together.  pd[j] is the same for every lane; it is
+//             fetched eight cells ahead with 16-byte loads.  The window minimum
+//             is Algorithm 4's monotone queue, kept per lane as a ring in LDS
+//             laid out [slot][lane] (bank = lane, so lanes at different depths
+//             never conflict), with the head entry and the tail value mirrored
+//             in registers.  Expiry compares the stored key P[h] + s with
+//             P[j-1], so l(i) is never computed.  Only values are needed here, so
+//             equal tails are dropped too and the queue is strictly increasing.
+//             The ring has 16 slots.  A value that finds it full is not stored
+//             but remembered as a "hole" (smallest value, oldest and newest key
+//             of the holes).  Holes vanish when a later value not above them
+//             arrives (the queue would have dropped them) or when they leave the
+//             window; the lane's result is exact unless the head moves past the
+//             oldest hole while a hole is alive.  Only then does the lane raise
+//             its bit in the wave's flag word for the next kernel.  Deep tail
+//             entries are recent large values that are nearly always dropped
+//             before they could become the head, so this is rare on unsorted
+//             sizes.
 //   overflow  one WAVE per flagged budget: F_s kept in LDS, the window minimum
 //             taken by a wave reduction over the window.  Any queue depth, no
 //             scratch in HBM.
@@ -31,12 +41,16 @@
 //             per-wave partial results (the smallest optimal budget value s*),
 //             then F_{s*} again with the smallest minimal predecessor recorded
 //             for every j, and the walk back from n that writes the mask.
+#include <limits>
+
 #include "ckpt_internal.h"
 
 namespace ckpt {
 namespace {
 
 constexpr int64_t kInf = INT64_MAX;
+constexpr int kCells = 8;  // cells per fetch of the (P, d) table
+constexpr int kPad = 16;   // table entries past n+1, so a fetch never leaves the table
 
 struct ChainMeta {
     int32_t status;
@@ -50,10 +64,15 @@ struct Partial {
     int64_t s;
 };
 
+template <typename V>
+struct alignas(2 * sizeof(V)) PD {
+    V P;  // P[j-1] (0 for j = 0)
+    V d;  // d_j
+};
+
 struct CubicWs {
     ChainMeta *meta;      // [batch]
-    int64_t *dn;          // [batch][n+1] normalised sizes (int32 view when mode32)
-    int64_t *Pn;          // [batch][n+1] normalised prefix sums
+    char *pd;             // [batch][table_len(n)] of PD<int64_t> (PD<int32_t> in the same bytes when mode32)
     Partial *partial;     // [batch][waves_per_chain]
     uint64_t *flags;      // [batch][waves_per_chain] lanes to recompute
     int32_t *pred;        // [batch][n+1]
@@ -61,6 +80,13 @@ struct CubicWs {
 
 __host__ __device__ inline int64_t num_budgets(int n) { return (int64_t)n * (n - 1) / 2 + 1; }
 __host__ __device__ inline int64_t waves_per_chain(int n) { return (num_budgets(n) + kWave - 1) / kWave; }
+__host__ __device__ inline size_t table_len(int n) { return ((size_t)n + 1 + kPad + kCells - 1) / kCells * kCells; }
+
+template <typename V>
+__device__ inline const PD<V> *chain_table(const CubicWs &w, int64_t c, int n)
+{
+    return (const PD<V> *)(w.pd + (size_t)c * table_len(n) * sizeof(PD<int64_t>));
+}
 
 __host__ CubicWs carve_cubic(void *ws, int64_t batch, int n)
 {
@@ -68,11 +94,10 @@ __host__ CubicWs carve_cubic(void *ws, int64_t batch, int n)
     const size_t n1 = (size_t)n + 1, B = (size_t)batch, wpc = (size_t)waves_per_chain(n);
     CubicWs w;
     w.meta = (ChainMeta *)p;    p += align_up(B * sizeof(ChainMeta));
-    w.dn = (int64_t *)p;        p += align_up(B * n1 * 8);
-    w.Pn = (int64_t *)p;        p += align_up(B * n1 * 8);
+    w.pd = p;                   p += align_up(B * table_len(n) * sizeof(PD<int64_t>));
     w.partial = (Partial *)p;   p += align_up(B * wpc * sizeof(Partial));
     w.flags = (uint64_t *)p;    p += align_up(B * wpc * 8);
-    w.pred = (int32_t *)p;
+    w.pred = (int32_t *)p;      p += align_up(B * n1 * 4);
     return w;
 }
 
@@ -154,21 +179,25 @@ __global__ __launch_bounds__(kWave) void cubic_prologue_kernel(const int64_t *__
     if (lane == 0) w.meta[c] = meta;
     if (meta.status != CKPT_OK) return;
 
-    uint64_t run = incl - sum;  // exclusive prefix of this lane's chunk
-    int64_t *dn64 = w.dn + c * n1;
-    int64_t *Pn64 = w.Pn + c * n1;
-    int32_t *dn32 = (int32_t *)dn64;
-    int32_t *Pn32 = (int32_t *)Pn64;
+    // pd[j] = (P[j-1], d_j): lane chunks write their own j; the padding is zeroed
+    uint64_t run = incl - sum;  // P[k0-1]
+    PD<int64_t> *pd64 = (PD<int64_t> *)chain_table<int64_t>(w, c, n);
+    PD<int32_t> *pd32 = (PD<int32_t> *)pd64;
     for (int k = k0; k < k1; ++k) {
         const uint64_t x = (uint64_t)dp[(int64_t)k * pstride];
+        if (meta.mode32)
+            pd32[k] = PD<int32_t>{(int32_t)(run >> meta.shift), (int32_t)(x >> meta.shift)};
+        else
+            pd64[k] = PD<int64_t>{(int64_t)(run >> meta.shift), (int64_t)(x >> meta.shift)};
         run += x;
-        if (meta.mode32) {
-            dn32[k] = (int32_t)(x >> meta.shift);
-            Pn32[k] = (int32_t)(run >> meta.shift);
-        } else {
-            dn64[k] = (int64_t)(x >> meta.shift);
-            Pn64[k] = (int64_t)(run >> meta.shift);
-        }
+    }
+    const int len = (int)table_len(n);
+    for (int k = n1 + lane; k < len; k += kWave) {
+        const uint64_t last = k == n1 ? total : 0;  // pd[n+1].P = P[n]
+        if (meta.mode32)
+            pd32[k] = PD<int32_t>{(int32_t)(last >> meta.shift), 0};
+        else
+            pd64[k] = PD<int64_t>{(int64_t)(last >> meta.shift), 0};
     }
 }
 
@@ -192,20 +221,20 @@ __device__ inline void budget_range(int64_t idx, int n, int &a, int &len)
 }
 
 template <typename V>
-__device__ inline V budget_value(const V *__restrict__ Pn, int64_t idx, int n)
+__device__ inline V budget_value(const PD<V> *__restrict__ pd, int64_t idx, int n)
 {
     if (idx == 0) return 0;
     int a, len;
     budget_range(idx, n, a, len);
-    return Pn[a + len - 1] - Pn[a - 1];
+    return pd[a + len].P - pd[a].P;  // P[a+len-1] - P[a-1]
 }
 
 // ---- budgets kernel: one lane per budget -----------------------------------------
 
 template <typename V>
-struct QueueEntry {
+struct alignas(2 * sizeof(V)) QueueEntry {
     V F;  // F_s(h)
-    V K;  // P[h], the key the expiry test compares with P[j-1] - s
+    V K;  // P[h] + s: the entry leaves the window once this is below P[j-1]
 };
 
 // RING slots per lane, BLOCK lanes per workgroup: RING * BLOCK * sizeof(QueueEntry) bytes of LDS.
@@ -213,6 +242,8 @@ template <typename V, int RING, int BLOCK>
 __global__ __launch_bounds__(BLOCK) void cubic_budgets_kernel(int n, int64_t blocks_per_chain, CubicWs w)
 {
     __shared__ QueueEntry<V> ring[RING][BLOCK];
+    constexpr V kLow = std::numeric_limits<V>::min();
+    constexpr V kHigh = std::numeric_limits<V>::max();
 
     const int64_t c = blockIdx.x / blocks_per_chain;
     const int64_t tile = blockIdx.x % blocks_per_chain;
@@ -220,45 +251,87 @@ __global__ __launch_bounds__(BLOCK) void cubic_budgets_kernel(int n, int64_t blo
     if (meta.status != CKPT_OK || (meta.mode32 != 0) != (sizeof(V) == 4)) return;
 
     const int tid = threadIdx.x;
-    const int n1 = n + 1;
-    const V *__restrict__ dn = (const V *)(w.dn + c * n1);
-    const V *__restrict__ Pn = (const V *)(w.Pn + c * n1);
+    const PD<V> *__restrict__ pd = chain_table<V>(w, c, n);
     const int64_t K = num_budgets(n);
     const int64_t idx = tile * BLOCK + tid;
     const int64_t wave_in_chain = idx / kWave;   // uniform per wave
     if (wave_in_chain * kWave >= K) return;      // whole wave beyond the list
     const bool live = idx < K;
-    const V s = live ? budget_value<V>(Pn, idx, n) : 0;
+    const V s = live ? budget_value<V>(pd, idx, n) : 0;
 
-    // The queue occupies ring slots hd..tl (mod RING); its head entry and its
+    // The queue occupies ring slots hd..tl (mod RING); the head entry and the
     // tail value are mirrored in registers.  It starts as {h = 0}.
     int hd = 0, tl = 0;
-    V hF = dn[0], hK = Pn[0], tF = hF;
+    V hF = pd[0].d, hK = pd[1].P + s, tF = hF;
     ring[0][tid] = QueueEntry<V>{hF, hK};
+    V holeF = kLow, holeOld = kHigh, holeNew = kLow;  // no hole
     bool over = false;
-    V Fprev = dn[1] + hF;  // F(1) = d_1 + F(0)
-    for (int j = 2; j <= n; ++j) {
-        const V Pj1 = Pn[j - 1];
-        const V dj = dn[j];
-        // insert h = j-1 behind every strictly smaller value; the head is
-        // smaller than F(j-1) = d_{j-1} + head, so it is never dropped here
-        while (tF >= Fprev && tl > hd) {
-            --tl;
-            tF = ring[tl & (RING - 1)][tid].F;
+    V Fprev = pd[1].d + hF;  // F(1) = d_1 + F(0)
+
+    // One cell: insert h = j-1 (value Fprev, key Pj1 + s), expire, F(j) = d_j + head.
+    // The two queue loops run while ANY lane of the wave still has work, with
+    // the lanes that are done masked by selects, so the control flow is scalar.
+    auto cell = [&](const V Pj1, const V dj) {
+        // drop tails not smaller than the new value; the head is smaller than
+        // F(j-1) = d_{j-1} + head, so it always stays
+        for (;;) {
+            const bool more = (tF >= Fprev) & (tl > hd);
+            if (__builtin_amdgcn_ballot_w64(more) == 0) break;
+            const int t2 = tl - 1;
+            const V f2 = ring[t2 & (RING - 1)][tid].F;
+            tl = more ? t2 : tl;
+            tF = more ? f2 : tF;
         }
-        ++tl;
-        ring[tl & (RING - 1)][tid] = QueueEntry<V>{Fprev, Pj1};
-        tF = Fprev;
-        over |= (tl - hd) >= RING;
-        // drop heads whose segment h+1..j-1 no longer fits in s (h = j-1 always fits)
-        const V theta = Pj1 - s;
-        while (hK < theta && hd < tl) {
-            ++hd;
-            const QueueEntry<V> e = ring[hd & (RING - 1)][tid];
-            hF = e.F;
-            hK = e.K;
+        const V key = Pj1 + s;
+        const bool full = (tl - hd) >= RING - 1;
+        const bool holes = __builtin_amdgcn_ballot_w64(full | (holeOld != kHigh)) != 0;
+        if (!holes) {
+            ++tl;
+            ring[tl & (RING - 1)][tid] = QueueEntry<V>{Fprev, key};
+            tF = Fprev;
+        } else {
+            // holes vanish when this value would have dropped them, or when they left the window
+            const bool gone = (Fprev <= holeF) | (holeNew < Pj1);
+            holeF = gone ? kLow : holeF;
+            holeOld = gone ? kHigh : holeOld;
+            holeNew = gone ? kLow : holeNew;
+            holeF = (full & (holeOld == kHigh)) ? Fprev : holeF;
+            holeOld = (full & (key < holeOld)) ? key : holeOld;
+            holeNew = full ? key : holeNew;
+            if (!full) {
+                ++tl;
+                ring[tl & (RING - 1)][tid] = QueueEntry<V>{Fprev, key};
+                tF = Fprev;
+            }
         }
+        // drop heads whose segment h+1..j-1 no longer fits in s
+        for (;;) {
+            const bool more = (hK < Pj1) & (hd < tl);
+            if (__builtin_amdgcn_ballot_w64(more) == 0) break;
+            const int h2 = hd + 1;
+            const QueueEntry<V> e = ring[h2 & (RING - 1)][tid];
+            hd = more ? h2 : hd;
+            hF = more ? e.F : hF;
+            hK = more ? e.K : hK;
+        }
+        if (holes) over |= (hK < Pj1) | (hK > holeOld);  // nothing valid left, or the head passed a hole
         Fprev = dj + hF;
+    };
+
+    // pd[j] is fetched kCells cells ahead of its use
+    PD<V> cur[kCells], ahead[kCells];
+#pragma unroll
+    for (int u = 0; u < kCells; ++u) cur[u] = pd[u];
+    for (int j0 = 0; j0 <= n; j0 += kCells) {
+#pragma unroll
+        for (int u = 0; u < kCells; ++u) ahead[u] = pd[j0 + kCells + u];
+#pragma unroll
+        for (int u = 0; u < kCells; ++u) {
+            const int j = j0 + u;
+            if (j >= 2 && j <= n) cell(cur[u].P, cur[u].d);
+        }
+#pragma unroll
+        for (int u = 0; u < kCells; ++u) cur[u] = ahead[u];
     }
 
     const bool redo = live && over;
@@ -288,24 +361,23 @@ void launch_budgets(int n, int64_t batch, CubicWs w, hipStream_t stream)
 // the window with minimal F (lane 0 writes).  Must be called by a full wave
 // that is the whole workgroup.
 template <typename V>
-__device__ V wave_budget_table(const V *__restrict__ dn, const V *__restrict__ Pn, int n, V s, V *F,
-                               int32_t *pred)
+__device__ V wave_budget_table(const PD<V> *__restrict__ pd, int n, V s, V *F, int32_t *pred)
 {
     const int lane = threadIdx.x;
-    if (lane == 0) F[0] = dn[0];
+    if (lane == 0) F[0] = pd[0].d;
     __syncthreads();
     int l = 0;  // window start, uniform
-    V last = dn[0];
+    V last = pd[0].d;
     for (int j = 1; j <= n; ++j) {
-        const V Pj1 = Pn[j - 1];
-        while (Pj1 - Pn[l] > s) ++l;
+        const V Pj1 = pd[j].P;
+        while (Pj1 - pd[l + 1].P > s) ++l;  // P[j-1] - P[l] > s
         int64_t bv = kInf, bh = kInf;
         for (int h = l + lane; h <= j - 1; h += kWave) {
             const int64_t v = (int64_t)F[h];
             if (v < bv) { bv = v; bh = h; }
         }
         wave_min_pair(bv, bh);
-        last = dn[j] + (V)bv;
+        last = pd[j].d + (V)bv;
         if (lane == 0) {
             F[j] = last;
             if (pred) pred[j] = (int32_t)bh;
@@ -320,7 +392,6 @@ extern __shared__ __align__(16) unsigned char dyn_lds[];
 __global__ __launch_bounds__(kWave) void cubic_overflow_kernel(int n, int64_t n_words, CubicWs w)
 {
     const int64_t wpc = waves_per_chain(n);
-    const int n1 = n + 1;
     for (int64_t word = blockIdx.x; word < n_words; word += gridDim.x) {
         const int64_t c = word / wpc;
         const int64_t base = (word % wpc) * kWave;
@@ -334,16 +405,14 @@ __global__ __launch_bounds__(kWave) void cubic_overflow_kernel(int n, int64_t n_
             flag &= flag - 1;
             int64_t s64, cost;
             if (meta.mode32) {
-                const int32_t *dn = (const int32_t *)(w.dn + c * n1);
-                const int32_t *Pn = (const int32_t *)(w.Pn + c * n1);
-                const int32_t s = budget_value<int32_t>(Pn, base + bit, n);
+                const PD<int32_t> *pd = chain_table<int32_t>(w, c, n);
+                const int32_t s = budget_value<int32_t>(pd, base + bit, n);
                 s64 = s;
-                cost = s64 + wave_budget_table<int32_t>(dn, Pn, n, s, (int32_t *)dyn_lds, nullptr);
+                cost = s64 + wave_budget_table<int32_t>(pd, n, s, (int32_t *)dyn_lds, nullptr);
             } else {
-                const int64_t *dn = w.dn + c * n1;
-                const int64_t *Pn = w.Pn + c * n1;
-                s64 = budget_value<int64_t>(Pn, base + bit, n);
-                cost = s64 + wave_budget_table<int64_t>(dn, Pn, n, s64, (int64_t *)dyn_lds, nullptr);
+                const PD<int64_t> *pd = chain_table<int64_t>(w, c, n);
+                s64 = budget_value<int64_t>(pd, base + bit, n);
+                cost = s64 + wave_budget_table<int64_t>(pd, n, s64, (int64_t *)dyn_lds, nullptr);
             }
             if (cost < best.cost || (cost == best.cost && s64 < best.s)) best = Partial{cost, s64};
             __syncthreads();
@@ -384,10 +453,9 @@ __global__ __launch_bounds__(kWave) void cubic_epilogue_kernel(int n, int64_t cs
 
     int32_t *pred = w.pred + c * n1;
     if (meta.mode32)
-        wave_budget_table<int32_t>((const int32_t *)(w.dn + c * n1), (const int32_t *)(w.Pn + c * n1), n,
-                                   (int32_t)s, (int32_t *)dyn_lds, pred);
+        wave_budget_table<int32_t>(chain_table<int32_t>(w, c, n), n, (int32_t)s, (int32_t *)dyn_lds, pred);
     else
-        wave_budget_table<int64_t>(w.dn + c * n1, w.Pn + c * n1, n, s, (int64_t *)dyn_lds, pred);
+        wave_budget_table<int64_t>(chain_table<int64_t>(w, c, n), n, s, (int64_t *)dyn_lds, pred);
 
     // the table is no longer needed: reuse its LDS as the mark array
     uint8_t *mark = dyn_lds;
@@ -413,8 +481,8 @@ __global__ __launch_bounds__(kWave) void cubic_epilogue_kernel(int n, int64_t cs
 size_t cubic_workspace_bytes(int64_t batch, int n)
 {
     const size_t n1 = (size_t)n + 1, B = (size_t)batch, wpc = (size_t)waves_per_chain(n);
-    return align_up(B * sizeof(ChainMeta)) + 2 * align_up(B * n1 * 8) + align_up(B * wpc * sizeof(Partial)) +
-           align_up(B * wpc * 8) + align_up(B * n1 * 4) + 256;
+    return align_up(B * sizeof(ChainMeta)) + align_up(B * table_len(n) * sizeof(PD<int64_t>)) +
+           align_up(B * wpc * sizeof(Partial)) + align_up(B * wpc * 8) + align_up(B * n1 * 4) + 256;
 }
 
 hipError_t launch_solve_cubic(const int64_t *d, int64_t batch, int n, Strides st, uint8_t *mask_out,
@@ -424,21 +492,15 @@ hipError_t launch_solve_cubic(const int64_t *d, int64_t batch, int n, Strides st
     if (batch == 0) return hipSuccess;
     CubicWs w = carve_cubic(ws, batch, n);
     const int64_t K = num_budgets(n);
-    const int64_t total_blocks = (K + 127) / 128 * batch;
+    const int64_t total_blocks = (K + 255) / 256 * batch;
     const int64_t n_words = waves_per_chain(n) * batch;
-    if (total_blocks > 0x7fffffffLL || batch > 0x7fffffffLL) return hipErrorInvalidConfiguration;
+    if (total_blocks > 0x7fffffffLL) return hipErrorInvalidConfiguration;
     const size_t table_lds = ((size_t)n + 1) * 8;
 
     hipLaunchKernelGGL(cubic_prologue_kernel, dim3((unsigned)batch), dim3(kWave), 0, stream, d, batch, n,
                        st.chain, st.pos, w);
-    // Queue depth grows like log(window length): 16 slots for short chains, 32 beyond.
-    if (n <= 512) {
-        launch_budgets<int32_t, 16, 256>(n, batch, w, stream);
-        launch_budgets<int64_t, 16, 256>(n, batch, w, stream);
-    } else {
-        launch_budgets<int32_t, 32, 256>(n, batch, w, stream);
-        launch_budgets<int64_t, 32, 128>(n, batch, w, stream);
-    }
+    launch_budgets<int32_t, 16, 256>(n, batch, w, stream);
+    launch_budgets<int64_t, 16, 256>(n, batch, w, stream);
     const unsigned over_grid = (unsigned)(n_words < 4096 ? n_words : 4096);
     hipLaunchKernelGGL(cubic_overflow_kernel, dim3(over_grid), dim3(kWave), table_lds, stream, n, n_words, w);
     hipLaunchKernelGGL(cubic_epilogue_kernel, dim3((unsigned)batch), dim3(kWave), table_lds, stream, n, st.chain,
