@@ -52,6 +52,10 @@ constexpr int64_t kInf = INT64_MAX;
 constexpr int kCells = 8;  // cells per fetch of the (P, d) table
 constexpr int kPad = 16;   // table entries past n+1, so a fetch never leaves the table
 
+#ifndef CKPT_CUBIC_ASM_CELL
+#define CKPT_CUBIC_ASM_CELL 1  // 0: use the portable form of the recurrence cell for 32-bit values too
+#endif
+
 struct ChainMeta {
     int32_t status;
     int32_t mode32;   // 1: normalised values fit 32-bit arithmetic
@@ -241,9 +245,15 @@ struct alignas(2 * sizeof(V)) QueueEntry {
 template <typename V, int RING, int BLOCK>
 __global__ __launch_bounds__(BLOCK) void cubic_budgets_kernel(int n, int64_t blocks_per_chain, CubicWs w)
 {
-    __shared__ QueueEntry<V> ring[RING][BLOCK];
+    __shared__ __attribute__((aligned(65536))) QueueEntry<V> ring[RING][BLOCK];
     constexpr V kLow = std::numeric_limits<V>::min();
     constexpr V kHigh = std::numeric_limits<V>::max();
+    // Queue positions are kept pre-multiplied by the byte stride of a ring slot,
+    // so the LDS address of a position is one AND-OR away.
+    constexpr uint32_t kStep = (uint32_t)(BLOCK * sizeof(QueueEntry<V>));
+    constexpr uint32_t kSlotMask = (uint32_t)(RING - 1) * kStep;
+    constexpr uint32_t kFull = (uint32_t)(RING - 1) * kStep;  // tl - hd at RING entries
+    static_assert((kStep & (kStep - 1)) == 0 && (RING & (RING - 1)) == 0, "power-of-two ring");
 
     const int64_t c = blockIdx.x / blocks_per_chain;
     const int64_t tile = blockIdx.x % blocks_per_chain;
@@ -259,90 +269,216 @@ __global__ __launch_bounds__(BLOCK) void cubic_budgets_kernel(int n, int64_t blo
     const bool live = idx < K;
     const V s = live ? budget_value<V>(pd, idx, n) : 0;
 
-    // The queue occupies ring slots hd..tl (mod RING); the head entry and the
-    // tail value are mirrored in registers.  It starts as {h = 0}.
-    int hd = 0, tl = 0;
+    // LDS byte address of this lane's slot 0 (the ring is aligned to its own size,
+    // so a position's address is (pos & kSlotMask) | lane_base)
+    typedef __attribute__((address_space(3))) V *LdsPtr;  // [0] = F, [1] = K of an entry
+    const uint32_t lane_base = (uint32_t)(uintptr_t)(LdsPtr)&ring[0][tid].F;
+    auto slot = [&](uint32_t pos) -> LdsPtr { return (LdsPtr)(uintptr_t)((pos & kSlotMask) | lane_base); };
+    auto store_entry = [&](uint32_t pos, V F, V key) {
+        LdsPtr e = slot(pos);
+        e[0] = F;
+        e[1] = key;
+    };
+
+    // The queue occupies positions hd..tl; the head entry and the tail value are
+    // mirrored in registers.  It starts as {h = 0}.
+    uint32_t hd = 0, tl = 0;
     V hF = pd[0].d, hK = pd[1].P + s, tF = hF;
-    ring[0][tid] = QueueEntry<V>{hF, hK};
+    store_entry(0, hF, hK);
     V holeF = kLow, holeOld = kHigh, holeNew = kLow;  // no hole
+    uint64_t hole_lanes = 0;                          // lanes with a live hole (wave-uniform)
     bool over = false;
+    uint32_t over_bits = 0;  // the assembly cell keeps the flag as a word
     V Fprev = pd[1].d + hF;  // F(1) = d_1 + F(0)
 
     // One cell: insert h = j-1 (value Fprev, key Pj1 + s), expire, F(j) = d_j + head.
-    // The two queue loops run while ANY lane of the wave still has work, with
-    // the lanes that are done masked by selects, so the control flow is scalar.
-    auto cell = [&](const V Pj1, const V dj) {
-        // drop tails not smaller than the new value; the head is smaller than
-        // F(j-1) = d_{j-1} + head, so it always stays
+    // The two queue loops run while ANY lane of the wave still has work; lanes
+    // that are done sit out under the exec mask.
+    //  - tails not smaller than the new value are dropped.  The head is smaller
+    //    than F(j-1) = d_{j-1} + head, and tF = hF when one entry is left, so
+    //    the head always stays.
+    //  - heads whose segment h+1..j-1 no longer fits in s are dropped.  When the
+    //    new value has been stored that loop stops at it at the latest (it fits).
+    //  - when some lane's ring is full or has a live hole the whole wave takes
+    //    the slow path, which is the same cell with the hole bookkeeping.
+    auto cell_generic = [&](const V Pj1, const V dj) {
         for (;;) {
-            const bool more = (tF >= Fprev) & (tl > hd);
+            const bool more = tF >= Fprev;
             if (__builtin_amdgcn_ballot_w64(more) == 0) break;
-            const int t2 = tl - 1;
-            const V f2 = ring[t2 & (RING - 1)][tid].F;
-            tl = more ? t2 : tl;
-            tF = more ? f2 : tF;
+            if (more) {
+                tl -= kStep;
+                tF = slot(tl)[0];
+            }
         }
         const V key = Pj1 + s;
-        const bool full = (tl - hd) >= RING - 1;
-        const bool holes = __builtin_amdgcn_ballot_w64(full | (holeOld != kHigh)) != 0;
-        if (!holes) {
-            ++tl;
-            ring[tl & (RING - 1)][tid] = QueueEntry<V>{Fprev, key};
-            tF = Fprev;
-        } else {
+        const bool full = (tl - hd) >= kFull;
+        if ((__builtin_amdgcn_ballot_w64(full) | hole_lanes) != 0) {
             // holes vanish when this value would have dropped them, or when they left the window
             const bool gone = (Fprev <= holeF) | (holeNew < Pj1);
             holeF = gone ? kLow : holeF;
             holeOld = gone ? kHigh : holeOld;
             holeNew = gone ? kLow : holeNew;
-            holeF = (full & (holeOld == kHigh)) ? Fprev : holeF;
-            holeOld = (full & (key < holeOld)) ? key : holeOld;
-            holeNew = full ? key : holeNew;
-            if (!full) {
-                ++tl;
-                ring[tl & (RING - 1)][tid] = QueueEntry<V>{Fprev, key};
-                tF = Fprev;
+            if (full) {  // not stored: becomes a hole
+                holeF = holeOld == kHigh ? Fprev : holeF;
+                holeOld = key < holeOld ? key : holeOld;
+                holeNew = key;
             }
         }
-        // drop heads whose segment h+1..j-1 no longer fits in s
-        for (;;) {
-            const bool more = (hK < Pj1) & (hd < tl);
-            if (__builtin_amdgcn_ballot_w64(more) == 0) break;
-            const int h2 = hd + 1;
-            const QueueEntry<V> e = ring[h2 & (RING - 1)][tid];
-            hd = more ? h2 : hd;
-            hF = more ? e.F : hF;
-            hK = more ? e.K : hK;
+        if (!full) {
+            tl += kStep;
+            store_entry(tl, Fprev, key);
+            tF = Fprev;
         }
-        if (holes) over |= (hK < Pj1) | (hK > holeOld);  // nothing valid left, or the head passed a hole
+        for (;;) {
+            const bool more = (hK < Pj1) & (hd != tl);
+            if (__builtin_amdgcn_ballot_w64(more) == 0) break;
+            if (more) {
+                hd += kStep;
+                hF = slot(hd)[0];
+                hK = slot(hd)[1];
+            }
+        }
+        over |= (hK < Pj1) | (hK > holeOld);  // nothing valid left, or the head passed a hole
+        hole_lanes = __builtin_amdgcn_ballot_w64(holeOld != kHigh);
         Fprev = dj + hF;
+    };
+
+#if CKPT_CUBIC_ASM_CELL
+    // The same cell for 32-bit values, written out: 9 vector instructions when
+    // nothing is dropped, 3 more per dropped entry.  (The compiler's lowering of
+    // the generic form costs about three times as many.)
+    V vLow = kLow, vHigh = kHigh;
+    auto cell_asm = [&](const int32_t Pj1, const int32_t dj) {
+        uint32_t ad, key, t0;
+        uint64_t sv, sfull, st;
+        asm volatile(
+            // ---- drop tails
+            "Lpop_%=:\n\t"
+            "v_cmp_ge_i32 vcc, %[tF], %[F]\n\t"
+            "s_cbranch_vccz Lpop_done_%=\n\t"
+            "s_and_saveexec_b64 %[sv], vcc\n\t"
+            "v_subrev_u32 %[tl], %[step], %[tl]\n\t"
+            "v_and_or_b32 %[ad], %[tl], %[mask], %[lo]\n\t"
+            "ds_read_b32 %[tF], %[ad]\n\t"
+            "s_mov_b64 exec, %[sv]\n\t"
+            "s_waitcnt lgkmcnt(0)\n\t"
+            "s_branch Lpop_%=\n\t"
+            "Lpop_done_%=:\n\t"
+            // ---- full ring or live hole anywhere in the wave?
+            "v_add_u32 %[key], %[P], %[s]\n\t"
+            "v_sub_u32 %[t0], %[tl], %[hd]\n\t"
+            "v_cmp_le_u32 vcc, %[full], %[t0]\n\t"
+            "s_or_b64 %[st], vcc, %[hl]\n\t"
+            "s_cmp_lg_u64 %[st], 0\n\t"
+            "s_cbranch_scc1 Lslow_%=\n\t"
+            // ---- fast path: store, drop heads
+            "v_add_u32 %[tl], %[step], %[tl]\n\t"
+            "v_and_or_b32 %[ad], %[tl], %[mask], %[lo]\n\t"
+            "ds_write2_b32 %[ad], %[F], %[key] offset1:1\n\t"
+            "v_mov_b32 %[tF], %[F]\n\t"
+            "Lexp_%=:\n\t"
+            "v_cmp_gt_i32 vcc, %[P], %[hK]\n\t"
+            "s_cbranch_vccz Ljoin_%=\n\t"
+            "s_and_saveexec_b64 %[sv], vcc\n\t"
+            "v_add_u32 %[hd], %[step], %[hd]\n\t"
+            "v_and_or_b32 %[ad], %[hd], %[mask], %[lo]\n\t"
+            "ds_read_b32 %[hF], %[ad]\n\t"
+            "ds_read_b32 %[hK], %[ad] offset:4\n\t"
+            "s_mov_b64 exec, %[sv]\n\t"
+            "s_waitcnt lgkmcnt(0)\n\t"
+            "s_branch Lexp_%=\n\t"
+            // ---- slow path (vcc = lanes whose ring is full)
+            "Lslow_%=:\n\t"
+            "s_mov_b64 %[sfull], vcc\n\t"
+            "v_cmp_le_i32 vcc, %[F], %[oF]\n\t"
+            "v_cmp_gt_i32 %[st], %[P], %[oNew]\n\t"
+            "s_or_b64 vcc, vcc, %[st]\n\t"
+            "v_cndmask_b32 %[oF], %[oF], %[vLow], vcc\n\t"
+            "v_cndmask_b32 %[oOld], %[oOld], %[vHigh], vcc\n\t"
+            "v_cndmask_b32 %[oNew], %[oNew], %[vLow], vcc\n\t"
+            "s_and_saveexec_b64 %[sv], %[sfull]\n\t"
+            "v_cmp_eq_u32 vcc, %[oOld], %[vHigh]\n\t"
+            "v_cndmask_b32 %[oF], %[oF], %[F], vcc\n\t"
+            "v_min_i32 %[oOld], %[oOld], %[key]\n\t"
+            "v_mov_b32 %[oNew], %[key]\n\t"
+            "s_andn2_b64 exec, %[sv], %[sfull]\n\t"
+            "v_add_u32 %[tl], %[step], %[tl]\n\t"
+            "v_and_or_b32 %[ad], %[tl], %[mask], %[lo]\n\t"
+            "ds_write2_b32 %[ad], %[F], %[key] offset1:1\n\t"
+            "v_mov_b32 %[tF], %[F]\n\t"
+            "s_mov_b64 exec, %[sv]\n\t"
+            "Lsexp_%=:\n\t"
+            "v_cmp_gt_i32 vcc, %[P], %[hK]\n\t"
+            "v_cmp_ne_u32 %[st], %[hd], %[tl]\n\t"
+            "s_and_b64 vcc, vcc, %[st]\n\t"
+            "s_cbranch_vccz Lsexp_done_%=\n\t"
+            "s_and_saveexec_b64 %[sv], vcc\n\t"
+            "v_add_u32 %[hd], %[step], %[hd]\n\t"
+            "v_and_or_b32 %[ad], %[hd], %[mask], %[lo]\n\t"
+            "ds_read_b32 %[hF], %[ad]\n\t"
+            "ds_read_b32 %[hK], %[ad] offset:4\n\t"
+            "s_mov_b64 exec, %[sv]\n\t"
+            "s_waitcnt lgkmcnt(0)\n\t"
+            "s_branch Lsexp_%=\n\t"
+            "Lsexp_done_%=:\n\t"
+            "v_cmp_gt_i32 vcc, %[P], %[hK]\n\t"
+            "v_cmp_gt_i32 %[st], %[hK], %[oOld]\n\t"
+            "s_or_b64 vcc, vcc, %[st]\n\t"
+            "v_cndmask_b32 %[t0], 0, 1, vcc\n\t"
+            "v_or_b32 %[over], %[over], %[t0]\n\t"
+            "v_cmp_ne_u32 %[hl], %[oOld], %[vHigh]\n\t"
+            // ---- F(j) = d_j + head
+            "Ljoin_%=:\n\t"
+            "v_add_u32 %[F], %[D], %[hF]\n\t"
+            : [tl] "+v"(tl), [hd] "+v"(hd), [tF] "+v"(tF), [hF] "+v"(hF), [hK] "+v"(hK), [F] "+v"(Fprev),
+              [oF] "+v"(holeF), [oOld] "+v"(holeOld), [oNew] "+v"(holeNew), [over] "+v"(over_bits),
+              [hl] "+s"(hole_lanes), [ad] "=&v"(ad), [key] "=&v"(key), [t0] "=&v"(t0), [sv] "=&s"(sv),
+              [sfull] "=&s"(sfull), [st] "=&s"(st)
+            : [P] "s"(Pj1), [D] "s"(dj), [s] "v"(s), [lo] "v"(lane_base), [mask] "s"(kSlotMask),
+              [vLow] "v"(vLow), [vHigh] "v"(vHigh), [step] "i"(kStep), [full] "i"(kFull)
+            : "vcc", "scc", "memory");
+    };
+#endif
+    auto cell = [&](const V Pj1, const V dj) {
+#if CKPT_CUBIC_ASM_CELL
+        if constexpr (sizeof(V) == 4) {
+            cell_asm(Pj1, dj);
+            return;
+        }
+#endif
+        cell_generic(Pj1, dj);
     };
 
     // pd[j] is fetched kCells cells ahead of its use
     PD<V> cur[kCells], ahead[kCells];
 #pragma unroll
     for (int u = 0; u < kCells; ++u) cur[u] = pd[u];
-    for (int j0 = 0; j0 <= n; j0 += kCells) {
+    auto chunk = [&](const int j0, const bool guarded) {
 #pragma unroll
         for (int u = 0; u < kCells; ++u) ahead[u] = pd[j0 + kCells + u];
 #pragma unroll
         for (int u = 0; u < kCells; ++u) {
             const int j = j0 + u;
-            if (j >= 2 && j <= n) cell(cur[u].P, cur[u].d);
+            if (!guarded || (j >= 2 && j <= n)) cell(cur[u].P, cur[u].d);
         }
 #pragma unroll
         for (int u = 0; u < kCells; ++u) cur[u] = ahead[u];
-    }
+    };
+    const int last_full = (n + 1) / kCells * kCells;  // chunks [kCells, last_full) lie inside 2..n
+    chunk(0, true);
+    for (int j0 = kCells; j0 < last_full; j0 += kCells) chunk(j0, false);
+    if (last_full >= kCells && last_full <= n) chunk(last_full, true);
 
+    over |= over_bits != 0;
     const bool redo = live && over;
     const uint64_t flag = __ballot(redo);
     int64_t cost = (live && !over) ? (int64_t)s + (int64_t)Fprev : kInf;
     int64_t sv = (int64_t)s;
     wave_min_pair(cost, sv);
     if ((tid & (kWave - 1)) == 0) {
-        const int64_t slot = c * waves_per_chain(n) + wave_in_chain;
-        w.partial[slot] = Partial{cost, sv};
-        w.flags[slot] = flag;
+        const int64_t slot_id = c * waves_per_chain(n) + wave_in_chain;
+        w.partial[slot_id] = Partial{cost, sv};
+        w.flags[slot_id] = flag;
     }
 }
 
