@@ -635,7 +635,7 @@ hipError_t launch_solve_cubic(const int64_t *d, int64_t batch, int n, Strides st
 
     hipLaunchKernelGGL(cubic_prologue_kernel, dim3((unsigned)batch), dim3(kWave), 0, stream, d, batch, n,
                        st.chain, st.pos, w);
-    launch_budgets<int32_t, 16, 256>(n, batch, w, stream);
+    launch_budgets<int32_t, 8, 256>(n, batch, w, stream);
     launch_budgets<int64_t, 16, 256>(n, batch, w, stream);
     const unsigned over_grid = (unsigned)(n_words < 4096 ? n_words : 4096);
     hipLaunchKernelGGL(cubic_overflow_kernel, dim3(over_grid), dim3(kWave), table_lds, stream, n, n_words, w);
