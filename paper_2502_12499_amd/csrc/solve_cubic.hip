@@ -523,6 +523,76 @@ __device__ V wave_budget_table(const PD<V> *__restrict__ pd, int n, V s, V *F, i
     return last;
 }
 
+// Bytes of LDS that queue_budget_pred needs for a chain of n layers.
+template <typename V>
+__host__ __device__ inline size_t queue_pred_bytes(int n) { return ((size_t)n + 1) * (2 * sizeof(V) + 4); }
+
+// Predecessors for one budget by Algorithm 4's queue itself, run as a single
+// sequential pass (every lane carries the same state; lane 0 does the stores).
+// Only strictly larger tails are dropped, so among equal minima the oldest
+// stays at the head: pred16[j] is the smallest h in the window with minimal F.
+// The queue has full capacity n+1 in LDS: entry (F, P[h] + s, h).
+template <typename V>
+__device__ void queue_budget_pred(const PD<V> *__restrict__ pd, int n, V s, unsigned char *lds, uint16_t *&pred16)
+{
+    const int n1 = n + 1;
+    V *qF = (V *)lds;
+    V *qK = qF + n1;
+    uint16_t *qH = (uint16_t *)(qK + n1);
+    pred16 = qH + n1;
+    const bool writer = threadIdx.x == 0;
+    int hd = 0, tl = 0;
+    V hF = pd[0].d, tF = hF, hK = pd[1].P + s;
+    int hH = 0;
+    if (writer) {
+        qF[0] = hF;
+        qK[0] = hK;
+        qH[0] = 0;
+        pred16[1] = 0;
+    }
+    V Fprev = pd[1].d + hF;
+    PD<V> cur[kCells], ahead[kCells];
+#pragma unroll
+    for (int u = 0; u < kCells; ++u) cur[u] = pd[u];
+    for (int j0 = 0; j0 <= n; j0 += kCells) {
+#pragma unroll
+        for (int u = 0; u < kCells; ++u) ahead[u] = pd[j0 + kCells + u];
+#pragma unroll
+        for (int u = 0; u < kCells; ++u) {
+            const int j = j0 + u;
+            if (j < 2 || j > n) continue;
+            const V Pj1 = cur[u].P;
+            while (tF > Fprev) {  // the head is smaller than F(j-1), so this stops at it
+                --tl;
+                tF = qF[tl];
+            }
+            ++tl;
+            const V key = Pj1 + s;
+            if (writer) {
+                qF[tl] = Fprev;
+                qK[tl] = key;
+                qH[tl] = (uint16_t)(j - 1);
+            }
+            tF = Fprev;
+            if (hd == tl - 1 && hK < Pj1) {  // the entry just stored becomes the head
+                hd = tl;
+                hF = Fprev; hK = key; hH = j - 1;
+            }
+            while (hK < Pj1) {
+                ++hd;
+                hF = qF[hd];
+                hK = qK[hd];
+                hH = qH[hd];
+            }
+            if (writer) pred16[j] = (uint16_t)hH;
+            Fprev = cur[u].d + hF;
+        }
+#pragma unroll
+        for (int u = 0; u < kCells; ++u) cur[u] = ahead[u];
+    }
+    __syncthreads();
+}
+
 extern __shared__ __align__(16) unsigned char dyn_lds[];
 
 __global__ __launch_bounds__(kWave) void cubic_overflow_kernel(int n, int64_t n_words, CubicWs w)
@@ -559,8 +629,8 @@ __global__ __launch_bounds__(kWave) void cubic_overflow_kernel(int n, int64_t n_
 
 // ---- epilogue --------------------------------------------------------------------
 
-__global__ __launch_bounds__(kWave) void cubic_epilogue_kernel(int n, int64_t cstride, int64_t pstride,
-                                                               uint8_t *__restrict__ mask_out,
+__global__ __launch_bounds__(kWave) void cubic_epilogue_kernel(int n, size_t lds_bytes, int64_t cstride,
+                                                               int64_t pstride, uint8_t *__restrict__ mask_out,
                                                                int64_t *__restrict__ peak_out,
                                                                int64_t *__restrict__ budget_out,
                                                                int32_t *__restrict__ status_out, CubicWs w)
@@ -587,13 +657,24 @@ __global__ __launch_bounds__(kWave) void cubic_epilogue_kernel(int n, int64_t cs
     }
     wave_min_pair(cost, s);
 
+    // predecessors: the sequential queue when its arrays fit the LDS granted to
+    // the kernel, else the wave-per-window table
     int32_t *pred = w.pred + c * n1;
-    if (meta.mode32)
-        wave_budget_table<int32_t>(chain_table<int32_t>(w, c, n), n, (int32_t)s, (int32_t *)dyn_lds, pred);
-    else
-        wave_budget_table<int64_t>(chain_table<int64_t>(w, c, n), n, s, (int64_t *)dyn_lds, pred);
+    uint16_t *pred16 = nullptr;
+    if (meta.mode32) {
+        if (queue_pred_bytes<int32_t>(n) <= lds_bytes)
+            queue_budget_pred<int32_t>(chain_table<int32_t>(w, c, n), n, (int32_t)s, dyn_lds, pred16);
+        else
+            wave_budget_table<int32_t>(chain_table<int32_t>(w, c, n), n, (int32_t)s, (int32_t *)dyn_lds, pred);
+    } else {
+        if (queue_pred_bytes<int64_t>(n) <= lds_bytes)
+            queue_budget_pred<int64_t>(chain_table<int64_t>(w, c, n), n, s, dyn_lds, pred16);
+        else
+            wave_budget_table<int64_t>(chain_table<int64_t>(w, c, n), n, s, (int64_t *)dyn_lds, pred);
+    }
 
-    // the table is no longer needed: reuse its LDS as the mark array
+    // the value table is no longer needed: its LDS (the first n+1 bytes, below
+    // pred16) becomes the mark array
     uint8_t *mark = dyn_lds;
     __syncthreads();
     for (int k = lane; k < n1; k += kWave) mark[k] = 0;
@@ -602,7 +683,7 @@ __global__ __launch_bounds__(kWave) void cubic_epilogue_kernel(int n, int64_t cs
         int j = n;
         mark[n] = 1;
         while (j > 0) {
-            j = pred[j];
+            j = pred16 ? (int)pred16[j] : pred[j];
             mark[j] = 1;
         }
         peak_out[c] = cost << meta.shift;
@@ -639,8 +720,12 @@ hipError_t launch_solve_cubic(const int64_t *d, int64_t batch, int n, Strides st
     launch_budgets<int64_t, 16, 256>(n, batch, w, stream);
     const unsigned over_grid = (unsigned)(n_words < 4096 ? n_words : 4096);
     hipLaunchKernelGGL(cubic_overflow_kernel, dim3(over_grid), dim3(kWave), table_lds, stream, n, n_words, w);
-    hipLaunchKernelGGL(cubic_epilogue_kernel, dim3((unsigned)batch), dim3(kWave), table_lds, stream, n, st.chain,
-                       st.pos, mask_out, peak_out, budget_out, status_out, w);
+    // the epilogue takes as much LDS as the queue form of the predecessor pass wants, up to 64 KiB
+    size_t epi_lds = queue_pred_bytes<int64_t>(n);
+    if (epi_lds > 65536) epi_lds = queue_pred_bytes<int32_t>(n);
+    if (epi_lds > 65536 || epi_lds < table_lds) epi_lds = table_lds;
+    hipLaunchKernelGGL(cubic_epilogue_kernel, dim3((unsigned)batch), dim3(kWave), epi_lds, stream, n, epi_lds,
+                       st.chain, st.pos, mask_out, peak_out, budget_out, status_out, w);
     return hipGetLastError();
 }
 
