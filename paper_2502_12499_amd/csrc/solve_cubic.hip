@@ -24,7 +24,7 @@
 //             in registers.  Expiry compares the stored key P[h] + s with
 //             P[j-1], so l(i) is never computed.  Only values are needed here, so
 //             equal tails are dropped too and the queue is strictly increasing.
-//             The ring has 16 slots.  A value that finds it full is not stored
+//             The ring has 8 slots (16 for 64-bit values).  A value that finds it full is not stored
 //             but remembered as a "hole" (smallest value, oldest and newest key
 //             of the holes).  Holes vanish when a later value not above them
 //             arrives (the queue would have dropped them) or when they leave the

@@ -1,0 +1,89 @@
+"""Parity at the full sizes of the benchmark configurations, in the launch
+configuration bench.py times: whole outputs where the oracle finishes in
+seconds, otherwise sampled chains against the oracle plus properties that hold
+for every chain."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2502_12499_amd import binding as B
+from paper_2502_12499_amd import inputs
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+
+def say(msg):
+    print(msg, flush=True)
+
+
+def test_config3_full_batch_all_three_calls():
+    say("config 3: 65,536 chains, n = 64")
+    d, m = inputs.config3()
+    dc, mc = inputs.chain_major(d), inputs.chain_major(m)
+    dt, mt = torch.from_numpy(d).to(DEV), torch.from_numpy(m).to(DEV)
+    for obj in (B.OBJ_STATIC, B.OBJ_DYNAMIC):
+        peak, status = B.ckpt_eval_peak(dt, mt, obj)
+        assert (status.cpu().numpy() == 0).all()
+        assert np.array_equal(peak.cpu().numpy(), oracle.batch_peak(dc, mc, obj))
+    say("  linear")
+    mask, peak, status = B.ckpt_solve_linear(dt)
+    want_peak, want_mask = oracle.batch_solve_dynamic(dc)
+    assert (status.cpu().numpy() == 0).all()
+    assert np.array_equal(peak.cpu().numpy(), want_peak)
+    assert np.array_equal(mask.cpu().numpy().T, want_mask)
+    say("  cubic")
+    mask, peak, budget, status = B.ckpt_solve_cubic(dt)
+    torch.cuda.synchronize()
+    want_peak, want_mask, want_s = oracle.batch_solve_static(dc)
+    assert (status.cpu().numpy() == 0).all()
+    assert np.array_equal(peak.cpu().numpy(), want_peak)
+    assert np.array_equal(budget.cpu().numpy(), want_s)
+    assert np.array_equal(mask.cpu().numpy().T, want_mask)
+
+
+def test_config5_single_chain_cubic_n4096():
+    say("config 5: cubic on one chain, n = 4096 (3.4e10 cells; the oracle takes a while)")
+    d = inputs.config5_single(4096)
+    mask, peak, budget, status = B.ckpt_solve_cubic(torch.from_numpy(d).to(DEV))
+    torch.cuda.synchronize()
+    say("  gpu done, oracle running")
+    v, mk, s = oracle.solve_static(d[:, 0])
+    assert int(status.cpu()[0]) == 0
+    assert int(peak.cpu()[0]) == v and int(budget.cpu()[0]) == s
+    assert np.array_equal(mask.cpu().numpy()[:, 0], mk)
+
+
+def test_config5_full_batch_linear_and_eval():
+    batch, n = 1048576, 256
+    say("config 5: 1,048,576 chains, n = 256")
+    d, m = inputs.config5_batch(batch, n)
+    dt, mt = torch.from_numpy(d).to(DEV), torch.from_numpy(m).to(DEV)
+    rng = np.random.default_rng(5)
+    sample = np.unique(np.concatenate([rng.integers(0, batch, 4096), [0, 63, 64, batch - 1]]))
+    ds = inputs.chain_major(d[:, sample])
+    ms = inputs.chain_major(m[:, sample])
+
+    for obj in (B.OBJ_STATIC, B.OBJ_DYNAMIC):
+        peak, status = B.ckpt_eval_peak(dt, mt, obj)
+        assert int(status.abs().sum()) == 0
+        assert np.array_equal(peak.cpu().numpy()[sample], oracle.batch_peak(ds, ms, obj))
+        # any peak is at least the checkpoint memory of the forced ends plus ... and at most sum + max
+        total = dt.sum(dim=0)
+        assert bool((peak >= dt[0] + dt[n]).all()) and bool((peak <= total + dt.max(dim=0).values).all())
+
+    say("  linear")
+    mask, peak, status = B.ckpt_solve_linear(dt)
+    assert int(status.abs().sum()) == 0
+    want_peak, want_mask = oracle.batch_solve_dynamic(ds)
+    assert np.array_equal(peak.cpu().numpy()[sample], want_peak)
+    assert np.array_equal(mask.cpu().numpy()[:, sample].T, want_mask)
+    # for every chain: the returned set has both ends, is 0/1, and evaluates (by the
+    # independent evaluation kernel) to exactly the returned optimum; the optimum is
+    # no worse than the random sets' peaks
+    assert bool((mask[0] == 1).all()) and bool((mask[n] == 1).all()) and int(mask.max()) == 1
+    again, _ = B.ckpt_eval_peak(dt, mask, B.OBJ_DYNAMIC)
+    assert bool((again == peak).all())
+    rand_peak, _ = B.ckpt_eval_peak(dt, mt, B.OBJ_DYNAMIC)
+    assert bool((peak <= rand_peak).all())
