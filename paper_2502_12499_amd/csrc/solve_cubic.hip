@@ -284,7 +284,7 @@ __global__ __launch_bounds__(BLOCK) void cubic_budgets_kernel(int n, int64_t blo
     // mirrored in registers.  It starts as {h = 0}.
     uint32_t hd = 0, tl = 0;
     V hF = pd[0].d, hK = pd[1].P + s, tF = hF;
-    store_entry(0, hF, hK);
+    store_entry(0, hF, (CKPT_CUBIC_ASM_CELL && sizeof(V) == 4) ? pd[1].P : hK);  // the assembly cell stores raw keys
     V holeF = kLow, holeOld = kHigh, holeNew = kLow;  // no hole
     uint64_t hole_lanes = 0;                          // lanes with a live hole (wave-uniform)
     bool over = false;
@@ -344,68 +344,80 @@ __global__ __launch_bounds__(BLOCK) void cubic_budgets_kernel(int n, int64_t blo
     };
 
 #if CKPT_CUBIC_ASM_CELL
-    // The same cell for 32-bit values, written out: 9 vector instructions when
-    // nothing is dropped, 3 more per dropped entry.  (The compiler's lowering of
-    // the generic form costs about three times as many.)
+    // The same cell for 32-bit values, written out: 6 vector instructions when
+    // nothing is dropped, 3 more per dropped entry (the compiler's lowering of the
+    // generic form costs about three times as many).  Differences in bookkeeping:
+    //  - ring keys are the raw P[h]; the head's key is kept in a register as
+    //    P[h] + s (hK), and the hole keys are raw too;
+    //  - "ring full" is "the next slot is the head's slot" (hdA = its LDS address);
+    //  - the value register and the tail mirror swap roles every cell: after the
+    //    store the tail mirror IS the stored value, so the new F(j) is written
+    //    over the old mirror and the names are exchanged (free in straight-line
+    //    code), except for lanes that could not store.
     V vLow = kLow, vHigh = kHigh;
+    uint32_t hdA = lane_base;
+    // hole state of the assembly cell: smallest hole value (kHigh: none), oldest
+    // and newest hole key plus s (kHigh / kLow: none); flagged lanes as a lane mask
+    V aF = kHigh, aOld = kHigh, aNew = kLow;
+    uint64_t over_lanes = 0;
     auto cell_asm = [&](const int32_t Pj1, const int32_t dj) {
-        uint32_t ad, key, t0;
+        uint32_t ad, t0;
         uint64_t sv, sfull, st;
         asm volatile(
-            // ---- drop tails
+            // ---- drop tails (X = tail mirror, Y = value to insert)
             "Lpop_%=:\n\t"
-            "v_cmp_ge_i32 vcc, %[tF], %[F]\n\t"
+            "v_cmp_ge_i32 vcc, %[X], %[Y]\n\t"
             "s_cbranch_vccz Lpop_done_%=\n\t"
             "s_and_saveexec_b64 %[sv], vcc\n\t"
             "v_subrev_u32 %[tl], %[step], %[tl]\n\t"
             "v_and_or_b32 %[ad], %[tl], %[mask], %[lo]\n\t"
-            "ds_read_b32 %[tF], %[ad]\n\t"
+            "ds_read_b32 %[X], %[ad]\n\t"
             "s_mov_b64 exec, %[sv]\n\t"
             "s_waitcnt lgkmcnt(0)\n\t"
             "s_branch Lpop_%=\n\t"
             "Lpop_done_%=:\n\t"
-            // ---- full ring or live hole anywhere in the wave?
-            "v_add_u32 %[key], %[P], %[s]\n\t"
-            "v_sub_u32 %[t0], %[tl], %[hd]\n\t"
-            "v_cmp_le_u32 vcc, %[full], %[t0]\n\t"
+            // ---- next slot; full ring or live hole anywhere in the wave?
+            "v_add_u32 %[tl], %[step], %[tl]\n\t"
+            "v_and_or_b32 %[ad], %[tl], %[mask], %[lo]\n\t"
+            "v_cmp_eq_u32 vcc, %[ad], %[hdA]\n\t"
             "s_or_b64 %[st], vcc, %[hl]\n\t"
             "s_cmp_lg_u64 %[st], 0\n\t"
             "s_cbranch_scc1 Lslow_%=\n\t"
             // ---- fast path: store, drop heads
-            "v_add_u32 %[tl], %[step], %[tl]\n\t"
-            "v_and_or_b32 %[ad], %[tl], %[mask], %[lo]\n\t"
-            "ds_write2_b32 %[ad], %[F], %[key] offset1:1\n\t"
-            "v_mov_b32 %[tF], %[F]\n\t"
+            "ds_write2_b32 %[ad], %[Y], %[P] offset1:1\n\t"
             "Lexp_%=:\n\t"
             "v_cmp_gt_i32 vcc, %[P], %[hK]\n\t"
             "s_cbranch_vccz Ljoin_%=\n\t"
             "s_and_saveexec_b64 %[sv], vcc\n\t"
             "v_add_u32 %[hd], %[step], %[hd]\n\t"
-            "v_and_or_b32 %[ad], %[hd], %[mask], %[lo]\n\t"
-            "ds_read_b32 %[hF], %[ad]\n\t"
-            "ds_read_b32 %[hK], %[ad] offset:4\n\t"
-            "s_mov_b64 exec, %[sv]\n\t"
+            "v_and_or_b32 %[hdA], %[hd], %[mask], %[lo]\n\t"
+            "ds_read_b32 %[hF], %[hdA]\n\t"
+            "ds_read_b32 %[hK], %[hdA] offset:4\n\t"
             "s_waitcnt lgkmcnt(0)\n\t"
+            "v_add_u32 %[hK], %[hK], %[s]\n\t"
+            "s_mov_b64 exec, %[sv]\n\t"
             "s_branch Lexp_%=\n\t"
-            // ---- slow path (vcc = lanes whose ring is full)
+            // ---- some lane has a full ring (vcc) or a live hole
             "Lslow_%=:\n\t"
             "s_mov_b64 %[sfull], vcc\n\t"
-            "v_cmp_le_i32 vcc, %[F], %[oF]\n\t"
+            // holes vanish when this value would have dropped them or they left the window
+            "v_cmp_le_i32 vcc, %[Y], %[oF]\n\t"
             "v_cmp_gt_i32 %[st], %[P], %[oNew]\n\t"
             "s_or_b64 vcc, vcc, %[st]\n\t"
-            "v_cndmask_b32 %[oF], %[oF], %[vLow], vcc\n\t"
+            "v_cndmask_b32 %[oF], %[oF], %[vHigh], vcc\n\t"
             "v_cndmask_b32 %[oOld], %[oOld], %[vHigh], vcc\n\t"
             "v_cndmask_b32 %[oNew], %[oNew], %[vLow], vcc\n\t"
+            "s_cmp_lg_u64 %[sfull], 0\n\t"
+            "s_cbranch_scc0 Lnofull_%=\n\t"
+            // -- full lanes: the value is not stored and becomes a hole
+            "v_add_u32 %[t0], %[P], %[s]\n\t"
             "s_and_saveexec_b64 %[sv], %[sfull]\n\t"
-            "v_cmp_eq_u32 vcc, %[oOld], %[vHigh]\n\t"
-            "v_cndmask_b32 %[oF], %[oF], %[F], vcc\n\t"
-            "v_min_i32 %[oOld], %[oOld], %[key]\n\t"
-            "v_mov_b32 %[oNew], %[key]\n\t"
+            "v_subrev_u32 %[tl], %[step], %[tl]\n\t"
+            "v_min_i32 %[oF], %[oF], %[Y]\n\t"
+            "v_min_i32 %[oOld], %[oOld], %[t0]\n\t"
+            "v_mov_b32 %[oNew], %[t0]\n\t"
             "s_andn2_b64 exec, %[sv], %[sfull]\n\t"
-            "v_add_u32 %[tl], %[step], %[tl]\n\t"
-            "v_and_or_b32 %[ad], %[tl], %[mask], %[lo]\n\t"
-            "ds_write2_b32 %[ad], %[F], %[key] offset1:1\n\t"
-            "v_mov_b32 %[tF], %[F]\n\t"
+            "ds_write2_b32 %[ad], %[Y], %[P] offset1:1\n\t"
             "s_mov_b64 exec, %[sv]\n\t"
             "Lsexp_%=:\n\t"
             "v_cmp_gt_i32 vcc, %[P], %[hK]\n\t"
@@ -414,29 +426,59 @@ __global__ __launch_bounds__(BLOCK) void cubic_budgets_kernel(int n, int64_t blo
             "s_cbranch_vccz Lsexp_done_%=\n\t"
             "s_and_saveexec_b64 %[sv], vcc\n\t"
             "v_add_u32 %[hd], %[step], %[hd]\n\t"
-            "v_and_or_b32 %[ad], %[hd], %[mask], %[lo]\n\t"
-            "ds_read_b32 %[hF], %[ad]\n\t"
-            "ds_read_b32 %[hK], %[ad] offset:4\n\t"
-            "s_mov_b64 exec, %[sv]\n\t"
+            "v_and_or_b32 %[hdA], %[hd], %[mask], %[lo]\n\t"
+            "ds_read_b32 %[hF], %[hdA]\n\t"
+            "ds_read_b32 %[hK], %[hdA] offset:4\n\t"
             "s_waitcnt lgkmcnt(0)\n\t"
+            "v_add_u32 %[hK], %[hK], %[s]\n\t"
+            "s_mov_b64 exec, %[sv]\n\t"
             "s_branch Lsexp_%=\n\t"
             "Lsexp_done_%=:\n\t"
+            // flag: nothing valid left, or the head passed the oldest hole
             "v_cmp_gt_i32 vcc, %[P], %[hK]\n\t"
-            "v_cmp_gt_i32 %[st], %[hK], %[oOld]\n\t"
-            "s_or_b64 vcc, vcc, %[st]\n\t"
-            "v_cndmask_b32 %[t0], 0, 1, vcc\n\t"
-            "v_or_b32 %[over], %[over], %[t0]\n\t"
+            "s_or_b64 %[ov], %[ov], vcc\n\t"
+            "v_cmp_gt_i32 vcc, %[hK], %[oOld]\n\t"
+            "s_or_b64 %[ov], %[ov], vcc\n\t"
             "v_cmp_ne_u32 %[hl], %[oOld], %[vHigh]\n\t"
-            // ---- F(j) = d_j + head
+            // F(j) = d_j + head; lanes that could not store keep their tail mirror
+            "v_add_u32 %[t0], %[D], %[hF]\n\t"
+            "v_cndmask_b32 %[Y], %[Y], %[X], %[sfull]\n\t"
+            "v_mov_b32 %[X], %[t0]\n\t"
+            "s_branch Lend_%=\n\t"
+            // -- holes alive but every lane can store
+            "Lnofull_%=:\n\t"
+            "ds_write2_b32 %[ad], %[Y], %[P] offset1:1\n\t"
+            "Lhexp_%=:\n\t"
+            "v_cmp_gt_i32 vcc, %[P], %[hK]\n\t"
+            "s_cbranch_vccz Lhexp_done_%=\n\t"
+            "s_and_saveexec_b64 %[sv], vcc\n\t"
+            "v_add_u32 %[hd], %[step], %[hd]\n\t"
+            "v_and_or_b32 %[hdA], %[hd], %[mask], %[lo]\n\t"
+            "ds_read_b32 %[hF], %[hdA]\n\t"
+            "ds_read_b32 %[hK], %[hdA] offset:4\n\t"
+            "s_waitcnt lgkmcnt(0)\n\t"
+            "v_add_u32 %[hK], %[hK], %[s]\n\t"
+            "s_mov_b64 exec, %[sv]\n\t"
+            "s_branch Lhexp_%=\n\t"
+            "Lhexp_done_%=:\n\t"
+            "v_cmp_gt_i32 vcc, %[hK], %[oOld]\n\t"
+            "s_or_b64 %[ov], %[ov], vcc\n\t"
+            "v_cmp_ne_u32 %[hl], %[oOld], %[vHigh]\n\t"
+            // ---- F(j) = d_j + head, written over the old tail mirror
             "Ljoin_%=:\n\t"
-            "v_add_u32 %[F], %[D], %[hF]\n\t"
-            : [tl] "+v"(tl), [hd] "+v"(hd), [tF] "+v"(tF), [hF] "+v"(hF), [hK] "+v"(hK), [F] "+v"(Fprev),
-              [oF] "+v"(holeF), [oOld] "+v"(holeOld), [oNew] "+v"(holeNew), [over] "+v"(over_bits),
-              [hl] "+s"(hole_lanes), [ad] "=&v"(ad), [key] "=&v"(key), [t0] "=&v"(t0), [sv] "=&s"(sv),
-              [sfull] "=&s"(sfull), [st] "=&s"(st)
-            : [P] "s"(Pj1), [D] "s"(dj), [s] "v"(s), [lo] "v"(lane_base), [mask] "s"(kSlotMask),
-              [vLow] "v"(vLow), [vHigh] "v"(vHigh), [step] "i"(kStep), [full] "i"(kFull)
+            "v_add_u32 %[X], %[D], %[hF]\n\t"
+            "Lend_%=:\n\t"
+            : [tl] "+v"(tl), [hd] "+v"(hd), [hdA] "+v"(hdA), [X] "+v"(tF), [Y] "+v"(Fprev), [hF] "+v"(hF),
+              [hK] "+v"(hK), [oF] "+v"(aF), [oOld] "+v"(aOld), [oNew] "+v"(aNew), [ov] "+s"(over_lanes),
+              [hl] "+s"(hole_lanes), [ad] "=&v"(ad), [t0] "=&v"(t0), [sv] "=&s"(sv), [sfull] "=&s"(sfull),
+              [st] "=&s"(st)
+            : [P] "v"(Pj1), [D] "v"(dj), [s] "v"(s), [lo] "v"(lane_base), [mask] "s"(kSlotMask),
+              [vLow] "v"(vLow), [vHigh] "v"(vHigh), [step] "i"(kStep)
             : "vcc", "scc", "memory");
+        // the registers have exchanged roles
+        const V t = tF;
+        tF = Fprev;
+        Fprev = t;
     };
 #endif
     auto cell = [&](const V Pj1, const V dj) {
@@ -470,6 +512,9 @@ __global__ __launch_bounds__(BLOCK) void cubic_budgets_kernel(int n, int64_t blo
     if (last_full >= kCells && last_full <= n) chunk(last_full, true);
 
     over |= over_bits != 0;
+#if CKPT_CUBIC_ASM_CELL
+    if constexpr (sizeof(V) == 4) over |= ((over_lanes >> (tid & (kWave - 1))) & 1) != 0;
+#endif
     const bool redo = live && over;
     const uint64_t flag = __ballot(redo);
     int64_t cost = (live && !over) ? (int64_t)s + (int64_t)Fprev : kInf;
