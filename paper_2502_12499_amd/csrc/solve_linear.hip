@@ -17,21 +17,25 @@
 //        M(i) > U(i,j_pt) >= M(j_pt).  Entries beyond pt are dead.  The
 //        minimum of Equation (TU) is at pt (value U(i,j_pt)) or at the entry
 //        just before it, the "candidate" (value M); ties go to the lower index.
-//   rec  the prefix-maximum records of d_i, d_{i+1}, ..: positions k whose d_k
-//        exceeds everything between i and k, as a stack (top = i).  R(i,j) is
-//        the value of the record with the largest k < j.  R for the pt entry
-//        and for the candidate are kept in registers (R <- max(R, d_i) each
-//        step); the stack is walked only when pt moves and a new candidate
-//        needs its R: a range maximum cannot be undone when j moves left, the
-//        walk over records can.  Records at or beyond j_pt are dead.
+//   R    the range maximum cannot be undone when j moves left (the paper's
+//        "U(i,j') from U(i,j)"), so it is kept exactly in another form: every
+//        entry carries G = max of d from its own position up to the next entry
+//        towards the far end (fixed when the entry is pushed: the front maximum
+//        joined with the G of the entries it replaced), and R(i,j) of an entry
+//        is the maximum of d since the head was pushed ("front") joined with
+//        the G of the entries above it.  R of the pt entry and of the candidate
+//        live in registers (R <- max(R, d_i) each step); the join over the
+//        entries above is only taken when pt moves and a new candidate needs
+//        its R.  (The general kernel below uses the stack of prefix-maximum
+//        records of d_i, d_{i+1}, .. for the same purpose.)
 //   nxt  the chosen j for every i; the set is read off by following nxt from 0.
 // Every entry enters and leaves each stack once and the pointers move one way
 // between pushes, so the work per chain is O(n).
 //
 // Kernels:
 //   ring kernel     one lane per chain, every chain of the batch.  Only the live
-//        parts of the two stacks are kept, as 16-slot rings in LDS laid out
-//        [slot][lane] (bank = lane).  Values are held as 32-bit multiples of
+//        part of the stack is kept, as a 16-slot ring in LDS laid out
+//        [slot][lane].  Values are held as 32-bit multiples of
 //        2^sh, sh the number of trailing zero bits common to the sizes read so
 //        far (stored values are shifted left when a size with fewer trailing
 //        zeros arrives).  nxt(i) - i - 1 is parked as a byte in the chain's
@@ -78,17 +82,27 @@ __global__ void linear_reset_kernel(LinearWs w) { *w.count = 0; }
 // ring kernel
 // ---------------------------------------------------------------------------
 
+struct RingEntry {
+    uint32_t M;  // M(j)
+    uint32_t A;  // M(j) + T(j)
+    uint32_t G;  // max of d over [j, j'), j' the next entry towards the far end
+    uint32_t J;  // j
+};
+
 __global__ __launch_bounds__(kWave) void linear_ring_kernel(const int64_t *__restrict__ d, int64_t batch, int n,
                                                             int64_t cstride, int64_t pstride,
                                                             uint8_t *__restrict__ mask_out,
                                                             int64_t *__restrict__ peak_out,
                                                             int32_t *__restrict__ status_out, LinearWs w)
 {
-    __shared__ uint32_t qM[kRing][kWave];
-    __shared__ uint32_t qA[kRing][kWave];
-    __shared__ uint32_t recD[kRing][kWave];
-    __shared__ uint16_t qJ[kRing][kWave];
-    __shared__ uint16_t recK[kRing][kWave];
+    // Ring positions are kept pre-multiplied by the byte stride of a slot, so
+    // the LDS address of a position is one AND-OR away (the ring is aligned to
+    // its own size).
+    __shared__ __attribute__((aligned(16384))) RingEntry ring[kRing][kWave];
+    constexpr uint32_t kStep = (uint32_t)(kWave * sizeof(RingEntry));
+    constexpr uint32_t kSlotMask = (uint32_t)(kRing - 1) * kStep;
+    constexpr uint32_t kNone = 0xffffffffu;  // "no candidate": never passes a test
+    static_assert(kStep * kRing == 16384, "ring size and alignment");
 
     const int lane = threadIdx.x;
     const int64_t c = (int64_t)blockIdx.x * kWave + lane;
@@ -96,8 +110,11 @@ __global__ __launch_bounds__(kWave) void linear_ring_kernel(const int64_t *__res
     const int64_t cc = live ? c : batch - 1;  // idle lanes shadow the last chain and write nothing
     const int64_t *dp = d + cc * cstride;
     uint8_t *mp = mask_out + cc * cstride;
-    constexpr int kMsk = kRing - 1;
     constexpr uint32_t kLimit = 1u << 30;
+
+    typedef __attribute__((address_space(3))) uint32_t *LdsPtr;
+    const uint32_t lane_base = (uint32_t)(uintptr_t)(LdsPtr)&ring[0][lane].M;
+    auto entry = [&](uint32_t pos) -> LdsPtr { return (LdsPtr)(uintptr_t)((pos & kSlotMask) | lane_base); };
 
     const int64_t xn = dp[(int64_t)n * pstride];
     bool defer = xn <= 0;
@@ -106,40 +123,39 @@ __global__ __launch_bounds__(kWave) void linear_ring_kernel(const int64_t *__res
     defer |= xs >= kLimit;
 
     // Q = {n}: it is the crossover entry (U(i,n) > d_n = M(n) for every i)
-    int hd = 0, pt = 0;
-    uint32_t Mhd = (uint32_t)xs;   // M of the head entry
-    uint32_t Tpt = 0, Jpt = n;     // T(j_pt), j_pt
-    uint32_t Rp = 0;               // R(i, j_pt)
-    bool cand = false;             // is there an entry between pt and the head side, i.e. pt < hd
-    uint32_t Mc = 0, Ac = 0, Jc = 0, Rc = 0;  // the candidate (entry pt+1): M, A, j, R(i, j)
-    int top = -1;                  // records occupy rp..top
-    int rp = 0x3fffffff, rc = 0x3fffffff;  // lowest record index with k < j_pt / k < j_c (clamped to top)
-    uint32_t Ti = 0;               // T(i) / 2^sh
-    uint32_t dnext = (uint32_t)xs; // d_{i+1} / 2^sh
+    uint32_t hd = 0, pt = 0;                   // ring positions of the head and of the crossover entry
+    uint32_t Mhd = (uint32_t)xs, Ghd = 0;      // M and G of the head entry
+    uint32_t front = 0;                        // max of d over [i, j_head)
+    uint32_t Tpt = 0, Jpt = n, Rp = 0;         // crossover entry: T(j), j, R(i, j)
+    uint32_t Mc = kNone, Ac = kNone, Jc = 0, Rc = 0;  // candidate (the entry before pt): M, A, j, R(i, j)
+    uint32_t Ti = 0;                           // T(i) / 2^sh
+    uint32_t dnext = (uint32_t)xs;             // d_{i+1} / 2^sh
     uint32_t dmax = dnext;
     uint32_t Mi = dnext;
-    qM[0][lane] = Mhd;
-    qA[0][lane] = Mhd;  // T(n) = 0
-    qJ[0][lane] = (uint16_t)n;
+    {
+        LdsPtr e = entry(0);
+        e[0] = Mhd; e[1] = Mhd; e[2] = 0; e[3] = (uint32_t)n;  // T(n) = 0
+    }
 
     // One step of the recurrence for position i, whose size x is already in a register.
     auto step_fn = [&](const int i, const int64_t x) {
         defer |= x <= 0;
         // common trailing zeros: rescale everything held so far if this size has fewer
         const int tz = x > 0 ? __ffsll((unsigned long long)x) - 1 : sh;
-        if (__any(tz < sh)) {
+        if (__builtin_amdgcn_ballot_w64(tz < sh) != 0) {
             if (tz < sh) {
                 const int k = sh - tz;
                 const bool fits = k < 30 && ((Ti + dnext + dmax) >> (30 - k)) == 0;
                 defer |= !fits;
                 const int kk = fits ? k : 0;
 #pragma unroll
-                for (int s = 0; s < kRing; ++s) {
-                    qM[s][lane] <<= kk;
-                    qA[s][lane] <<= kk;
-                    recD[s][lane] <<= kk;
+                for (int t = 0; t < kRing; ++t) {
+                    LdsPtr e = entry((uint32_t)t * kStep);
+                    e[0] <<= kk; e[1] <<= kk; e[2] <<= kk;
                 }
-                Mhd <<= kk; Tpt <<= kk; Rp <<= kk; Mc <<= kk; Ac <<= kk; Rc <<= kk;
+                Mhd <<= kk; Ghd <<= kk; front <<= kk; Tpt <<= kk; Rp <<= kk; Rc <<= kk;
+                Mc = Mc == kNone ? kNone : Mc << kk;
+                Ac = Ac == kNone ? kNone : Ac << kk;
                 Ti <<= kk; dnext <<= kk; dmax <<= kk;
                 sh = tz;
             }
@@ -150,39 +166,63 @@ __global__ __launch_bounds__(kWave) void linear_ring_kernel(const int64_t *__res
         Ti += dnext;
         dmax = di > dmax ? di : dmax;
         defer |= (Ti + di + dmax) >= kLimit;  // bounds M(i) and every U(i,j)
-
-        // records: d_i hides every record not larger than it; the top record is d_{i+1}
-        if (top >= 0 && dnext <= di) {
-            --top;
-            while (top >= rp && (uint32_t)recD[top & kMsk][lane] <= di) --top;
-        }
-        ++top;
-        recD[top & kMsk][lane] = di;
-        recK[top & kMsk][lane] = (uint16_t)i;
-        rp = rp < top ? rp : top;
-        rc = rc < top ? rc : top;
+        front = di > front ? di : front;
         Rp = di > Rp ? di : Rp;
         Rc = di > Rc ? di : Rc;
-        defer |= (top - rp) >= kRing;
 
-        // move the crossover towards the head while the candidate satisfies U(i,j) >= M(j)
-        while (cand && Ti + Rc >= Ac) {
-            ++pt;
-            Tpt = Ac - Mc; Jpt = Jc; Rp = Rc; rp = rc;
-            cand = pt < hd;
-            if (cand) {
-                const int e = (pt + 1) & kMsk;
-                Mc = (uint32_t)qM[e][lane];
-                Ac = (uint32_t)qA[e][lane];
-                Jc = qJ[e][lane];
-                int r = rc;
-                while (r < top && recK[r & kMsk][lane] >= Jc) ++r;  // the top record has k = i < j_c
-                rc = r;
-                Rc = (uint32_t)recD[r & kMsk][lane];
-            }
+        // Move the crossover towards the head while the candidate satisfies
+        // U(i,j) >= M(j).  A new candidate's R is the front maximum joined with the
+        // G of the entries above it.  Runs while ANY lane has to move; lanes that
+        // are done sit out under the exec mask.  (In assembly: the compiler's
+        // lowering of this doubly nested divergent loop is several times longer.)
+        {
+            uint32_t ad, e, t0;
+            uint64_t sv, sv2, sv3;
+            asm volatile(
+                "Lw_%=:\n\t"
+                "v_add_u32 %[t0], %[Ti], %[Rc]\n\t"
+                "v_cmp_ge_u32 vcc, %[t0], %[Ac]\n\t"
+                "s_cbranch_vccz Lw_done_%=\n\t"
+                "s_and_saveexec_b64 %[sv], vcc\n\t"
+                "v_add_u32 %[pt], %[step], %[pt]\n\t"
+                "v_sub_u32 %[Tpt], %[Ac], %[Mc]\n\t"
+                "v_mov_b32 %[Jpt], %[Jc]\n\t"
+                "v_mov_b32 %[Rp], %[Rc]\n\t"
+                "v_mov_b32 %[Ac], -1\n\t"
+                "v_mov_b32 %[Mc], -1\n\t"
+                "v_cmp_ne_u32 vcc, %[pt], %[hd]\n\t"
+                "s_and_saveexec_b64 %[sv2], vcc\n\t"
+                "v_add_u32 %[e], %[step], %[pt]\n\t"
+                "v_and_or_b32 %[ad], %[e], %[mask], %[lo]\n\t"
+                "ds_read_b32 %[Mc], %[ad]\n\t"
+                "ds_read_b32 %[Ac], %[ad] offset:4\n\t"
+                "ds_read_b32 %[Jc], %[ad] offset:12\n\t"
+                "v_mov_b32 %[Rc], %[front]\n\t"
+                "Lg_%=:\n\t"
+                "v_cmp_ne_u32 vcc, %[e], %[hd]\n\t"
+                "s_cbranch_vccz Lg_done_%=\n\t"
+                "s_and_saveexec_b64 %[sv3], vcc\n\t"
+                "v_add_u32 %[e], %[step], %[e]\n\t"
+                "v_and_or_b32 %[ad], %[e], %[mask], %[lo]\n\t"
+                "ds_read_b32 %[t0], %[ad] offset:8\n\t"
+                "s_waitcnt lgkmcnt(0)\n\t"
+                "v_max_u32 %[Rc], %[Rc], %[t0]\n\t"
+                "s_mov_b64 exec, %[sv3]\n\t"
+                "s_branch Lg_%=\n\t"
+                "Lg_done_%=:\n\t"
+                "s_waitcnt lgkmcnt(0)\n\t"
+                "s_mov_b64 exec, %[sv]\n\t"
+                "s_branch Lw_%=\n\t"
+                "Lw_done_%=:\n\t"
+                : [pt] "+v"(pt), [Tpt] "+v"(Tpt), [Jpt] "+v"(Jpt), [Rp] "+v"(Rp), [Mc] "+v"(Mc), [Ac] "+v"(Ac),
+                  [Jc] "+v"(Jc), [Rc] "+v"(Rc), [ad] "=&v"(ad), [e] "=&v"(e), [t0] "=&v"(t0), [sv] "=&s"(sv),
+                  [sv2] "=&s"(sv2), [sv3] "=&s"(sv3)
+                : [Ti] "v"(Ti), [hd] "v"(hd), [front] "v"(front), [lo] "v"(lane_base), [mask] "s"(kSlotMask),
+                  [step] "i"(kStep)
+                : "vcc", "memory");
         }
         const uint32_t Upt = Ti + Rp - Tpt;  // U(i, j_pt)
-        const bool take_cand = cand && Mc <= Upt;
+        const bool take_cand = Mc <= Upt;    // ties go to the lower index; kNone never wins
         const uint32_t best = take_cand ? Mc : Upt;
         const uint32_t nx = take_cand ? Jc : Jpt;
         Mi = di + best;
@@ -190,21 +230,47 @@ __global__ __launch_bounds__(kWave) void linear_ring_kernel(const int64_t *__res
         defer |= step > 255u;
         if (live) mp[(int64_t)i * pstride] = (uint8_t)step;
 
-        // Q: drop the entries that M(i) dominates (never the crossover entry), then push i
-        if (hd > pt && Mhd >= Mi) {
-            --hd;
-            while (hd > pt && (uint32_t)qM[hd & kMsk][lane] >= Mi) --hd;
+        // Q: drop the entries that M(i) dominates (never the crossover entry),
+        // folding their G into the new entry's, then push i
+        uint32_t Gacc = front;
+        {
+            uint32_t ad;
+            uint64_t sv, st;
+            asm volatile(
+                "Lq_%=:\n\t"
+                "v_cmp_ge_u32 vcc, %[Mhd], %[Mi]\n\t"
+                "v_cmp_ne_u32 %[st], %[hd], %[pt]\n\t"
+                "s_and_b64 vcc, vcc, %[st]\n\t"
+                "s_cbranch_vccz Lq_done_%=\n\t"
+                "s_and_saveexec_b64 %[sv], vcc\n\t"
+                "v_max_u32 %[G], %[G], %[Ghd]\n\t"
+                "v_subrev_u32 %[hd], %[step], %[hd]\n\t"
+                "v_and_or_b32 %[ad], %[hd], %[mask], %[lo]\n\t"
+                "ds_read_b32 %[Mhd], %[ad]\n\t"
+                "ds_read_b32 %[Ghd], %[ad] offset:8\n\t"
+                "s_waitcnt lgkmcnt(0)\n\t"
+                "s_mov_b64 exec, %[sv]\n\t"
+                "s_branch Lq_%=\n\t"
+                "Lq_done_%=:\n\t"
+                : [hd] "+v"(hd), [Mhd] "+v"(Mhd), [Ghd] "+v"(Ghd), [G] "+v"(Gacc), [ad] "=&v"(ad), [sv] "=&s"(sv),
+                  [st] "=&s"(st)
+                : [Mi] "v"(Mi), [pt] "v"(pt), [lo] "v"(lane_base), [mask] "s"(kSlotMask), [step] "i"(kStep)
+                : "vcc", "memory");
         }
-        ++hd;
-        qM[hd & kMsk][lane] = Mi;
-        qA[hd & kMsk][lane] = Mi + Ti;
-        qJ[hd & kMsk][lane] = (uint16_t)i;
+        hd += kStep;
+        {
+            LdsPtr e = entry(hd);
+            e[0] = Mi; e[1] = Mi + Ti; e[2] = Gacc; e[3] = (uint32_t)i;
+        }
         Mhd = Mi;
-        defer |= (hd - pt) >= kRing;
-        if (hd == pt + 1) {  // the new entry is the candidate; no record has k < i yet
-            cand = true;
-            Mc = Mi; Ac = Mi + Ti; Jc = (uint32_t)i; Rc = 0; rc = 0x3fffffff;
-        }
+        Ghd = Gacc;
+        front = 0;
+        defer |= (hd - pt) >= (uint32_t)kRing * kStep;
+        const bool fresh = hd == pt + kStep;  // the new entry is the candidate; R(i', i) starts empty
+        Mc = fresh ? Mi : Mc;
+        Ac = fresh ? Mi + Ti : Ac;
+        Jc = fresh ? (uint32_t)i : Jc;
+        Rc = fresh ? 0u : Rc;
         dnext = di;
     };
 
