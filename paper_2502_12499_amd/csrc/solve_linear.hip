@@ -228,7 +228,11 @@ __global__ __launch_bounds__(kWave) void linear_ring_kernel(const int64_t *__res
         Mi = di + best;
         const uint32_t step = nx - (uint32_t)i - 1u;
         defer |= step > 255u;
-        if (live) mp[(int64_t)i * pstride] = (uint8_t)step;
+        // Parked with a store the compiler does not count, so that its waits on the
+        // rows fetched ahead stay partial (a counted store would make it wait for
+        // everything in flight; an uncounted one can only lengthen a wait).
+        if (live)
+            asm volatile("global_store_byte %0, %1, off" : : "v"(mp + (int64_t)i * pstride), "v"(step) : "memory");
 
         // Q: drop the entries that M(i) dominates (never the crossover entry),
         // folding their G into the new entry's, then push i
@@ -278,13 +282,11 @@ __global__ __launch_bounds__(kWave) void linear_ring_kernel(const int64_t *__res
     // latency of a row overlaps the work on the rows before it.
     int64_t rows[kChunk], ahead[kChunk];
 #pragma unroll
-    for (int u = 0; u < kChunk; ++u) rows[u] = (n - 1 - u) >= 0 ? dp[(int64_t)(n - 1 - u) * pstride] : 1;
+    for (int u = 0; u < kChunk; ++u) rows[u] = dp[(int64_t)max(n - 1 - u, 0) * pstride];
     for (int ihi = n - 1; ihi >= 0; ihi -= kChunk) {
 #pragma unroll
-        for (int u = 0; u < kChunk; ++u) {
-            const int k = ihi - kChunk - u;
-            ahead[u] = k >= 0 ? dp[(int64_t)k * pstride] : 1;
-        }
+        for (int u = 0; u < kChunk; ++u)  // rows below 0 re-read row 0 and are not used
+            ahead[u] = dp[(int64_t)max(ihi - kChunk - u, 0) * pstride];
 #pragma unroll
         for (int u = 0; u < kChunk; ++u)
             if (ihi - u >= 0) step_fn(ihi - u, rows[u]);
@@ -301,7 +303,8 @@ __global__ __launch_bounds__(kWave) void linear_ring_kernel(const int64_t *__res
     }
     peak_out[c] = (int64_t)((uint64_t)Mi << sh);
     if (status_out) status_out[c] = CKPT_OK;
-    // forward sweep: replace the parked steps by the mask
+    // forward sweep: replace the parked steps by the mask (once they have all landed)
+    asm volatile("s_waitcnt vmcnt(0)" : : : "memory");
     int cur = 0;
     for (int k0 = 0; k0 <= n; k0 += kChunk) {
         uint8_t b[kChunk];
