@@ -51,6 +51,8 @@ namespace {
 constexpr int64_t kInf = INT64_MAX;
 constexpr int kCells = 8;  // cells per fetch of the (P, d) table
 constexpr int kPad = 16;   // table entries past n+1, so a fetch never leaves the table
+constexpr int kReduceBlocks = 64;      // second-level reduction: workgroups per chain
+constexpr int64_t kReduceFrom = 4096;  // ... used when a chain has more per-wave partial results than this
 
 #ifndef CKPT_CUBIC_ASM_CELL
 #define CKPT_CUBIC_ASM_CELL 1  // 0: use the portable form of the recurrence cell for 32-bit values too
@@ -79,6 +81,7 @@ struct CubicWs {
     char *pd;             // [batch][table_len(n)] of PD<int64_t> (PD<int32_t> in the same bytes when mode32)
     Partial *partial;     // [batch][waves_per_chain]
     uint64_t *flags;      // [batch][waves_per_chain] lanes to recompute
+    Partial *partial2;    // [batch][kReduceBlocks] second-level partial results (long chains only)
     int32_t *pred;        // [batch][n+1]
 };
 
@@ -101,6 +104,7 @@ __host__ CubicWs carve_cubic(void *ws, int64_t batch, int n)
     w.pd = p;                   p += align_up(B * table_len(n) * sizeof(PD<int64_t>));
     w.partial = (Partial *)p;   p += align_up(B * wpc * sizeof(Partial));
     w.flags = (uint64_t *)p;    p += align_up(B * wpc * 8);
+    w.partial2 = (Partial *)p;  p += align_up(B * kReduceBlocks * sizeof(Partial));
     w.pred = (int32_t *)p;      p += align_up(B * n1 * 4);
     return w;
 }
@@ -568,18 +572,31 @@ __device__ V wave_budget_table(const PD<V> *__restrict__ pd, int n, V s, V *F, i
     return last;
 }
 
+// A value that is the same in every lane, moved to scalar registers so that the
+// arithmetic that follows runs on the scalar unit.
+__device__ inline int32_t uniform(int32_t v) { return __builtin_amdgcn_readfirstlane(v); }
+__device__ inline int64_t uniform(int64_t v)
+{
+    const uint32_t lo = (uint32_t)__builtin_amdgcn_readfirstlane((int32_t)(uint32_t)v);
+    const uint32_t hi = (uint32_t)__builtin_amdgcn_readfirstlane((int32_t)(uint32_t)((uint64_t)v >> 32));
+    return (int64_t)(((uint64_t)hi << 32) | lo);
+}
+
 // Bytes of LDS that queue_budget_pred needs for a chain of n layers.
 template <typename V>
 __host__ __device__ inline size_t queue_pred_bytes(int n) { return ((size_t)n + 1) * (2 * sizeof(V) + 4); }
 
 // Predecessors for one budget by Algorithm 4's queue itself, run as a single
-// sequential pass (every lane carries the same state; lane 0 does the stores).
+// sequential pass (every lane carries the same state, held in scalar registers;
+// lane 0 does the stores).
 // Only strictly larger tails are dropped, so among equal minima the oldest
 // stays at the head: pred16[j] is the smallest h in the window with minimal F.
 // The queue has full capacity n+1 in LDS: entry (F, P[h] + s, h).
 template <typename V>
-__device__ void queue_budget_pred(const PD<V> *__restrict__ pd, int n, V s, unsigned char *lds, uint16_t *&pred16)
+__device__ void queue_budget_pred(const PD<V> *__restrict__ pd, int n, V s_in, unsigned char *lds,
+                                  uint16_t *&pred16)
 {
+    const V s = uniform(s_in);
     const int n1 = n + 1;
     V *qF = (V *)lds;
     V *qK = qF + n1;
@@ -609,7 +626,7 @@ __device__ void queue_budget_pred(const PD<V> *__restrict__ pd, int n, V s, unsi
             const V Pj1 = cur[u].P;
             while (tF > Fprev) {  // the head is smaller than F(j-1), so this stops at it
                 --tl;
-                tF = qF[tl];
+                tF = uniform(qF[tl]);
             }
             ++tl;
             const V key = Pj1 + s;
@@ -625,9 +642,9 @@ __device__ void queue_budget_pred(const PD<V> *__restrict__ pd, int n, V s, unsi
             }
             while (hK < Pj1) {
                 ++hd;
-                hF = qF[hd];
-                hK = qK[hd];
-                hH = qH[hd];
+                hF = uniform(qF[hd]);
+                hK = uniform(qK[hd]);
+                hH = uniform((int32_t)qH[hd]);
             }
             if (writer) pred16[j] = (uint16_t)hH;
             Fprev = cur[u].d + hF;
@@ -672,6 +689,38 @@ __global__ __launch_bounds__(kWave) void cubic_overflow_kernel(int n, int64_t n_
     }
 }
 
+// ---- second-level reduction for long chains ------------------------------------------
+
+// A chain of n = 4096 layers leaves 131,073 per-wave results; one wave reading
+// them one after the other would take longer than the budgets kernel's tail, so
+// kReduceBlocks workgroups per chain fold them first.
+__global__ __launch_bounds__(256) void cubic_reduce_kernel(int n, CubicWs w)
+{
+    __shared__ Partial part[4];
+    const int64_t c = blockIdx.y;
+    if (w.meta[c].status != CKPT_OK) return;
+    const int64_t wpc = waves_per_chain(n);
+    const int64_t per = (wpc + kReduceBlocks - 1) / kReduceBlocks;
+    const int64_t lo = (int64_t)blockIdx.x * per;
+    const int64_t hi = lo + per < wpc ? lo + per : wpc;
+    const Partial *src = w.partial + c * wpc;
+    int64_t cost = kInf, s = kInf;
+#pragma unroll 4
+    for (int64_t t = lo + threadIdx.x; t < hi; t += 256) {
+        const Partial p = src[t];
+        if (p.cost < cost || (p.cost == cost && p.s < s)) { cost = p.cost; s = p.s; }
+    }
+    wave_min_pair(cost, s);
+    if ((threadIdx.x & (kWave - 1)) == 0) part[threadIdx.x / kWave] = Partial{cost, s};
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        Partial best = part[0];
+        for (int k = 1; k < 4; ++k)
+            if (part[k].cost < best.cost || (part[k].cost == best.cost && part[k].s < best.s)) best = part[k];
+        w.partial2[c * kReduceBlocks + blockIdx.x] = best;
+    }
+}
+
 // ---- epilogue --------------------------------------------------------------------
 
 __global__ __launch_bounds__(kWave) void cubic_epilogue_kernel(int n, size_t lds_bytes, int64_t cstride,
@@ -695,9 +744,12 @@ __global__ __launch_bounds__(kWave) void cubic_epilogue_kernel(int n, size_t lds
         return;
     }
     const int64_t wpc = waves_per_chain(n);
+    const bool folded = wpc > kReduceFrom;
+    const Partial *src = folded ? w.partial2 + c * kReduceBlocks : w.partial + c * wpc;
+    const int64_t count = folded ? kReduceBlocks : wpc;
     int64_t cost = kInf, s = kInf;
-    for (int64_t t = lane; t < wpc; t += kWave) {
-        const Partial p = w.partial[c * wpc + t];
+    for (int64_t t = lane; t < count; t += kWave) {
+        const Partial p = src[t];
         if (p.cost < cost || (p.cost == cost && p.s < s)) { cost = p.cost; s = p.s; }
     }
     wave_min_pair(cost, s);
@@ -744,7 +796,8 @@ size_t cubic_workspace_bytes(int64_t batch, int n)
 {
     const size_t n1 = (size_t)n + 1, B = (size_t)batch, wpc = (size_t)waves_per_chain(n);
     return align_up(B * sizeof(ChainMeta)) + align_up(B * table_len(n) * sizeof(PD<int64_t>)) +
-           align_up(B * wpc * sizeof(Partial)) + align_up(B * wpc * 8) + align_up(B * n1 * 4) + 256;
+           align_up(B * wpc * sizeof(Partial)) + align_up(B * wpc * 8) +
+           align_up(B * kReduceBlocks * sizeof(Partial)) + align_up(B * n1 * 4) + 256;
 }
 
 hipError_t launch_solve_cubic(const int64_t *d, int64_t batch, int n, Strides st, uint8_t *mask_out,
@@ -765,6 +818,8 @@ hipError_t launch_solve_cubic(const int64_t *d, int64_t batch, int n, Strides st
     launch_budgets<int64_t, 16, 256>(n, batch, w, stream);
     const unsigned over_grid = (unsigned)(n_words < 4096 ? n_words : 4096);
     hipLaunchKernelGGL(cubic_overflow_kernel, dim3(over_grid), dim3(kWave), table_lds, stream, n, n_words, w);
+    if (waves_per_chain(n) > kReduceFrom)
+        hipLaunchKernelGGL(cubic_reduce_kernel, dim3(kReduceBlocks, (unsigned)batch), dim3(256), 0, stream, n, w);
     // the epilogue takes as much LDS as the queue form of the predecessor pass wants, up to 64 KiB
     size_t epi_lds = queue_pred_bytes<int64_t>(n);
     if (epi_lds > 65536) epi_lds = queue_pred_bytes<int32_t>(n);
