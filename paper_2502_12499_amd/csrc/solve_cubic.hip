@@ -292,7 +292,6 @@ __global__ __launch_bounds__(BLOCK) void cubic_budgets_kernel(int n, int64_t blo
     V holeF = kLow, holeOld = kHigh, holeNew = kLow;  // no hole
     uint64_t hole_lanes = 0;                          // lanes with a live hole (wave-uniform)
     bool over = false;
-    uint32_t over_bits = 0;  // the assembly cell keeps the flag as a word
     V Fprev = pd[1].d + hF;  // F(1) = d_1 + F(0)
 
     // One cell: insert h = j-1 (value Fprev, key Pj1 + s), expire, F(j) = d_j + head.
@@ -515,7 +514,6 @@ __global__ __launch_bounds__(BLOCK) void cubic_budgets_kernel(int n, int64_t blo
     for (int j0 = kCells; j0 < last_full; j0 += kCells) chunk(j0, false);
     if (last_full >= kCells && last_full <= n) chunk(last_full, true);
 
-    over |= over_bits != 0;
 #if CKPT_CUBIC_ASM_CELL
     if constexpr (sizeof(V) == 4) over |= ((over_lanes >> (tid & (kWave - 1))) & 1) != 0;
 #endif
@@ -660,32 +658,41 @@ extern __shared__ __align__(16) unsigned char dyn_lds[];
 __global__ __launch_bounds__(kWave) void cubic_overflow_kernel(int n, int64_t n_words, CubicWs w)
 {
     const int64_t wpc = waves_per_chain(n);
-    for (int64_t word = blockIdx.x; word < n_words; word += gridDim.x) {
-        const int64_t c = word / wpc;
-        const int64_t base = (word % wpc) * kWave;
-        const ChainMeta meta = w.meta[c];
-        if (meta.status != CKPT_OK) continue;  // its flag words were never written
-        uint64_t flag = w.flags[word];
-        if (flag == 0) continue;
-        Partial best = w.partial[word];
-        while (flag) {
-            const int bit = __ffsll((unsigned long long)flag) - 1;
-            flag &= flag - 1;
-            int64_t s64, cost;
-            if (meta.mode32) {
-                const PD<int32_t> *pd = chain_table<int32_t>(w, c, n);
-                const int32_t s = budget_value<int32_t>(pd, base + bit, n);
-                s64 = s;
-                cost = s64 + wave_budget_table<int32_t>(pd, n, s, (int32_t *)dyn_lds, nullptr);
-            } else {
-                const PD<int64_t> *pd = chain_table<int64_t>(w, c, n);
-                s64 = budget_value<int64_t>(pd, base + bit, n);
-                cost = s64 + wave_budget_table<int64_t>(pd, n, s64, (int64_t *)dyn_lds, nullptr);
+    const int lane = threadIdx.x;
+    // 64 flag words are looked at per step, one per lane; flagged ones are then
+    // taken one at a time by the whole wave
+    for (int64_t w0 = (int64_t)blockIdx.x * kWave; w0 < n_words; w0 += (int64_t)gridDim.x * kWave) {
+        uint64_t mine = 0;
+        if (w0 + lane < n_words && w.meta[(w0 + lane) / wpc].status == CKPT_OK) mine = w.flags[w0 + lane];
+        uint64_t pending = __builtin_amdgcn_ballot_w64(mine != 0);  // chains in error never wrote their words
+        while (pending) {
+            const int src = __ffsll((unsigned long long)pending) - 1;
+            pending &= pending - 1;
+            const int64_t word = w0 + src;
+            uint64_t flag = (uint64_t)shfl_i64((int64_t)mine, src);
+            const int64_t c = word / wpc;
+            const int64_t base = (word % wpc) * kWave;
+            const ChainMeta meta = w.meta[c];
+            Partial best = w.partial[word];
+            while (flag) {
+                const int bit = __ffsll((unsigned long long)flag) - 1;
+                flag &= flag - 1;
+                int64_t s64, cost;
+                if (meta.mode32) {
+                    const PD<int32_t> *pd = chain_table<int32_t>(w, c, n);
+                    const int32_t s = budget_value<int32_t>(pd, base + bit, n);
+                    s64 = s;
+                    cost = s64 + wave_budget_table<int32_t>(pd, n, s, (int32_t *)dyn_lds, nullptr);
+                } else {
+                    const PD<int64_t> *pd = chain_table<int64_t>(w, c, n);
+                    s64 = budget_value<int64_t>(pd, base + bit, n);
+                    cost = s64 + wave_budget_table<int64_t>(pd, n, s64, (int64_t *)dyn_lds, nullptr);
+                }
+                if (cost < best.cost || (cost == best.cost && s64 < best.s)) best = Partial{cost, s64};
+                __syncthreads();
             }
-            if (cost < best.cost || (cost == best.cost && s64 < best.s)) best = Partial{cost, s64};
-            __syncthreads();
+            if (lane == 0) w.partial[word] = best;
         }
-        if (threadIdx.x == 0) w.partial[word] = best;
     }
 }
 
@@ -816,7 +823,8 @@ hipError_t launch_solve_cubic(const int64_t *d, int64_t batch, int n, Strides st
                        st.chain, st.pos, w);
     launch_budgets<int32_t, 8, 256>(n, batch, w, stream);
     launch_budgets<int64_t, 16, 256>(n, batch, w, stream);
-    const unsigned over_grid = (unsigned)(n_words < 4096 ? n_words : 4096);
+    const int64_t word_groups = (n_words + kWave - 1) / kWave;
+    const unsigned over_grid = (unsigned)(word_groups < 4096 ? word_groups : 4096);
     hipLaunchKernelGGL(cubic_overflow_kernel, dim3(over_grid), dim3(kWave), table_lds, stream, n, n_words, w);
     if (waves_per_chain(n) > kReduceFrom)
         hipLaunchKernelGGL(cubic_reduce_kernel, dim3(kReduceBlocks, (unsigned)batch), dim3(256), 0, stream, n, w);
