@@ -41,6 +41,8 @@
 //             per-wave partial results (the smallest optimal budget value s*),
 //             then F_{s*} again with the smallest minimal predecessor recorded
 //             for every j, and the walk back from n that writes the mask.
+#include <hipcub/hipcub.hpp>
+
 #include <limits>
 
 #include "ckpt_internal.h"
@@ -76,9 +78,41 @@ struct alignas(2 * sizeof(V)) PD {
     V d;  // d_j
 };
 
+// What cell j = t+1 of a 32-bit chain consumes about position t, and the links
+// of the monotone stack of sizes: below(t) is the nearest earlier position with
+// a strictly smaller size (-1: none), depth(t) the length of the chain
+// t, below(t), below(below(t)), ...  That chain is the set of positions h <= t
+// with d_h < d_h' for every h' in (h, t]: what a monotone queue of the values
+// d_h + const would hold after position t.
+constexpr int kSnap = 8;  // chain elements per snapshot
+struct alignas(16) El {
+    int32_t P;      // P[t]
+    int32_t d;      // d_t
+    int32_t below;  // the chain element kSnap places below t, the snapshot's last (-1: the chain is shorter)
+    int32_t depth;
+};
+// What every cell reads about its position
+struct alignas(8) Step {
+    int32_t d;      // d_t
+    int32_t under;  // depth(t) - 1: the depth the size stack drops to before t goes on it
+};
+// (P[h], d_h) of the kSnap elements of t's chain that follow t itself; zeros past its end
+struct alignas(64) Snap {
+    PD<int32_t> e[kSnap];
+};
+
 struct CubicWs {
     ChainMeta *meta;      // [batch]
     char *pd;             // [batch][table_len(n)] of PD<int64_t> (PD<int32_t> in the same bytes when mode32)
+    El *el;               // [batch][table_len(n)], 32-bit chains only
+    Snap *snap;           // [batch][table_len(n)], 32-bit chains only
+    Step *step;           // [batch][step_len(n)], 32-bit chains only
+    int32_t *budgets;     // [batch][K] budget values in enumeration order (zeros for other chains) ...
+    int32_t *sorted;      // ... and in ascending order per chain: lane i of wave w takes sorted[w*64 + i]
+    int32_t *redo_count;  // number of waves whose ring was too small ...
+    int64_t *redo;        // [batch * waves_per_chain] ... and their slots, for a second run with a larger ring
+    void *sort_tmp;       // scratch of the sort
+    size_t sort_tmp_bytes;
     Partial *partial;     // [batch][waves_per_chain]
     uint64_t *flags;      // [batch][waves_per_chain] lanes to recompute
     Partial *partial2;    // [batch][kReduceBlocks] second-level partial results (long chains only)
@@ -89,10 +123,52 @@ __host__ __device__ inline int64_t num_budgets(int n) { return (int64_t)n * (n -
 __host__ __device__ inline int64_t waves_per_chain(int n) { return (num_budgets(n) + kWave - 1) / kWave; }
 __host__ __device__ inline size_t table_len(int n) { return ((size_t)n + 1 + kPad + kCells - 1) / kCells * kCells; }
 
+__host__ __device__ inline size_t step_len(int n) { return table_len(n) + 32; }  // read up to two blocks of 16 past n
+
 template <typename V>
 __device__ inline const PD<V> *chain_table(const CubicWs &w, int64_t c, int n)
 {
     return (const PD<V> *)(w.pd + (size_t)c * table_len(n) * sizeof(PD<int64_t>));
+}
+
+// ---- sorting the budget values ---------------------------------------------------
+//
+// Lanes of a wave that hold nearly equal budgets see the same head leave at the
+// same cell, so the rare part of a cell runs once for all of them.
+
+struct SegmentStart {
+    int64_t K;
+    __host__ __device__ int operator()(int c) const { return (int)(c * K); }
+};
+typedef hipcub::TransformInputIterator<int, SegmentStart, hipcub::CountingInputIterator<int>> SegmentIter;
+
+// chains sorted per call: the segmented sort counts items in an int
+__host__ inline int64_t sort_chains_per_call(int64_t batch, int n)
+{
+    const int64_t fit = 0x7fffffffLL / num_budgets(n);
+    return fit < 1 ? 0 : (fit < batch ? fit : batch);
+}
+
+// Sorts chains [0, chains) of `in` into `out`, or with tmp == nullptr only sets tmp_bytes.
+__host__ inline hipError_t sort_budgets(void *tmp, size_t &tmp_bytes, const int32_t *in, int32_t *out,
+                                         int64_t chains, int n, hipStream_t stream)
+{
+    const int64_t K = num_budgets(n);
+    if (chains == 1) return hipcub::DeviceRadixSort::SortKeys(tmp, tmp_bytes, in, out, (int)K, 0, 31, stream);
+    const SegmentIter begin(hipcub::CountingInputIterator<int>(0), SegmentStart{K});
+    const SegmentIter end(hipcub::CountingInputIterator<int>(1), SegmentStart{K});
+    return hipcub::DeviceSegmentedRadixSort::SortKeys(tmp, tmp_bytes, in, out, (int)(chains * K), (int)chains, begin,
+                                                      end, 0, 31, stream);
+}
+
+__host__ inline size_t sort_tmp_bytes(int64_t batch, int n)
+{
+    const int64_t per = sort_chains_per_call(batch, n);
+    if (per == 0) return 0;
+    size_t a = 0, b = 0;
+    (void)sort_budgets(nullptr, a, nullptr, nullptr, per, n, nullptr);
+    if (batch % per) (void)sort_budgets(nullptr, b, nullptr, nullptr, batch % per, n, nullptr);
+    return a > b ? a : b;
 }
 
 __host__ CubicWs carve_cubic(void *ws, int64_t batch, int n)
@@ -102,6 +178,15 @@ __host__ CubicWs carve_cubic(void *ws, int64_t batch, int n)
     CubicWs w;
     w.meta = (ChainMeta *)p;    p += align_up(B * sizeof(ChainMeta));
     w.pd = p;                   p += align_up(B * table_len(n) * sizeof(PD<int64_t>));
+    w.el = (El *)p;             p += align_up(B * table_len(n) * sizeof(El));
+    w.snap = (Snap *)p;         p += align_up(B * table_len(n) * sizeof(Snap));
+    w.step = (Step *)p;         p += align_up(B * step_len(n) * sizeof(Step));
+    w.budgets = (int32_t *)p;   p += align_up(B * (size_t)num_budgets(n) * 4);
+    w.sorted = (int32_t *)p;    p += align_up(B * (size_t)num_budgets(n) * 4);
+    w.redo_count = (int32_t *)p; p += 256;
+    w.redo = (int64_t *)p;      p += align_up(B * wpc * 8);
+    w.sort_tmp_bytes = sort_tmp_bytes(batch, n);
+    w.sort_tmp = p;             p += align_up(w.sort_tmp_bytes);
     w.partial = (Partial *)p;   p += align_up(B * wpc * sizeof(Partial));
     w.flags = (uint64_t *)p;    p += align_up(B * wpc * 8);
     w.partial2 = (Partial *)p;  p += align_up(B * kReduceBlocks * sizeof(Partial));
@@ -136,6 +221,7 @@ __global__ __launch_bounds__(kWave) void cubic_prologue_kernel(const int64_t *__
 {
     const int64_t c = blockIdx.x;
     const int lane = threadIdx.x;
+    if (c == 0 && lane == 0) *w.redo_count = 0;
     const int64_t *dp = d + c * cstride;
     const int n1 = n + 1;
     const int chunk = (n1 + kWave - 1) / kWave;
@@ -207,6 +293,138 @@ __global__ __launch_bounds__(kWave) void cubic_prologue_kernel(const int64_t *__
         else
             pd64[k] = PD<int64_t>{(int64_t)(last >> meta.shift), 0};
     }
+}
+
+// ---- links of the monotone stack of sizes (32-bit chains) ---------------------------
+
+extern __shared__ __align__(16) unsigned char dyn_lds[];
+
+constexpr int kLinksBlock = 1024;
+
+__host__ __device__ inline size_t links_lds_bytes(int n) { return ((size_t)n + 2) * 10 + 16; }
+
+// One workgroup per chain.  below(t) comes from a stack pass over 64 contiguous
+// pieces (one per lane of the first wave) and, for the positions whose answer
+// lies in an earlier piece, a search through the pieces' minima and final
+// stacks; depth(t) from below(t) by pointer jumping; then every position's
+// snapshot.  LDS: 10 bytes per position.
+__global__ __launch_bounds__(kLinksBlock) void cubic_links_kernel(int n, CubicWs w)
+{
+    const int64_t c = blockIdx.x;
+    const ChainMeta meta = w.meta[c];
+    if (meta.status != CKPT_OK || !meta.mode32) return;
+    const int tid = threadIdx.x;
+    const int n1 = n + 1;
+    const PD<int32_t> *__restrict__ pd = chain_table<int32_t>(w, c, n);
+    El *__restrict__ el = w.el + (size_t)c * table_len(n);
+    Snap *__restrict__ snap = w.snap + (size_t)c * table_len(n);
+
+    // link[t] = (jump << 16) | dist: jump is a position further down t's chain (n1: past its
+    // end), dist the number of chain elements from t (inclusive) to jump (exclusive)
+    uint32_t *link = (uint32_t *)dyn_lds;              // [n1 + 1]
+    int32_t *dl = (int32_t *)(link + n1 + 1);          // [n1] the sizes
+    uint16_t *stk = (uint16_t *)(dl + n1);             // [n1 + 1] the pieces' stacks, later below(t)
+    __shared__ int32_t piece_min[kWave];                // smallest size of each piece
+    __shared__ int32_t pieces_min[kWave];               // ... of pieces 0..q
+    __shared__ int32_t piece_sp[kWave];                 // final stack height of each piece
+    const uint32_t kEnd = (uint32_t)n1;
+
+    for (int t = tid; t < n1; t += kLinksBlock) dl[t] = pd[t].d;
+    __syncthreads();
+
+    const int piece = (n1 + kWave - 1) / kWave;
+    const int k0 = min(tid * piece, n1), k1 = min(k0 + piece, n1);
+    if (tid < kWave) {
+        // pass 1: stack pass inside the piece (top of the stack mirrored in registers)
+        int sp = 0;
+        int32_t top_d = 0, low = INT32_MAX;
+        for (int t = k0; t < k1; ++t) {
+            const int32_t x = dl[t];
+            while (sp > 0 && top_d >= x) {
+                --sp;
+                if (sp > 0) top_d = dl[stk[k0 + sp - 1]];
+            }
+            link[t] = ((sp > 0 ? (uint32_t)stk[k0 + sp - 1] : kEnd) << 16) | 1u;  // kEnd for now: not in this piece
+            stk[k0 + sp] = (uint16_t)t;
+            ++sp;
+            top_d = x;
+            low = x < low ? x : low;
+        }
+        piece_min[tid] = low;
+        piece_sp[tid] = sp;
+    }
+    __syncthreads();
+    if (tid == 0) {
+        int32_t run = INT32_MAX;
+        for (int q = 0; q < kWave; ++q) {
+            run = piece_min[q] < run ? piece_min[q] : run;
+            pieces_min[q] = run;
+        }
+        link[n1] = kEnd << 16;
+    }
+    __syncthreads();
+    if (tid < kWave) {
+        // pass 2: positions with nothing smaller before them in their own piece (their sizes
+        // do not increase, so the piece that answers only moves towards the front)
+        int q = tid - 1;
+        for (int t = k0; t < k1; ++t) {
+            if ((link[t] >> 16) != kEnd) continue;
+            const int32_t x = dl[t];
+            if (q < 0 || pieces_min[q] >= x) break;  // nothing smaller anywhere before; the same holds for the rest
+            while (piece_min[q] >= x) --q;           // stops: pieces_min[q] < x
+            const int q0 = min(q * piece, n1);
+            int h = piece_sp[q] - 1;                 // topmost stack entry below x; the bottom one is the piece's minimum
+            while (dl[stk[q0 + h]] >= x) --h;
+            link[t] = ((uint32_t)stk[q0 + h] << 16) | 1u;
+        }
+    }
+    __syncthreads();
+    // below(t) is final; it replaces the stacks
+    for (int t = tid; t <= n1; t += kLinksBlock) stk[t] = (uint16_t)(link[t] >> 16);  // link[n1] points at itself
+    uint16_t *below = stk;
+    __syncthreads();
+
+    // depth by pointer jumping, in place: every update keeps "dist = elements from t to jump"
+    // (a word is read and written whole, so any mix of old and new words is consistent)
+    for (;;) {
+        int moved = 0;
+        for (int t = tid; t < n1; t += kLinksBlock) {
+            const uint32_t a = link[t];
+            if ((a >> 16) == kEnd) continue;
+            const uint32_t b = link[a >> 16];
+            link[t] = (b & 0xffff0000u) | ((a & 0xffffu) + (b & 0xffffu));
+            moved = 1;
+        }
+        if (!__syncthreads_or(moved)) break;
+    }
+
+    for (int t = tid; t < (int)table_len(n); t += kLinksBlock) {
+        El e;
+        Snap sn;
+        if (t < n1) {
+            uint32_t h = (uint32_t)t;
+#pragma unroll
+            for (int k = 0; k < kSnap; ++k) {
+                h = below[h];  // below[kEnd] is kEnd
+                const bool in = h != kEnd;
+                sn.e[k].P = in ? pd[h + 1].P : 0;
+                sn.e[k].d = in ? dl[h] : 0;
+            }
+            e.P = pd[t + 1].P;
+            e.d = dl[t];
+            e.below = h == kEnd ? -1 : (int32_t)h;
+            e.depth = (int32_t)(link[t] & 0xffffu);
+        } else {
+#pragma unroll
+            for (int k = 0; k < kSnap; ++k) sn.e[k] = PD<int32_t>{0, 0};
+            e.P = pd[n1].P; e.d = 0; e.below = -1; e.depth = 1;
+        }
+        el[t] = e;
+        snap[t] = sn;
+    }
+    Step *__restrict__ st = w.step + (size_t)c * step_len(n);
+    for (int t = tid; t < (int)step_len(n); t += kLinksBlock)
+        st[t] = t < n1 ? Step{dl[t], (int32_t)(link[t] & 0xffffu) - 1} : Step{0, 0};
 }
 
 // ---- budget index -> (range length, start) ------------------------------------
@@ -537,6 +755,410 @@ void launch_budgets(int n, int64_t batch, CubicWs w, hipStream_t stream)
                        dim3(BLOCK), 0, stream, n, blocks_per_chain, w);
 }
 
+// ---- budget values of the 32-bit chains, in enumeration order ------------------------------
+__global__ __launch_bounds__(256) void cubic_values_kernel(int n, int64_t blocks_per_chain, CubicWs w)
+{
+    const int64_t c = blockIdx.x / blocks_per_chain;
+    const int64_t idx = (blockIdx.x % blocks_per_chain) * 256 + threadIdx.x;
+    const int64_t K = num_budgets(n);
+    if (idx >= K) return;
+    const ChainMeta meta = w.meta[c];
+    int32_t s = 0;
+    if (meta.status == CKPT_OK && meta.mode32) s = budget_value<int32_t>(chain_table<int32_t>(w, c, n), idx, n);
+    w.budgets[c * K + idx] = s;
+}
+
+// ---- budgets kernel for 32-bit chains: the queue's shared part factored out -------------
+//
+// F_s(j) = d_j + m with m the head's value, and m changes only when the head
+// leaves the window.  Between two such changes every value a lane inserts is
+// d_h + m with the same m, so which of them survive at the tail does not depend
+// on the lane: they are the chain t, below(t), .. of the size stack (El), cut
+// off at the depth the stack had when the lane's head last changed, or has
+// dropped to since (`base`).  A lane therefore stores nothing while its head
+// stays.  When the head leaves, the lane writes that implicit part of its queue
+// out to its ring (values d_h + m with the old m: they no longer compare like
+// their sizes against what comes next), takes the new head from the ring's
+// bottom, and starts an empty implicit part.  Entries in the ring are dropped
+// from the top by the usual comparison with the incoming value; if the implicit
+// part is not empty that comparison is false by itself (its bottom entry is
+// below the incoming value and above everything in the ring).
+// Per cell: one add (F), one min (base), two compares; the rest is rare.
+// A value that is the same in every lane, moved to scalar registers so that the
+// arithmetic that follows runs on the scalar unit.
+__device__ inline int32_t uniform(int32_t v) { return __builtin_amdgcn_readfirstlane(v); }
+__device__ inline int64_t uniform(int64_t v)
+{
+    const uint32_t lo = (uint32_t)__builtin_amdgcn_readfirstlane((int32_t)(uint32_t)v);
+    const uint32_t hi = (uint32_t)__builtin_amdgcn_readfirstlane((int32_t)(uint32_t)((uint64_t)v >> 32));
+    return (int64_t)(((uint64_t)hi << 32) | lo);
+}
+
+// Reads of the per-chain tables at a wave-uniform index, through the constant
+// address space: they then go through the scalar unit whatever the compiler can
+// or cannot prove about stores in between.  (The tables are written by an
+// earlier kernel and only read here.)
+typedef int32_t i32x2 __attribute__((ext_vector_type(2)));
+typedef int32_t i32x4 __attribute__((ext_vector_type(4)));
+typedef int32_t i32x16 __attribute__((ext_vector_type(16)));
+#define CKPT_CONST_AS __attribute__((address_space(4)))
+__device__ inline Step uniform_load(const Step *p, int i)
+{
+    const i32x2 v = ((const CKPT_CONST_AS i32x2 *)p)[i];
+    return Step{v.x, v.y};
+}
+__device__ inline El uniform_load(const El *p, int i)
+{
+    const i32x4 v = ((const CKPT_CONST_AS i32x4 *)p)[i];
+    return El{v.x, v.y, v.z, v.w};
+}
+__device__ inline Snap uniform_load(const Snap *p, int i)
+{
+    const i32x16 v = ((const CKPT_CONST_AS i32x16 *)p)[i];
+    Snap s;
+#pragma unroll
+    for (int k = 0; k < kSnap; ++k) s.e[k] = PD<int32_t>{v[2 * k], v[2 * k + 1]};
+    return s;
+}
+
+struct SharedLane {
+    uint32_t hd, tl;   // the ring holds the written-out entries above the head at positions (hd, tl]
+    int32_t hF, hK;    // the head: its value, its key P[h] + s
+    int32_t X;         // value of the ring's top entry (kLow: the ring is empty)
+    int32_t base;      // stack depth below the implicit part
+    uint32_t over;     // the ring was too small at some point: the lane's result is not to be used
+};
+
+// The rare part of a cell, kept out of line so that the unrolled cells stay
+// short: drop ring entries not below the incoming value Y, and if the head has
+// left the window write the implicit entries out and take the new head.
+// t, P = P[t], depth = depth(t) describe the position being inserted; every
+// lane of the wave calls this together.
+template <int RING, int BLOCK>
+__device__ __attribute__((noinline)) SharedLane shared_rare(SharedLane L, const uint32_t lane_base, const int32_t s,
+                                                            const El *el, const Snap *snap, const int t_in,
+                                                            const int32_t P_in, const int32_t depth_in,
+                                                            const int32_t Y, bool pop, const bool gone)
+{
+    typedef int32_t V;
+    typedef __attribute__((address_space(3))) V *LdsPtr;
+    constexpr V kLow = std::numeric_limits<V>::min();
+    constexpr uint32_t kStep = (uint32_t)(BLOCK * sizeof(QueueEntry<V>));
+    constexpr uint32_t kSlotMask = (uint32_t)(RING - 1) * kStep;
+    auto slot = [&](uint32_t pos) -> LdsPtr { return (LdsPtr)(uintptr_t)((pos & kSlotMask) | lane_base); };
+    // arguments arrive in vector registers; these are the same in every lane
+    el = (const El *)uniform((int64_t)(uintptr_t)el);
+    snap = (const Snap *)uniform((int64_t)(uintptr_t)snap);
+    const int t = __builtin_amdgcn_readfirstlane(t_in);
+    const int32_t P = __builtin_amdgcn_readfirstlane(P_in);
+    const int32_t depth = __builtin_amdgcn_readfirstlane(depth_in);
+
+    while (__builtin_amdgcn_ballot_w64(pop) != 0) {
+        if (pop) {
+            L.tl -= kStep;
+            L.X = L.tl != L.hd ? slot(L.tl)[0] : kLow;
+            pop = L.X >= Y;
+        }
+    }
+    if (__builtin_amdgcn_ballot_w64(gone) == 0) return L;
+    // the head has left: write the implicit entries out, top (this position) first
+    const int32_t count = gone ? depth - L.base : 0;
+    const V m_old = L.hF;
+    uint32_t wp = L.tl + (uint32_t)count * kStep;
+    if (gone) {
+        L.over |= (wp - L.hd) > (uint32_t)RING * kStep;
+        L.tl = wp;
+        L.base = depth;
+        L.X = Y;
+    }
+    if (gone) {
+        LdsPtr p = slot(wp);
+        p[0] = Y;
+        p[1] = P;
+        wp -= kStep;
+    }
+    int at = t;
+    for (int k0 = 1; __builtin_amdgcn_ballot_w64(k0 < count) != 0; k0 += kSnap) {
+        const Snap sn = uniform_load(snap, at);
+        const int next = uniform_load(el, at).below;
+#pragma unroll
+        for (int u = 0; u < kSnap; ++u) {
+            if (__builtin_amdgcn_ballot_w64(k0 + u < count) == 0) break;
+            if (k0 + u < count) {
+                LdsPtr p = slot(wp);
+                p[0] = sn.e[u].d + m_old;
+                p[1] = sn.e[u].P;
+                wp -= kStep;
+            }
+        }
+        at = next > 0 ? next : 0;
+    }
+    // new head: the lowest entry still inside the window (the top one always is)
+    bool seek = gone;
+    while (__builtin_amdgcn_ballot_w64(seek) != 0) {
+        if (seek) {
+            L.hd += kStep;
+            LdsPtr p = slot(L.hd);
+            L.hF = p[0];
+            L.hK = p[1] + s;
+            seek = (P > L.hK) & (L.hd != L.tl);
+        }
+    }
+    if (gone && L.hd == L.tl) L.X = kLow;
+    return L;
+}
+
+// With REDO the workgroups (one wave each) take the waves listed in w.redo
+// instead of the waves of their own index.
+template <int RING, int BLOCK, bool REDO>
+__global__ __launch_bounds__(BLOCK) void cubic_shared_kernel(int n, int64_t blocks_per_chain, CubicWs w)
+{
+    typedef int32_t V;
+    __shared__ __attribute__((aligned(RING * BLOCK * 8))) QueueEntry<V> ring[RING][BLOCK];
+    constexpr V kLow = std::numeric_limits<V>::min();
+    static_assert((BLOCK & (BLOCK - 1)) == 0 && (RING & (RING - 1)) == 0, "power-of-two ring");
+    static_assert(!REDO || BLOCK == kWave, "the list is taken one wave at a time");
+
+    const int64_t items = REDO ? *w.redo_count : 1;
+    for (int64_t item = REDO ? blockIdx.x : 0; item < items; item += REDO ? gridDim.x : 1) {
+    const int64_t listed = REDO ? w.redo[item] : 0;
+    const int64_t c = REDO ? listed / waves_per_chain(n) : blockIdx.x / blocks_per_chain;
+    const int64_t tile = REDO ? listed % waves_per_chain(n) : blockIdx.x % blocks_per_chain;
+    const ChainMeta meta = w.meta[c];
+    if (meta.status != CKPT_OK || !meta.mode32) continue;
+
+    const int tid = threadIdx.x;
+    const El *__restrict__ el = w.el + (size_t)c * table_len(n);
+    const Snap *__restrict__ snap = w.snap + (size_t)c * table_len(n);
+    const Step *__restrict__ st = w.step + (size_t)c * step_len(n);
+    const int64_t K = num_budgets(n);
+    const int64_t idx = tile * BLOCK + tid;
+    const int64_t wave_in_chain = idx / kWave;
+    if (wave_in_chain * kWave >= K) continue;
+    const bool live = idx < K;
+    const V s = live ? w.sorted[c * K + idx] : 0;
+
+    typedef __attribute__((address_space(3))) V *LdsPtr;
+    const uint32_t lane_base = (uint32_t)(uintptr_t)(LdsPtr)&ring[0][tid].F;
+
+    SharedLane L;
+    L.hd = 0; L.tl = 0;
+    L.hF = el[0].d; L.hK = el[0].P + s; L.X = kLow;
+    L.base = 1;  // the chain of position 0 is the head itself
+    L.over = 0;
+    V P = el[0].P;  // P[t], carried along on the scalar unit
+
+    // cell t + 1: insert position t (implicitly), drop ring entries, check the head
+#if CKPT_CUBIC_ASM_CELL
+    // Written out: 4 vector instructions when nothing happens; the rare part is
+    // the same as shared_rare, with the wave's exec mask narrowed to the lanes
+    // concerned.  t = t0 + u with u a literal, so that nothing is computed for the
+    // rare part until it runs.  s84..s99 receive a snapshot.
+    constexpr uint32_t kStep = (uint32_t)(BLOCK * sizeof(QueueEntry<V>));
+    constexpr uint32_t kSlotMask = (uint32_t)(RING - 1) * kStep;
+    constexpr int kShift = __builtin_ctz(kStep);
+    const uint32_t snap_lo = (uint32_t)(uintptr_t)snap, snap_hi = (uint32_t)((uintptr_t)snap >> 32);
+    const uint32_t el_lo = (uint32_t)(uintptr_t)el, el_hi = (uint32_t)((uintptr_t)el >> 32);
+    const uint64_t snap_base = ((uint64_t)snap_hi << 32) | snap_lo, el_base = ((uint64_t)el_hi << 32) | el_lo;
+    const V vLow = kLow;
+#define CKPT_SNAP_STEP(PREG, DREG)                         \
+    "v_cmp_lt_u32 vcc, %[sK], %[cnt]\n\t"                   \
+    "s_cbranch_vccz Lmat_done_%=\n\t"                       \
+    "s_mov_b64 exec, vcc\n\t"                               \
+    "v_add_u32 %[f], " DREG ", %[m]\n\t"                    \
+    "v_mov_b32 %[k], " PREG "\n\t"                          \
+    "v_and_or_b32 %[ad], %[wp], %[mask], %[lo]\n\t"         \
+    "ds_write2_b32 %[ad], %[f], %[k] offset1:1\n\t"         \
+    "v_subrev_u32 %[wp], %[step], %[wp]\n\t"                \
+    "s_add_u32 %[sK], %[sK], 1\n\t"
+#define CKPT_SHARED_CELL(T0, U, E)                                                                        \
+    {                                                                                                     \
+        P += (E).d;                                                                                       \
+        V Y;                                                                                              \
+        uint32_t ad, f, k, cnt, wp, m, sK, sOff, sNext;                                                   \
+        uint64_t sv0, sgone, st;                                                                          \
+        asm volatile( \
+            "v_add_u32 %[Y], %[sd], %[hF]\n\t" \
+            "v_min_i32 %[base], %[su], %[base]\n\t" \
+            "v_cmp_ge_i32 vcc, %[X], %[Y]\n\t" \
+            "v_cmp_gt_i32 %[sgone], %[sP], %[hK]\n\t" \
+            "s_or_b64 %[st], vcc, %[sgone]\n\t" \
+            "s_cbranch_scc0 Lend_%=\n\t" \
+            /* ---- rare.  If a head has left, ask for the snapshot of t now. */ \
+            "s_cmp_eq_u64 %[sgone], 0\n\t" \
+            "s_cbranch_scc1 Lpop_%=\n\t" \
+            "s_add_u32 %[sOff], %[t0], %[u]\n\t" \
+            "s_lshl_b32 %[sNext], %[sOff], 6\n\t" \
+            "s_load_dwordx16 s[84:99], %[snapb], %[sNext]\n\t" \
+            "s_lshl_b32 %[sOff], %[sOff], 4\n\t" \
+            "s_add_u32 %[sOff], %[sOff], 8\n\t" \
+            "s_load_dword %[sNext], %[elb], %[sOff]\n\t" \
+            /* ---- ring entries not below the incoming value go */ \
+            "Lpop_%=:\n\t" \
+            "s_cbranch_vccz Lpop_done_%=\n\t" \
+            "s_and_saveexec_b64 %[sv0], vcc\n\t" \
+            "v_subrev_u32 %[tl], %[step], %[tl]\n\t" \
+            "v_and_or_b32 %[ad], %[tl], %[mask], %[lo]\n\t" \
+            "v_cmp_ne_u32 vcc, %[tl], %[hd]\n\t" \
+            "v_mov_b32 %[X], %[vLow]\n\t" \
+            "s_and_b64 exec, exec, vcc\n\t" \
+            "ds_read_b32 %[X], %[ad]\n\t" \
+            "s_waitcnt lgkmcnt(0)\n\t" \
+            "s_mov_b64 exec, %[sv0]\n\t" \
+            "v_cmp_ge_i32 vcc, %[X], %[Y]\n\t" \
+            "s_branch Lpop_%=\n\t" \
+            "Lpop_done_%=:\n\t" \
+            "s_cmp_eq_u64 %[sgone], 0\n\t" \
+            "s_cbranch_scc1 Lend_%=\n\t" \
+            /* ---- the head has left (lanes sgone): write the implicit entries out, top first */ \
+            "s_and_saveexec_b64 %[sv0], %[sgone]\n\t" \
+            "s_add_u32 %[sOff], %[su], 1\n\t" \
+            "v_sub_u32 %[cnt], %[sOff], %[base]\n\t" \
+            "v_mov_b32 %[base], %[sOff]\n\t" \
+            "v_mov_b32 %[m], %[hF]\n\t" \
+            "v_lshl_add_u32 %[tl], %[cnt], %[shift], %[tl]\n\t" \
+            "v_mov_b32 %[X], %[Y]\n\t" \
+            "v_sub_u32 %[f], %[tl], %[hd]\n\t" \
+            "v_cmp_lt_u32 vcc, %[cap], %[f]\n\t" \
+            "v_cndmask_b32_e64 %[over], %[over], 1, vcc\n\t" \
+            "v_mov_b32 %[k], %[sP]\n\t" \
+            "v_and_or_b32 %[ad], %[tl], %[mask], %[lo]\n\t" \
+            "ds_write2_b32 %[ad], %[Y], %[k] offset1:1\n\t" \
+            "v_subrev_u32 %[wp], %[step], %[tl]\n\t" \
+            "v_cmp_lt_u32 vcc, 1, %[cnt]\n\t" \
+            "s_cbranch_vccz Lmat_done_%=\n\t" \
+            "s_mov_b32 %[sK], 1\n\t" \
+            "Lgroup_%=:\n\t" \
+            "s_waitcnt lgkmcnt(0)\n\t" \
+            CKPT_SNAP_STEP("s84", "s85") CKPT_SNAP_STEP("s86", "s87") CKPT_SNAP_STEP("s88", "s89") \
+            CKPT_SNAP_STEP("s90", "s91") CKPT_SNAP_STEP("s92", "s93") CKPT_SNAP_STEP("s94", "s95") \
+            CKPT_SNAP_STEP("s96", "s97") CKPT_SNAP_STEP("s98", "s99") \
+            "v_cmp_lt_u32 vcc, %[sK], %[cnt]\n\t" \
+            "s_cbranch_vccz Lmat_done_%=\n\t" \
+            /* longer than a snapshot: go on with the snapshot of its last element */ \
+            "s_lshl_b32 %[sOff], %[sNext], 6\n\t" \
+            "s_load_dwordx16 s[84:99], %[snapb], %[sOff]\n\t" \
+            "s_lshl_b32 %[sOff], %[sNext], 4\n\t" \
+            "s_add_u32 %[sOff], %[sOff], 8\n\t" \
+            "s_load_dword %[sNext], %[elb], %[sOff]\n\t" \
+            "s_branch Lgroup_%=\n\t" \
+            "Lmat_done_%=:\n\t" \
+            "s_mov_b64 exec, %[sgone]\n\t" \
+            /* ---- new head: the lowest entry still inside the window (the top one always is) */ \
+            "Lseek_%=:\n\t" \
+            "v_add_u32 %[hd], %[step], %[hd]\n\t" \
+            "v_and_or_b32 %[ad], %[hd], %[mask], %[lo]\n\t" \
+            "ds_read_b32 %[hF], %[ad]\n\t" \
+            "ds_read_b32 %[k], %[ad] offset:4\n\t" \
+            "s_waitcnt lgkmcnt(0)\n\t" \
+            "v_add_u32 %[hK], %[k], %[s]\n\t" \
+            "v_cmp_gt_i32 vcc, %[sP], %[hK]\n\t" \
+            "v_cmp_ne_u32 %[st], %[hd], %[tl]\n\t" \
+            "s_and_b64 vcc, vcc, %[st]\n\t" \
+            "s_cbranch_vccz Lseek_done_%=\n\t" \
+            "s_mov_b64 exec, vcc\n\t" \
+            "s_branch Lseek_%=\n\t" \
+            "Lseek_done_%=:\n\t" \
+            "s_mov_b64 exec, %[sgone]\n\t" \
+            "v_cmp_eq_u32 vcc, %[hd], %[tl]\n\t" \
+            "v_cndmask_b32 %[X], %[X], %[vLow], vcc\n\t" \
+            "s_mov_b64 exec, %[sv0]\n\t" \
+            "Lend_%=:\n\t" \
+            : [hd] "+v"(L.hd), [tl] "+v"(L.tl), [hF] "+v"(L.hF), [hK] "+v"(L.hK), [X] "+v"(L.X), [base] "+v"(L.base), \
+              [over] "+v"(L.over), [Y] "=&v"(Y), [ad] "=&v"(ad), [f] "=&v"(f), [k] "=&v"(k), [cnt] "=&v"(cnt), \
+              [wp] "=&v"(wp), [m] "=&v"(m), [sK] "=&s"(sK), [sOff] "=&s"(sOff), [sNext] "=&s"(sNext), [sv0] "=&s"(sv0), \
+              [sgone] "=&s"(sgone), [st] "=&s"(st) \
+            : [sd] "s"((E).d), [su] "s"((E).under), [sP] "s"(P), [t0] "s"(T0), [u] "i"(U), \
+              [snapb] "s"(snap_base), [elb] "s"(el_base), [lo] "v"(lane_base), [s] "v"(s), [vLow] "v"(vLow), \
+              [mask] "s"(kSlotMask), [step] "i"(kStep), [shift] "i"(kShift), [cap] "i"(RING * kStep) \
+            : "vcc", "scc", "memory", "s84", "s85", "s86", "s87", "s88", "s89", "s90", "s91", "s92", "s93", "s94", "s95", \
+              "s96", "s97", "s98", "s99"); \
+    }
+#else
+#define CKPT_SHARED_CELL(T0, U, E)                                                                    \
+    {                                                                                                 \
+        P += (E).d;                                                                                   \
+        const V Y = (E).d + L.hF; /* F(t) */                                                          \
+        L.base = L.base < (E).under ? L.base : (E).under;                                             \
+        const bool pop = L.X >= Y;                                                                    \
+        const bool gone = P > L.hK;                                                                   \
+        if (__builtin_amdgcn_ballot_w64(pop | gone) != 0)                                             \
+            L = shared_rare<RING, BLOCK>(L, lane_base, s, el, snap, (T0) + (U), P, (E).under + 1, Y, pop, gone); \
+    }
+#endif
+
+    // The (d, depth) stream is read a block of kBlockCells positions ahead; two
+    // register sets take turns, so nothing is copied.
+    constexpr int kBlockCells = 8;
+    Step A[kBlockCells], B[kBlockCells];
+#define CKPT_GUARDED_CELL(U)                                         \
+    if (!guarded || (t0 + (U) >= 1 && t0 + (U) <= n - 1)) CKPT_SHARED_CELL(t0, U, cur[U])
+    auto block = [&](Step(&cur)[kBlockCells], Step(&ahead)[kBlockCells], const int t0, const bool guarded) {
+        // Scalar loads return in any order, so waiting for this block's data also
+        // waits for whatever else is in flight: make that wait happen here, before
+        // the next block's loads are issued, not after.
+        asm volatile("" : : "s"(cur[0].d), "s"(cur[kBlockCells - 1].under) : "memory");
+#pragma unroll
+        for (int u = 0; u < kBlockCells; ++u) ahead[u] = uniform_load(st, t0 + kBlockCells + u);
+        CKPT_GUARDED_CELL(0) CKPT_GUARDED_CELL(1) CKPT_GUARDED_CELL(2) CKPT_GUARDED_CELL(3)
+        CKPT_GUARDED_CELL(4) CKPT_GUARDED_CELL(5) CKPT_GUARDED_CELL(6) CKPT_GUARDED_CELL(7)
+        static_assert(kBlockCells == 8, "eight cells are written out");
+    };
+#undef CKPT_GUARDED_CELL
+#undef CKPT_SHARED_CELL
+#undef CKPT_SNAP_STEP
+#pragma unroll
+    for (int u = 0; u < kBlockCells; ++u) A[u] = uniform_load(st, u);
+    // blocks [kBlockCells, last_full) lie inside 1..n-1
+    const int last_full = n / kBlockCells * kBlockCells;
+    block(A, B, 0, true);
+    int t0 = kBlockCells;
+    for (; t0 + kBlockCells < last_full; t0 += 2 * kBlockCells) {
+        block(B, A, t0, false);
+        block(A, B, t0 + kBlockCells, false);
+    }
+    // here the next block's data is in B; at most one more full block and the tail remain
+    if (t0 < last_full) {
+        block(B, A, t0, false);
+        t0 += kBlockCells;
+        if (t0 <= n - 1) block(A, B, t0, true);
+    } else if (t0 <= n - 1) {
+        block(B, A, t0, true);
+    }
+    const V Fn = el[n].d + L.hF;
+    const bool over = L.over != 0;
+
+    const bool redo = live && over;
+    const uint64_t flag = __ballot(redo);
+    int64_t cost = (live && !over) ? (int64_t)s + (int64_t)Fn : kInf;
+    int64_t sv = (int64_t)s;
+    wave_min_pair(cost, sv);
+    if ((tid & (kWave - 1)) == 0) {
+        const int64_t slot_id = c * waves_per_chain(n) + wave_in_chain;
+        w.partial[slot_id] = Partial{cost, sv};
+        w.flags[slot_id] = flag;
+        if (!REDO && flag != 0) w.redo[atomicAdd(w.redo_count, 1)] = slot_id;
+    }
+    }
+}
+
+constexpr int kRedoBlocks = 2048;
+
+// First all waves with a ring of RING entries per lane, then the waves in which
+// it was too small again with kRedoRing entries; lanes flagged after that are
+// left to the wave-per-budget kernel.
+template <int RING, int BLOCK, int REDO_RING>
+void launch_shared(int n, int64_t batch, CubicWs w, hipStream_t stream)
+{
+    const int64_t blocks_per_chain = (num_budgets(n) + BLOCK - 1) / BLOCK;
+    hipLaunchKernelGGL((cubic_shared_kernel<RING, BLOCK, false>), dim3((unsigned)(blocks_per_chain * batch)),
+                       dim3(BLOCK), 0, stream, n, blocks_per_chain, w);
+    const int64_t waves = waves_per_chain(n) * batch;
+    hipLaunchKernelGGL((cubic_shared_kernel<REDO_RING, kWave, true>),
+                       dim3((unsigned)(waves < kRedoBlocks ? waves : kRedoBlocks)), dim3(kWave), 0, stream, n,
+                       blocks_per_chain, w);
+}
+
 // ---- one budget per wave ---------------------------------------------------------
 
 // F_s(0..n) into LDS array F by a wave reduction over each window; returns
@@ -568,16 +1190,6 @@ __device__ V wave_budget_table(const PD<V> *__restrict__ pd, int n, V s, V *F, i
         __syncthreads();
     }
     return last;
-}
-
-// A value that is the same in every lane, moved to scalar registers so that the
-// arithmetic that follows runs on the scalar unit.
-__device__ inline int32_t uniform(int32_t v) { return __builtin_amdgcn_readfirstlane(v); }
-__device__ inline int64_t uniform(int64_t v)
-{
-    const uint32_t lo = (uint32_t)__builtin_amdgcn_readfirstlane((int32_t)(uint32_t)v);
-    const uint32_t hi = (uint32_t)__builtin_amdgcn_readfirstlane((int32_t)(uint32_t)((uint64_t)v >> 32));
-    return (int64_t)(((uint64_t)hi << 32) | lo);
 }
 
 // Bytes of LDS that queue_budget_pred needs for a chain of n layers.
@@ -653,8 +1265,6 @@ __device__ void queue_budget_pred(const PD<V> *__restrict__ pd, int n, V s_in, u
     __syncthreads();
 }
 
-extern __shared__ __align__(16) unsigned char dyn_lds[];
-
 __global__ __launch_bounds__(kWave) void cubic_overflow_kernel(int n, int64_t n_words, CubicWs w)
 {
     const int64_t wpc = waves_per_chain(n);
@@ -680,7 +1290,7 @@ __global__ __launch_bounds__(kWave) void cubic_overflow_kernel(int n, int64_t n_
                 int64_t s64, cost;
                 if (meta.mode32) {
                     const PD<int32_t> *pd = chain_table<int32_t>(w, c, n);
-                    const int32_t s = budget_value<int32_t>(pd, base + bit, n);
+                    const int32_t s = w.sorted[c * num_budgets(n) + base + bit];
                     s64 = s;
                     cost = s64 + wave_budget_table<int32_t>(pd, n, s, (int32_t *)dyn_lds, nullptr);
                 } else {
@@ -803,6 +1413,9 @@ size_t cubic_workspace_bytes(int64_t batch, int n)
 {
     const size_t n1 = (size_t)n + 1, B = (size_t)batch, wpc = (size_t)waves_per_chain(n);
     return align_up(B * sizeof(ChainMeta)) + align_up(B * table_len(n) * sizeof(PD<int64_t>)) +
+           align_up(B * table_len(n) * sizeof(El)) + align_up(B * table_len(n) * sizeof(Snap)) +
+           align_up(B * step_len(n) * sizeof(Step)) + 2 * align_up(B * (size_t)num_budgets(n) * 4) +
+           align_up(sort_tmp_bytes(batch, n)) + 256 + align_up(B * wpc * 8) +
            align_up(B * wpc * sizeof(Partial)) + align_up(B * wpc * 8) +
            align_up(B * kReduceBlocks * sizeof(Partial)) + align_up(B * n1 * 4) + 256;
 }
@@ -814,14 +1427,32 @@ hipError_t launch_solve_cubic(const int64_t *d, int64_t batch, int n, Strides st
     if (batch == 0) return hipSuccess;
     CubicWs w = carve_cubic(ws, batch, n);
     const int64_t K = num_budgets(n);
-    const int64_t total_blocks = (K + 255) / 256 * batch;
+    const int64_t total_blocks = (K + 127) / 128 * batch;
     const int64_t n_words = waves_per_chain(n) * batch;
     if (total_blocks > 0x7fffffffLL) return hipErrorInvalidConfiguration;
     const size_t table_lds = ((size_t)n + 1) * 8;
 
     hipLaunchKernelGGL(cubic_prologue_kernel, dim3((unsigned)batch), dim3(kWave), 0, stream, d, batch, n,
                        st.chain, st.pos, w);
-    launch_budgets<int32_t, 8, 256>(n, batch, w, stream);
+    if (links_lds_bytes(n) > 65536) {  // beyond the default limit for dynamic LDS
+        const hipError_t e = hipFuncSetAttribute((const void *)cubic_links_kernel,
+                                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)links_lds_bytes(n));
+        if (e != hipSuccess) return e;
+    }
+    hipLaunchKernelGGL(cubic_links_kernel, dim3((unsigned)batch), dim3(kLinksBlock), links_lds_bytes(n), stream, n, w);
+    {
+        const int64_t vblocks = (K + 255) / 256;
+        hipLaunchKernelGGL(cubic_values_kernel, dim3((unsigned)(vblocks * batch)), dim3(256), 0, stream, n, vblocks, w);
+        const int64_t per = sort_chains_per_call(batch, n);
+        if (per == 0) return hipErrorInvalidConfiguration;
+        for (int64_t c0 = 0; c0 < batch; c0 += per) {
+            size_t bytes = w.sort_tmp_bytes;
+            const int64_t chains = batch - c0 < per ? batch - c0 : per;
+            const hipError_t e = sort_budgets(w.sort_tmp, bytes, w.budgets + c0 * K, w.sorted + c0 * K, chains, n, stream);
+            if (e != hipSuccess) return e;
+        }
+    }
+    launch_shared<16, 256, 64>(n, batch, w, stream);
     launch_budgets<int64_t, 16, 256>(n, batch, w, stream);
     const int64_t word_groups = (n_words + kWave - 1) / kWave;
     const unsigned over_grid = (unsigned)(word_groups < 4096 ? word_groups : 4096);
