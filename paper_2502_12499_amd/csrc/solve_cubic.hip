@@ -1074,6 +1074,169 @@ __global__ __launch_bounds__(BLOCK) void cubic_shared_kernel(int n, int64_t bloc
             : "vcc", "scc", "memory", "s84", "s85", "s86", "s87", "s88", "s89", "s90", "s91", "s92", "s93", "s94", "s95", \
               "s96", "s97", "s98", "s99"); \
     }
+    // ---- the unguarded middle of the chain as one loop in assembly ------------------
+    // Sixteen cells per round from two register sets (s[36:51], s[52:67]: eight
+    // (d, under) pairs each) that are loaded in turn one set ahead.  A cell is
+    //     P += d;  base = min(base, under);  pop = d <= Xr;  gone = P > hK
+    // with Xr = X - hF (so that F(t) = d + hF need not be formed to compare it),
+    // and falls through unless some lane pops or has lost its head; the rare parts
+    // of the sixteen cells sit behind the loop and jump back.
+    // Fixed registers: v80 Y, v81 address, v82/v83 entry, v84 count, v85 write
+    // position, v86 old head value; s[68:83] snapshot, s[84:85] stream address,
+    // s[86:87] saved exec, s[88:89] lanes whose head left, s[90:91] scratch mask,
+    // s92 element counter, s93 offset, s94 next snapshot's position, s95 t of the
+    // round's first cell, s96 rounds left.
+#define SH_FAST(D, U, TAG)                                   \
+    "s_add_u32 %[P], %[P], " D "\n\t"                        \
+    "v_min_i32 %[base], " U ", %[base]\n\t"                  \
+    "v_cmp_le_i32 vcc, " D ", %[Xr]\n\t"                     \
+    "v_cmp_gt_i32 s[88:89], %[P], %[hK]\n\t"                 \
+    "s_or_b64 s[90:91], vcc, s[88:89]\n\t"                   \
+    "s_cbranch_scc1 Lrare_" TAG "_%=\n\t"                    \
+    "Lback_" TAG "_%=:\n\t"
+#define SH_SNAP_STEP(PREG, DREG, TAG)                        \
+    "v_cmp_lt_u32 vcc, s92, v84\n\t"                         \
+    "s_cbranch_vccz Lmat_done_" TAG "_%=\n\t"                \
+    "s_mov_b64 exec, vcc\n\t"                                \
+    "v_add_u32 v82, " DREG ", v86\n\t"                       \
+    "v_mov_b32 v83, " PREG "\n\t"                            \
+    "v_and_or_b32 v81, v85, %[mask], %[lo]\n\t"              \
+    "ds_write2_b32 v81, v82, v83 offset1:1\n\t"              \
+    "v_subrev_u32 v85, %[step], v85\n\t"                     \
+    "s_add_u32 s92, s92, 1\n\t"
+#define SH_RARE(D, U, TAG, TOFF)                             \
+    "Lrare_" TAG "_%=:\n\t"                                  \
+    "v_add_u32 v80, " D ", %[hF]\n\t"                        \
+    "s_cmp_eq_u64 s[88:89], 0\n\t"                           \
+    "s_cbranch_scc1 Lpop_" TAG "_%=\n\t"                     \
+    "s_add_u32 s93, s95, " TOFF "\n\t"                       \
+    "s_lshl_b32 s94, s93, 6\n\t"                             \
+    "s_load_dwordx16 s[68:83], %[snapb], s94\n\t"            \
+    "s_lshl_b32 s93, s93, 4\n\t"                             \
+    "s_add_u32 s93, s93, 8\n\t"                              \
+    "s_load_dword s94, %[elb], s93\n\t"                      \
+    /* ring entries not below the incoming value go */       \
+    "Lpop_" TAG "_%=:\n\t"                                   \
+    "s_cbranch_vccz Lpop_done_" TAG "_%=\n\t"                \
+    "s_and_saveexec_b64 s[86:87], vcc\n\t"                   \
+    "v_subrev_u32 %[tl], %[step], %[tl]\n\t"                 \
+    "v_and_or_b32 v81, %[tl], %[mask], %[lo]\n\t"            \
+    "v_cmp_ne_u32 vcc, %[tl], %[hd]\n\t"                     \
+    "v_mov_b32 %[X], %[vLow]\n\t"                            \
+    "s_and_b64 exec, exec, vcc\n\t"                          \
+    "ds_read_b32 %[X], v81\n\t"                              \
+    "s_waitcnt lgkmcnt(0)\n\t"                               \
+    "s_mov_b64 exec, s[86:87]\n\t"                           \
+    "v_cmp_ge_i32 vcc, %[X], v80\n\t"                        \
+    "s_branch Lpop_" TAG "_%=\n\t"                           \
+    "Lpop_done_" TAG "_%=:\n\t"                              \
+    "s_cmp_eq_u64 s[88:89], 0\n\t"                           \
+    "s_cbranch_scc1 Lfin_" TAG "_%=\n\t"                     \
+    /* the head has left (lanes s[88:89]): write the implicit entries out, top first */ \
+    "s_and_saveexec_b64 s[86:87], s[88:89]\n\t"              \
+    "s_add_u32 s93, " U ", 1\n\t"                            \
+    "v_sub_u32 v84, s93, %[base]\n\t"                        \
+    "v_mov_b32 %[base], s93\n\t"                             \
+    "v_mov_b32 v86, %[hF]\n\t"                               \
+    "v_lshl_add_u32 %[tl], v84, %[shift], %[tl]\n\t"         \
+    "v_mov_b32 %[X], v80\n\t"                                \
+    "v_sub_u32 v82, %[tl], %[hd]\n\t"                        \
+    "v_cmp_lt_u32 vcc, %[cap], v82\n\t"                      \
+    "v_cndmask_b32_e64 %[over], %[over], 1, vcc\n\t"         \
+    "v_mov_b32 v83, %[P]\n\t"                                \
+    "v_and_or_b32 v81, %[tl], %[mask], %[lo]\n\t"            \
+    "ds_write2_b32 v81, v80, v83 offset1:1\n\t"              \
+    "v_subrev_u32 v85, %[step], %[tl]\n\t"                   \
+    "v_cmp_lt_u32 vcc, 1, v84\n\t"                           \
+    "s_cbranch_vccz Lmat_done_" TAG "_%=\n\t"                \
+    "s_mov_b32 s92, 1\n\t"                                   \
+    "Lgroup_" TAG "_%=:\n\t"                                 \
+    "s_waitcnt lgkmcnt(0)\n\t"                               \
+    SH_SNAP_STEP("s68", "s69", TAG) SH_SNAP_STEP("s70", "s71", TAG) SH_SNAP_STEP("s72", "s73", TAG) \
+    SH_SNAP_STEP("s74", "s75", TAG) SH_SNAP_STEP("s76", "s77", TAG) SH_SNAP_STEP("s78", "s79", TAG) \
+    SH_SNAP_STEP("s80", "s81", TAG) SH_SNAP_STEP("s82", "s83", TAG) \
+    "v_cmp_lt_u32 vcc, s92, v84\n\t"                         \
+    "s_cbranch_vccz Lmat_done_" TAG "_%=\n\t"                \
+    /* longer than a snapshot: go on with the snapshot of its last element */ \
+    "s_lshl_b32 s93, s94, 6\n\t"                             \
+    "s_load_dwordx16 s[68:83], %[snapb], s93\n\t"            \
+    "s_lshl_b32 s93, s94, 4\n\t"                             \
+    "s_add_u32 s93, s93, 8\n\t"                              \
+    "s_load_dword s94, %[elb], s93\n\t"                      \
+    "s_branch Lgroup_" TAG "_%=\n\t"                         \
+    "Lmat_done_" TAG "_%=:\n\t"                              \
+    "s_mov_b64 exec, s[88:89]\n\t"                           \
+    /* new head: the lowest entry still inside the window (the top one always is) */ \
+    "Lseek_" TAG "_%=:\n\t"                                  \
+    "v_add_u32 %[hd], %[step], %[hd]\n\t"                    \
+    "v_and_or_b32 v81, %[hd], %[mask], %[lo]\n\t"            \
+    "ds_read_b32 %[hF], v81\n\t"                             \
+    "ds_read_b32 v83, v81 offset:4\n\t"                      \
+    "s_waitcnt lgkmcnt(0)\n\t"                               \
+    "v_add_u32 %[hK], v83, %[s]\n\t"                         \
+    "v_cmp_gt_i32 vcc, %[P], %[hK]\n\t"                      \
+    "v_cmp_ne_u32 s[90:91], %[hd], %[tl]\n\t"                \
+    "s_and_b64 vcc, vcc, s[90:91]\n\t"                       \
+    "s_cbranch_vccz Lseek_done_" TAG "_%=\n\t"               \
+    "s_mov_b64 exec, vcc\n\t"                                \
+    "s_branch Lseek_" TAG "_%=\n\t"                          \
+    "Lseek_done_" TAG "_%=:\n\t"                             \
+    "s_mov_b64 exec, s[86:87]\n\t"                           \
+    /* every lane: the top entry's value again, relative to the head's; none if the ring is empty */ \
+    "Lfin_" TAG "_%=:\n\t"                                   \
+    "v_cmp_eq_u32 vcc, %[hd], %[tl]\n\t"                     \
+    "v_sub_u32 %[Xr], %[X], %[hF]\n\t"                       \
+    "v_cndmask_b32 %[X], %[X], %[vLow], vcc\n\t"             \
+    "v_cndmask_b32 %[Xr], %[Xr], %[vLow], vcc\n\t"           \
+    "s_branch Lback_" TAG "_%=\n\t"
+    auto middle = [&](const int t_first, const int rounds) {
+        V Xr = L.hd == L.tl ? kLow : L.X - L.hF;
+        const uint64_t stream = (uint64_t)(uintptr_t)(st + t_first);
+        asm volatile(
+            "s_mov_b64 s[84:85], %[stream]\n\t"
+            "s_mov_b32 s95, %[t_first]\n\t"
+            "s_mov_b32 s96, %[rounds]\n\t"
+            "s_load_dwordx16 s[36:51], s[84:85], 0x0\n\t"
+            "Lround_%=:\n\t"
+            "s_waitcnt lgkmcnt(0)\n\t"
+            "s_load_dwordx16 s[52:67], s[84:85], 0x40\n\t"
+            SH_FAST("s36", "s37", "a0") SH_FAST("s38", "s39", "a1") SH_FAST("s40", "s41", "a2")
+            SH_FAST("s42", "s43", "a3") SH_FAST("s44", "s45", "a4") SH_FAST("s46", "s47", "a5")
+            SH_FAST("s48", "s49", "a6") SH_FAST("s50", "s51", "a7")
+            "s_waitcnt lgkmcnt(0)\n\t"
+            "s_load_dwordx16 s[36:51], s[84:85], 0x80\n\t"
+            SH_FAST("s52", "s53", "b0") SH_FAST("s54", "s55", "b1") SH_FAST("s56", "s57", "b2")
+            SH_FAST("s58", "s59", "b3") SH_FAST("s60", "s61", "b4") SH_FAST("s62", "s63", "b5")
+            SH_FAST("s64", "s65", "b6") SH_FAST("s66", "s67", "b7")
+            "s_add_u32 s84, s84, 0x80\n\t"
+            "s_addc_u32 s85, s85, 0\n\t"
+            "s_add_u32 s95, s95, 16\n\t"
+            "s_sub_u32 s96, s96, 1\n\t"
+            "s_cmp_lg_u32 s96, 0\n\t"
+            "s_cbranch_scc1 Lround_%=\n\t"
+            "s_waitcnt lgkmcnt(0)\n\t"
+            "s_branch Lexit_%=\n\t"
+            SH_RARE("s36", "s37", "a0", "0") SH_RARE("s38", "s39", "a1", "1") SH_RARE("s40", "s41", "a2", "2")
+            SH_RARE("s42", "s43", "a3", "3") SH_RARE("s44", "s45", "a4", "4") SH_RARE("s46", "s47", "a5", "5")
+            SH_RARE("s48", "s49", "a6", "6") SH_RARE("s50", "s51", "a7", "7")
+            SH_RARE("s52", "s53", "b0", "8") SH_RARE("s54", "s55", "b1", "9") SH_RARE("s56", "s57", "b2", "10")
+            SH_RARE("s58", "s59", "b3", "11") SH_RARE("s60", "s61", "b4", "12") SH_RARE("s62", "s63", "b5", "13")
+            SH_RARE("s64", "s65", "b6", "14") SH_RARE("s66", "s67", "b7", "15")
+            "Lexit_%=:\n\t"
+            : [hd] "+v"(L.hd), [tl] "+v"(L.tl), [hF] "+v"(L.hF), [hK] "+v"(L.hK), [X] "+v"(L.X), [Xr] "+v"(Xr),
+              [base] "+v"(L.base), [over] "+v"(L.over), [P] "+s"(P)
+            : [stream] "s"(stream), [t_first] "s"(t_first), [rounds] "s"(rounds), [snapb] "s"(snap_base),
+              [elb] "s"(el_base), [lo] "v"(lane_base), [s] "v"(s), [vLow] "v"(vLow), [mask] "s"(kSlotMask),
+              [step] "i"(kStep), [shift] "i"(kShift), [cap] "i"(RING * kStep)
+            : "vcc", "scc", "memory", "v80", "v81", "v82", "v83", "v84", "v85", "v86", "s36", "s37", "s38", "s39", "s40",
+              "s41", "s42", "s43", "s44", "s45", "s46", "s47", "s48", "s49", "s50", "s51", "s52", "s53", "s54", "s55",
+              "s56", "s57", "s58", "s59", "s60", "s61", "s62", "s63", "s64", "s65", "s66", "s67", "s68", "s69", "s70",
+              "s71", "s72", "s73", "s74", "s75", "s76", "s77", "s78", "s79", "s80", "s81", "s82", "s83", "s84", "s85",
+              "s86", "s87", "s88", "s89", "s90", "s91", "s92", "s93", "s94", "s95", "s96");
+    };
+#undef SH_FAST
+#undef SH_SNAP_STEP
+#undef SH_RARE
 #else
 #define CKPT_SHARED_CELL(T0, U, E)                                                                    \
     {                                                                                                 \
@@ -1113,6 +1276,15 @@ __global__ __launch_bounds__(BLOCK) void cubic_shared_kernel(int n, int64_t bloc
     const int last_full = n / kBlockCells * kBlockCells;
     block(A, B, 0, true);
     int t0 = kBlockCells;
+#if CKPT_CUBIC_ASM_CELL
+    if (last_full - t0 >= 16) {
+        const int rounds = (last_full - t0) / 16;
+        middle(t0, rounds);
+        t0 += 16 * rounds;
+#pragma unroll
+        for (int u = 0; u < kBlockCells; ++u) B[u] = uniform_load(st, t0 + u);
+    }
+#endif
     for (; t0 + kBlockCells < last_full; t0 += 2 * kBlockCells) {
         block(B, A, t0, false);
         block(A, B, t0 + kBlockCells, false);
