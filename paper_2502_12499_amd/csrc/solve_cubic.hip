@@ -506,7 +506,7 @@ __global__ __launch_bounds__(BLOCK) void cubic_budgets_kernel(int n, int64_t blo
     // mirrored in registers.  It starts as {h = 0}.
     uint32_t hd = 0, tl = 0;
     V hF = pd[0].d, hK = pd[1].P + s, tF = hF;
-    store_entry(0, hF, (CKPT_CUBIC_ASM_CELL && sizeof(V) == 4) ? pd[1].P : hK);  // the assembly cell stores raw keys
+    store_entry(0, hF, hK);
     V holeF = kLow, holeOld = kHigh, holeNew = kLow;  // no hole
     uint64_t hole_lanes = 0;                          // lanes with a live hole (wave-uniform)
     bool over = false;
@@ -564,153 +564,7 @@ __global__ __launch_bounds__(BLOCK) void cubic_budgets_kernel(int n, int64_t blo
         Fprev = dj + hF;
     };
 
-#if CKPT_CUBIC_ASM_CELL
-    // The same cell for 32-bit values, written out: 6 vector instructions when
-    // nothing is dropped, 3 more per dropped entry (the compiler's lowering of the
-    // generic form costs about three times as many).  Differences in bookkeeping:
-    //  - ring keys are the raw P[h]; the head's key is kept in a register as
-    //    P[h] + s (hK), and the hole keys are raw too;
-    //  - "ring full" is "the next slot is the head's slot" (hdA = its LDS address);
-    //  - the value register and the tail mirror swap roles every cell: after the
-    //    store the tail mirror IS the stored value, so the new F(j) is written
-    //    over the old mirror and the names are exchanged (free in straight-line
-    //    code), except for lanes that could not store.
-    V vLow = kLow, vHigh = kHigh;
-    uint32_t hdA = lane_base;
-    // hole state of the assembly cell: smallest hole value (kHigh: none), oldest
-    // and newest hole key plus s (kHigh / kLow: none); flagged lanes as a lane mask
-    V aF = kHigh, aOld = kHigh, aNew = kLow;
-    uint64_t over_lanes = 0;
-    auto cell_asm = [&](const int32_t Pj1, const int32_t dj) {
-        uint32_t ad, t0;
-        uint64_t sv, sfull, st;
-        asm volatile(
-            // ---- drop tails (X = tail mirror, Y = value to insert)
-            "Lpop_%=:\n\t"
-            "v_cmp_ge_i32 vcc, %[X], %[Y]\n\t"
-            "s_cbranch_vccz Lpop_done_%=\n\t"
-            "s_and_saveexec_b64 %[sv], vcc\n\t"
-            "v_subrev_u32 %[tl], %[step], %[tl]\n\t"
-            "v_and_or_b32 %[ad], %[tl], %[mask], %[lo]\n\t"
-            "ds_read_b32 %[X], %[ad]\n\t"
-            "s_mov_b64 exec, %[sv]\n\t"
-            "s_waitcnt lgkmcnt(0)\n\t"
-            "s_branch Lpop_%=\n\t"
-            "Lpop_done_%=:\n\t"
-            // ---- next slot; full ring or live hole anywhere in the wave?
-            "v_add_u32 %[tl], %[step], %[tl]\n\t"
-            "v_and_or_b32 %[ad], %[tl], %[mask], %[lo]\n\t"
-            "v_cmp_eq_u32 vcc, %[ad], %[hdA]\n\t"
-            "s_or_b64 %[st], vcc, %[hl]\n\t"
-            "s_cmp_lg_u64 %[st], 0\n\t"
-            "s_cbranch_scc1 Lslow_%=\n\t"
-            // ---- fast path: store, drop heads
-            "ds_write2_b32 %[ad], %[Y], %[P] offset1:1\n\t"
-            "Lexp_%=:\n\t"
-            "v_cmp_gt_i32 vcc, %[P], %[hK]\n\t"
-            "s_cbranch_vccz Ljoin_%=\n\t"
-            "s_and_saveexec_b64 %[sv], vcc\n\t"
-            "v_add_u32 %[hd], %[step], %[hd]\n\t"
-            "v_and_or_b32 %[hdA], %[hd], %[mask], %[lo]\n\t"
-            "ds_read_b32 %[hF], %[hdA]\n\t"
-            "ds_read_b32 %[hK], %[hdA] offset:4\n\t"
-            "s_waitcnt lgkmcnt(0)\n\t"
-            "v_add_u32 %[hK], %[hK], %[s]\n\t"
-            "s_mov_b64 exec, %[sv]\n\t"
-            "s_branch Lexp_%=\n\t"
-            // ---- some lane has a full ring (vcc) or a live hole
-            "Lslow_%=:\n\t"
-            "s_mov_b64 %[sfull], vcc\n\t"
-            // holes vanish when this value would have dropped them or they left the window
-            "v_cmp_le_i32 vcc, %[Y], %[oF]\n\t"
-            "v_cmp_gt_i32 %[st], %[P], %[oNew]\n\t"
-            "s_or_b64 vcc, vcc, %[st]\n\t"
-            "v_cndmask_b32 %[oF], %[oF], %[vHigh], vcc\n\t"
-            "v_cndmask_b32 %[oOld], %[oOld], %[vHigh], vcc\n\t"
-            "v_cndmask_b32 %[oNew], %[oNew], %[vLow], vcc\n\t"
-            "s_cmp_lg_u64 %[sfull], 0\n\t"
-            "s_cbranch_scc0 Lnofull_%=\n\t"
-            // -- full lanes: the value is not stored and becomes a hole
-            "v_add_u32 %[t0], %[P], %[s]\n\t"
-            "s_and_saveexec_b64 %[sv], %[sfull]\n\t"
-            "v_subrev_u32 %[tl], %[step], %[tl]\n\t"
-            "v_min_i32 %[oF], %[oF], %[Y]\n\t"
-            "v_min_i32 %[oOld], %[oOld], %[t0]\n\t"
-            "v_mov_b32 %[oNew], %[t0]\n\t"
-            "s_andn2_b64 exec, %[sv], %[sfull]\n\t"
-            "ds_write2_b32 %[ad], %[Y], %[P] offset1:1\n\t"
-            "s_mov_b64 exec, %[sv]\n\t"
-            "Lsexp_%=:\n\t"
-            "v_cmp_gt_i32 vcc, %[P], %[hK]\n\t"
-            "v_cmp_ne_u32 %[st], %[hd], %[tl]\n\t"
-            "s_and_b64 vcc, vcc, %[st]\n\t"
-            "s_cbranch_vccz Lsexp_done_%=\n\t"
-            "s_and_saveexec_b64 %[sv], vcc\n\t"
-            "v_add_u32 %[hd], %[step], %[hd]\n\t"
-            "v_and_or_b32 %[hdA], %[hd], %[mask], %[lo]\n\t"
-            "ds_read_b32 %[hF], %[hdA]\n\t"
-            "ds_read_b32 %[hK], %[hdA] offset:4\n\t"
-            "s_waitcnt lgkmcnt(0)\n\t"
-            "v_add_u32 %[hK], %[hK], %[s]\n\t"
-            "s_mov_b64 exec, %[sv]\n\t"
-            "s_branch Lsexp_%=\n\t"
-            "Lsexp_done_%=:\n\t"
-            // flag: nothing valid left, or the head passed the oldest hole
-            "v_cmp_gt_i32 vcc, %[P], %[hK]\n\t"
-            "s_or_b64 %[ov], %[ov], vcc\n\t"
-            "v_cmp_gt_i32 vcc, %[hK], %[oOld]\n\t"
-            "s_or_b64 %[ov], %[ov], vcc\n\t"
-            "v_cmp_ne_u32 %[hl], %[oOld], %[vHigh]\n\t"
-            // F(j) = d_j + head; lanes that could not store keep their tail mirror
-            "v_add_u32 %[t0], %[D], %[hF]\n\t"
-            "v_cndmask_b32 %[Y], %[Y], %[X], %[sfull]\n\t"
-            "v_mov_b32 %[X], %[t0]\n\t"
-            "s_branch Lend_%=\n\t"
-            // -- holes alive but every lane can store
-            "Lnofull_%=:\n\t"
-            "ds_write2_b32 %[ad], %[Y], %[P] offset1:1\n\t"
-            "Lhexp_%=:\n\t"
-            "v_cmp_gt_i32 vcc, %[P], %[hK]\n\t"
-            "s_cbranch_vccz Lhexp_done_%=\n\t"
-            "s_and_saveexec_b64 %[sv], vcc\n\t"
-            "v_add_u32 %[hd], %[step], %[hd]\n\t"
-            "v_and_or_b32 %[hdA], %[hd], %[mask], %[lo]\n\t"
-            "ds_read_b32 %[hF], %[hdA]\n\t"
-            "ds_read_b32 %[hK], %[hdA] offset:4\n\t"
-            "s_waitcnt lgkmcnt(0)\n\t"
-            "v_add_u32 %[hK], %[hK], %[s]\n\t"
-            "s_mov_b64 exec, %[sv]\n\t"
-            "s_branch Lhexp_%=\n\t"
-            "Lhexp_done_%=:\n\t"
-            "v_cmp_gt_i32 vcc, %[hK], %[oOld]\n\t"
-            "s_or_b64 %[ov], %[ov], vcc\n\t"
-            "v_cmp_ne_u32 %[hl], %[oOld], %[vHigh]\n\t"
-            // ---- F(j) = d_j + head, written over the old tail mirror
-            "Ljoin_%=:\n\t"
-            "v_add_u32 %[X], %[D], %[hF]\n\t"
-            "Lend_%=:\n\t"
-            : [tl] "+v"(tl), [hd] "+v"(hd), [hdA] "+v"(hdA), [X] "+v"(tF), [Y] "+v"(Fprev), [hF] "+v"(hF),
-              [hK] "+v"(hK), [oF] "+v"(aF), [oOld] "+v"(aOld), [oNew] "+v"(aNew), [ov] "+s"(over_lanes),
-              [hl] "+s"(hole_lanes), [ad] "=&v"(ad), [t0] "=&v"(t0), [sv] "=&s"(sv), [sfull] "=&s"(sfull),
-              [st] "=&s"(st)
-            : [P] "v"(Pj1), [D] "v"(dj), [s] "v"(s), [lo] "v"(lane_base), [mask] "s"(kSlotMask),
-              [vLow] "v"(vLow), [vHigh] "v"(vHigh), [step] "i"(kStep)
-            : "vcc", "scc", "memory");
-        // the registers have exchanged roles
-        const V t = tF;
-        tF = Fprev;
-        Fprev = t;
-    };
-#endif
-    auto cell = [&](const V Pj1, const V dj) {
-#if CKPT_CUBIC_ASM_CELL
-        if constexpr (sizeof(V) == 4) {
-            cell_asm(Pj1, dj);
-            return;
-        }
-#endif
-        cell_generic(Pj1, dj);
-    };
+    auto cell = [&](const V Pj1, const V dj) { cell_generic(Pj1, dj); };
 
     // pd[j] is fetched kCells cells ahead of its use
     PD<V> cur[kCells], ahead[kCells];
@@ -732,9 +586,6 @@ __global__ __launch_bounds__(BLOCK) void cubic_budgets_kernel(int n, int64_t blo
     for (int j0 = kCells; j0 < last_full; j0 += kCells) chunk(j0, false);
     if (last_full >= kCells && last_full <= n) chunk(last_full, true);
 
-#if CKPT_CUBIC_ASM_CELL
-    if constexpr (sizeof(V) == 4) over |= ((over_lanes >> (tid & (kWave - 1))) & 1) != 0;
-#endif
     const bool redo = live && over;
     const uint64_t flag = __ballot(redo);
     int64_t cost = (live && !over) ? (int64_t)s + (int64_t)Fprev : kInf;
@@ -807,6 +658,7 @@ __device__ inline Step uniform_load(const Step *p, int i)
     const i32x2 v = ((const CKPT_CONST_AS i32x2 *)p)[i];
     return Step{v.x, v.y};
 }
+#if !CKPT_CUBIC_ASM_CELL
 __device__ inline El uniform_load(const El *p, int i)
 {
     const i32x4 v = ((const CKPT_CONST_AS i32x4 *)p)[i];
@@ -820,6 +672,7 @@ __device__ inline Snap uniform_load(const Snap *p, int i)
     for (int k = 0; k < kSnap; ++k) s.e[k] = PD<int32_t>{v[2 * k], v[2 * k + 1]};
     return s;
 }
+#endif
 
 struct SharedLane {
     uint32_t hd, tl;   // the ring holds the written-out entries above the head at positions (hd, tl]
@@ -829,6 +682,7 @@ struct SharedLane {
     uint32_t over;     // the ring was too small at some point: the lane's result is not to be used
 };
 
+#if !CKPT_CUBIC_ASM_CELL
 // The rare part of a cell, kept out of line so that the unrolled cells stay
 // short: drop ring entries not below the incoming value Y, and if the head has
 // left the window write the implicit entries out and take the new head.
@@ -907,6 +761,7 @@ __device__ __attribute__((noinline)) SharedLane shared_rare(SharedLane L, const 
     if (gone && L.hd == L.tl) L.X = kLow;
     return L;
 }
+#endif
 
 // With REDO the workgroups (one wave each) take the waves listed in w.redo
 // instead of the waves of their own index.
@@ -1437,6 +1292,115 @@ __device__ void queue_budget_pred(const PD<V> *__restrict__ pd, int n, V s_in, u
     __syncthreads();
 }
 
+// Bytes of LDS that epoch_budget_pred needs for a chain of n layers, without and
+// with its own copy of the (P, d) table.
+template <typename V>
+__host__ __device__ inline size_t epoch_pred_bytes(int n, bool staged)
+{
+    return ((size_t)n + 2) * (sizeof(V) + 2 + (staged ? 2 * sizeof(V) : 0));
+}
+
+// Predecessors for one budget, a whole wave working on it.  While the head h of
+// the window stays inside it, F(j) = d_j + F(h) and the predecessor of j is h,
+// for every j at once; only when h leaves (cell e) is the new head looked for,
+// as the smallest index with minimal F in the window of e.  That is the
+// smallest minimal predecessor for every j until it leaves in turn: what
+// enters the window later is larger than the minimum, and what lies before it
+// is larger or gone.  STAGED: the (P, d) table is copied to LDS first, which
+// takes the memory latency out of the steps from one head to the next.  Gives
+// up (returns false) after `max_heads` heads; pred16[1..n] is then unset.
+template <typename V, bool STAGED>
+__device__ bool epoch_budget_pred(const PD<V> *__restrict__ pd, int n, V s_in, unsigned char *lds, int max_heads,
+                                  uint16_t *&pred16)
+{
+    const V s = uniform(s_in);
+    const int lane = threadIdx.x;
+    const int n1 = n + 1;
+    V *F = (V *)lds;                         // [n1]
+    V *Pl = F + n1;                          // [n1 + 1]: Pl[j] = P[j-1]
+    V *dl = Pl + n1 + 1;                     // [n1]
+    pred16 = STAGED ? (uint16_t *)(dl + n1) : (uint16_t *)(F + n1);
+    if (STAGED) {
+        for (int j = lane; j <= n1; j += kWave) {
+            const PD<V> x = pd[j];
+            Pl[j] = x.P;
+            if (j < n1) dl[j] = x.d;
+        }
+        __syncthreads();
+    }
+    auto P_at = [&](int j) -> V { return STAGED ? Pl[j] : pd[j].P; };  // P[j-1]
+    auto d_at = [&](int j) -> V { return STAGED ? dl[j] : pd[j].d; };
+    if (lane == 0) F[0] = d_at(0);
+    int h = 0, heads = 1;
+    V m = d_at(0);          // F(h)
+    V limit = P_at(1) + s;  // cells j with P[j-1] above this no longer see h
+    int t = 1;
+    while (t <= n) {
+        // cells t.. up to the first one that no longer sees h
+        int e = n1;
+        for (int j0 = t; j0 <= n; j0 += kWave) {
+            const int j = j0 + lane;
+            const int jc = j < n1 ? j : n;
+            const V xP = P_at(jc), xd = d_at(jc);
+            const uint64_t out = __builtin_amdgcn_ballot_w64(j <= n && xP > limit);
+            const int first = out ? j0 + (__ffsll((unsigned long long)out) - 1) : n1;
+            if (j <= n && j < first) {
+                F[j] = xd + m;
+                pred16[j] = (uint16_t)h;
+            }
+            if (out) {
+                e = first;
+                break;
+            }
+        }
+        if (e > n) break;
+        if (++heads > max_heads) return false;
+        __syncthreads();
+        // window of e: indices i in (h, e-1] with P[e-1] - P[i] <= s; its start is near h
+        const V Pe = P_at(e);
+        int l = e - 1;
+        for (int i0 = h + 1; i0 <= e - 1; i0 += kWave) {
+            const int i = i0 + lane;
+            const uint64_t in = __builtin_amdgcn_ballot_w64(i <= e - 1 && Pe - P_at((i < n ? i : n) + 1) <= s);
+            if (in) {
+                l = i0 + (__ffsll((unsigned long long)in) - 1);
+                break;
+            }
+        }
+        int64_t bv = kInf, bh = kInf;
+        for (int i = l + lane; i <= e - 1; i += kWave) {
+            const int64_t v = (int64_t)F[i];
+            if (v < bv) { bv = v; bh = i; }
+        }
+        wave_min_pair(bv, bh);
+        h = (int)bh;
+        m = (V)bv;
+        limit = P_at(h + 1) + s;
+        t = e;
+    }
+    __syncthreads();
+    return true;
+}
+
+// Tries the forms of the predecessor pass that fit the LDS granted to the kernel, fastest first.
+// Returns with pred16 (in LDS) set, or nullptr when the predecessors are in pred (in the workspace).
+template <typename V>
+__device__ void budget_pred(const PD<V> *__restrict__ pd, int n, V s, unsigned char *lds, size_t lds_bytes,
+                            int32_t *pred, uint16_t *&pred16)
+{
+    if (epoch_pred_bytes<V>(n, true) <= lds_bytes) {
+        if (epoch_budget_pred<V, true>(pd, n, s, lds, n / 16 + 8, pred16)) return;
+    } else if (epoch_pred_bytes<V>(n, false) <= lds_bytes) {
+        if (epoch_budget_pred<V, false>(pd, n, s, lds, n / 16 + 8, pred16)) return;
+    }
+    if (queue_pred_bytes<V>(n) <= lds_bytes) {
+        queue_budget_pred<V>(pd, n, s, lds, pred16);
+        return;
+    }
+    pred16 = nullptr;
+    wave_budget_table<V>(pd, n, s, (V *)lds, pred);
+}
+
 __global__ __launch_bounds__(kWave) void cubic_overflow_kernel(int n, int64_t n_words, CubicWs w)
 {
     const int64_t wpc = waves_per_chain(n);
@@ -1547,17 +1511,10 @@ __global__ __launch_bounds__(kWave) void cubic_epilogue_kernel(int n, size_t lds
     // the kernel, else the wave-per-window table
     int32_t *pred = w.pred + c * n1;
     uint16_t *pred16 = nullptr;
-    if (meta.mode32) {
-        if (queue_pred_bytes<int32_t>(n) <= lds_bytes)
-            queue_budget_pred<int32_t>(chain_table<int32_t>(w, c, n), n, (int32_t)s, dyn_lds, pred16);
-        else
-            wave_budget_table<int32_t>(chain_table<int32_t>(w, c, n), n, (int32_t)s, (int32_t *)dyn_lds, pred);
-    } else {
-        if (queue_pred_bytes<int64_t>(n) <= lds_bytes)
-            queue_budget_pred<int64_t>(chain_table<int64_t>(w, c, n), n, s, dyn_lds, pred16);
-        else
-            wave_budget_table<int64_t>(chain_table<int64_t>(w, c, n), n, s, (int64_t *)dyn_lds, pred);
-    }
+    if (meta.mode32)
+        budget_pred<int32_t>(chain_table<int32_t>(w, c, n), n, (int32_t)s, dyn_lds, lds_bytes, pred, pred16);
+    else
+        budget_pred<int64_t>(chain_table<int64_t>(w, c, n), n, s, dyn_lds, lds_bytes, pred, pred16);
 
     // the value table is no longer needed: its LDS (the first n+1 bytes, below
     // pred16) becomes the mark array
@@ -1631,10 +1588,13 @@ hipError_t launch_solve_cubic(const int64_t *d, int64_t batch, int n, Strides st
     hipLaunchKernelGGL(cubic_overflow_kernel, dim3(over_grid), dim3(kWave), table_lds, stream, n, n_words, w);
     if (waves_per_chain(n) > kReduceFrom)
         hipLaunchKernelGGL(cubic_reduce_kernel, dim3(kReduceBlocks, (unsigned)batch), dim3(256), 0, stream, n, w);
-    // the epilogue takes as much LDS as the queue form of the predecessor pass wants, up to 64 KiB
-    size_t epi_lds = queue_pred_bytes<int64_t>(n);
-    if (epi_lds > 65536) epi_lds = queue_pred_bytes<int32_t>(n);
-    if (epi_lds > 65536 || epi_lds < table_lds) epi_lds = table_lds;
+    // the epilogue takes as much LDS as the largest form of the predecessor pass that fits 64 KiB wants
+    size_t epi_lds = table_lds;
+    const size_t wishes[] = {queue_pred_bytes<int32_t>(n), queue_pred_bytes<int64_t>(n),
+                             epoch_pred_bytes<int32_t>(n, false), epoch_pred_bytes<int64_t>(n, false),
+                             epoch_pred_bytes<int32_t>(n, true), epoch_pred_bytes<int64_t>(n, true)};
+    for (const size_t wish : wishes)
+        if (wish <= 65536 && wish > epi_lds) epi_lds = wish;
     hipLaunchKernelGGL(cubic_epilogue_kernel, dim3((unsigned)batch), dim3(kWave), epi_lds, stream, n, epi_lds,
                        st.chain, st.pos, mask_out, peak_out, budget_out, status_out, w);
     return hipGetLastError();
