@@ -13,34 +13,43 @@
 //             divides everything by the largest common power of two and picks
 //             32-bit arithmetic when sum(d)+max(d) then fits (it does for
 //             aligned tensor sizes), else 64-bit.  Writes the table
-//             pd[j] = (P[j-1], d_j), the pair every cell j consumes.
+//             pd[j] = (P[j-1], d_j).
+//   32-bit chains:
+//   links     the monotone stack of the sizes themselves: for every position
+//             the nearest earlier smaller size, the stack depth, and a snapshot
+//             of the stack's next eight entries.
+//   values +  the budget values in enumeration order, then sorted per chain
+//   sort      (library radix sort), so that the 64 lanes of a wave hold nearly
+//             equal budgets and meet the same events at the same cells.
+//   shared    one LANE per budget, all lanes walking j together.  F_s(j) is
+//             d_j + m with m the value at the window's head; as long as a lane's
+//             head stays, the part of Algorithm 4's queue that the lane builds
+//             is the stack of the sizes (cut off at a lane-specific depth), the
+//             same for every lane and every budget, so it is not stored at all.
+//             A cell is one min and two compares against wave-uniform values;
+//             only when a head leaves does the lane write that part of its queue
+//             out to its ring in LDS (from the snapshot), and only such
+//             written-out entries are ever dropped by value.  See the comment
+//             at cubic_shared_kernel.  Waves whose 16-entry ring was too small
+//             are listed and run again with 64 entries.
+//   64-bit chains:
 //   budgets   one LANE per budget, 64 budgets of equal range length and
-//             consecutive start per wave (the segment-length anti-diagonal), all
-//             lanes walking j together.  pd[j] is the same for every lane; it is
-//             fetched eight cells ahead with 16-byte loads.  The window minimum
-//             is Algorithm 4's monotone queue, kept per lane as a ring in LDS
-//             laid out [slot][lane] (bank = lane, so lanes at different depths
-//             never conflict), with the head entry and the tail value mirrored
-//             in registers.  Expiry compares the stored key P[h] + s with
-//             P[j-1], so l(i) is never computed.  Only values are needed here, so
-//             equal tails are dropped too and the queue is strictly increasing.
-//             The ring has 8 slots (16 for 64-bit values).  A value that finds it full is not stored
-//             but remembered as a "hole" (smallest value, oldest and newest key
-//             of the holes).  Holes vanish when a later value not above them
-//             arrives (the queue would have dropped them) or when they leave the
-//             window; the lane's result is exact unless the head moves past the
-//             oldest hole while a hole is alive.  Only then does the lane raise
-//             its bit in the wave's flag word for the next kernel.  Deep tail
-//             entries are recent large values that are nearly always dropped
-//             before they could become the head, so this is rare on unsorted
-//             sizes.
-//   overflow  one WAVE per flagged budget: F_s kept in LDS, the window minimum
-//             taken by a wave reduction over the window.  Any queue depth, no
-//             scratch in HBM.
+//             consecutive start per wave, the queue kept per lane as a 16-entry
+//             ring in LDS laid out [slot][lane], head entry and tail value
+//             mirrored in registers, keys stored as P[h] + s so that expiry is
+//             one compare with P[j-1].  A value that finds the ring full is not
+//             stored but remembered as a "hole" (smallest value, oldest and
+//             newest key); holes vanish when a later value not above them
+//             arrives or when they leave the window; the lane is exact unless
+//             the head moves past the oldest live hole, and only then flagged.
+//   both:
+//   overflow  one WAVE per budget still flagged: F_s kept in LDS, the window
+//             minimum taken by a wave reduction.  Any queue depth.
+//   reduce    (long chains) folds the per-wave results.
 //   epilogue  one wave per chain: lexicographic minimum of (s + c_s, s) over the
-//             per-wave partial results (the smallest optimal budget value s*),
-//             then F_{s*} again with the smallest minimal predecessor recorded
-//             for every j, and the walk back from n that writes the mask.
+//             partial results (the smallest optimal budget value s*), then the
+//             predecessors for s* (smallest minimal predecessor of every j) and
+//             the walk back from n that writes the mask.
 #include <hipcub/hipcub.hpp>
 
 #include <limits>
@@ -634,7 +643,9 @@ __global__ __launch_bounds__(256) void cubic_values_kernel(int n, int64_t blocks
 // from the top by the usual comparison with the incoming value; if the implicit
 // part is not empty that comparison is false by itself (its bottom entry is
 // below the incoming value and above everything in the ring).
-// Per cell: one add (F), one min (base), two compares; the rest is rare.
+// Per cell: one min (base) and two compares, "is the ring's top entry at least
+// F(t) = d_t + m" taken as d_t <= X - m with X - m kept in a register, and
+// "has the head left"; F(t) itself is formed when it is stored.  The rest is rare.
 // A value that is the same in every lane, moved to scalar registers so that the
 // arithmetic that follows runs on the scalar unit.
 __device__ inline int32_t uniform(int32_t v) { return __builtin_amdgcn_readfirstlane(v); }
