@@ -87,3 +87,40 @@ def test_config5_full_batch_linear_and_eval():
     assert bool((again == peak).all())
     rand_peak, _ = B.ckpt_eval_peak(dt, mt, B.OBJ_DYNAMIC)
     assert bool((peak <= rand_peak).all())
+
+
+def test_cubic_largest_chain_n8191():
+    """The longest chain the cubic solver takes.  The oracle needs minutes for it, so: a chain of
+    equal sizes against the closed form (gaps of at most k layers need ceil(n/(k+1))-1 interior
+    checkpoints, cost (k + ceil(n/(k+1)) + 1) d), and a random chain through properties: the set
+    returned costs what is reported, the reported budget attains it, no sampled budget does better."""
+    n = 8191  # CKPT_CUBIC_MAX_LAYERS
+    say(f"cubic, n = {n}: equal sizes")
+    unit = 3 << 20
+    d = np.full((n + 1, 1), unit, dtype=np.int64)
+    mask, peak, budget, status = B.ckpt_solve_cubic(torch.from_numpy(d).to(DEV))
+    torch.cuda.synchronize()
+    costs = [(k + -(-n // (k + 1)) + 1) * unit for k in range(n)]
+    best = min(costs)
+    assert int(status.cpu()[0]) == 0
+    assert int(peak.cpu()[0]) == best
+    assert int(budget.cpu()[0]) == costs.index(best) * unit  # the smallest optimal budget
+    mk = mask.cpu().numpy()[:, 0]
+    assert oracle.peak_static(d[:, 0], mk) == best
+
+    say(f"cubic, n = {n}: random sizes")
+    d = inputs.config5_single(n)
+    mask, peak, budget, status = B.ckpt_solve_cubic(torch.from_numpy(d).to(DEV))
+    torch.cuda.synchronize()
+    v, s = int(peak.cpu()[0]), int(budget.cpu()[0])
+    mk = mask.cpu().numpy()[:, 0]
+    assert int(status.cpu()[0]) == 0
+    assert mk[0] == 1 and mk[n] == 1
+    assert oracle.peak_static(d[:, 0], mk) == v
+    assert s + oracle.static_cs(d[:, 0], s) == v
+    say("  sampled budgets")
+    K = n * (n - 1) // 2 + 1
+    rng = np.random.default_rng(5)
+    for first in [0, K - 4096] + [int(x) for x in rng.integers(0, K - 4096, 6)]:
+        cost, _ = oracle.solve_static_range(d[:, 0], first, 4096)
+        assert cost >= v
