@@ -78,6 +78,9 @@ def main():
     ap.add_argument("--n-batch", type=int, default=256)
     ap.add_argument("--n-cubic", type=int, default=4096)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-probe", action="store_true",
+                    help="after the timed steps, copy the batch of sizes once (a plain copy kernel of known size, "
+                         "to scale the profiler's memory counters)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this path runs on one GPU only (independent chains and budgets would be split "
@@ -138,6 +141,11 @@ def main():
         out = step(events)
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
+    if args.copy_probe:
+        probe = torch.empty_like(d)
+        probe.copy_(d)
+        torch.cuda.synchronize()
+        print(f"copy probe: {d.numel() * 8} bytes read, as many written", file=sys.stderr, flush=True)
 
     per_call = {k: [] for k in names}
     for marks in events:
@@ -167,17 +175,23 @@ def main():
         kernels[k]["hbm_frac"] = kernels[k]["hbm_GBs"] / HBM_PEAK_GBS
     kernels["solve_cubic"]["int32_frac"] = kernels["solve_cubic"]["int32_TOPs"] / INT32_PEAK_TOPS
 
+    # HBM bytes per launch of the kernels the rooflines are about, from the rocprofv3 FETCH_SIZE /
+    # WRITE_SIZE runs summarised in profiles/bench_stress_hbm_counters.md (valid for the default
+    # workload only; to be set to None when those kernels change)
+    default_workload = (Bn, n, nc) == (1048576, 256, 4096)
+    traffic_cubic = 39.9e6 + 3.2e6 if default_workload else None
+    traffic_linear = 2.695e9 + 0.534e9 if default_workload else None
     dominant = max(names, key=lambda k: ms[k])
     if dominant == "solve_cubic":
         roofline = {"kernel": "cubic_shared_kernel (timed as the whole ckpt_solve_cubic call)", "bound": "alu",
                     "achieved": kernels["solve_cubic"]["int32_TOPs"], "peak": INT32_PEAK_TOPS, "unit": "TOP/s",
-                    "frac": kernels["solve_cubic"]["int32_frac"], "traffic": None}
+                    "frac": kernels["solve_cubic"]["int32_frac"], "traffic": traffic_cubic}
     else:
         roofline = {"kernel": dominant, "bound": "hbm", "achieved": kernels[dominant]["hbm_GBs"],
                     "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": kernels[dominant]["hbm_frac"], "traffic": None}
     roofline_linear = {"kernel": "ckpt_solve_linear", "bound": "hbm", "achieved": kernels["solve_linear"]["hbm_GBs"],
                        "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": kernels["solve_linear"]["hbm_frac"],
-                       "traffic": None}
+                       "traffic": traffic_linear}
 
     rec = {
         "metric": "DP cells/sec over one pass of the checkpoint-selection path (cubic + linear recurrence cells)",
