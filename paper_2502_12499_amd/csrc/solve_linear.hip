@@ -84,8 +84,8 @@ __global__ void linear_reset_kernel(LinearWs w) { *w.count = 0; }
 
 struct RingEntry {
     uint32_t M;  // M(j)
-    uint32_t A;  // M(j) + T(j)
     uint32_t G;  // max of d over [j, j'), j' the next entry towards the far end
+    uint32_t A;  // M(j) + T(j)
     uint32_t J;  // j
 };
 
@@ -125,7 +125,10 @@ __global__ __launch_bounds__(kWave) void linear_ring_kernel(const int64_t *__res
     // Q = {n}: it is the crossover entry (U(i,n) > d_n = M(n) for every i)
     uint32_t hd = 0, pt = 0;                   // ring positions of the head and of the crossover entry
     uint32_t Mhd = (uint32_t)xs, Ghd = 0;      // M and G of the head entry
-    uint32_t front = 0;                        // max of d over [i, j_head)
+    // (M, G) of the three entries under the head, read back after every push so
+    // that the steps that follow find them in registers (what lies beyond the
+    // crossover entry is never looked at, so it does not matter what they hold there)
+    uint32_t M1 = 0, G1 = 0, M2 = 0, G2 = 0, M3 = 0, G3 = 0;
     uint32_t Tpt = 0, Jpt = n, Rp = 0;         // crossover entry: T(j), j, R(i, j)
     uint32_t Mc = kNone, Ac = kNone, Jc = 0, Rc = 0;  // candidate (the entry before pt): M, A, j, R(i, j)
     uint32_t Ti = 0;                           // T(i) / 2^sh
@@ -134,7 +137,7 @@ __global__ __launch_bounds__(kWave) void linear_ring_kernel(const int64_t *__res
     uint32_t Mi = dnext;
     {
         LdsPtr e = entry(0);
-        e[0] = Mhd; e[1] = Mhd; e[2] = 0; e[3] = (uint32_t)n;  // T(n) = 0
+        e[0] = Mhd; e[1] = 0; e[2] = Mhd; e[3] = (uint32_t)n;  // T(n) = 0
     }
 
     // One step of the recurrence for position i, whose size x is already in a register.
@@ -153,7 +156,8 @@ __global__ __launch_bounds__(kWave) void linear_ring_kernel(const int64_t *__res
                     LdsPtr e = entry((uint32_t)t * kStep);
                     e[0] <<= kk; e[1] <<= kk; e[2] <<= kk;
                 }
-                Mhd <<= kk; Ghd <<= kk; front <<= kk; Tpt <<= kk; Rp <<= kk; Rc <<= kk;
+                Mhd <<= kk; Ghd <<= kk; Tpt <<= kk; Rp <<= kk; Rc <<= kk;
+                M1 <<= kk; G1 <<= kk; M2 <<= kk; G2 <<= kk; M3 <<= kk; G3 <<= kk;
                 Mc = Mc == kNone ? kNone : Mc << kk;
                 Ac = Ac == kNone ? kNone : Ac << kk;
                 Ti <<= kk; dnext <<= kk; dmax <<= kk;
@@ -166,7 +170,6 @@ __global__ __launch_bounds__(kWave) void linear_ring_kernel(const int64_t *__res
         Ti += dnext;
         dmax = di > dmax ? di : dmax;
         defer |= (Ti + di + dmax) >= kLimit;  // bounds M(i) and every U(i,j)
-        front = di > front ? di : front;
         Rp = di > Rp ? di : Rp;
         Rc = di > Rc ? di : Rc;
 
@@ -177,7 +180,7 @@ __global__ __launch_bounds__(kWave) void linear_ring_kernel(const int64_t *__res
         // lowering of this doubly nested divergent loop is several times longer.)
         {
             uint32_t ad, e, t0;
-            uint64_t sv, sv2, sv3;
+            uint64_t sv, sv2;
             asm volatile(
                 "Lw_%=:\n\t"
                 "v_add_u32 %[t0], %[Ti], %[Rc]\n\t"
@@ -192,33 +195,51 @@ __global__ __launch_bounds__(kWave) void linear_ring_kernel(const int64_t *__res
                 "v_mov_b32 %[Mc], -1\n\t"
                 "v_cmp_ne_u32 vcc, %[pt], %[hd]\n\t"
                 "s_and_saveexec_b64 %[sv2], vcc\n\t"
+                // the new candidate, and its R from the G of the entries above it:
+                // the head's and the three under it are in registers
                 "v_add_u32 %[e], %[step], %[pt]\n\t"
                 "v_and_or_b32 %[ad], %[e], %[mask], %[lo]\n\t"
                 "ds_read_b32 %[Mc], %[ad]\n\t"
-                "ds_read_b32 %[Ac], %[ad] offset:4\n\t"
+                "ds_read_b32 %[Ac], %[ad] offset:8\n\t"
                 "ds_read_b32 %[Jc], %[ad] offset:12\n\t"
-                "v_mov_b32 %[Rc], %[front]\n\t"
+                "v_sub_u32 %[t0], %[hd], %[e]\n\t"
+                "v_mov_b32 %[Rc], %[di]\n\t"
+                "v_cmp_le_u32 vcc, %[step], %[t0]\n\t"
+                "s_and_b64 exec, exec, vcc\n\t"
+                "v_max_u32 %[Rc], %[Rc], %[Ghd]\n\t"
+                "v_cmp_le_u32 vcc, 2*%[step], %[t0]\n\t"
+                "s_and_b64 exec, exec, vcc\n\t"
+                "v_max_u32 %[Rc], %[Rc], %[G1]\n\t"
+                "v_cmp_le_u32 vcc, 3*%[step], %[t0]\n\t"
+                "s_and_b64 exec, exec, vcc\n\t"
+                "v_max_u32 %[Rc], %[Rc], %[G2]\n\t"
+                "v_cmp_le_u32 vcc, 4*%[step], %[t0]\n\t"
+                "s_and_b64 exec, exec, vcc\n\t"
+                "v_max_u32 %[Rc], %[Rc], %[G3]\n\t"
+                // more than four entries above it: the rest from the ring
+                "v_subrev_u32 %[e], 3*%[step], %[hd]\n\t"
                 "Lg_%=:\n\t"
-                "v_cmp_ne_u32 vcc, %[e], %[hd]\n\t"
-                "s_cbranch_vccz Lg_done_%=\n\t"
-                "s_and_saveexec_b64 %[sv3], vcc\n\t"
-                "v_add_u32 %[e], %[step], %[e]\n\t"
+                "v_subrev_u32 %[e], %[step], %[e]\n\t"
+                "v_sub_u32 %[t0], %[e], %[pt]\n\t"
+                "v_cmp_lt_u32 vcc, %[step], %[t0]\n\t"
+                "s_and_b64 exec, exec, vcc\n\t"
+                "s_cbranch_execz Lg_done_%=\n\t"
                 "v_and_or_b32 %[ad], %[e], %[mask], %[lo]\n\t"
-                "ds_read_b32 %[t0], %[ad] offset:8\n\t"
+                "ds_read_b32 %[t0], %[ad] offset:4\n\t"
                 "s_waitcnt lgkmcnt(0)\n\t"
                 "v_max_u32 %[Rc], %[Rc], %[t0]\n\t"
-                "s_mov_b64 exec, %[sv3]\n\t"
                 "s_branch Lg_%=\n\t"
                 "Lg_done_%=:\n\t"
+                "s_mov_b64 exec, %[sv2]\n\t"
                 "s_waitcnt lgkmcnt(0)\n\t"
                 "s_mov_b64 exec, %[sv]\n\t"
                 "s_branch Lw_%=\n\t"
                 "Lw_done_%=:\n\t"
                 : [pt] "+v"(pt), [Tpt] "+v"(Tpt), [Jpt] "+v"(Jpt), [Rp] "+v"(Rp), [Mc] "+v"(Mc), [Ac] "+v"(Ac),
                   [Jc] "+v"(Jc), [Rc] "+v"(Rc), [ad] "=&v"(ad), [e] "=&v"(e), [t0] "=&v"(t0), [sv] "=&s"(sv),
-                  [sv2] "=&s"(sv2), [sv3] "=&s"(sv3)
-                : [Ti] "v"(Ti), [hd] "v"(hd), [front] "v"(front), [lo] "v"(lane_base), [mask] "s"(kSlotMask),
-                  [step] "i"(kStep)
+                  [sv2] "=&s"(sv2)
+                : [Ti] "v"(Ti), [hd] "v"(hd), [di] "v"(di), [Ghd] "v"(Ghd), [G1] "v"(G1), [G2] "v"(G2), [G3] "v"(G3),
+                  [lo] "v"(lane_base), [mask] "s"(kSlotMask), [step] "i"(kStep)
                 : "vcc", "memory");
         }
         const uint32_t Upt = Ti + Rp - Tpt;  // U(i, j_pt)
@@ -236,39 +257,68 @@ __global__ __launch_bounds__(kWave) void linear_ring_kernel(const int64_t *__res
 
         // Q: drop the entries that M(i) dominates (never the crossover entry),
         // folding their G into the new entry's, then push i
-        uint32_t Gacc = front;
+        uint32_t Gacc = di;
         {
-            uint32_t ad;
-            uint64_t sv, st;
-            asm volatile(
-                "Lq_%=:\n\t"
-                "v_cmp_ge_u32 vcc, %[Mhd], %[Mi]\n\t"
-                "v_cmp_ne_u32 %[st], %[hd], %[pt]\n\t"
-                "s_and_b64 vcc, vcc, %[st]\n\t"
-                "s_cbranch_vccz Lq_done_%=\n\t"
-                "s_and_saveexec_b64 %[sv], vcc\n\t"
-                "v_max_u32 %[G], %[G], %[Ghd]\n\t"
-                "v_subrev_u32 %[hd], %[step], %[hd]\n\t"
-                "v_and_or_b32 %[ad], %[hd], %[mask], %[lo]\n\t"
-                "ds_read_b32 %[Mhd], %[ad]\n\t"
-                "ds_read_b32 %[Ghd], %[ad] offset:8\n\t"
-                "s_waitcnt lgkmcnt(0)\n\t"
-                "s_mov_b64 exec, %[sv]\n\t"
-                "s_branch Lq_%=\n\t"
-                "Lq_done_%=:\n\t"
-                : [hd] "+v"(hd), [Mhd] "+v"(Mhd), [Ghd] "+v"(Ghd), [G] "+v"(Gacc), [ad] "=&v"(ad), [sv] "=&s"(sv),
-                  [st] "=&s"(st)
-                : [Mi] "v"(Mi), [pt] "v"(pt), [lo] "v"(lane_base), [mask] "s"(kSlotMask), [step] "i"(kStep)
-                : "vcc", "memory");
+            // up to three drops are decided on the mirrors.  The crossover entry is never
+            // dropped: for a chain in range M(i) is above its value anyway, but a lane whose
+            // values have gone wrong (it will be deferred) must keep hd >= pt too, or the
+            // loops over the ring would not end
+            const uint32_t room = hd - pt;
+            const bool p0 = (Mhd >= Mi) & (room >= kStep);
+            const bool p1 = p0 & (M1 >= Mi) & (room >= 2 * kStep);
+            const bool p2 = p1 & (M2 >= Mi) & (room >= 3 * kStep);
+            const bool p3 = p2 & (M3 >= Mi) & (room >= 4 * kStep);
+            Gacc = p0 ? (Ghd > Gacc ? Ghd : Gacc) : Gacc;
+            Gacc = p1 ? (G1 > Gacc ? G1 : Gacc) : Gacc;
+            Gacc = p2 ? (G2 > Gacc ? G2 : Gacc) : Gacc;
+            hd -= p0 ? kStep : 0u;
+            hd -= p1 ? kStep : 0u;
+            hd -= p2 ? kStep : 0u;
+            Mhd = p2 ? M3 : (p1 ? M2 : (p0 ? M1 : Mhd));
+            Ghd = p2 ? G3 : (p1 ? G2 : (p0 ? G1 : Ghd));
+            if (__builtin_amdgcn_ballot_w64(p3) != 0) {
+                // more: from the ring, one at a time (the position test also ends the loop
+                // for a lane whose values have gone wrong and that will be deferred)
+                uint32_t ad, t0;
+                uint64_t sv, st;
+                asm volatile(
+                    "Lq_%=:\n\t"
+                    "v_sub_u32 %[t0], %[hd], %[pt]\n\t"
+                    "v_subrev_u32 %[t0], 1, %[t0]\n\t"
+                    "v_cmp_ge_u32 vcc, %[Mhd], %[Mi]\n\t"
+                    "v_cmp_gt_u32 %[st], %[span], %[t0]\n\t"
+                    "s_and_b64 vcc, vcc, %[st]\n\t"
+                    "s_cbranch_vccz Lq_done_%=\n\t"
+                    "s_and_saveexec_b64 %[sv], vcc\n\t"
+                    "v_max_u32 %[G], %[G], %[Ghd]\n\t"
+                    "v_subrev_u32 %[hd], %[step], %[hd]\n\t"
+                    "v_and_or_b32 %[ad], %[hd], %[mask], %[lo]\n\t"
+                    "ds_read_b32 %[Mhd], %[ad]\n\t"
+                    "ds_read_b32 %[Ghd], %[ad] offset:4\n\t"
+                    "s_waitcnt lgkmcnt(0)\n\t"
+                    "s_mov_b64 exec, %[sv]\n\t"
+                    "s_branch Lq_%=\n\t"
+                    "Lq_done_%=:\n\t"
+                    : [hd] "+v"(hd), [Mhd] "+v"(Mhd), [Ghd] "+v"(Ghd), [G] "+v"(Gacc), [ad] "=&v"(ad), [t0] "=&v"(t0),
+                      [sv] "=&s"(sv), [st] "=&s"(st)
+                    : [Mi] "v"(Mi), [pt] "v"(pt), [lo] "v"(lane_base), [mask] "s"(kSlotMask), [step] "i"(kStep),
+                      [span] "s"((uint32_t)kRing * kStep)
+                    : "vcc", "memory");
+            }
         }
         hd += kStep;
         {
             LdsPtr e = entry(hd);
-            e[0] = Mi; e[1] = Mi + Ti; e[2] = Gacc; e[3] = (uint32_t)i;
+            e[0] = Mi; e[1] = Gacc; e[2] = Mi + Ti; e[3] = (uint32_t)i;
         }
         Mhd = Mi;
         Ghd = Gacc;
-        front = 0;
+        {
+            LdsPtr e1 = entry(hd - kStep), e2 = entry(hd - 2 * kStep), e3 = entry(hd - 3 * kStep);
+            M1 = e1[0]; G1 = e1[1];
+            M2 = e2[0]; G2 = e2[1];
+            M3 = e3[0]; G3 = e3[1];
+        }
         defer |= (hd - pt) >= (uint32_t)kRing * kStep;
         const bool fresh = hd == pt + kStep;  // the new entry is the candidate; R(i', i) starts empty
         Mc = fresh ? Mi : Mc;
