@@ -40,12 +40,18 @@
 //        far (stored values are shifted left when a size with fewer trailing
 //        zeros arrives).  nxt(i) - i - 1 is parked as a byte in the chain's
 //        mask_out slot i and replaced by the mask in a final forward sweep.
-//        A lane defers its chain to the list kernel when a ring fills, the
-//        values outgrow 30 bits, a step exceeds 255 positions, or a size is not
-//        positive: it appends the chain to a list in the workspace.
-//   list kernel     one wave per deferred chain (lane 0 works), 64-bit values,
-//        stacks of full capacity n+1 in LDS (n <= 2047) or in the workspace.
-//        Correct for any input, and the only writer of error statuses.
+//        A lane defers its chain when a ring fills, the values outgrow 30 bits,
+//        a step exceeds 255 positions, or a size is not positive: it appends
+//        the chain to a list in the workspace.
+//   wide kernel     one lane per chain on that list: the same algorithm in
+//        64-bit arithmetic with plain loops (sizes that are not multiples of a
+//        large power of two end up here).  Chains it cannot take either (ring
+//        full, step beyond 255, sizes not positive, sums beyond 64 bits) go on
+//        a second list.
+//   list kernel     one wave per chain of the second list (lane 0 works),
+//        64-bit values, stacks of full capacity n+1 in LDS (n <= 2047) or in
+//        the workspace.  Correct for any input, and the only writer of error
+//        statuses.
 #include "ckpt_internal.h"
 
 namespace ckpt {
@@ -57,8 +63,10 @@ constexpr int kListBlocks = 1024;
 constexpr int kLdsStackMaxN = 2047;
 
 struct LinearWs {
-    int32_t *count;   // [1] number of deferred chains (first 256 bytes)
-    int32_t *list;    // [batch]
+    int32_t *count;   // [2] chains deferred by the ring kernel, chains deferred again by the wide kernel
+                      // (first 256 bytes)
+    int32_t *list;    // [batch] the former
+    int32_t *list2;   // [batch] the latter
     char *scratch;    // kListBlocks * stack_bytes(n)
 };
 
@@ -72,11 +80,12 @@ __host__ LinearWs carve_linear(void *ws, int64_t batch, int n)
     LinearWs w;
     w.count = (int32_t *)p; p += 256;
     w.list = (int32_t *)p;  p += align_up((size_t)batch * 4);
+    w.list2 = (int32_t *)p; p += align_up((size_t)batch * 4);
     w.scratch = p;
     return w;
 }
 
-__global__ void linear_reset_kernel(LinearWs w) { *w.count = 0; }
+__global__ void linear_reset_kernel(LinearWs w) { w.count[0] = 0; w.count[1] = 0; }
 
 // ---------------------------------------------------------------------------
 // ring kernel
@@ -374,6 +383,121 @@ __global__ __launch_bounds__(kWave) void linear_ring_kernel(const int64_t *__res
 }
 
 // ---------------------------------------------------------------------------
+// wide kernel: one lane per chain deferred by the ring kernel, 64-bit values
+// ---------------------------------------------------------------------------
+
+struct alignas(32) WideEntry {
+    int64_t M;   // M(j)
+    int64_t G;   // max of d over [j, j'), j' the next entry towards the far end
+    int64_t A;   // M(j) + T(j)
+    int32_t J;   // j
+    int32_t pad;
+};
+
+constexpr int kWideBlocks = 2048;
+
+// The ring kernel's algorithm again, in 64-bit arithmetic and with plain loops,
+// for the chains whose values did not fit 32 bits there.  The lanes of a wave
+// take listed chains and walk i together.  A chain with a size that is not
+// positive, with sums beyond 64 bits, with more than kRing live entries or with
+// a step beyond 255 positions goes on to the list kernel.
+__global__ __launch_bounds__(kWave) void linear_wide_kernel(const int64_t *__restrict__ d, int n, int64_t cstride,
+                                                            int64_t pstride, uint8_t *__restrict__ mask_out,
+                                                            int64_t *__restrict__ peak_out,
+                                                            int32_t *__restrict__ status_out, LinearWs w)
+{
+    __shared__ WideEntry ring[kRing][kWave];
+    const int lane = threadIdx.x;
+    const int count = w.count[0];
+    for (int item0 = blockIdx.x * kWave; item0 < count; item0 += gridDim.x * kWave) {
+        const bool live = item0 + lane < count;
+        const int64_t c = w.list[live ? item0 + lane : count - 1];
+        const int64_t *dp = d + c * cstride;
+        uint8_t *mp = mask_out + c * cstride;
+        auto at = [&](int pos) -> WideEntry & { return ring[pos & (kRing - 1)][lane]; };
+
+        int64_t x = dp[(int64_t)n * pstride];
+        bool out = x <= 0;  // no longer this kernel's chain
+        int64_t dmax = x, dnext = x, Mi = x;
+        uint64_t T = 0;
+        int hd = 0, pt = 0;
+        at(0) = WideEntry{x, 0, x, n, 0};
+        int64_t Tpt = 0, Rp = 0;
+        int Jpt = n;
+        bool has_c = false;
+        int64_t Mc = 0, Ac = 0, Rc = 0;
+        int Jc = 0;
+
+        for (int i = n - 1; i >= 0; --i) {
+            const int64_t di = dp[(int64_t)i * pstride];
+            out |= di <= 0;
+            dmax = di > dmax ? di : dmax;
+            T += (uint64_t)dnext;
+            dnext = di;
+            out |= T > (uint64_t)INT64_MAX;
+            if (!out) out |= (T + (uint64_t)di + (uint64_t)dmax) > (uint64_t)INT64_MAX;  // bounds M(i), every U(i,j)
+            if (out) continue;
+            const int64_t Ti = (int64_t)T;
+            Rp = di > Rp ? di : Rp;
+            Rc = di > Rc ? di : Rc;
+            // the crossover moves towards the head while the candidate satisfies U(i,j) >= M(j)
+            while (has_c && Ti + Rc >= Ac) {
+                ++pt;
+                Tpt = Ac - Mc;
+                Jpt = Jc;
+                Rp = Rc;
+                has_c = pt != hd;
+                if (has_c) {
+                    const WideEntry e = at(pt + 1);
+                    Mc = e.M; Ac = e.A; Jc = e.J;
+                    Rc = di;  // joined with the G of the entries above the new candidate
+                    for (int q = pt + 2; q <= hd; ++q) {
+                        const int64_t g = at(q).G;
+                        Rc = g > Rc ? g : Rc;
+                    }
+                }
+            }
+            const int64_t Upt = Ti + Rp - Tpt;  // U(i, j_pt)
+            const bool take = has_c && Mc <= Upt;  // ties go to the lower index
+            Mi = di + (take ? Mc : Upt);
+            const int step = (take ? Jc : Jpt) - i - 1;
+            out |= step > 255;
+            if (live) mp[(int64_t)i * pstride] = (uint8_t)step;
+            // Q: drop the entries that M(i) dominates (never the crossover entry), then push i
+            int64_t Gacc = di;
+            while (hd > pt && at(hd).M >= Mi) {
+                const int64_t g = at(hd).G;
+                Gacc = g > Gacc ? g : Gacc;
+                --hd;
+            }
+            ++hd;
+            out |= hd - pt >= kRing;
+            at(hd) = WideEntry{Mi, Gacc, Mi + Ti, i, 0};
+            if (hd == pt + 1) {
+                has_c = true;
+                Mc = Mi; Ac = Mi + Ti; Jc = i; Rc = 0;
+            }
+        }
+        if (!live) continue;
+        if (out) {
+            w.list2[atomicAdd(w.count + 1, 1)] = (int32_t)c;
+            continue;
+        }
+        peak_out[c] = Mi;
+        if (status_out) status_out[c] = CKPT_OK;
+        // forward sweep: replace the parked steps by the mask
+        __threadfence_block();
+        int cur = 0;
+        for (int k = 0; k <= n; ++k) {
+            uint8_t *q = mp + (int64_t)k * pstride;
+            const bool on = k == cur;
+            if (on) cur = k + 1 + *q;
+            *q = on ? 1 : 0;
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------
 // list kernel: one wave per deferred chain, full-capacity stacks, 64-bit
 // ---------------------------------------------------------------------------
 
@@ -385,7 +509,7 @@ __global__ __launch_bounds__(kWave) void linear_list_kernel(const int64_t *__res
                                                             int64_t *__restrict__ peak_out,
                                                             int32_t *__restrict__ status_out, LinearWs w)
 {
-    const int count = *w.count;
+    const int count = w.count[1];
     const size_t n1 = (size_t)n + 1;
     char *base = w.scratch + (size_t)blockIdx.x * stack_bytes(n);
     int32_t *nxt = (int32_t *)(base + n1 * 32);
@@ -398,7 +522,7 @@ __global__ __launch_bounds__(kWave) void linear_list_kernel(const int64_t *__res
 
     for (int item = blockIdx.x; item < count; item += gridDim.x) {
         if (threadIdx.x != 0) continue;
-        const int64_t c = w.list[item];
+        const int64_t c = w.list2[item];
         const int64_t *dp = d + c * cstride;
         uint8_t *mp = mask_out + c * cstride;
 
@@ -484,7 +608,7 @@ __global__ __launch_bounds__(kWave) void linear_list_kernel(const int64_t *__res
 
 size_t linear_workspace_bytes(int64_t batch, int n)
 {
-    return 256 + align_up((size_t)batch * 4) + (size_t)kListBlocks * stack_bytes(n) + 256;
+    return 256 + 2 * align_up((size_t)batch * 4) + (size_t)kListBlocks * stack_bytes(n) + 256;
 }
 
 hipError_t launch_solve_linear(const int64_t *d, int64_t batch, int n, Strides st, uint8_t *mask_out,
@@ -496,6 +620,9 @@ hipError_t launch_solve_linear(const int64_t *d, int64_t batch, int n, Strides s
     hipLaunchKernelGGL(linear_reset_kernel, dim3(1), dim3(1), 0, stream, w);
     hipLaunchKernelGGL(linear_ring_kernel, dim3(grid), dim3(kWave), 0, stream, d, batch, n, st.chain, st.pos,
                        mask_out, peak_out, status_out, w);
+    const int64_t wide_blocks = (batch + kWave - 1) / kWave;
+    hipLaunchKernelGGL(linear_wide_kernel, dim3((unsigned)(wide_blocks < kWideBlocks ? wide_blocks : kWideBlocks)),
+                       dim3(kWave), 0, stream, d, n, st.chain, st.pos, mask_out, peak_out, status_out, w);
     const unsigned lgrid = (unsigned)(batch < kListBlocks ? batch : kListBlocks);
     if (n <= kLdsStackMaxN)
         hipLaunchKernelGGL(linear_list_kernel<true>, dim3(lgrid), dim3(kWave), lds_stack_bytes(n), stream, d, n,
