@@ -119,7 +119,8 @@ __global__ __launch_bounds__(kWave) void linear_ring_kernel(const int64_t *__res
     const int64_t cc = live ? c : batch - 1;  // idle lanes shadow the last chain and write nothing
     const int64_t *dp = d + cc * cstride;
     uint8_t *mp = mask_out + cc * cstride;
-    constexpr uint32_t kLimit = 1u << 30;
+    constexpr uint32_t kLimit = 1u << 30;       // bound on T(i) + d_i + max d, hence on every M(i) and U(i,j)
+    constexpr uint32_t kChunkLimit = 1u << 26;  // bound on a single size (kChunk of them leave T below 2^31)
 
     typedef __attribute__((address_space(3))) uint32_t *LdsPtr;
     const uint32_t lane_base = (uint32_t)(uintptr_t)(LdsPtr)&ring[0][lane].M;
@@ -128,8 +129,9 @@ __global__ __launch_bounds__(kWave) void linear_ring_kernel(const int64_t *__res
     const int64_t xn = dp[(int64_t)n * pstride];
     bool defer = xn <= 0;
     int sh = defer ? 0 : __ffsll((unsigned long long)xn) - 1;
+    sh = sh < 31 ? sh : 31;  // so that a size's low word alone says whether it is a multiple of 2^sh
     uint64_t xs = (uint64_t)xn >> sh;
-    defer |= xs >= kLimit;
+    defer |= xs >= kChunkLimit;
 
     // Q = {n}: it is the crossover entry (U(i,n) > d_n = M(n) for every i)
     uint32_t hd = 0, pt = 0;                   // ring positions of the head and of the crossover entry
@@ -142,7 +144,8 @@ __global__ __launch_bounds__(kWave) void linear_ring_kernel(const int64_t *__res
     uint32_t Mc = kNone, Ac = kNone, Jc = 0, Rc = 0;  // candidate (the entry before pt): M, A, j, R(i, j)
     uint32_t Ti = 0;                           // T(i) / 2^sh
     uint32_t dnext = (uint32_t)xs;             // d_{i+1} / 2^sh
-    uint32_t dmax = dnext;
+    uint32_t dmax = dnext, dmin = dnext;
+    uint32_t smax = 0;  // longest step chosen
     uint32_t Mi = dnext;
     {
         LdsPtr e = entry(0);
@@ -150,12 +153,15 @@ __global__ __launch_bounds__(kWave) void linear_ring_kernel(const int64_t *__res
     }
 
     // One step of the recurrence for position i, whose size x is already in a register.
-    auto step_fn = [&](const int i, const int64_t x) {
-        defer |= x <= 0;
-        // common trailing zeros: rescale everything held so far if this size has fewer
-        const int tz = x > 0 ? __ffsll((unsigned long long)x) - 1 : sh;
-        if (__builtin_amdgcn_ballot_w64(tz < sh) != 0) {
-            if (tz < sh) {
+    // Range and alignment are settled for kChunk rows at a time, before their steps:
+    // `all` is the OR of the rows (so its trailing zeros are the fewest of theirs and
+    // its magnitude bounds each of them; a negative size shows as a huge one).
+    auto chunk_check = [&](const uint64_t all) {
+        const uint32_t low = (uint32_t)all & ((1u << sh) - 1u);
+        if (__builtin_amdgcn_ballot_w64(low != 0) != 0) {
+            if (low != 0) {
+                // fewer common trailing zeros: rescale everything held so far
+                const int tz = __ffs(low) - 1;
                 const int k = sh - tz;
                 const bool fits = k < 30 && ((Ti + dnext + dmax) >> (30 - k)) == 0;
                 defer |= !fits;
@@ -173,12 +179,17 @@ __global__ __launch_bounds__(kWave) void linear_ring_kernel(const int64_t *__res
                 sh = tz;
             }
         }
-        xs = (uint64_t)x >> sh;
-        defer |= xs >= kLimit;
-        const uint32_t di = (uint32_t)xs;
+        // sizes below 2^26 and T(i) + d + max d below 2^30 now: no sum of this chunk wraps
+        defer |= (all >> sh) >= kChunkLimit;
+        defer |= (Ti + dnext + dmax) >= kLimit;
+    };
+
+    // One step of the recurrence for position i, whose size x is already in a register.
+    auto step_fn = [&](const int i, const int64_t x) {
+        const uint32_t di = __builtin_amdgcn_alignbit((uint32_t)((uint64_t)x >> 32), (uint32_t)x, (uint32_t)sh);
+        dmin = di < dmin ? di : dmin;  // a size of zero
         Ti += dnext;
         dmax = di > dmax ? di : dmax;
-        defer |= (Ti + di + dmax) >= kLimit;  // bounds M(i) and every U(i,j)
         Rp = di > Rp ? di : Rp;
         Rc = di > Rc ? di : Rc;
 
@@ -257,7 +268,7 @@ __global__ __launch_bounds__(kWave) void linear_ring_kernel(const int64_t *__res
         const uint32_t nx = take_cand ? Jc : Jpt;
         Mi = di + best;
         const uint32_t step = nx - (uint32_t)i - 1u;
-        defer |= step > 255u;
+        smax = step > smax ? step : smax;
         // Parked with a store the compiler does not count, so that its waits on the
         // rows fetched ahead stay partial (a counted store would make it wait for
         // everything in flight; an uncounted one can only lengthen a wait).
@@ -346,13 +357,17 @@ __global__ __launch_bounds__(kWave) void linear_ring_kernel(const int64_t *__res
 #pragma unroll
         for (int u = 0; u < kChunk; ++u)  // rows below 0 re-read row 0 and are not used
             ahead[u] = dp[(int64_t)max(ihi - kChunk - u, 0) * pstride];
+        uint64_t all = 0;
+#pragma unroll
+        for (int u = 0; u < kChunk; ++u) all |= (uint64_t)rows[ihi - u >= 0 ? u : 0];
+        chunk_check(all);
 #pragma unroll
         for (int u = 0; u < kChunk; ++u)
             if (ihi - u >= 0) step_fn(ihi - u, rows[u]);
 #pragma unroll
         for (int u = 0; u < kChunk; ++u) rows[u] = ahead[u];
     }
-    defer |= sh > 32;  // results must fit 64 bits after shifting back
+    defer |= dmin == 0 || smax > 255u || (Ti + dnext + dmax) >= kLimit;
 
     if (!live) return;
     if (defer) {
