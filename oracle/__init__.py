@@ -41,6 +41,9 @@ def _load():
             "orc_peak_dynamic": (I, [P, U, N]),
             "orc_sim_static": (I, [P, U, N]),
             "orc_sim_dynamic": (I, [P, U, N]),
+            "orc_timeline": (None, [P, U, N, N, P]),
+            "orc_select_baseline": (None, [N, N, U]),
+            "orc_batch_timeline": (None, [P, U, I, N, N, P]),
             "orc_brute": (I, [P, N, N, P, P]),
             "orc_num_budgets": (I, [N]),
             "orc_budgets": (None, [P, N, P]),
@@ -96,6 +99,25 @@ def sim_static(d, mask):
 def sim_dynamic(d, mask):
     d, dp = _d(d); mask, mp = _m(mask)
     return int(_load().orc_sim_dynamic(dp, mp, len(d) - 1))
+
+
+def timeline(d, mask, objective):
+    """Memory per training phase index 0..2n+1 (Algorithm 2 / Algorithm 3 events)."""
+    d, dp = _d(d); mask, mp = _m(mask)
+    n = len(d) - 1
+    out = np.empty(2 * n + 2, dtype=np.int64)
+    _load().orc_timeline(dp, mp, n, int(objective), out.ctypes.data_as(_i64p))
+    return out
+
+
+SELECT_NONE, SELECT_ALL, SELECT_SQRT = 0, 1, 2
+
+
+def select_baseline(n, kind):
+    """Size-independent checkpoint sets: ends only, every position, sqrt(n) rule."""
+    mask = np.zeros(n + 1, dtype=np.uint8)
+    _load().orc_select_baseline(int(n), int(kind), mask.ctypes.data_as(_u8p))
+    return mask
 
 
 # ---- brute force ---------------------------------------------------------------
@@ -183,6 +205,14 @@ def batch_peak(d, mask, objective):
     B, n1 = d.shape
     out = np.empty(B, dtype=np.int64)
     _load().orc_batch_peak(dp, mp, B, n1 - 1, int(objective), out.ctypes.data_as(_i64p))
+    return out
+
+
+def batch_timeline(d, mask, objective):
+    d, dp = _d(d); mask, mp = _m(mask)
+    B, n1 = d.shape
+    out = np.empty((B, 2 * n1), dtype=np.int64)
+    _load().orc_batch_timeline(dp, mp, B, n1 - 1, int(objective), out.ctypes.data_as(_i64p))
     return out
 
 

@@ -35,8 +35,12 @@
  *
  * Pinned by tests/test_oracle_*.py: brute force over all subsets (n <= 20),
  * closed forms for fixed sets and uniform chains, monotonicity and bounds,
- * hand-worked tiny chains, the paper's VGG-19 sets and memory gaps, and the
- * event simulators of Algorithms 2 and 3 against the closed forms.
+ * hand-worked tiny chains, the paper's VGG-19 sets and memory gaps, the
+ * event simulators of Algorithms 2 and 3 against the closed forms, the
+ * per-phase timeline against the printed prediction curve of Section 5.2
+ * (phase indices 0..36; the rest of that curve is not consistent with
+ * Equation (memory), so the later backward stages are pinned by hand-worked
+ * chains and closed forms only), and the sqrt(n) sets of the peak-memory table.
  */
 #include <stdint.h>
 #include <stdlib.h>
@@ -146,6 +150,84 @@ i64 orc_sim_dynamic(const i64 *d, const uint8_t *mask, int n)
         live -= d[i];                            /* release d_i */
     }
     return peak;
+}
+
+/* Memory per training phase index (Section 5.1, "Models and Definitions":
+ * index 0 is the stage before training, 1..n the forward stage of layer i,
+ * n+1..2n the backward stages of layers n..1, 2n+1 the stage after
+ * training), read off the allocate/free events of Algorithm 2 (objective 0)
+ * or Algorithm 3 (objective 1).  The value of a stage is the number of live
+ * bytes once the stage has made its allocations and before it releases
+ * anything at its end: in a forward stage d_i is allocated while d_{i-1} is
+ * still there; a backward stage of Algorithm 3 is sampled before "release
+ * the memory d_i" (so a checkpoint stage gives m(i) of Equation (memory) and
+ * the other stages m(i') of Equation (iprime)); the old gradient buffer is
+ * released before the segment is recomputed, as in orc_sim_dynamic.  Before
+ * and after training only the input d_0 is resident.  out has 2n+2 entries;
+ * they are all -1 if an end is not a checkpoint. */
+void orc_timeline(const i64 *d, const uint8_t *mask, int n, int objective, i64 *out)
+{
+    if (!mask[0] || !mask[n]) {
+        for (int t = 0; t <= 2 * n + 1; t++) out[t] = -1;
+        return;
+    }
+    i64 live = d[0];
+    out[0] = live;
+    for (int i = 1; i <= n; i++) {               /* forward phase */
+        live += d[i];                            /* allocate d_i */
+        out[i] = live;
+        if (!mask[i - 1]) live -= d[i - 1];      /* free a non-checkpoint */
+    }
+    if (objective == 0) {                        /* Algorithm 2 */
+        int seg_lo = 1, seg_hi = 0;              /* live recomputed segment */
+        for (int i = n; i >= 1; i--) {
+            if (mask[i]) {
+                for (int k = seg_lo; k <= seg_hi; k++) live -= d[k];
+                int h = i - 1;
+                while (!mask[h]) h--;
+                seg_lo = h + 1; seg_hi = i - 1;
+                for (int k = seg_lo; k <= seg_hi; k++) live += d[k];
+            }
+            out[2 * n + 1 - i] = live;
+        }
+    } else {                                     /* Algorithm 3 */
+        i64 r = 0;                               /* gradient buffer size */
+        for (int i = n; i >= 1; i--) {
+            if (mask[i]) {
+                int h = i - 1;
+                while (!mask[h]) h--;
+                live -= r;
+                for (int k = h + 1; k <= i - 1; k++) live += d[k];
+                r = 0;
+                for (int k = h; k <= i - 1; k++) if (d[k] > r) r = d[k];
+                live += r;
+            }
+            out[2 * n + 1 - i] = live;
+            live -= d[i];                        /* release d_i */
+        }
+    }
+    out[2 * n + 1] = d[0];
+}
+
+/* ------------------------------------------------------------------------ */
+/* Checkpoint sets that do not look at the sizes (Section 2.1)               */
+/* ------------------------------------------------------------------------ */
+
+/* kind 0: no interior checkpoint (only d_0 and d_n);  kind 1: every position;
+ * kind 2: Chen et al.'s sqrt(n) rule as the paper applies it in Section 5 -
+ * segments of k = ceil(sqrt(n)) layers, i.e. checkpoints at the multiples of
+ * k below n, plus the forced ends (n = 24 gives {5,10,15,20,24}, n = 15 gives
+ * {4,8,12,15}, the sets of the peak-memory table). */
+void orc_select_baseline(int n, int kind, uint8_t *mask_out)
+{
+    int k = 1;
+    while ((i64)k * k < n) k++;
+    for (int i = 0; i <= n; i++) {
+        uint8_t on = (i == 0 || i == n);
+        if (kind == 1) on = 1;
+        if (kind == 2 && i % k == 0) on = 1;
+        mask_out[i] = on;
+    }
 }
 
 /* ------------------------------------------------------------------------ */
@@ -430,6 +512,14 @@ void orc_batch_peak(const i64 *d, const uint8_t *mask, i64 batch, int n, int obj
         const uint8_t *mc = mask + c * ((i64)n + 1);
         peak_out[c] = objective ? orc_peak_dynamic(dc, mc, n) : orc_peak_static(dc, mc, n);
     }
+}
+
+void orc_batch_timeline(const i64 *d, const uint8_t *mask, i64 batch, int n, int objective, i64 *out)
+{
+#pragma omp parallel for schedule(static)
+    for (i64 c = 0; c < batch; c++)
+        orc_timeline(d + c * ((i64)n + 1), mask + c * ((i64)n + 1), n, objective,
+                     out + c * (2 * (i64)n + 2));
 }
 
 void orc_batch_solve_dynamic(const i64 *d, i64 batch, int n, uint8_t *mask_out, i64 *peak_out)

@@ -361,3 +361,97 @@ def test_generators_are_counter_based_and_in_range():
     assert 0.2 < m3[1:64].mean() < 0.3
     assert inputs.config2().shape == (153, 1) and inputs.config4().shape == (1002, 1)
     assert inputs.config5_single().shape == (4097, 1)
+
+
+# --------------------------------------------------------------------------
+# Memory per training phase index (Section 5.1; Algorithms 2 and 3 as events)
+# --------------------------------------------------------------------------
+
+def test_timeline_worked_examples():
+    with open(os.path.join(GOLDEN, "worked_examples.json")) as f:
+        ex = json.load(f)["timelines"]
+    for e in ex:
+        d = np.array(e["d"], dtype=np.int64)
+        mask = positions_to_mask(len(d) - 1, e["set"])
+        assert list(oracle.timeline(d, mask, 0)) == e["static"]
+        assert list(oracle.timeline(d, mask, 1)) == e["dynamic"]
+
+
+def test_timeline_paper_vgg19_prediction_curve():
+    """The printed 'Algo. Prediction' series of Section 5.2 for the set
+    {3, 11, 24}: forward stages 1..24 and the backward stages of the first
+    recomputed segment (indices 25..36), relative to the constant part at
+    index 0 (which also holds the input d_0)."""
+    with open(os.path.join(GOLDEN, "paper_vgg19_timeline.json")) as f:
+        fx = json.load(f)
+    d = inputs.vgg19_chain(fx["batch"])[:, 0]
+    n = len(d) - 1
+    mask = positions_to_mask(n, fx["set"])
+    tl = oracle.timeline(d, mask, 1)
+    gib = fx["prediction_gib"]
+    for t in range(1, len(gib)):
+        printed_bytes = (gib[t] - gib[0]) * 2.0 ** 30       # printed with 13-14 significant digits
+        # (forward stage 24 of the printed series counts the last layer's 512,000 bytes as 0.49 MiB)
+        tol = 0.005 * 2 ** 20 if t == 24 else 1.0
+        assert abs(float(tl[t] - d[0]) - printed_bytes) < tol, t
+    # index 25 is Equation (memory) at the last layer, and the largest stage of all is the peak
+    assert tl[25] == d[3] + d[11] + d[24] + d[12:24].sum() + d[11:24].max() + d[0]
+    assert tl.max() == oracle.peak_dynamic(d, mask)
+
+
+@pytest.mark.parametrize("kind", ["wide", "ties", "aligned", "spiky"])
+def test_timeline_maximum_is_the_peak_and_closed_forms(kind):
+    rng = np.random.default_rng(77)
+    for n in (1, 2, 3, 7, 20, 65):
+        d = random_chain(rng, n, kind)
+        P = np.cumsum(d)
+        for trial in range(6):
+            mask = (rng.random(n + 1) < 0.3).astype(np.uint8)
+            mask[0] = mask[n] = 1
+            for obj, peak in ((0, oracle.peak_static), (1, oracle.peak_dynamic)):
+                tl = oracle.timeline(d, mask, obj)
+                assert tl[0] == d[0] and tl[-1] == d[0]
+                assert tl[n + 1:2 * n + 1].max() == peak(d, mask)      # Equation (cost) / (memory)
+                assert (tl[1:n + 1] <= tl[2 * n:n:-1]).all()            # a layer's forward stage never tops its backward stage
+        none = positions_to_mask(n, [n])
+        full = np.ones(n + 1, dtype=np.uint8)
+        # no interior checkpoint: Algorithm 2 recomputes everything at once; Algorithm 3 sheds d_n..d_1
+        assert (oracle.timeline(d, none, 0)[n + 1:2 * n + 1] == d.sum()).all()
+        bwd = oracle.timeline(d, none, 1)[n + 1:2 * n + 1][::-1]        # layers 1..n
+        assert (bwd == P[1:] + d[:n].max()).all()
+        fwd = oracle.timeline(d, none, 1)[1:n + 1]
+        assert (fwd == d[0] + d[1:] + np.concatenate(([0], d[1:n]))).all()
+        # every position a checkpoint: nothing is recomputed
+        assert (oracle.timeline(d, full, 0)[n + 1:2 * n + 1] == d.sum()).all()
+        assert (oracle.timeline(d, full, 1)[n + 1:2 * n + 1][::-1] == P[1:] + d[:n]).all()
+        assert (oracle.timeline(d, full, 0)[1:n + 1] == P[1:]).all()
+
+
+def test_timeline_rejects_a_set_without_both_ends():
+    d = np.array([3, 4, 5], dtype=np.int64)
+    assert (oracle.timeline(d, np.array([1, 1, 0], dtype=np.uint8), 1) == -1).all()
+    assert (oracle.timeline(d, np.array([0, 1, 1], dtype=np.uint8), 0) == -1).all()
+
+
+# --------------------------------------------------------------------------
+# Size-independent sets (Section 2.1; the sqrt(n) sets of the peak-memory table)
+# --------------------------------------------------------------------------
+
+def test_baseline_sets():
+    with open(os.path.join(GOLDEN, "paper_vgg19.json")) as f:
+        vgg = json.load(f)
+    assert list(np.flatnonzero(oracle.select_baseline(24, oracle.SELECT_SQRT))[1:]) == vgg["set_sqrt_n"]
+    # AlexNet row of the same table: n = 15, {4, 8, 12, 15}
+    assert list(np.flatnonzero(oracle.select_baseline(15, oracle.SELECT_SQRT))[1:]) == [4, 8, 12, 15]
+    for n in (1, 2, 3, 4, 5, 16, 17, 100, 1001):
+        k = math.isqrt(n - 1) + 1 if n > 1 else 1           # ceil(sqrt(n))
+        m = oracle.select_baseline(n, oracle.SELECT_SQRT)
+        assert m[0] == 1 and m[n] == 1
+        assert set(np.flatnonzero(m)) == set(range(0, n, k)) | {n}
+        assert list(np.flatnonzero(oracle.select_baseline(n, oracle.SELECT_NONE))) == sorted({0, n})
+        assert oracle.select_baseline(n, oracle.SELECT_ALL).all()
+    # uniform sizes: the sqrt(n) set stays within a constant factor of the optimum (Section 2.1)
+    for n in (16, 100, 400):
+        d = np.ones(n + 1, dtype=np.int64)
+        opt, _, _ = oracle.solve_static(d)
+        assert oracle.peak_static(d, oracle.select_baseline(n, oracle.SELECT_SQRT)) <= 2 * opt
