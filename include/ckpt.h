@@ -61,6 +61,13 @@ typedef enum {
     CKPT_OBJ_DYNAMIC = 1  /* Equation (memory), Section 4: early release + output-gradient buffer */
 } ckpt_objective;
 
+/* Checkpoint sets that do not look at the sizes (ckpt_select_baseline). */
+typedef enum {
+    CKPT_SELECT_ENDS = 0, /* only d_0 and d_n: everything is recomputed in one segment */
+    CKPT_SELECT_ALL = 1,  /* every position: nothing is recomputed (Algorithm 1) */
+    CKPT_SELECT_SQRT = 2  /* segments of ceil(sqrt(n)) layers (Section 2.1) */
+} ckpt_baseline;
+
 typedef enum { CKPT_CALL_EVAL_PEAK = 0, CKPT_CALL_SOLVE_CUBIC = 1, CKPT_CALL_SOLVE_LINEAR = 2 } ckpt_call;
 
 /* Largest n accepted by ckpt_eval_peak and ckpt_solve_linear, and by
@@ -116,6 +123,40 @@ int ckpt_solve_cubic(const int64_t *d, const ckpt_layout *layout, uint8_t *mask_
 int ckpt_solve_linear(const int64_t *d, const ckpt_layout *layout, uint8_t *mask_out,
                       int64_t *peak_out, int32_t *status_out,
                       void *ws, size_t ws_bytes, void *hip_stream);
+
+/* Memory per training phase index of a given checkpoint set, per chain
+ * (Section 5.1, "training phase index": 0 is the stage before training, 1..n
+ * the forward stage of layer i, n+1..2n the backward stages of layers n..1,
+ * 2n+1 the stage after training; the curves of Section 5 plot this).  A stage
+ * is sampled after its allocations and before the release at its end:
+ *   forward stage i: the checkpoints up to i-1, d_i, and d_{i-1} if it is no
+ *       checkpoint (the forward loop of Algorithms 2 and 3);
+ *   backward stage of layer i, h the last checkpoint below i, nx the first
+ *       checkpoint at or above i:
+ *     CKPT_OBJ_DYNAMIC (Algorithm 3): sum_{c in C, c <= h} d_c + sum_{k=h+1}^{i} d_k
+ *       + max_{h<=k<nx} d_k, i.e. Equation (memory) at a checkpoint and
+ *       Equation (iprime) between checkpoints;
+ *     CKPT_OBJ_STATIC (Algorithm 2): sum_{c in C} d_c + sum_{h<k<nx} d_k;
+ *   indices 0 and 2n+1: d_0.
+ * The largest backward stage equals the peak of ckpt_eval_peak.
+ * d, mask [in] as for ckpt_eval_peak.  timeline_out [out] int64, 2n+2 values
+ * per chain: phase t of chain c at timeline_out[c*out_chain_stride +
+ * t*out_phase_stride] (strides in elements, both > 0; the fast layout is
+ * out_chain_stride = 1, out_phase_stride = batch); it must not overlap the
+ * inputs.  status_out as above; a chain with a data error gets -1 in every
+ * phase.  Needs no scratch. */
+int ckpt_eval_timeline(const int64_t *d, const uint8_t *mask, const ckpt_layout *layout,
+                       int objective, int64_t *timeline_out, int64_t out_chain_stride,
+                       int64_t out_phase_stride, int32_t *status_out, void *hip_stream);
+
+/* The size-independent checkpoint sets that the paper compares against
+ * (Section 2.1 and the peak-memory table of Section 5), written for every
+ * chain of the layout: `kind` is a ckpt_baseline.  CKPT_SELECT_SQRT puts a
+ * checkpoint at every multiple of ceil(sqrt(n)) below n (n = 24: {5, 10, 15,
+ * 20, 24}; n = 15: {4, 8, 12, 15}); positions 0 and n are always set.
+ * mask_out [out] bytes 0/1 in `layout`.  Needs no sizes and no scratch;
+ * evaluate the sets with ckpt_eval_peak or ckpt_eval_timeline. */
+int ckpt_select_baseline(const ckpt_layout *layout, int kind, uint8_t *mask_out, void *hip_stream);
 
 /* Number of recurrence cells one ckpt_solve_cubic call evaluates per chain:
  * (n(n-1)/2 + 1) budgets times n positions.  Host-only. */

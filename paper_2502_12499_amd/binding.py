@@ -22,8 +22,10 @@ CKPT_OK = 0
 OBJ_STATIC, OBJ_DYNAMIC = 0, 1
 CALL_EVAL_PEAK, CALL_SOLVE_CUBIC, CALL_SOLVE_LINEAR = 0, 1, 2
 
-EXPORTS = ("ckpt_workspace_bytes", "ckpt_eval_peak", "ckpt_solve_cubic", "ckpt_solve_linear",
-           "ckpt_cubic_cells", "ckpt_status_string")
+SELECT_ENDS, SELECT_ALL, SELECT_SQRT = 0, 1, 2
+
+EXPORTS = ("ckpt_workspace_bytes", "ckpt_eval_peak", "ckpt_eval_timeline", "ckpt_select_baseline",
+           "ckpt_solve_cubic", "ckpt_solve_linear", "ckpt_cubic_cells", "ckpt_status_string")
 
 
 class Layout(ctypes.Structure):
@@ -48,6 +50,10 @@ def load():
         lib.ckpt_workspace_bytes.argtypes = [ctypes.c_int, LP]
         lib.ckpt_eval_peak.restype = ctypes.c_int
         lib.ckpt_eval_peak.argtypes = [vp, vp, LP, ctypes.c_int, vp, vp, vp, ctypes.c_size_t, vp]
+        lib.ckpt_eval_timeline.restype = ctypes.c_int
+        lib.ckpt_eval_timeline.argtypes = [vp, vp, LP, ctypes.c_int, vp, ctypes.c_int64, ctypes.c_int64, vp, vp]
+        lib.ckpt_select_baseline.restype = ctypes.c_int
+        lib.ckpt_select_baseline.argtypes = [LP, ctypes.c_int, vp, vp]
         lib.ckpt_solve_cubic.restype = ctypes.c_int
         lib.ckpt_solve_cubic.argtypes = [vp, LP, vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
         lib.ckpt_solve_linear.restype = ctypes.c_int
@@ -129,6 +135,38 @@ def ckpt_eval_peak(d, mask, objective, chain_major=False, want_status=True):
     if rc != CKPT_OK:
         raise CkptError("ckpt_eval_peak", rc)
     return peak, status
+
+
+def ckpt_eval_timeline(d, mask, objective, chain_major=False, want_status=True):
+    """Memory per training phase index 0..2n+1 of each chain's set.  Returns
+    (timeline, status); timeline has shape (2n+2, batch), or (batch, 2n+2) with
+    ``chain_major``."""
+    _check_inputs(d, mask)
+    L = layout_of(d, chain_major)
+    phases = 2 * L.n_layers + 2
+    if chain_major:
+        out = torch.empty((L.batch, phases), dtype=torch.int64, device=d.device)
+        ocs, ops = phases, 1
+    else:
+        out = torch.empty((phases, L.batch), dtype=torch.int64, device=d.device)
+        ocs, ops = 1, max(L.batch, 1)
+    status = torch.empty(L.batch, dtype=torch.int32, device=d.device) if want_status else None
+    rc = load().ckpt_eval_timeline(_ptr(d), _ptr(mask), ctypes.byref(L), int(objective), _ptr(out), ocs, ops,
+                                   _ptr(status), _stream())
+    if rc != CKPT_OK:
+        raise CkptError("ckpt_eval_timeline", rc)
+    return out, status
+
+
+def ckpt_select_baseline(like, kind, chain_major=False):
+    """A size-independent checkpoint set for every chain; ``like`` is the sizes
+    tensor (or a mask) whose shape and strides the result takes."""
+    L = layout_of(like, chain_major)
+    mask = torch.empty_strided(like.shape, like.stride(), dtype=torch.uint8, device=like.device)
+    rc = load().ckpt_select_baseline(ctypes.byref(L), int(kind), _ptr(mask), _stream())
+    if rc != CKPT_OK:
+        raise CkptError("ckpt_select_baseline", rc)
+    return mask
 
 
 def ckpt_solve_cubic(d, chain_major=False, workspace=None, want_status=True):

@@ -54,6 +54,36 @@ int ckpt_eval_peak(const int64_t *d, const uint8_t *mask, const ckpt_layout *L, 
                                          objective, peak_out, status_out, (hipStream_t)hip_stream));
 }
 
+int ckpt_eval_timeline(const int64_t *d, const uint8_t *mask, const ckpt_layout *L, int objective,
+                       int64_t *timeline_out, int64_t out_chain_stride, int64_t out_phase_stride,
+                       int32_t *status_out, void *hip_stream)
+{
+    const int rc = check_layout(L, CKPT_MAX_LAYERS);
+    if (rc != CKPT_OK) return rc;
+    if (objective != CKPT_OBJ_STATIC && objective != CKPT_OBJ_DYNAMIC) return CKPT_ERR_SHAPE;
+    if (out_chain_stride <= 0 || out_phase_stride <= 0) return CKPT_ERR_SHAPE;
+    const __int128 last = (__int128)(L->batch > 0 ? L->batch - 1 : 0) * out_chain_stride +
+                          (__int128)(2 * (int64_t)L->n_layers + 1) * out_phase_stride;
+    if (last > (__int128)INT64_MAX / 8) return CKPT_ERR_SHAPE;
+    if (L->batch == 0) return CKPT_OK;
+    if (!d || !mask || !timeline_out) return CKPT_ERR_NULL;
+    return finish(ckpt::launch_eval_timeline(d, mask, L->batch, L->n_layers,
+                                             Strides{L->chain_stride, L->pos_stride}, objective, timeline_out,
+                                             Strides{out_chain_stride, out_phase_stride}, status_out,
+                                             (hipStream_t)hip_stream));
+}
+
+int ckpt_select_baseline(const ckpt_layout *L, int kind, uint8_t *mask_out, void *hip_stream)
+{
+    const int rc = check_layout(L, CKPT_MAX_LAYERS);
+    if (rc != CKPT_OK) return rc;
+    if (kind < CKPT_SELECT_ENDS || kind > CKPT_SELECT_SQRT) return CKPT_ERR_SHAPE;
+    if (L->batch == 0) return CKPT_OK;
+    if (!mask_out) return CKPT_ERR_NULL;
+    return finish(ckpt::launch_select_baseline(L->batch, L->n_layers, Strides{L->chain_stride, L->pos_stride},
+                                               kind, mask_out, (hipStream_t)hip_stream));
+}
+
 int ckpt_solve_cubic(const int64_t *d, const ckpt_layout *L, uint8_t *mask_out, int64_t *peak_out,
                      int64_t *budget_out, int32_t *status_out, void *ws, size_t ws_bytes, void *hip_stream)
 {
@@ -93,7 +123,7 @@ const char *ckpt_status_string(int status)
     switch (status) {
         case CKPT_OK: return "ok";
         case CKPT_ERR_NULL: return "null pointer";
-        case CKPT_ERR_SHAPE: return "bad shape, stride or objective";
+        case CKPT_ERR_SHAPE: return "bad shape, stride, objective or kind";
         case CKPT_ERR_SIZE: return "non-positive size";
         case CKPT_ERR_OVERFLOW: return "sum(d)+max(d) overflows int64";
         case CKPT_ERR_MASK: return "mask does not contain both ends";

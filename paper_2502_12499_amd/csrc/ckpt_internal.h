@@ -25,6 +25,13 @@ inline size_t align_up(size_t x, size_t a = 256) { return (x + a - 1) / a * a; }
 hipError_t launch_eval_peak(const int64_t *d, const uint8_t *mask, int64_t batch, int n, Strides st,
                             int objective, int64_t *peak_out, int32_t *status_out, hipStream_t stream);
 
+// ---- eval_timeline, select_baseline ------------------------------------------
+hipError_t launch_eval_timeline(const int64_t *d, const uint8_t *mask, int64_t batch, int n, Strides st,
+                                int objective, int64_t *out, Strides out_st, int32_t *status_out,
+                                hipStream_t stream);
+hipError_t launch_select_baseline(int64_t batch, int n, Strides st, int kind, uint8_t *mask_out,
+                                  hipStream_t stream);
+
 // ---- solve_linear ------------------------------------------------------------
 size_t linear_workspace_bytes(int64_t batch, int n);
 hipError_t launch_solve_linear(const int64_t *d, int64_t batch, int n, Strides st, uint8_t *mask_out,

@@ -1,0 +1,218 @@
+// Memory per training phase index for a given checkpoint set (Section 5.1,
+// "training phase index": 0 before training, 1..n the forward stage of layer
+// i, n+1..2n the backward stages of layers n..1, 2n+1 after training), under
+// the memory behaviour of Algorithm 2 (static objective) or Algorithm 3
+// (dynamic objective), one lane per chain.
+//
+// A stage's value is the live memory after the stage's allocations and before
+// the release at its end:
+//   forward stage i     sum_{c in C, c <= i-1} d_c + d_i + [i-1 not in C] d_{i-1}
+//   backward stage of layer i, with h the last checkpoint below i and nx the
+//   first checkpoint at or above i:
+//     Algorithm 3       sum_{c in C, c <= h} d_c + sum_{k=h+1}^{i} d_k + max_{h<=k<nx} d_k
+//                       (Equation (memory) for i = nx, Equation (iprime) otherwise)
+//     Algorithm 2       sum_{c in C} d_c + sum_{h<k<nx} d_k
+//   index 0 and 2n+1    d_0
+// so the largest backward stage is the peak that ckpt_eval_peak returns.
+//
+// A backward stage needs something from each side of position i: the part of
+// its segment below i (running sums from the pass itself) and the part above,
+// max or sum of d_i..d_{nx-1}.  The kernel walks the chain once, upwards, in
+// chunks of kChunk rows held in registers, with the next chunk already loaded
+// and the one after it in flight.  For a chunk it first finds what lies above
+// the chunk's last row (it scans the next chunk's registers up to the first
+// checkpoint; a lane whose next chunk holds no checkpoint reads on from
+// memory, which is rare and hits rows that are about to be loaded anyway),
+// then sweeps the chunk downwards in registers to get the part above every
+// row, then upwards to write both stages of every row.  Algorithm 3's stages
+// need nothing else, so that objective reads 9(n+1) bytes and writes 16(n+1)
+// per chain, which is what the method itself has to move.  Algorithm 2's
+// stages all contain the sum of ALL checkpoints, which is only known at the
+// end of the chain, so that objective reads the chain once more beforehand.
+#include "ckpt_internal.h"
+
+namespace ckpt {
+namespace {
+
+constexpr int kBlock = 256;
+constexpr int kChunk = 8;
+
+template <int OBJ>
+__global__ __launch_bounds__(kBlock) void eval_timeline_kernel(const int64_t *__restrict__ d,
+                                                               const uint8_t *__restrict__ mask, int64_t batch,
+                                                               int n, int64_t cstride, int64_t pstride,
+                                                               int64_t *__restrict__ out, int64_t ocstride,
+                                                               int64_t opstride, int32_t *__restrict__ status_out)
+{
+    const int64_t c = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+    if (c >= batch) return;
+    const int64_t *dp = d + c * cstride;
+    const uint8_t *mp = mask + c * cstride;
+    int64_t *op = out + c * ocstride;
+    const int64_t last = 2 * (int64_t)n + 1;
+    // the part of a segment above a row: its largest size (Algorithm 3) or its sum (Algorithm 2).
+    // Sums are unsigned so that an invalid chain cannot trip signed overflow.
+    auto join = [](uint64_t acc, int64_t x) -> uint64_t {
+        return OBJ == CKPT_OBJ_STATIC ? acc + (uint64_t)x : ((uint64_t)x > acc ? (uint64_t)x : acc);
+    };
+
+    const int64_t x0 = dp[0];
+    uint64_t ckpt_all = 0;  // sum of all checkpoints (Algorithm 2 only)
+    if (OBJ == CKPT_OBJ_STATIC) {
+#pragma unroll 8
+        for (int k = 0; k <= n; ++k)
+            if (mp[(int64_t)k * pstride]) ckpt_all += (uint64_t)dp[(int64_t)k * pstride];
+    }
+
+    // rows beyond n re-read row n and are not used
+    int64_t cur_d[kChunk], nxt_d[kChunk];
+    uint8_t cur_m[kChunk], nxt_m[kChunk];
+#pragma unroll
+    for (int u = 0; u < kChunk; ++u) {
+        const int64_t a = (int64_t)min(1 + u, n) * pstride, b = (int64_t)min(1 + kChunk + u, n) * pstride;
+        cur_d[u] = dp[a]; cur_m[u] = mp[a];
+        nxt_d[u] = dp[b]; nxt_m[u] = mp[b];
+    }
+
+    bool bad_size = x0 <= 0, ovf = false;
+    const bool bad_mask = mp[0] == 0 || mp[(int64_t)n * pstride] == 0;
+    uint64_t total = (uint64_t)x0;
+    int64_t dmax = x0;
+
+    op[0] = x0;
+    uint64_t below = (uint64_t)x0;  // checkpoints up to the last one below the row
+    uint64_t seg = 0;               // non-checkpoints since then
+    int64_t segmax = x0;            // largest size from that checkpoint up to the row before
+    int64_t prev = 0;               // the row before, if it is no checkpoint, else 0
+
+    for (int k0 = 1; k0 <= n; k0 += kChunk) {
+        int64_t far_d[kChunk];
+        uint8_t far_m[kChunk];
+#pragma unroll
+        for (int u = 0; u < kChunk; ++u) {
+            const int64_t a = (int64_t)min(k0 + 2 * kChunk + u, n) * pstride;
+            far_d[u] = dp[a]; far_m[u] = mp[a];
+        }
+
+        // what lies above the chunk's last row: d from the next chunk's first row up to (not
+        // including) the first checkpoint there
+        uint64_t acc = 0;
+        bool found = false;
+#pragma unroll
+        for (int u = 0; u < kChunk; ++u) {
+            const bool open = !found && (k0 + kChunk + u) <= n;
+            found |= (k0 + kChunk + u) > n || nxt_m[u] != 0;
+            if (open && nxt_m[u] == 0) acc = join(acc, nxt_d[u]);
+        }
+        for (int k = k0 + 2 * kChunk; !found; ++k) {
+            if (k > n) break;
+            const int64_t x = dp[(int64_t)k * pstride];
+            if (mp[(int64_t)k * pstride]) break;
+            acc = join(acc, x);
+        }
+
+        // downwards: the part above each row of the chunk (the row itself included)
+        uint64_t above[kChunk];
+#pragma unroll
+        for (int u = kChunk - 1; u >= 0; --u) {
+            if (k0 + u <= n) acc = cur_m[u] ? 0 : join(acc, cur_d[u]);
+            above[u] = acc;
+        }
+
+        // upwards: both stages of each row
+#pragma unroll
+        for (int u = 0; u < kChunk; ++u) {
+            const int i = k0 + u;
+            if (i > n) break;
+            const int64_t x = cur_d[u];
+            bad_size |= x <= 0;
+            total += (uint64_t)x;
+            ovf |= total > (uint64_t)INT64_MAX;
+            dmax = x > dmax ? x : dmax;
+            __builtin_nontemporal_store((int64_t)(below + (uint64_t)x + (uint64_t)prev), op + (int64_t)i * opstride);
+            uint64_t b;
+            if (OBJ == CKPT_OBJ_STATIC)
+                b = ckpt_all + seg + above[u];
+            else
+                b = below + seg + (uint64_t)x + ((uint64_t)segmax > above[u] ? (uint64_t)segmax : above[u]);
+            __builtin_nontemporal_store((int64_t)b, op + (last - i) * opstride);
+            if (cur_m[u]) {
+                below += (uint64_t)x;
+                seg = 0;
+                segmax = x;
+                prev = 0;
+            } else {
+                seg += (uint64_t)x;
+                segmax = x > segmax ? x : segmax;
+                prev = x;
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < kChunk; ++u) {
+            cur_d[u] = nxt_d[u]; cur_m[u] = nxt_m[u];
+            nxt_d[u] = far_d[u]; nxt_m[u] = far_m[u];
+        }
+    }
+    op[last * opstride] = x0;
+    ovf |= (total + (uint64_t)dmax) > (uint64_t)INT64_MAX;
+
+    int32_t status = CKPT_OK;
+    if (bad_size) status = CKPT_ERR_SIZE;
+    else if (ovf) status = CKPT_ERR_OVERFLOW;
+    else if (bad_mask) status = CKPT_ERR_MASK;
+    if (status_out) status_out[c] = status;
+    if (status != CKPT_OK)
+        for (int64_t t = 0; t <= last; ++t) op[t * opstride] = -1;
+}
+
+// Checkpoint sets that do not depend on the sizes: the two ends only, every
+// position, or segments of ceil(sqrt(n)) layers (the sqrt(n) rule of Section
+// 2.1 as Section 5 applies it: n = 24 gives {5,10,15,20,24}).
+__global__ __launch_bounds__(kBlock) void select_baseline_kernel(int64_t batch, int n, int64_t cstride,
+                                                                 int64_t pstride, int kind, int seg_len,
+                                                                 uint8_t *__restrict__ mask_out)
+{
+    const int64_t c = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+    if (c >= batch) return;
+    uint8_t *mp = mask_out + c * cstride;
+    int next_multiple = 0;
+    for (int k = 0; k <= n; ++k) {
+        bool on = k == 0 || k == n || kind == CKPT_SELECT_ALL;
+        if (k == next_multiple) {
+            on |= kind == CKPT_SELECT_SQRT;
+            next_multiple += seg_len;
+        }
+        mp[(int64_t)k * pstride] = on ? 1 : 0;
+    }
+}
+
+}  // namespace
+
+hipError_t launch_eval_timeline(const int64_t *d, const uint8_t *mask, int64_t batch, int n, Strides st,
+                                int objective, int64_t *out, Strides out_st, int32_t *status_out,
+                                hipStream_t stream)
+{
+    if (batch == 0) return hipSuccess;
+    const unsigned grid = (unsigned)((batch + kBlock - 1) / kBlock);
+    if (objective == CKPT_OBJ_STATIC)
+        hipLaunchKernelGGL(eval_timeline_kernel<CKPT_OBJ_STATIC>, dim3(grid), dim3(kBlock), 0, stream, d, mask,
+                           batch, n, st.chain, st.pos, out, out_st.chain, out_st.pos, status_out);
+    else
+        hipLaunchKernelGGL(eval_timeline_kernel<CKPT_OBJ_DYNAMIC>, dim3(grid), dim3(kBlock), 0, stream, d, mask,
+                           batch, n, st.chain, st.pos, out, out_st.chain, out_st.pos, status_out);
+    return hipGetLastError();
+}
+
+hipError_t launch_select_baseline(int64_t batch, int n, Strides st, int kind, uint8_t *mask_out,
+                                  hipStream_t stream)
+{
+    if (batch == 0) return hipSuccess;
+    int seg_len = 1;  // ceil(sqrt(n))
+    while ((int64_t)seg_len * seg_len < n) ++seg_len;
+    const unsigned grid = (unsigned)((batch + kBlock - 1) / kBlock);
+    hipLaunchKernelGGL(select_baseline_kernel, dim3(grid), dim3(kBlock), 0, stream, batch, n, st.chain, st.pos,
+                       kind, seg_len, mask_out);
+    return hipGetLastError();
+}
+
+}  // namespace ckpt

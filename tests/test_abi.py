@@ -19,7 +19,8 @@ def declared_functions():
 
 def test_header_declares_the_three_calls():
     names = declared_functions()
-    for want in ("ckpt_eval_peak", "ckpt_solve_cubic", "ckpt_solve_linear", "ckpt_workspace_bytes"):
+    for want in ("ckpt_eval_peak", "ckpt_solve_cubic", "ckpt_solve_linear", "ckpt_workspace_bytes",
+                 "ckpt_eval_timeline", "ckpt_select_baseline"):
         assert want in names
 
 
@@ -70,6 +71,17 @@ def test_host_detectable_errors_return_without_launching():
     E = B.Layout(0, 8, 1, 1)
     assert lib.ckpt_solve_cubic(None, ctypes.byref(E), None, None, None, None, None, 0, None) == 0
     assert lib.ckpt_eval_peak(None, None, ctypes.byref(E), 1, None, None, None, 0, None) == 0
+
+
+def test_timeline_and_baseline_host_checks():
+    lib = B.load()
+    L = B.Layout(4, 8, 1, 4)
+    fake = ctypes.c_void_p(4096)        # never dereferenced: validation fails first
+    assert lib.ckpt_eval_timeline(fake, fake, ctypes.byref(L), 1, fake, 0, 4, None, None) == 2
+    assert lib.ckpt_eval_timeline(fake, fake, ctypes.byref(L), 3, fake, 1, 4, None, None) == 2
+    assert lib.ckpt_eval_timeline(fake, fake, ctypes.byref(L), 1, None, 1, 4, None, None) == 1
+    assert lib.ckpt_select_baseline(ctypes.byref(L), 3, fake, None) == 2
+    assert lib.ckpt_select_baseline(ctypes.byref(L), 0, None, None) == 1
 
 
 def test_binding_refuses_cpu_tensors():

@@ -1,0 +1,131 @@
+"""Parity of ckpt_eval_timeline and ckpt_select_baseline (through the C ABI)
+with the CPU oracle, element by element; integers, so bit-exact."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2502_12499_amd import binding as B
+from paper_2502_12499_amd import inputs
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+
+def to_dev(x):
+    return torch.from_numpy(np.ascontiguousarray(x)).to(DEV)
+
+
+def say(msg):
+    print(msg, flush=True)
+
+
+def check_timeline(d, m):
+    """d, m: position-major numpy (n+1, batch); both layouts, both objectives."""
+    dc, mc = inputs.chain_major(d), inputs.chain_major(m)
+    for obj in (B.OBJ_STATIC, B.OBJ_DYNAMIC):
+        want = oracle.batch_timeline(dc, mc, obj)                    # (batch, 2n+2)
+        tl, status = B.ckpt_eval_timeline(to_dev(d), to_dev(m), obj)
+        assert (status.cpu().numpy() == 0).all()
+        assert np.array_equal(tl.cpu().numpy().T, want), f"objective {obj}, position-major"
+        tl, status = B.ckpt_eval_timeline(to_dev(dc), to_dev(mc), obj, chain_major=True)
+        assert (status.cpu().numpy() == 0).all()
+        assert np.array_equal(tl.cpu().numpy(), want), f"objective {obj}, chain-major"
+
+
+@pytest.mark.parametrize("batch,n", [(1, 1), (1, 12), (3, 2), (64, 64), (1000, 64), (777, 257), (4096, 256)])
+def test_timeline_batches(batch, n):
+    say(f"eval_timeline batch={batch} n={n}")
+    check_timeline(inputs.log_uniform_chains(21, n, batch), inputs.bernoulli_masks(21, n, batch))
+
+
+def test_timeline_fixed_sets():
+    say("eval_timeline: VGG-19 with the paper's sets, the extreme sets")
+    d = inputs.vgg19_chain()
+    for positions in ([3, 11, 24], [3, 6, 24], [5, 10, 15, 20, 24], [24], list(range(1, 25))):
+        m = np.zeros((25, 1), dtype=np.uint8)
+        m[0] = 1
+        m[positions] = 1
+        check_timeline(d, m)
+    rng = np.random.default_rng(3)
+    d = rng.integers(1, 4, size=(41, 256)).astype(np.int64)          # ties everywhere
+    m = (rng.random((41, 256)) < 0.5).astype(np.uint8)
+    m[0] = m[40] = 1
+    check_timeline(d, m)
+
+
+def test_timeline_data_errors():
+    say("eval_timeline: per-chain data errors")
+    d = np.full((9, 6), 1000, dtype=np.int64)
+    m = np.ones((9, 6), dtype=np.uint8)
+    d[4, 1] = 0
+    d[0, 2] = -5
+    d[:, 3] = (1 << 62)
+    m[0, 4] = 0
+    m[8, 5] = 0
+    for obj in (B.OBJ_STATIC, B.OBJ_DYNAMIC):
+        tl, status = B.ckpt_eval_timeline(to_dev(d), to_dev(m), obj)
+        assert status.cpu().numpy().tolist() == [0, 3, 3, 4, 5, 5]
+        got = tl.cpu().numpy()
+        assert (got[:, 1:] == -1).all()
+        assert np.array_equal(got[:, 0], oracle.timeline(d[:, 0], m[:, 0], obj))
+
+
+def test_timeline_largest_stage_is_the_peak_config3():
+    say("eval_timeline: config 3 whole batch against the oracle, and max = ckpt_eval_peak")
+    d, m = inputs.config3()
+    dt, mt = to_dev(d), to_dev(m)
+    n = d.shape[0] - 1
+    dc, mc = inputs.chain_major(d), inputs.chain_major(m)
+    for obj in (B.OBJ_STATIC, B.OBJ_DYNAMIC):
+        tl, status = B.ckpt_eval_timeline(dt, mt, obj)
+        assert int(status.abs().sum()) == 0
+        assert np.array_equal(tl.cpu().numpy().T, oracle.batch_timeline(dc, mc, obj))
+        peak, _ = B.ckpt_eval_peak(dt, mt, obj)
+        assert bool((tl[n + 1:2 * n + 1].max(dim=0).values == peak).all())
+
+
+def test_timeline_config5_sampled():
+    batch, n = 1048576, 256
+    say("eval_timeline: 1,048,576 chains, n = 256, sampled chains and properties of all")
+    d, m = inputs.config5_batch(batch, n)
+    dt, mt = to_dev(d), to_dev(m)
+    rng = np.random.default_rng(6)
+    sample = np.unique(np.concatenate([rng.integers(0, batch, 2048), [0, 255, 256, batch - 1]]))
+    ds, ms = inputs.chain_major(d[:, sample]), inputs.chain_major(m[:, sample])
+    for obj in (B.OBJ_STATIC, B.OBJ_DYNAMIC):
+        tl, status = B.ckpt_eval_timeline(dt, mt, obj)
+        assert int(status.abs().sum()) == 0
+        assert np.array_equal(tl.cpu().numpy()[:, sample].T, oracle.batch_timeline(ds, ms, obj))
+        peak, _ = B.ckpt_eval_peak(dt, mt, obj)
+        assert bool((tl[n + 1:2 * n + 1].max(dim=0).values == peak).all())
+        assert bool((tl[0] == dt[0]).all()) and bool((tl[2 * n + 1] == dt[0]).all())
+        del tl
+
+
+@pytest.mark.parametrize("batch,n", [(1, 1), (1, 24), (5, 15), (300, 64), (70, 1001)])
+def test_select_baseline(batch, n):
+    say(f"select_baseline batch={batch} n={n}")
+    like = torch.empty((n + 1, batch), dtype=torch.int64, device=DEV)
+    for kind in (B.SELECT_ENDS, B.SELECT_ALL, B.SELECT_SQRT):
+        want = oracle.select_baseline(n, kind)
+        got = B.ckpt_select_baseline(like, kind).cpu().numpy()
+        assert (got == want[:, None]).all()
+        got = B.ckpt_select_baseline(like.T.contiguous(), kind, chain_major=True).cpu().numpy()
+        assert (got == want[None, :]).all()
+
+
+def test_baseline_sets_under_both_objectives_vgg19():
+    """The model-side comparison of the peak-memory table: the sqrt(n) set against the
+    optimal sets on the paper's VGG-19 chain, every step on the GPU."""
+    say("select_baseline + eval_peak + solvers on VGG-19")
+    d = to_dev(inputs.vgg19_chain())
+    sq = B.ckpt_select_baseline(d, B.SELECT_SQRT)
+    assert np.flatnonzero(sq.cpu().numpy()[:, 0]).tolist() == [0, 5, 10, 15, 20, 24]
+    lin_mask, lin_peak, _ = B.ckpt_solve_linear(d)
+    cub_mask, cub_peak, _, _ = B.ckpt_solve_cubic(d)
+    sq_dyn, _ = B.ckpt_eval_peak(d, sq, B.OBJ_DYNAMIC)
+    cub_dyn, _ = B.ckpt_eval_peak(d, cub_mask, B.OBJ_DYNAMIC)
+    mib = 1 << 20
+    assert (int(sq_dyn[0]) - int(lin_peak[0])) == 1960 * mib        # the table's 8,404 - 6,444 MiB
+    assert (int(cub_dyn[0]) - int(lin_peak[0])) == 392 * mib        # and 6,836 - 6,444 MiB
