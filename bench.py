@@ -69,6 +69,46 @@ def cpu_baseline(d_batch_np, d_single_np, n_cubic, linear_cells, cubic_cells):
     }
 
 
+def time_extras(torch, B, inputs, d, m, Bn, n, reps=3):
+    """The calls that are not part of the timed step, each timed on its own with HIP events on
+    the stream it runs on: the per-phase memory timeline and the sqrt(n) sets on the same batch,
+    the quadratic-time solver on the ResNet-1001-shaped chain and on the first 4096 chains."""
+    def timed(fn):
+        fn()
+        torch.cuda.synchronize()
+        ts = []
+        for _ in range(reps):
+            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            a.record()
+            fn()
+            b.record()
+            torch.cuda.synchronize()
+            ts.append(a.elapsed_time(b))
+        return float(np.mean(ts))
+
+    out = {}
+    tl_bytes = Bn * 25 * (n + 1)  # 9(n+1) in, 8(2n+2) out per chain
+    for name, obj in (("eval_timeline_static", B.OBJ_STATIC), ("eval_timeline_dynamic", B.OBJ_DYNAMIC)):
+        t = timed(lambda: B.ckpt_eval_timeline(d, m, obj, want_status=False))
+        out[name] = {"ms": t, "instances_per_s": Bn / (t * 1e-3), "hbm_GBs": tl_bytes / (t * 1e-3) / 1e9,
+                     "hbm_frac": tl_bytes / (t * 1e-3) / 1e9 / HBM_PEAK_GBS}
+    t = timed(lambda: B.ckpt_select_baseline(d, B.SELECT_SQRT))
+    out["select_baseline_sqrt"] = {"ms": t, "instances_per_s": Bn / (t * 1e-3),
+                                   "hbm_GBs": Bn * (n + 1) / (t * 1e-3) / 1e9,
+                                   "hbm_frac": Bn * (n + 1) / (t * 1e-3) / 1e9 / HBM_PEAK_GBS}
+    d4 = torch.from_numpy(inputs.config4()).to(d.device)
+    n4 = d4.shape[0] - 1
+    t = timed(lambda: B.ckpt_solve_quadratic(d4, want_values=False, want_status=False))
+    out["solve_quadratic_n1001"] = {"ms": t, "instances_per_s": 1.0 / (t * 1e-3),
+                                    "candidates_per_s": n4 * (n4 + 1) / 2 / (t * 1e-3)}
+    small = min(Bn, 4096)
+    ds = d[:, :small].contiguous()
+    t = timed(lambda: B.ckpt_solve_quadratic(ds, want_values=False, want_status=False))
+    out[f"solve_quadratic_{small}x{n}"] = {"ms": t, "instances_per_s": small / (t * 1e-3),
+                                           "candidates_per_s": small * n * (n + 1) / 2 / (t * 1e-3)}
+    return out
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -78,6 +118,8 @@ def main():
     ap.add_argument("--n-batch", type=int, default=256)
     ap.add_argument("--n-cubic", type=int, default=4096)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-extras", action="store_true",
+                    help="skip the calls outside the timed step (timeline, baseline sets, quadratic solver)")
     ap.add_argument("--copy-probe", action="store_true",
                     help="after the timed steps, copy the batch of sizes once (a plain copy kernel of known size, "
                          "to scale the profiler's memory counters)")
@@ -141,6 +183,7 @@ def main():
         out = step(events)
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
+    extras = None if args.no_extras else time_extras(torch, B, inputs, d, m, args.batch, args.n_batch)
     if args.copy_probe:
         probe = torch.empty_like(d)
         probe.copy_(d)
@@ -210,6 +253,8 @@ def main():
         "roofline_linear": roofline_linear,
         "paper_context": "Python on a Xeon Gold 6226R, VGG-19 (n=24): Algorithm 4 20 ms, Algorithm 6 1.1 ms per chain",
     }
+    if extras is not None:
+        rec["other_calls"] = extras
     if not args.no_cpu_baseline:
         rec["cpu_baseline"] = cpu_baseline(d_np, d1_np, nc, linear_cells, cubic_cells)
     print(json.dumps(rec), flush=True)

@@ -74,6 +74,8 @@ typedef enum { CKPT_CALL_EVAL_PEAK = 0, CKPT_CALL_SOLVE_CUBIC = 1, CKPT_CALL_SOL
  * ckpt_solve_cubic (whose work grows as n^3). */
 #define CKPT_MAX_LAYERS 65535
 #define CKPT_CUBIC_MAX_LAYERS 8191
+/* Largest n accepted by ckpt_solve_quadratic (its per-chain state lives in LDS). */
+#define CKPT_QUADRATIC_MAX_LAYERS 4095
 
 typedef struct {
     int64_t batch;        /* number of chains, 0 .. 2^31-1 (0: the call does nothing) */
@@ -157,6 +159,20 @@ int ckpt_eval_timeline(const int64_t *d, const uint8_t *mask, const ckpt_layout 
  * mask_out [out] bytes 0/1 in `layout`.  Needs no sizes and no scratch;
  * evaluate the sets with ckpt_eval_peak or ckpt_eval_timeline. */
 int ckpt_select_baseline(const ckpt_layout *layout, int kind, uint8_t *mask_out, void *hip_stream);
+
+/* The same optimum and the same canonical set as ckpt_solve_linear, by the
+ * quadratic-time recurrence of Section 4.1 (Equation (T-rec), Algorithm 5,
+ * Theorem 2) evaluated directly: for every i all j > i are tried, one
+ * wavefront per chain with the candidates j across its lanes.  It shares
+ * nothing with the linear-time kernel (no queue, no crossover pointer) and so
+ * cross-checks it on the device; it is also the quicker call for a single
+ * chain or a small batch.  n <= CKPT_QUADRATIC_MAX_LAYERS.
+ * mask_out, peak_out, status_out as for ckpt_solve_linear; value_out [out]
+ * int64 in `layout`, M(i) for every position i (all -1 for a chain with a data
+ * error), or NULL.  Needs no scratch. */
+int ckpt_solve_quadratic(const int64_t *d, const ckpt_layout *layout, uint8_t *mask_out,
+                         int64_t *peak_out, int64_t *value_out, int32_t *status_out,
+                         void *hip_stream);
 
 /* Number of recurrence cells one ckpt_solve_cubic call evaluates per chain:
  * (n(n-1)/2 + 1) budgets times n positions.  Host-only. */

@@ -25,7 +25,8 @@ CALL_EVAL_PEAK, CALL_SOLVE_CUBIC, CALL_SOLVE_LINEAR = 0, 1, 2
 SELECT_ENDS, SELECT_ALL, SELECT_SQRT = 0, 1, 2
 
 EXPORTS = ("ckpt_workspace_bytes", "ckpt_eval_peak", "ckpt_eval_timeline", "ckpt_select_baseline",
-           "ckpt_solve_cubic", "ckpt_solve_linear", "ckpt_cubic_cells", "ckpt_status_string")
+           "ckpt_solve_cubic", "ckpt_solve_linear", "ckpt_solve_quadratic", "ckpt_cubic_cells",
+           "ckpt_status_string")
 
 
 class Layout(ctypes.Structure):
@@ -58,6 +59,8 @@ def load():
         lib.ckpt_solve_cubic.argtypes = [vp, LP, vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
         lib.ckpt_solve_linear.restype = ctypes.c_int
         lib.ckpt_solve_linear.argtypes = [vp, LP, vp, vp, vp, vp, ctypes.c_size_t, vp]
+        lib.ckpt_solve_quadratic.restype = ctypes.c_int
+        lib.ckpt_solve_quadratic.argtypes = [vp, LP, vp, vp, vp, vp, vp]
         lib.ckpt_cubic_cells.restype = ctypes.c_int64
         lib.ckpt_cubic_cells.argtypes = [ctypes.c_int32]
         lib.ckpt_status_string.restype = ctypes.c_char_p
@@ -198,3 +201,19 @@ def ckpt_solve_linear(d, chain_major=False, workspace=None, want_status=True):
     if rc != CKPT_OK:
         raise CkptError("ckpt_solve_linear", rc)
     return mask, peak, status
+
+
+def ckpt_solve_quadratic(d, chain_major=False, want_values=True, want_status=True):
+    """Optimal set under the dynamic objective by the quadratic-time recurrence.
+    Returns (mask, peak, values, status); values holds M(i) in the layout of d."""
+    _check_inputs(d)
+    L = layout_of(d, chain_major)
+    mask = torch.empty_strided(d.shape, d.stride(), dtype=torch.uint8, device=d.device)
+    peak = torch.empty(L.batch, dtype=torch.int64, device=d.device)
+    values = torch.empty_strided(d.shape, d.stride(), dtype=torch.int64, device=d.device) if want_values else None
+    status = torch.empty(L.batch, dtype=torch.int32, device=d.device) if want_status else None
+    rc = load().ckpt_solve_quadratic(_ptr(d), ctypes.byref(L), _ptr(mask), _ptr(peak), _ptr(values), _ptr(status),
+                                     _stream())
+    if rc != CKPT_OK:
+        raise CkptError("ckpt_solve_quadratic", rc)
+    return mask, peak, values, status

@@ -111,6 +111,18 @@ int ckpt_solve_linear(const int64_t *d, const ckpt_layout *L, uint8_t *mask_out,
                                             mask_out, peak_out, status_out, ws, (hipStream_t)hip_stream));
 }
 
+int ckpt_solve_quadratic(const int64_t *d, const ckpt_layout *L, uint8_t *mask_out, int64_t *peak_out,
+                         int64_t *value_out, int32_t *status_out, void *hip_stream)
+{
+    const int rc = check_layout(L, CKPT_QUADRATIC_MAX_LAYERS);
+    if (rc != CKPT_OK) return rc;
+    if (L->batch == 0) return CKPT_OK;
+    if (!d || !mask_out || !peak_out) return CKPT_ERR_NULL;
+    return finish(ckpt::launch_solve_quadratic(d, L->batch, L->n_layers, Strides{L->chain_stride, L->pos_stride},
+                                               mask_out, peak_out, value_out, status_out,
+                                               (hipStream_t)hip_stream));
+}
+
 int64_t ckpt_cubic_cells(int32_t n_layers)
 {
     if (n_layers < 1) return 0;

@@ -37,6 +37,11 @@ size_t linear_workspace_bytes(int64_t batch, int n);
 hipError_t launch_solve_linear(const int64_t *d, int64_t batch, int n, Strides st, uint8_t *mask_out,
                                int64_t *peak_out, int32_t *status_out, void *ws, hipStream_t stream);
 
+// ---- solve_quadratic ---------------------------------------------------------
+hipError_t launch_solve_quadratic(const int64_t *d, int64_t batch, int n, Strides st, uint8_t *mask_out,
+                                  int64_t *peak_out, int64_t *value_out, int32_t *status_out,
+                                  hipStream_t stream);
+
 // ---- solve_cubic -------------------------------------------------------------
 size_t cubic_workspace_bytes(int64_t batch, int n);
 hipError_t launch_solve_cubic(const int64_t *d, int64_t batch, int n, Strides st, uint8_t *mask_out,
