@@ -120,6 +120,21 @@ def vgg19_chain(batch_size=128, bytes_per=4):
     return _column(sizes)
 
 
+def alexnet_chain(batch_size=128, bytes_per=4):
+    """n = 15: AlexNet in the paper's extended specs (Section 5.4, "Standalone
+    Max-Pooling Layers"; Section 5.1.3 counts AdaptiveAvgPool2d, Flatten and
+    Dropout as layers): 5 convolutions, 3 standalone max-poolings, the average
+    pooling, flatten, two dropouts and 3 fully connected layers on a 224x224
+    crop, fp32 outputs."""
+    B = batch_size * bytes_per
+    shapes = [3 * 224 * 224,
+              64 * 55 * 55, 64 * 27 * 27, 192 * 27 * 27, 192 * 13 * 13,      # conv, pool, conv, pool
+              384 * 13 * 13, 256 * 13 * 13, 256 * 13 * 13, 256 * 6 * 6,      # conv x3, pool
+              256 * 6 * 6, 9216, 9216, 4096, 4096, 4096, 1000]               # avgpool, flatten, dropout, fc, dropout, fc, fc
+    assert len(shapes) == 16
+    return _column([B * s for s in shapes])
+
+
 # The five benchmark configurations ------------------------------------------------
 
 def config1():

@@ -91,6 +91,7 @@ def special_chains():
         ("wide_130", rng.integers(1, 1 << 40, size=131)),                   # 64-bit arithmetic
         ("odd_bytes_65", rng.integers(1, 1 << 20, size=66) * 2 + 1),        # no common factor
         ("vgg19", inputs.vgg19_chain()[:, 0]),
+        ("alexnet", inputs.alexnet_chain()[:, 0]),
     ]
     return [(k, np.asarray(v, dtype=np.int64)) for k, v in out]
 

@@ -455,3 +455,21 @@ def test_baseline_sets():
         d = np.ones(n + 1, dtype=np.int64)
         opt, _, _ = oracle.solve_static(d)
         assert oracle.peak_static(d, oracle.select_baseline(n, oracle.SELECT_SQRT)) <= 2 * opt
+
+
+def test_paper_alexnet_sets():
+    """The AlexNet row of the peak-memory table (Section 5.3) on the extended specs of Section 5.4."""
+    with open(os.path.join(GOLDEN, "paper_vgg19.json")) as f:
+        ax = json.load(f)["alexnet"]
+    d = inputs.alexnet_chain(ax["batch"])[:, 0]
+    n = len(d) - 1
+    assert n == 15
+    v, mask, s = oracle.solve_static(d)
+    assert list(np.flatnonzero(mask)[1:]) == ax["set_algorithm4"]             # the canonical set is the printed one
+    assert v == oracle.brute(d, 0)[0]
+    w, dmask, M = oracle.solve_dynamic(d)
+    assert w == oracle.brute(d, 1)[0]
+    assert oracle.peak_dynamic(d, positions_to_mask(n, ax["set_algorithm6"])) == w
+    assert oracle.peak_dynamic(d, positions_to_mask(n, ax["set_algorithm4"])) == w   # 1,002 vs 1,003 MiB measured
+    assert oracle.peak_dynamic(d, positions_to_mask(n, ax["set_sqrt_n"])) > w
+    assert list(np.flatnonzero(oracle.select_baseline(n, oracle.SELECT_SQRT))[1:]) == ax["set_sqrt_n"]
