@@ -69,10 +69,11 @@ def cpu_baseline(d_batch_np, d_single_np, n_cubic, linear_cells, cubic_cells):
     }
 
 
-def time_extras(torch, B, inputs, d, m, Bn, n, reps=3):
+def time_extras(torch, B, inputs, d, m, d1, ws_cub, Bn, n, reps=3):
     """The calls that are not part of the timed step, each timed on its own with HIP events on
     the stream it runs on: the per-phase memory timeline and the sqrt(n) sets on the same batch,
-    the quadratic-time solver on the ResNet-1001-shaped chain and on the first 4096 chains."""
+    the cubic solver without the budgets that cannot be optimal on the step's long chain, the
+    quadratic-time solver on the ResNet-1001-shaped chain and on the first 4096 chains."""
     def timed(fn):
         fn()
         torch.cuda.synchronize()
@@ -96,6 +97,12 @@ def time_extras(torch, B, inputs, d, m, Bn, n, reps=3):
     out["select_baseline_sqrt"] = {"ms": t, "instances_per_s": Bn / (t * 1e-3),
                                    "hbm_GBs": Bn * (n + 1) / (t * 1e-3) / 1e9,
                                    "hbm_frac": Bn * (n + 1) / (t * 1e-3) / 1e9 / HBM_PEAK_GBS}
+    n1 = d1.shape[0] - 1
+    t = timed(lambda: B.ckpt_solve_cubic_pruned(d1, workspace=ws_cub, want_status=False))
+    run = int(B.ckpt_solve_cubic_pruned(d1, workspace=ws_cub, want_status=False)[3][0])
+    out[f"solve_cubic_pruned_n{n1}"] = {"ms": t, "instances_per_s": 1.0 / (t * 1e-3), "budgets_run": run,
+                                        "budgets": n1 * (n1 - 1) // 2 + 1,
+                                        "cells_evaluated_per_s": run * n1 / (t * 1e-3)}
     d4 = torch.from_numpy(inputs.config4()).to(d.device)
     n4 = d4.shape[0] - 1
     t = timed(lambda: B.ckpt_solve_quadratic(d4, want_values=False, want_status=False))
@@ -183,7 +190,7 @@ def main():
         out = step(events)
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
-    extras = None if args.no_extras else time_extras(torch, B, inputs, d, m, args.batch, args.n_batch)
+    extras = None if args.no_extras else time_extras(torch, B, inputs, d, m, d1, ws_cub, args.batch, args.n_batch)
     if args.copy_probe:
         probe = torch.empty_like(d)
         probe.copy_(d)

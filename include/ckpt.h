@@ -116,6 +116,24 @@ int ckpt_solve_cubic(const int64_t *d, const ckpt_layout *layout, uint8_t *mask_
                      int64_t *peak_out, int64_t *budget_out, int32_t *status_out,
                      void *ws, size_t ws_bytes, void *hip_stream);
 
+/* The same result as ckpt_solve_cubic, without running the recurrence for
+ * budgets that cannot be optimal.  Any cost s + c_s that has been reached
+ * bounds the optimum from above (UB), and c_s >= d_0 + d_n for every budget
+ * (both ends are checkpoints), so a budget s > UB - d_0 - d_n costs more than
+ * UB.  The call first runs one tile in 64 of the sorted budgets, takes UB from
+ * them, and then runs only the budgets up to the bound: the optimum, the
+ * smallest optimal budget and the canonical set are unchanged (the comparison
+ * is strict, so ties are never cut).  Chains whose values need 64-bit
+ * arithmetic, and chains of fewer than 2048 layers (where the two extra passes
+ * cost more than they save), are solved without pruning.
+ * evaluated_out [out] `batch` int64 or NULL: the number of budgets whose
+ * recurrence was run (sampled ones counted again when they run a second time),
+ * times n the recurrence cells actually evaluated; ckpt_solve_cubic always
+ * runs n(n-1)/2 + 1.  Other arguments and workspace as for ckpt_solve_cubic. */
+int ckpt_solve_cubic_pruned(const int64_t *d, const ckpt_layout *layout, uint8_t *mask_out,
+                            int64_t *peak_out, int64_t *budget_out, int64_t *evaluated_out,
+                            int32_t *status_out, void *ws, size_t ws_bytes, void *hip_stream);
+
 /* Optimal checkpoint set under Equation (memory) by the linear-time method of
  * Section 4.2 (Equation (TU), Lemmas 1-4, Algorithm 6, Theorem 3):
  *   M(n) = d_n,  M(i) = d_i + min_{i<j<=n} max(M(j), U(i,j)),

@@ -25,7 +25,7 @@ CALL_EVAL_PEAK, CALL_SOLVE_CUBIC, CALL_SOLVE_LINEAR = 0, 1, 2
 SELECT_ENDS, SELECT_ALL, SELECT_SQRT = 0, 1, 2
 
 EXPORTS = ("ckpt_workspace_bytes", "ckpt_eval_peak", "ckpt_eval_timeline", "ckpt_select_baseline",
-           "ckpt_solve_cubic", "ckpt_solve_linear", "ckpt_solve_quadratic", "ckpt_cubic_cells",
+           "ckpt_solve_cubic", "ckpt_solve_cubic_pruned", "ckpt_solve_linear", "ckpt_solve_quadratic", "ckpt_cubic_cells",
            "ckpt_status_string")
 
 
@@ -57,6 +57,8 @@ def load():
         lib.ckpt_select_baseline.argtypes = [LP, ctypes.c_int, vp, vp]
         lib.ckpt_solve_cubic.restype = ctypes.c_int
         lib.ckpt_solve_cubic.argtypes = [vp, LP, vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
+        lib.ckpt_solve_cubic_pruned.restype = ctypes.c_int
+        lib.ckpt_solve_cubic_pruned.argtypes = [vp, LP, vp, vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
         lib.ckpt_solve_linear.restype = ctypes.c_int
         lib.ckpt_solve_linear.argtypes = [vp, LP, vp, vp, vp, vp, ctypes.c_size_t, vp]
         lib.ckpt_solve_quadratic.restype = ctypes.c_int
@@ -186,6 +188,24 @@ def ckpt_solve_cubic(d, chain_major=False, workspace=None, want_status=True):
     if rc != CKPT_OK:
         raise CkptError("ckpt_solve_cubic", rc)
     return mask, peak, budget, status
+
+
+def ckpt_solve_cubic_pruned(d, chain_major=False, workspace=None, want_status=True):
+    """ckpt_solve_cubic without the budgets that cannot be optimal.  Returns
+    (mask, peak, budget, evaluated, status); evaluated counts the budgets run."""
+    _check_inputs(d)
+    L = layout_of(d, chain_major)
+    mask = torch.empty_strided(d.shape, d.stride(), dtype=torch.uint8, device=d.device)
+    peak = torch.empty(L.batch, dtype=torch.int64, device=d.device)
+    budget = torch.empty(L.batch, dtype=torch.int64, device=d.device)
+    evaluated = torch.empty(L.batch, dtype=torch.int64, device=d.device)
+    status = torch.empty(L.batch, dtype=torch.int32, device=d.device) if want_status else None
+    ws, ws_bytes = _workspace(CALL_SOLVE_CUBIC, L, d.device, workspace)
+    rc = load().ckpt_solve_cubic_pruned(_ptr(d), ctypes.byref(L), _ptr(mask), _ptr(peak), _ptr(budget),
+                                        _ptr(evaluated), _ptr(status), _ptr(ws), ws_bytes, _stream())
+    if rc != CKPT_OK:
+        raise CkptError("ckpt_solve_cubic_pruned", rc)
+    return mask, peak, budget, evaluated, status
 
 
 def ckpt_solve_linear(d, chain_major=False, workspace=None, want_status=True):

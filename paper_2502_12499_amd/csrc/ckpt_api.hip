@@ -25,6 +25,22 @@ int max_layers_of(int which)
 
 int finish(hipError_t e) { return e == hipSuccess ? CKPT_OK : CKPT_ERR_DEVICE; }
 
+// ckpt_solve_cubic and ckpt_solve_cubic_pruned: the same checks and launches
+int solve_cubic(const int64_t *d, const ckpt_layout *L, uint8_t *mask_out, int64_t *peak_out, int64_t *budget_out,
+                int32_t *status_out, bool pruned, int64_t *evaluated_out, void *ws, size_t ws_bytes,
+                void *hip_stream)
+{
+    const int rc = check_layout(L, CKPT_CUBIC_MAX_LAYERS);
+    if (rc != CKPT_OK) return rc;
+    if (L->batch == 0) return CKPT_OK;
+    if (!d || !mask_out || !peak_out || !ws) return CKPT_ERR_NULL;
+    if (((uintptr_t)ws & 255u) != 0 || ws_bytes < ckpt::cubic_workspace_bytes(L->batch, L->n_layers))
+        return CKPT_ERR_WORKSPACE;
+    return finish(ckpt::launch_solve_cubic(d, L->batch, L->n_layers, Strides{L->chain_stride, L->pos_stride},
+                                           mask_out, peak_out, budget_out, status_out, pruned, evaluated_out, ws,
+                                           (hipStream_t)hip_stream));
+}
+
 }  // namespace
 
 extern "C" {
@@ -87,15 +103,15 @@ int ckpt_select_baseline(const ckpt_layout *L, int kind, uint8_t *mask_out, void
 int ckpt_solve_cubic(const int64_t *d, const ckpt_layout *L, uint8_t *mask_out, int64_t *peak_out,
                      int64_t *budget_out, int32_t *status_out, void *ws, size_t ws_bytes, void *hip_stream)
 {
-    const int rc = check_layout(L, CKPT_CUBIC_MAX_LAYERS);
-    if (rc != CKPT_OK) return rc;
-    if (L->batch == 0) return CKPT_OK;
-    if (!d || !mask_out || !peak_out || !ws) return CKPT_ERR_NULL;
-    if (((uintptr_t)ws & 255u) != 0 || ws_bytes < ckpt::cubic_workspace_bytes(L->batch, L->n_layers))
-        return CKPT_ERR_WORKSPACE;
-    return finish(ckpt::launch_solve_cubic(d, L->batch, L->n_layers, Strides{L->chain_stride, L->pos_stride},
-                                           mask_out, peak_out, budget_out, status_out, ws,
-                                           (hipStream_t)hip_stream));
+    return solve_cubic(d, L, mask_out, peak_out, budget_out, status_out, false, nullptr, ws, ws_bytes, hip_stream);
+}
+
+int ckpt_solve_cubic_pruned(const int64_t *d, const ckpt_layout *L, uint8_t *mask_out, int64_t *peak_out,
+                            int64_t *budget_out, int64_t *evaluated_out, int32_t *status_out, void *ws,
+                            size_t ws_bytes, void *hip_stream)
+{
+    return solve_cubic(d, L, mask_out, peak_out, budget_out, status_out, true, evaluated_out, ws, ws_bytes,
+                       hip_stream);
 }
 
 int ckpt_solve_linear(const int64_t *d, const ckpt_layout *L, uint8_t *mask_out, int64_t *peak_out,

@@ -44,8 +44,10 @@ hipError_t launch_solve_quadratic(const int64_t *d, int64_t batch, int n, Stride
 
 // ---- solve_cubic -------------------------------------------------------------
 size_t cubic_workspace_bytes(int64_t batch, int n);
+// pruned: budgets that a sample of the budgets shows cannot be optimal are skipped (same results);
+// evaluated_out (may be null) receives the number of budgets whose recurrence was run, per chain
 hipError_t launch_solve_cubic(const int64_t *d, int64_t batch, int n, Strides st, uint8_t *mask_out,
-                              int64_t *peak_out, int64_t *budget_out, int32_t *status_out, void *ws,
-                              hipStream_t stream);
+                              int64_t *peak_out, int64_t *budget_out, int32_t *status_out, bool pruned,
+                              int64_t *evaluated_out, void *ws, hipStream_t stream);
 
 }  // namespace ckpt

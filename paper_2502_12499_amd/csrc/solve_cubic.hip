@@ -126,6 +126,8 @@ struct CubicWs {
     uint64_t *flags;      // [batch][waves_per_chain] lanes to recompute
     Partial *partial2;    // [batch][kReduceBlocks] second-level partial results (long chains only)
     int32_t *pred;        // [batch][n+1]
+    int32_t *prune;       // [batch] budgets above this (normalised) value cannot be optimal; pruned calls only
+    unsigned long long *evaluated;  // [batch] budgets whose recurrence was run; pruned calls only
 };
 
 __host__ __device__ inline int64_t num_budgets(int n) { return (int64_t)n * (n - 1) / 2 + 1; }
@@ -200,6 +202,8 @@ __host__ CubicWs carve_cubic(void *ws, int64_t batch, int n)
     w.flags = (uint64_t *)p;    p += align_up(B * wpc * 8);
     w.partial2 = (Partial *)p;  p += align_up(B * kReduceBlocks * sizeof(Partial));
     w.pred = (int32_t *)p;      p += align_up(B * n1 * 4);
+    w.prune = (int32_t *)p;     p += align_up(B * 4);
+    w.evaluated = (unsigned long long *)p; p += align_up(B * 8);
     return w;
 }
 
@@ -231,6 +235,10 @@ __global__ __launch_bounds__(kWave) void cubic_prologue_kernel(const int64_t *__
     const int64_t c = blockIdx.x;
     const int lane = threadIdx.x;
     if (c == 0 && lane == 0) *w.redo_count = 0;
+    if (lane == 0) {
+        w.prune[c] = INT32_MAX;
+        w.evaluated[c] = 0;
+    }
     const int64_t *dp = d + c * cstride;
     const int n1 = n + 1;
     const int chunk = (n1 + kWave - 1) / kWave;
@@ -776,8 +784,16 @@ __device__ __attribute__((noinline)) SharedLane shared_rare(SharedLane L, const 
 
 // With REDO the workgroups (one wave each) take the waves listed in w.redo
 // instead of the waves of their own index.
+// Otherwise workgroup b of a chain takes tile b * tile_stride of the sorted
+// budgets (tile_stride > 1: a sample of the budgets).  mode kSharedAll runs
+// every tile it is given; kSharedCount also adds the budgets it runs to
+// w.evaluated; kSharedPrune in addition skips a wave whose smallest budget is
+// above w.prune[c] (no budget of the wave can then be optimal).
+constexpr int kSharedAll = 0, kSharedCount = 1, kSharedPrune = 2;
+
 template <int RING, int BLOCK, bool REDO>
-__global__ __launch_bounds__(BLOCK) void cubic_shared_kernel(int n, int64_t blocks_per_chain, CubicWs w)
+__global__ __launch_bounds__(BLOCK) void cubic_shared_kernel(int n, int64_t blocks_per_chain, int tile_stride,
+                                                             int mode, CubicWs w)
 {
     typedef int32_t V;
     __shared__ __attribute__((aligned(RING * BLOCK * 8))) QueueEntry<V> ring[RING][BLOCK];
@@ -788,8 +804,9 @@ __global__ __launch_bounds__(BLOCK) void cubic_shared_kernel(int n, int64_t bloc
     const int64_t items = REDO ? *w.redo_count : 1;
     for (int64_t item = REDO ? blockIdx.x : 0; item < items; item += REDO ? gridDim.x : 1) {
     const int64_t listed = REDO ? w.redo[item] : 0;
-    const int64_t c = REDO ? listed / waves_per_chain(n) : blockIdx.x / blocks_per_chain;
-    const int64_t tile = REDO ? listed % waves_per_chain(n) : blockIdx.x % blocks_per_chain;
+    const int64_t launched = (blocks_per_chain + tile_stride - 1) / tile_stride;  // workgroups per chain
+    const int64_t c = REDO ? listed / waves_per_chain(n) : blockIdx.x / launched;
+    const int64_t tile = REDO ? listed % waves_per_chain(n) : (blockIdx.x % launched) * tile_stride;
     const ChainMeta meta = w.meta[c];
     if (meta.status != CKPT_OK || !meta.mode32) continue;
 
@@ -803,6 +820,20 @@ __global__ __launch_bounds__(BLOCK) void cubic_shared_kernel(int n, int64_t bloc
     if (wave_in_chain * kWave >= K) continue;
     const bool live = idx < K;
     const V s = live ? w.sorted[c * K + idx] : 0;
+    if (!REDO && mode != kSharedAll) {
+        const bool first = (tid & (kWave - 1)) == 0;
+        // budgets ascend along the sorted list: the wave's first lane holds its smallest
+        if (mode == kSharedPrune && __builtin_amdgcn_readfirstlane(s) > w.prune[c]) {
+            if (first) {
+                const int64_t slot_id = c * waves_per_chain(n) + wave_in_chain;
+                w.partial[slot_id] = Partial{kInf, (int64_t)s};
+                w.flags[slot_id] = 0;
+            }
+            continue;
+        }
+        const unsigned long long lanes = (unsigned long long)__popcll(__ballot(live));
+        if (first) atomicAdd(w.evaluated + c, lanes);
+    }
 
     typedef __attribute__((address_space(3))) V *LdsPtr;
     const uint32_t lane_base = (uint32_t)(uintptr_t)(LdsPtr)&ring[0][tid].F;
@@ -1182,19 +1213,66 @@ __global__ __launch_bounds__(BLOCK) void cubic_shared_kernel(int n, int64_t bloc
 
 constexpr int kRedoBlocks = 2048;
 
-// First all waves with a ring of RING entries per lane, then the waves in which
-// it was too small again with kRedoRing entries; lanes flagged after that are
-// left to the wave-per-budget kernel.
+constexpr int kSampleStride = 64;  // a pruned call first runs every 64th tile of the sorted budgets
+// Pruning costs two more passes of at least one wave's running time each, and the budgets it
+// keeps are the small ones, whose waves run longest: below this length it does not pay.
+constexpr int kPruneFromLayers = 2048;
+
+// From the sampled tiles' results: any s + c_s that was reached bounds the optimum from
+// above, and c_s >= d_0 + d_n for every s, so a budget above UB - d_0 - d_n cannot be
+// optimal (nor tie: the comparison is strict).  One workgroup per chain.
+__global__ __launch_bounds__(256) void cubic_bound_kernel(int n, int64_t blocks_per_chain, int tile_stride,
+                                                          int waves_per_tile, CubicWs w)
+{
+    __shared__ int64_t part[256];
+    const int64_t c = blockIdx.x;
+    const int tid = threadIdx.x;
+    if (c == 0 && tid == 0) *w.redo_count = 0;  // waves the sample flagged are run again anyway
+    const ChainMeta meta = w.meta[c];
+    if (meta.status != CKPT_OK || !meta.mode32) return;
+    const int64_t wpc = waves_per_chain(n);
+    const int64_t launched = (blocks_per_chain + tile_stride - 1) / tile_stride;
+    int64_t best = kInf;
+    for (int64_t t = tid; t < launched * waves_per_tile; t += 256) {
+        const int64_t wave = (t / waves_per_tile) * tile_stride * waves_per_tile + t % waves_per_tile;
+        if (wave < wpc) {
+            const int64_t cost = w.partial[c * wpc + wave].cost;
+            best = cost < best ? cost : best;
+        }
+    }
+    part[tid] = best;
+    __syncthreads();
+    for (int half = 128; half >= 1; half >>= 1) {
+        if (tid < half) part[tid] = part[tid + half] < part[tid] ? part[tid + half] : part[tid];
+        __syncthreads();
+    }
+    if (tid == 0 && part[0] != kInf) {
+        const El *el = w.el + (size_t)c * table_len(n);
+        w.prune[c] = (int32_t)(part[0] - el[0].d - el[n].d);
+    }
+}
+
+// All waves with a ring of RING entries per lane (for a pruned call: a sample of them, the
+// bound that the sample gives, then the waves that the bound leaves); then the waves in which
+// the ring was too small again with REDO_RING entries; lanes flagged after that are left to
+// the wave-per-budget kernel.
 template <int RING, int BLOCK, int REDO_RING>
-void launch_shared(int n, int64_t batch, CubicWs w, hipStream_t stream)
+void launch_shared(int n, int64_t batch, bool pruned, CubicWs w, hipStream_t stream)
 {
     const int64_t blocks_per_chain = (num_budgets(n) + BLOCK - 1) / BLOCK;
+    if (pruned) {
+        const int64_t sampled = (blocks_per_chain + kSampleStride - 1) / kSampleStride;
+        hipLaunchKernelGGL((cubic_shared_kernel<RING, BLOCK, false>), dim3((unsigned)(sampled * batch)), dim3(BLOCK),
+                           0, stream, n, blocks_per_chain, kSampleStride, kSharedCount, w);
+        hipLaunchKernelGGL(cubic_bound_kernel, dim3((unsigned)batch), dim3(256), 0, stream, n, blocks_per_chain,
+                           kSampleStride, BLOCK / kWave, w);
+    }
     hipLaunchKernelGGL((cubic_shared_kernel<RING, BLOCK, false>), dim3((unsigned)(blocks_per_chain * batch)),
-                       dim3(BLOCK), 0, stream, n, blocks_per_chain, w);
+                       dim3(BLOCK), 0, stream, n, blocks_per_chain, 1, pruned ? kSharedPrune : kSharedAll, w);
     const int64_t waves = waves_per_chain(n) * batch;
     hipLaunchKernelGGL((cubic_shared_kernel<REDO_RING, kWave, true>),
                        dim3((unsigned)(waves < kRedoBlocks ? waves : kRedoBlocks)), dim3(kWave), 0, stream, n,
-                       blocks_per_chain, w);
+                       blocks_per_chain, 1, kSharedAll, w);
 }
 
 // ---- one budget per wave ---------------------------------------------------------
@@ -1491,7 +1569,9 @@ __global__ __launch_bounds__(kWave) void cubic_epilogue_kernel(int n, size_t lds
                                                                int64_t pstride, uint8_t *__restrict__ mask_out,
                                                                int64_t *__restrict__ peak_out,
                                                                int64_t *__restrict__ budget_out,
-                                                               int32_t *__restrict__ status_out, CubicWs w)
+                                                               int32_t *__restrict__ status_out,
+                                                               int64_t *__restrict__ evaluated_out, bool pruned,
+                                                               CubicWs w)
 {
     const int64_t c = blockIdx.x;
     const int lane = threadIdx.x;
@@ -1499,6 +1579,9 @@ __global__ __launch_bounds__(kWave) void cubic_epilogue_kernel(int n, size_t lds
     const ChainMeta meta = w.meta[c];
     uint8_t *mp = mask_out + c * cstride;
     if (lane == 0 && status_out) status_out[c] = meta.status;
+    if (lane == 0 && evaluated_out)  // only the 32-bit path prunes
+        evaluated_out[c] = meta.status != CKPT_OK ? 0
+                           : (pruned && meta.mode32) ? (int64_t)w.evaluated[c] : num_budgets(n);
     if (meta.status != CKPT_OK) {
         for (int k = lane; k < n1; k += kWave) mp[(int64_t)k * pstride] = 0;
         if (lane == 0) {
@@ -1557,14 +1640,16 @@ size_t cubic_workspace_bytes(int64_t batch, int n)
            align_up(B * step_len(n) * sizeof(Step)) + 2 * align_up(B * (size_t)num_budgets(n) * 4) +
            align_up(sort_tmp_bytes(batch, n)) + 256 + align_up(B * wpc * 8) +
            align_up(B * wpc * sizeof(Partial)) + align_up(B * wpc * 8) +
-           align_up(B * kReduceBlocks * sizeof(Partial)) + align_up(B * n1 * 4) + 256;
+           align_up(B * kReduceBlocks * sizeof(Partial)) + align_up(B * n1 * 4) + align_up(B * 4) +
+           align_up(B * 8) + 256;
 }
 
 hipError_t launch_solve_cubic(const int64_t *d, int64_t batch, int n, Strides st, uint8_t *mask_out,
-                              int64_t *peak_out, int64_t *budget_out, int32_t *status_out, void *ws,
-                              hipStream_t stream)
+                              int64_t *peak_out, int64_t *budget_out, int32_t *status_out, bool pruned,
+                              int64_t *evaluated_out, void *ws, hipStream_t stream)
 {
     if (batch == 0) return hipSuccess;
+    pruned = pruned && n >= kPruneFromLayers;
     CubicWs w = carve_cubic(ws, batch, n);
     const int64_t K = num_budgets(n);
     const int64_t total_blocks = (K + 127) / 128 * batch;
@@ -1592,7 +1677,7 @@ hipError_t launch_solve_cubic(const int64_t *d, int64_t batch, int n, Strides st
             if (e != hipSuccess) return e;
         }
     }
-    launch_shared<16, 256, 64>(n, batch, w, stream);
+    launch_shared<16, 256, 64>(n, batch, pruned, w, stream);
     launch_budgets<int64_t, 16, 256>(n, batch, w, stream);
     const int64_t word_groups = (n_words + kWave - 1) / kWave;
     const unsigned over_grid = (unsigned)(word_groups < 4096 ? word_groups : 4096);
@@ -1607,7 +1692,7 @@ hipError_t launch_solve_cubic(const int64_t *d, int64_t batch, int n, Strides st
     for (const size_t wish : wishes)
         if (wish <= 65536 && wish > epi_lds) epi_lds = wish;
     hipLaunchKernelGGL(cubic_epilogue_kernel, dim3((unsigned)batch), dim3(kWave), epi_lds, stream, n, epi_lds,
-                       st.chain, st.pos, mask_out, peak_out, budget_out, status_out, w);
+                       st.chain, st.pos, mask_out, peak_out, budget_out, status_out, evaluated_out, pruned, w);
     return hipGetLastError();
 }
 

@@ -53,6 +53,14 @@ def test_config5_single_chain_cubic_n4096():
     assert int(status.cpu()[0]) == 0
     assert int(peak.cpu()[0]) == v and int(budget.cpu()[0]) == s
     assert np.array_equal(mask.cpu().numpy()[:, 0], mk)
+    say("  the same without the budgets that cannot be optimal")
+    mask, peak, budget, evaluated, status = B.ckpt_solve_cubic_pruned(torch.from_numpy(d).to(DEV))
+    assert int(status.cpu()[0]) == 0
+    assert int(peak.cpu()[0]) == v and int(budget.cpu()[0]) == s
+    assert np.array_equal(mask.cpu().numpy()[:, 0], mk)
+    K = 4096 * 4095 // 2 + 1
+    say(f"  {int(evaluated.cpu()[0])} of {K} budgets run")
+    assert int(evaluated.cpu()[0]) < K // 8
 
 
 def test_config5_full_batch_linear_and_eval():

@@ -59,19 +59,27 @@ def check_linear(d, chain_major=False):
 
 
 def check_cubic(d, chain_major=False):
+    """Both forms of the call (every budget; without the budgets that cannot be optimal)."""
     dc = inputs.chain_major(d)
-    if chain_major:
-        mask, peak, budget, status = B.ckpt_solve_cubic(to_dev(dc), chain_major=True)
-        got_mask = np_(mask)
-    else:
-        mask, peak, budget, status = B.ckpt_solve_cubic(to_dev(d))
-        got_mask = np_(mask).T
-    torch.cuda.synchronize()
     want_peak, want_mask, want_s = oracle.batch_solve_static(dc)
-    assert (np_(status) == 0).all()
-    assert np.array_equal(np_(peak), want_peak)
-    assert np.array_equal(np_(budget), want_s)
-    assert np.array_equal(got_mask, want_mask)
+    n = d.shape[0] - 1
+    K = n * (n - 1) // 2 + 1
+    for pruned in (False, True):
+        x = to_dev(dc) if chain_major else to_dev(d)
+        if pruned:
+            mask, peak, budget, evaluated, status = B.ckpt_solve_cubic_pruned(x, chain_major=chain_major)
+            # at most every budget once plus the sampled tiles (whole tiles of 256) a second time
+            assert bool((evaluated >= 1).all()) and bool((evaluated <= K + K // 64 + 512).all()), "evaluated"
+            if n < 2048:
+                assert bool((evaluated == K).all())
+        else:
+            mask, peak, budget, status = B.ckpt_solve_cubic(x, chain_major=chain_major)
+        torch.cuda.synchronize()
+        got_mask = np_(mask) if chain_major else np_(mask).T
+        assert (np_(status) == 0).all()
+        assert np.array_equal(np_(peak), want_peak), f"pruned={pruned}"
+        assert np.array_equal(np_(budget), want_s), f"pruned={pruned}"
+        assert np.array_equal(got_mask, want_mask), f"pruned={pruned}"
 
 
 def special_chains():
@@ -251,3 +259,28 @@ def test_solve_cubic_data_errors():
     for c in (0, 3):
         v, mk, s = oracle.solve_static(d[:, c])
         assert np_(peak)[c] == v and np_(budget)[c] == s and (np_(mask)[:, c] == mk).all()
+    mask, peak, budget, evaluated, status = B.ckpt_solve_cubic_pruned(to_dev(d))
+    assert np_(status).tolist() == [0, 3, 4, 0]
+    assert np_(peak)[[1, 2]].tolist() == [-1, -1] and np_(evaluated)[[1, 2]].tolist() == [0, 0]
+    for c in (0, 3):
+        v, mk, s = oracle.solve_static(d[:, c])
+        assert np_(peak)[c] == v and np_(budget)[c] == s and (np_(mask)[:, c] == mk).all()
+
+
+def test_solve_cubic_pruned_runs_few_budgets_on_long_chains():
+    """Where the optimum is far below the sum of the sizes most budgets cannot be optimal."""
+    n = 2500
+    say(f"solve_cubic_pruned n={n}: budgets run")
+    d = inputs.config5_single(n)
+    K = n * (n - 1) // 2 + 1
+    mask, peak, budget, evaluated, status = B.ckpt_solve_cubic_pruned(to_dev(d))
+    v, mk, s = oracle.solve_static(d[:, 0])
+    assert int(peak[0]) == v and int(budget[0]) == s and (np_(mask)[:, 0] == mk).all()
+    b = oracle.budgets(d[:, 0])
+    must = int((b <= v - d[0, 0] - d[n, 0]).sum())      # what the exact bound would leave
+    assert must <= int(evaluated[0]) <= K // 4
+    say(f"  {int(evaluated[0])} of {K} budgets run (the exact bound leaves {must})")
+    # shorter chains are solved without pruning
+    d = inputs.config4()
+    _, _, _, evaluated, _ = B.ckpt_solve_cubic_pruned(to_dev(d))
+    assert int(evaluated[0]) == 1001 * 1000 // 2 + 1
