@@ -11,7 +11,7 @@
 namespace ckpt {
 namespace {
 
-constexpr int kBlock = 256;
+constexpr int kBlock = 64;
 
 template <int OBJ>
 __global__ __launch_bounds__(kBlock) void eval_peak_kernel(const int64_t *__restrict__ d,
@@ -40,10 +40,10 @@ __global__ __launch_bounds__(kBlock) void eval_peak_kernel(const int64_t *__rest
     int64_t best = 0;       // OBJ 0: largest segment; OBJ 1: largest m(i)
     uint8_t last_mask = 1;
 
-#pragma unroll 8
+#pragma unroll 16
     for (int k = 1; k <= n; ++k) {
-        const int64_t x = dp[(int64_t)k * pstride];
-        const uint8_t m = mp[(int64_t)k * pstride];
+        const int64_t x = __builtin_nontemporal_load(dp + (int64_t)k * pstride);
+        const uint8_t m = __builtin_nontemporal_load(mp + (int64_t)k * pstride);
         bad_size |= x <= 0;
         total += (uint64_t)x;
         ovf |= total > (uint64_t)INT64_MAX;
