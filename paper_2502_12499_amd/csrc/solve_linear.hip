@@ -87,6 +87,17 @@ __host__ LinearWs carve_linear(void *ws, int64_t batch, int n)
 
 __global__ void linear_reset_kernel(LinearWs w) { w.count[0] = 0; w.count[1] = 0; }
 
+// Puts every chain on the first deferred list (layouts the ring kernel does not address).
+__global__ void linear_defer_all_kernel(int64_t batch, LinearWs w)
+{
+    const int64_t c = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (c < batch) w.list[c] = (int32_t)c;
+    if (c == 0) w.count[0] = (int32_t)batch;
+}
+
+// Largest chain stride (elements) for which 63 strides of 8-byte elements fit a 32-bit offset.
+constexpr int64_t kRingMaxChainStride = (int64_t)1 << 22;
+
 // ---------------------------------------------------------------------------
 // ring kernel
 // ---------------------------------------------------------------------------
@@ -114,10 +125,25 @@ __global__ __launch_bounds__(kWave) void linear_ring_kernel(const int64_t *__res
     static_assert(kStep * kRing == 16384, "ring size and alignment");
 
     const int lane = threadIdx.x;
-    const int64_t c = (int64_t)blockIdx.x * kWave + lane;
+    const int64_t c0 = (int64_t)blockIdx.x * kWave;
+    const int64_t c = c0 + lane;
     const bool live = c < batch;
     const int64_t cc = live ? c : batch - 1;  // idle lanes shadow the last chain and write nothing
-    const int64_t *dp = d + cc * cstride;
+    // Addresses are a wave-uniform base (scalar registers) plus a 32-bit lane offset: the
+    // launcher only takes this kernel when 63 chain strides fit 31 bits.
+    const char *dbase = (const char *)(d + c0 * cstride);
+    uint8_t *mbase = mask_out + c0 * cstride;
+    const uint32_t doff = (uint32_t)((cc - c0) * cstride) * 8u;
+    const uint32_t moff = (uint32_t)((cc - c0) * cstride);
+    // a wave-uniform 64-bit value, moved to scalar registers
+    auto scalar = [](uint64_t a) -> uint64_t {
+        return ((uint64_t)(uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)(a >> 32)) << 32) |
+               (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)a);
+    };
+    auto row = [&](int k) -> int64_t {  // k is the same in every lane: the row's base stays scalar
+        const int ks = __builtin_amdgcn_readfirstlane(k);
+        return *(const int64_t *)(dbase + (int64_t)ks * pstride * 8 + doff);
+    };
     uint8_t *mp = mask_out + cc * cstride;
     constexpr uint32_t kLimit = 1u << 30;       // bound on T(i) + d_i + max d, hence on every M(i) and U(i,j)
     constexpr uint32_t kChunkLimit = 1u << 26;  // bound on a single size (kChunk of them leave T below 2^31)
@@ -126,7 +152,7 @@ __global__ __launch_bounds__(kWave) void linear_ring_kernel(const int64_t *__res
     const uint32_t lane_base = (uint32_t)(uintptr_t)(LdsPtr)&ring[0][lane].M;
     auto entry = [&](uint32_t pos) -> LdsPtr { return (LdsPtr)(uintptr_t)((pos & kSlotMask) | lane_base); };
 
-    const int64_t xn = dp[(int64_t)n * pstride];
+    const int64_t xn = row(n);
     bool defer = xn <= 0;
     int sh = defer ? 0 : __ffsll((unsigned long long)xn) - 1;
     sh = sh < 31 ? sh : 31;  // so that a size's low word alone says whether it is a multiple of 2^sh
@@ -144,19 +170,21 @@ __global__ __launch_bounds__(kWave) void linear_ring_kernel(const int64_t *__res
     uint32_t Mc = kNone, Ac = kNone, Jc = 0, Rc = 0;  // candidate (the entry before pt): M, A, j, R(i, j)
     uint32_t Ti = 0;                           // T(i) / 2^sh
     uint32_t dnext = (uint32_t)xs;             // d_{i+1} / 2^sh
-    uint32_t dmax = dnext, dmin = dnext;
-    uint32_t smax = 0;  // longest step chosen
+    uint32_t dmax = dnext;                     // a bound on the sizes so far (below twice the largest)
     uint32_t Mi = dnext;
     {
         LdsPtr e = entry(0);
         e[0] = Mhd; e[1] = 0; e[2] = Mhd; e[3] = (uint32_t)n;  // T(n) = 0
     }
 
-    // One step of the recurrence for position i, whose size x is already in a register.
-    // Range and alignment are settled for kChunk rows at a time, before their steps:
-    // `all` is the OR of the rows (so its trailing zeros are the fewest of theirs and
-    // its magnitude bounds each of them; a negative size shows as a huge one).
-    auto chunk_check = [&](const uint64_t all) {
+    // Range and alignment are settled for kChunk rows at a time, before their steps, and a
+    // lane that cannot go on is switched off for good (its chain goes on the deferred list):
+    // the lanes that run a step hold exact values, which is what ends the loops below and
+    // keeps the stack's entries in order.
+    // `all` is the OR of the rows (so its trailing zeros are the fewest of theirs and its
+    // magnitude bounds each of them; a negative size shows as a huge one), `zero` says that
+    // one of them is 0, `ilow` is the lowest position of the chunk.
+    auto chunk_check = [&](const uint64_t all, const bool zero, const int ilow) {
         const uint32_t low = (uint32_t)all & ((1u << sh) - 1u);
         if (__builtin_amdgcn_ballot_w64(low != 0) != 0) {
             if (low != 0) {
@@ -179,17 +207,19 @@ __global__ __launch_bounds__(kWave) void linear_ring_kernel(const int64_t *__res
                 sh = tz;
             }
         }
-        // sizes below 2^26 and T(i) + d + max d below 2^30 now: no sum of this chunk wraps
-        defer |= (all >> sh) >= kChunkLimit;
+        // sizes positive and below 2^26, T(i) + d + max d below 2^30 now: no sum of this chunk wraps
+        const uint64_t scaled = all >> sh;
+        defer |= zero | (scaled >= kChunkLimit);
+        dmax = (uint32_t)scaled > dmax ? (uint32_t)scaled : dmax;
         defer |= (Ti + dnext + dmax) >= kLimit;
+        // every step of the chunk is at most j_pt - i - 1 of its lowest position: one byte holds it
+        defer |= (Jpt - (uint32_t)ilow) > 256u;
     };
 
     // One step of the recurrence for position i, whose size x is already in a register.
     auto step_fn = [&](const int i, const int64_t x) {
         const uint32_t di = __builtin_amdgcn_alignbit((uint32_t)((uint64_t)x >> 32), (uint32_t)x, (uint32_t)sh);
-        dmin = di < dmin ? di : dmin;  // a size of zero
         Ti += dnext;
-        dmax = di > dmax ? di : dmax;
         Rp = di > Rp ? di : Rp;
         Rc = di > Rc ? di : Rc;
 
@@ -268,46 +298,44 @@ __global__ __launch_bounds__(kWave) void linear_ring_kernel(const int64_t *__res
         const uint32_t nx = take_cand ? Jc : Jpt;
         Mi = di + best;
         const uint32_t step = nx - (uint32_t)i - 1u;
-        smax = step > smax ? step : smax;
         // Parked with a store the compiler does not count, so that its waits on the
         // rows fetched ahead stay partial (a counted store would make it wait for
         // everything in flight; an uncounted one can only lengthen a wait).
-        if (live)
-            asm volatile("global_store_byte %0, %1, off" : : "v"(mp + (int64_t)i * pstride), "v"(step) : "memory");
+        if (live) {
+            const uint64_t rowbase = scalar((uint64_t)(uintptr_t)(mbase + (int64_t)i * pstride));
+            // The compiler may form the scalar base with v_readfirstlane right before this
+            // statement; a vector memory instruction must not read such a register within five
+            // wait states, and the compiler does not look inside the statement: wait here.
+            asm volatile("s_nop 4\n\tglobal_store_byte %0, %1, %2" : : "v"(moff), "v"(step), "s"(rowbase) : "memory");
+        }
 
         // Q: drop the entries that M(i) dominates (never the crossover entry),
         // folding their G into the new entry's, then push i
         uint32_t Gacc = di;
         {
             // up to three drops are decided on the mirrors.  The crossover entry is never
-            // dropped: for a chain in range M(i) is above its value anyway, but a lane whose
-            // values have gone wrong (it will be deferred) must keep hd >= pt too, or the
-            // loops over the ring would not end
-            const uint32_t room = hd - pt;
-            const bool p0 = (Mhd >= Mi) & (room >= kStep);
-            const bool p1 = p0 & (M1 >= Mi) & (room >= 2 * kStep);
-            const bool p2 = p1 & (M2 >= Mi) & (room >= 3 * kStep);
-            const bool p3 = p2 & (M3 >= Mi) & (room >= 4 * kStep);
+            // dropped, M(i) being above its value, and the tests are nested, so what the
+            // mirrors hold beyond it is never looked at.
+            const bool p0 = Mhd >= Mi;
+            const bool p1 = p0 & (M1 >= Mi);
+            const bool p2 = p1 & (M2 >= Mi);
+            const bool p3 = p2 & (M3 >= Mi);
             Gacc = p0 ? (Ghd > Gacc ? Ghd : Gacc) : Gacc;
             Gacc = p1 ? (G1 > Gacc ? G1 : Gacc) : Gacc;
             Gacc = p2 ? (G2 > Gacc ? G2 : Gacc) : Gacc;
             hd -= p0 ? kStep : 0u;
             hd -= p1 ? kStep : 0u;
             hd -= p2 ? kStep : 0u;
-            Mhd = p2 ? M3 : (p1 ? M2 : (p0 ? M1 : Mhd));
-            Ghd = p2 ? G3 : (p1 ? G2 : (p0 ? G1 : Ghd));
             if (__builtin_amdgcn_ballot_w64(p3) != 0) {
-                // more: from the ring, one at a time (the position test also ends the loop
-                // for a lane whose values have gone wrong and that will be deferred)
-                uint32_t ad, t0;
-                uint64_t sv, st;
+                // more: from the ring, one at a time, down to the crossover entry at the latest.
+                // The lanes concerned go on from the third mirror; the others fail the first test.
+                Mhd = p3 ? M3 : 0u;
+                Ghd = G3;
+                uint32_t ad;
+                uint64_t sv;
                 asm volatile(
                     "Lq_%=:\n\t"
-                    "v_sub_u32 %[t0], %[hd], %[pt]\n\t"
-                    "v_subrev_u32 %[t0], 1, %[t0]\n\t"
                     "v_cmp_ge_u32 vcc, %[Mhd], %[Mi]\n\t"
-                    "v_cmp_gt_u32 %[st], %[span], %[t0]\n\t"
-                    "s_and_b64 vcc, vcc, %[st]\n\t"
                     "s_cbranch_vccz Lq_done_%=\n\t"
                     "s_and_saveexec_b64 %[sv], vcc\n\t"
                     "v_max_u32 %[G], %[G], %[Ghd]\n\t"
@@ -319,14 +347,16 @@ __global__ __launch_bounds__(kWave) void linear_ring_kernel(const int64_t *__res
                     "s_mov_b64 exec, %[sv]\n\t"
                     "s_branch Lq_%=\n\t"
                     "Lq_done_%=:\n\t"
-                    : [hd] "+v"(hd), [Mhd] "+v"(Mhd), [Ghd] "+v"(Ghd), [G] "+v"(Gacc), [ad] "=&v"(ad), [t0] "=&v"(t0),
-                      [sv] "=&s"(sv), [st] "=&s"(st)
-                    : [Mi] "v"(Mi), [pt] "v"(pt), [lo] "v"(lane_base), [mask] "s"(kSlotMask), [step] "i"(kStep),
-                      [span] "s"((uint32_t)kRing * kStep)
+                    : [hd] "+v"(hd), [Mhd] "+v"(Mhd), [Ghd] "+v"(Ghd), [G] "+v"(Gacc), [ad] "=&v"(ad), [sv] "=&s"(sv)
+                    : [Mi] "v"(Mi), [lo] "v"(lane_base), [mask] "s"(kSlotMask), [step] "i"(kStep)
                     : "vcc", "memory");
             }
         }
-        hd += kStep;
+        // a ring that is full keeps its entries: the chain is deferred and the new entry
+        // takes the head's slot, so that the lane's stack stays in order for the rest of the chunk
+        const bool full = (hd - pt) >= (uint32_t)(kRing - 1) * kStep;
+        defer |= full;
+        hd += full ? 0u : kStep;
         {
             LdsPtr e = entry(hd);
             e[0] = Mi; e[1] = Gacc; e[2] = Mi + Ti; e[3] = (uint32_t)i;
@@ -339,7 +369,6 @@ __global__ __launch_bounds__(kWave) void linear_ring_kernel(const int64_t *__res
             M2 = e2[0]; G2 = e2[1];
             M3 = e3[0]; G3 = e3[1];
         }
-        defer |= (hd - pt) >= (uint32_t)kRing * kStep;
         const bool fresh = hd == pt + kStep;  // the new entry is the candidate; R(i', i) starts empty
         Mc = fresh ? Mi : Mc;
         Ac = fresh ? Mi + Ti : Ac;
@@ -352,22 +381,28 @@ __global__ __launch_bounds__(kWave) void linear_ring_kernel(const int64_t *__res
     // latency of a row overlaps the work on the rows before it.
     int64_t rows[kChunk], ahead[kChunk];
 #pragma unroll
-    for (int u = 0; u < kChunk; ++u) rows[u] = dp[(int64_t)max(n - 1 - u, 0) * pstride];
+    for (int u = 0; u < kChunk; ++u) rows[u] = row(max(n - 1 - u, 0));
     for (int ihi = n - 1; ihi >= 0; ihi -= kChunk) {
 #pragma unroll
         for (int u = 0; u < kChunk; ++u)  // rows below 0 re-read row 0 and are not used
-            ahead[u] = dp[(int64_t)max(ihi - kChunk - u, 0) * pstride];
+            ahead[u] = row(max(ihi - kChunk - u, 0));
         uint64_t all = 0;
+        bool zero = false;
 #pragma unroll
-        for (int u = 0; u < kChunk; ++u) all |= (uint64_t)rows[ihi - u >= 0 ? u : 0];
-        chunk_check(all);
+        for (int u = 0; u < kChunk; ++u) {
+            const uint64_t x = (uint64_t)rows[u];  // a row below 0 holds row 0 again: harmless here
+            all |= x;
+            zero |= x == 0;
+        }
+        if (!defer) chunk_check(all, zero, max(ihi - kChunk + 1, 0));
+        if (!defer) {
 #pragma unroll
-        for (int u = 0; u < kChunk; ++u)
-            if (ihi - u >= 0) step_fn(ihi - u, rows[u]);
+            for (int u = 0; u < kChunk; ++u)
+                if (ihi - u >= 0) step_fn(ihi - u, rows[u]);
+        }
 #pragma unroll
         for (int u = 0; u < kChunk; ++u) rows[u] = ahead[u];
     }
-    defer |= dmin == 0 || smax > 255u || (Ti + dnext + dmax) >= kLimit;
 
     if (!live) return;
     if (defer) {
@@ -633,8 +668,12 @@ hipError_t launch_solve_linear(const int64_t *d, int64_t batch, int n, Strides s
     LinearWs w = carve_linear(ws, batch, n);
     const unsigned grid = (unsigned)((batch + kWave - 1) / kWave);
     hipLaunchKernelGGL(linear_reset_kernel, dim3(1), dim3(1), 0, stream, w);
-    hipLaunchKernelGGL(linear_ring_kernel, dim3(grid), dim3(kWave), 0, stream, d, batch, n, st.chain, st.pos,
-                       mask_out, peak_out, status_out, w);
+    if (st.chain <= kRingMaxChainStride)
+        hipLaunchKernelGGL(linear_ring_kernel, dim3(grid), dim3(kWave), 0, stream, d, batch, n, st.chain, st.pos,
+                           mask_out, peak_out, status_out, w);
+    else
+        hipLaunchKernelGGL(linear_defer_all_kernel, dim3((unsigned)((batch + 255) / 256)), dim3(256), 0, stream,
+                           batch, w);
     const int64_t wide_blocks = (batch + kWave - 1) / kWave;
     hipLaunchKernelGGL(linear_wide_kernel, dim3((unsigned)(wide_blocks < kWideBlocks ? wide_blocks : kWideBlocks)),
                        dim3(kWave), 0, stream, d, n, st.chain, st.pos, mask_out, peak_out, status_out, w);
