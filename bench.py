@@ -223,6 +223,7 @@ def main():
     }
     for k in ("eval_static", "eval_dynamic", "solve_linear"):
         kernels[k]["hbm_frac"] = kernels[k]["hbm_GBs"] / HBM_PEAK_GBS
+        kernels[k]["algorithmic_bytes"] = Bn * chain_bytes
     kernels["solve_cubic"]["int32_frac"] = kernels["solve_cubic"]["int32_TOPs"] / INT32_PEAK_TOPS
 
     # HBM bytes per launch of the kernels the rooflines are about, from the rocprofv3 FETCH_SIZE /
@@ -231,6 +232,10 @@ def main():
     default_workload = (Bn, n, nc) == (1048576, 256, 4096)
     traffic_cubic = 39.9e6 + 3.2e6 if default_workload else None
     traffic_linear = 2.695e9 + 0.534e9 if default_workload else None
+    traffic_eval = 2.695e9 + 8.4e6 if default_workload else None
+    kernels["eval_static"]["traffic"] = kernels["eval_dynamic"]["traffic"] = traffic_eval
+    kernels["solve_linear"]["traffic"] = traffic_linear
+    kernels["solve_cubic"]["traffic"] = traffic_cubic
     dominant = max(names, key=lambda k: ms[k])
     if dominant == "solve_cubic":
         roofline = {"kernel": "cubic_shared_kernel (timed as the whole ckpt_solve_cubic call)", "bound": "alu",
