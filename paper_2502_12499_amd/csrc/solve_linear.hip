@@ -102,12 +102,16 @@ constexpr int64_t kRingMaxChainStride = (int64_t)1 << 22;
 // ring kernel
 // ---------------------------------------------------------------------------
 
-struct RingEntry {
-    uint32_t M;  // M(j)
-    uint32_t G;  // max of d over [j, j'), j' the next entry towards the far end
-    uint32_t A;  // M(j) + T(j)
-    uint32_t J;  // j
-};
+// A ring entry is three words, each in a plane of its own laid out [slot][lane]
+// (so the 64 lanes of a wave always hit 64 different words of a plane, whatever
+// slot each of them is at: no bank conflicts):
+//   M    M(j)
+//   A    M(j) + T(j)
+//   GJ   G << 8 | (j & 255), G = max of d over [j, j'), j' the next entry towards the
+//        far end.  A maximum over such words orders by G first, which is all the
+//        folds below need; the low byte of j is enough because a step is at most
+//        255 positions (checked per chunk), and a byte is what gets stored of it.
+constexpr int kPlaneM = 0, kPlaneA = 1, kPlaneGJ = 2, kPlanes = 3;
 
 __global__ __launch_bounds__(kWave) void linear_ring_kernel(const int64_t *__restrict__ d, int64_t batch, int n,
                                                             int64_t cstride, int64_t pstride,
@@ -118,11 +122,13 @@ __global__ __launch_bounds__(kWave) void linear_ring_kernel(const int64_t *__res
     // Ring positions are kept pre-multiplied by the byte stride of a slot, so
     // the LDS address of a position is one AND-OR away (the ring is aligned to
     // its own size).
-    __shared__ __attribute__((aligned(16384))) RingEntry ring[kRing][kWave];
-    constexpr uint32_t kStep = (uint32_t)(kWave * sizeof(RingEntry));
+    __shared__ __attribute__((aligned(4096))) uint32_t ring[kPlanes][kRing][kWave];
+    constexpr uint32_t kStep = (uint32_t)(kWave * sizeof(uint32_t));  // bytes from a slot to the next
     constexpr uint32_t kSlotMask = (uint32_t)(kRing - 1) * kStep;
+    constexpr uint32_t kPlane = (uint32_t)kRing * kStep;              // bytes from a plane to the next
+    constexpr int kA = kPlaneA * (int)(kPlane / 4), kGJ = kPlaneGJ * (int)(kPlane / 4);  // in words
     constexpr uint32_t kNone = 0xffffffffu;  // "no candidate": never passes a test
-    static_assert(kStep * kRing == 16384, "ring size and alignment");
+    static_assert(kPlane == 4096, "plane size and alignment");
 
     const int lane = threadIdx.x;
     const int64_t c0 = (int64_t)blockIdx.x * kWave;
@@ -146,10 +152,10 @@ __global__ __launch_bounds__(kWave) void linear_ring_kernel(const int64_t *__res
     };
     uint8_t *mp = mask_out + cc * cstride;
     constexpr uint32_t kLimit = 1u << 30;       // bound on T(i) + d_i + max d, hence on every M(i) and U(i,j)
-    constexpr uint32_t kChunkLimit = 1u << 26;  // bound on a single size (kChunk of them leave T below 2^31)
+    constexpr uint32_t kChunkLimit = 1u << 24;  // bound on a single size (it shares a word with a byte of j)
 
     typedef __attribute__((address_space(3))) uint32_t *LdsPtr;
-    const uint32_t lane_base = (uint32_t)(uintptr_t)(LdsPtr)&ring[0][lane].M;
+    const uint32_t lane_base = (uint32_t)(uintptr_t)(LdsPtr)&ring[kPlaneM][0][lane];
     auto entry = [&](uint32_t pos) -> LdsPtr { return (LdsPtr)(uintptr_t)((pos & kSlotMask) | lane_base); };
 
     const int64_t xn = row(n);
@@ -161,8 +167,8 @@ __global__ __launch_bounds__(kWave) void linear_ring_kernel(const int64_t *__res
 
     // Q = {n}: it is the crossover entry (U(i,n) > d_n = M(n) for every i)
     uint32_t hd = 0, pt = 0;                   // ring positions of the head and of the crossover entry
-    uint32_t Mhd = (uint32_t)xs, Ghd = 0;      // M and G of the head entry
-    // (M, G) of the three entries under the head, read back after every push so
+    uint32_t Mhd = (uint32_t)xs, Ghd = 0;      // M and GJ of the head entry
+    // (M, GJ) of the three entries under the head, read back after every push so
     // that the steps that follow find them in registers (what lies beyond the
     // crossover entry is never looked at, so it does not matter what they hold there)
     uint32_t M1 = 0, G1 = 0, M2 = 0, G2 = 0, M3 = 0, G3 = 0;
@@ -174,7 +180,7 @@ __global__ __launch_bounds__(kWave) void linear_ring_kernel(const int64_t *__res
     uint32_t Mi = dnext;
     {
         LdsPtr e = entry(0);
-        e[0] = Mhd; e[1] = 0; e[2] = Mhd; e[3] = (uint32_t)n;  // T(n) = 0
+        e[0] = Mhd; e[kA] = Mhd; e[kGJ] = (uint32_t)n & 255u;  // T(n) = 0, nothing beyond n
     }
 
     // Range and alignment are settled for kChunk rows at a time, before their steps, and a
@@ -194,20 +200,21 @@ __global__ __launch_bounds__(kWave) void linear_ring_kernel(const int64_t *__res
                 const bool fits = k < 30 && ((Ti + dnext + dmax) >> (30 - k)) == 0;
                 defer |= !fits;
                 const int kk = fits ? k : 0;
+                auto scale_gj = [kk](uint32_t gj) -> uint32_t { return ((gj & ~255u) << kk) | (gj & 255u); };
 #pragma unroll
                 for (int t = 0; t < kRing; ++t) {
                     LdsPtr e = entry((uint32_t)t * kStep);
-                    e[0] <<= kk; e[1] <<= kk; e[2] <<= kk;
+                    e[0] <<= kk; e[kA] <<= kk; e[kGJ] = scale_gj(e[kGJ]);
                 }
-                Mhd <<= kk; Ghd <<= kk; Tpt <<= kk; Rp <<= kk; Rc <<= kk;
-                M1 <<= kk; G1 <<= kk; M2 <<= kk; G2 <<= kk; M3 <<= kk; G3 <<= kk;
+                Mhd <<= kk; Ghd = scale_gj(Ghd); Tpt <<= kk; Rp <<= kk; Rc <<= kk;
+                M1 <<= kk; G1 = scale_gj(G1); M2 <<= kk; G2 = scale_gj(G2); M3 <<= kk; G3 = scale_gj(G3);
                 Mc = Mc == kNone ? kNone : Mc << kk;
                 Ac = Ac == kNone ? kNone : Ac << kk;
                 Ti <<= kk; dnext <<= kk; dmax <<= kk;
                 sh = tz;
             }
         }
-        // sizes positive and below 2^26, T(i) + d + max d below 2^30 now: no sum of this chunk wraps
+        // sizes positive and below 2^24, T(i) + d + max d below 2^30 now: no sum of this chunk wraps
         const uint64_t scaled = all >> sh;
         defer |= zero | (scaled >= kChunkLimit);
         dmax = (uint32_t)scaled > dmax ? (uint32_t)scaled : dmax;
@@ -219,6 +226,7 @@ __global__ __launch_bounds__(kWave) void linear_ring_kernel(const int64_t *__res
     // One step of the recurrence for position i, whose size x is already in a register.
     auto step_fn = [&](const int i, const int64_t x) {
         const uint32_t di = __builtin_amdgcn_alignbit((uint32_t)((uint64_t)x >> 32), (uint32_t)x, (uint32_t)sh);
+        const uint32_t di8 = di << 8;  // as a GJ word
         Ti += dnext;
         Rp = di > Rp ? di : Rp;
         Rc = di > Rc ? di : Rc;
@@ -230,7 +238,7 @@ __global__ __launch_bounds__(kWave) void linear_ring_kernel(const int64_t *__res
         // lowering of this doubly nested divergent loop is several times longer.)
         {
             uint32_t ad, e, t0;
-            uint64_t sv, sv2;
+            uint64_t sv, sv2, sv3;
             asm volatile(
                 "Lw_%=:\n\t"
                 "v_add_u32 %[t0], %[Ti], %[Rc]\n\t"
@@ -239,21 +247,26 @@ __global__ __launch_bounds__(kWave) void linear_ring_kernel(const int64_t *__res
                 "s_and_saveexec_b64 %[sv], vcc\n\t"
                 "v_add_u32 %[pt], %[step], %[pt]\n\t"
                 "v_sub_u32 %[Tpt], %[Ac], %[Mc]\n\t"
-                "v_mov_b32 %[Jpt], %[Jc]\n\t"
+                // the candidate's position from its low byte: it lies 1..256 above i
+                "v_subrev_u32 %[Jpt], %[i1], %[Jc]\n\t"
+                "v_and_b32 %[Jpt], 0xff, %[Jpt]\n\t"
+                "v_add_u32 %[Jpt], %[i1], %[Jpt]\n\t"
                 "v_mov_b32 %[Rp], %[Rc]\n\t"
                 "v_mov_b32 %[Ac], -1\n\t"
                 "v_mov_b32 %[Mc], -1\n\t"
                 "v_cmp_ne_u32 vcc, %[pt], %[hd]\n\t"
                 "s_and_saveexec_b64 %[sv2], vcc\n\t"
-                // the new candidate, and its R from the G of the entries above it:
+                // the new candidate, and its R from the G of the entries above it
+                // (as GJ words; the shift at the end takes the byte of j off again):
                 // the head's and the three under it are in registers
+                "s_mov_b64 %[sv3], exec\n\t"
                 "v_add_u32 %[e], %[step], %[pt]\n\t"
                 "v_and_or_b32 %[ad], %[e], %[mask], %[lo]\n\t"
                 "ds_read_b32 %[Mc], %[ad]\n\t"
-                "ds_read_b32 %[Ac], %[ad] offset:8\n\t"
-                "ds_read_b32 %[Jc], %[ad] offset:12\n\t"
+                "ds_read_b32 %[Ac], %[ad] offset:4096\n\t"
+                "ds_read_b32 %[Jc], %[ad] offset:8192\n\t"
                 "v_sub_u32 %[t0], %[hd], %[e]\n\t"
-                "v_mov_b32 %[Rc], %[di]\n\t"
+                "v_mov_b32 %[Rc], %[di8]\n\t"
                 "v_cmp_le_u32 vcc, %[step], %[t0]\n\t"
                 "s_and_b64 exec, exec, vcc\n\t"
                 "v_max_u32 %[Rc], %[Rc], %[Ghd]\n\t"
@@ -275,11 +288,13 @@ __global__ __launch_bounds__(kWave) void linear_ring_kernel(const int64_t *__res
                 "s_and_b64 exec, exec, vcc\n\t"
                 "s_cbranch_execz Lg_done_%=\n\t"
                 "v_and_or_b32 %[ad], %[e], %[mask], %[lo]\n\t"
-                "ds_read_b32 %[t0], %[ad] offset:4\n\t"
+                "ds_read_b32 %[t0], %[ad] offset:8192\n\t"
                 "s_waitcnt lgkmcnt(0)\n\t"
                 "v_max_u32 %[Rc], %[Rc], %[t0]\n\t"
                 "s_branch Lg_%=\n\t"
                 "Lg_done_%=:\n\t"
+                "s_mov_b64 exec, %[sv3]\n\t"
+                "v_lshrrev_b32 %[Rc], 8, %[Rc]\n\t"
                 "s_mov_b64 exec, %[sv2]\n\t"
                 "s_waitcnt lgkmcnt(0)\n\t"
                 "s_mov_b64 exec, %[sv]\n\t"
@@ -287,9 +302,9 @@ __global__ __launch_bounds__(kWave) void linear_ring_kernel(const int64_t *__res
                 "Lw_done_%=:\n\t"
                 : [pt] "+v"(pt), [Tpt] "+v"(Tpt), [Jpt] "+v"(Jpt), [Rp] "+v"(Rp), [Mc] "+v"(Mc), [Ac] "+v"(Ac),
                   [Jc] "+v"(Jc), [Rc] "+v"(Rc), [ad] "=&v"(ad), [e] "=&v"(e), [t0] "=&v"(t0), [sv] "=&s"(sv),
-                  [sv2] "=&s"(sv2)
-                : [Ti] "v"(Ti), [hd] "v"(hd), [di] "v"(di), [Ghd] "v"(Ghd), [G1] "v"(G1), [G2] "v"(G2), [G3] "v"(G3),
-                  [lo] "v"(lane_base), [mask] "s"(kSlotMask), [step] "i"(kStep)
+                  [sv2] "=&s"(sv2), [sv3] "=&s"(sv3)
+                : [Ti] "v"(Ti), [hd] "v"(hd), [di8] "v"(di8), [Ghd] "v"(Ghd), [G1] "v"(G1), [G2] "v"(G2), [G3] "v"(G3),
+                  [lo] "v"(lane_base), [mask] "s"(kSlotMask), [step] "i"(kStep), [i1] "s"((uint32_t)i + 1u)
                 : "vcc", "memory");
         }
         const uint32_t Upt = Ti + Rp - Tpt;  // U(i, j_pt)
@@ -311,7 +326,7 @@ __global__ __launch_bounds__(kWave) void linear_ring_kernel(const int64_t *__res
 
         // Q: drop the entries that M(i) dominates (never the crossover entry),
         // folding their G into the new entry's, then push i
-        uint32_t Gacc = di;
+        uint32_t Gacc = di8;  // a GJ word: only its G part is used
         {
             // up to three drops are decided on the mirrors.  The crossover entry is never
             // dropped, M(i) being above its value, and the tests are nested, so what the
@@ -342,7 +357,7 @@ __global__ __launch_bounds__(kWave) void linear_ring_kernel(const int64_t *__res
                     "v_subrev_u32 %[hd], %[step], %[hd]\n\t"
                     "v_and_or_b32 %[ad], %[hd], %[mask], %[lo]\n\t"
                     "ds_read_b32 %[Mhd], %[ad]\n\t"
-                    "ds_read_b32 %[Ghd], %[ad] offset:4\n\t"
+                    "ds_read_b32 %[Ghd], %[ad] offset:8192\n\t"
                     "s_waitcnt lgkmcnt(0)\n\t"
                     "s_mov_b64 exec, %[sv]\n\t"
                     "s_branch Lq_%=\n\t"
@@ -358,16 +373,17 @@ __global__ __launch_bounds__(kWave) void linear_ring_kernel(const int64_t *__res
         defer |= full;
         hd += full ? 0u : kStep;
         {
+            Gacc = (Gacc & ~255u) | ((uint32_t)i & 255u);
             LdsPtr e = entry(hd);
-            e[0] = Mi; e[1] = Gacc; e[2] = Mi + Ti; e[3] = (uint32_t)i;
+            e[0] = Mi; e[kA] = Mi + Ti; e[kGJ] = Gacc;
         }
         Mhd = Mi;
         Ghd = Gacc;
         {
             LdsPtr e1 = entry(hd - kStep), e2 = entry(hd - 2 * kStep), e3 = entry(hd - 3 * kStep);
-            M1 = e1[0]; G1 = e1[1];
-            M2 = e2[0]; G2 = e2[1];
-            M3 = e3[0]; G3 = e3[1];
+            M1 = e1[0]; G1 = e1[kGJ];
+            M2 = e2[0]; G2 = e2[kGJ];
+            M3 = e3[0]; G3 = e3[kGJ];
         }
         const bool fresh = hd == pt + kStep;  // the new entry is the candidate; R(i', i) starts empty
         Mc = fresh ? Mi : Mc;
