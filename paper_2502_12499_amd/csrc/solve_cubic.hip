@@ -1652,7 +1652,7 @@ hipError_t launch_solve_cubic(const int64_t *d, int64_t batch, int n, Strides st
     pruned = pruned && n >= kPruneFromLayers;
     CubicWs w = carve_cubic(ws, batch, n);
     const int64_t K = num_budgets(n);
-    const int64_t total_blocks = (K + 127) / 128 * batch;
+    const int64_t total_blocks = (K + kWave - 1) / kWave * batch;  // the largest grid: one wave per workgroup
     const int64_t n_words = waves_per_chain(n) * batch;
     if (total_blocks > 0x7fffffffLL) return hipErrorInvalidConfiguration;
     const size_t table_lds = ((size_t)n + 1) * 8;
@@ -1677,7 +1677,7 @@ hipError_t launch_solve_cubic(const int64_t *d, int64_t batch, int n, Strides st
             if (e != hipSuccess) return e;
         }
     }
-    launch_shared<16, 256, 64>(n, batch, pruned, w, stream);
+    launch_shared<16, 64, 64>(n, batch, pruned, w, stream);
     launch_budgets<int64_t, 16, 256>(n, batch, w, stream);
     const int64_t word_groups = (n_words + kWave - 1) / kWave;
     const unsigned over_grid = (unsigned)(word_groups < 4096 ? word_groups : 4096);

@@ -68,7 +68,7 @@ def check_cubic(d, chain_major=False):
         x = to_dev(dc) if chain_major else to_dev(d)
         if pruned:
             mask, peak, budget, evaluated, status = B.ckpt_solve_cubic_pruned(x, chain_major=chain_major)
-            # at most every budget once plus the sampled tiles (whole tiles of 256) a second time
+            # at most every budget once plus the sampled tiles (whole tiles) a second time
             assert bool((evaluated >= 1).all()) and bool((evaluated <= K + K // 64 + 512).all()), "evaluated"
             if n < 2048:
                 assert bool((evaluated == K).all())
