@@ -172,7 +172,8 @@ __global__ __launch_bounds__(kWave) void linear_ring_kernel(const int64_t *__res
     // that the steps that follow find them in registers (what lies beyond the
     // crossover entry is never looked at, so it does not matter what they hold there)
     uint32_t M1 = 0, G1 = 0, M2 = 0, G2 = 0, M3 = 0, G3 = 0;
-    uint32_t Tpt = 0, Jpt = n, Rp = 0;         // crossover entry: T(j), j, R(i, j)
+    uint32_t Tpt = 0, Jpt = n, Rp = 0;         // crossover entry: T(j), j (only its low byte is kept up), R(i, j)
+    uint32_t Jfull = n;                        // its position in full, as of the last chunk check
     uint32_t Mc = kNone, Ac = kNone, Jc = 0, Rc = 0;  // candidate (the entry before pt): M, A, j, R(i, j)
     uint32_t Ti = 0;                           // T(i) / 2^sh
     uint32_t dnext = (uint32_t)xs;             // d_{i+1} / 2^sh
@@ -219,8 +220,11 @@ __global__ __launch_bounds__(kWave) void linear_ring_kernel(const int64_t *__res
         defer |= zero | (scaled >= kChunkLimit);
         dmax = (uint32_t)scaled > dmax ? (uint32_t)scaled : dmax;
         defer |= (Ti + dnext + dmax) >= kLimit;
-        // every step of the chunk is at most j_pt - i - 1 of its lowest position: one byte holds it
-        defer |= (Jpt - (uint32_t)ilow) > 256u;
+        // The crossover entry's position in full from its low byte: it has not moved up since the
+        // last check and lies above the last chunk's lowest position, fewer than 256 places in all.
+        // Every step of this chunk is at most j_pt - i - 1 of its lowest position: one byte holds it.
+        Jfull -= (Jfull - Jpt) & 255u;
+        defer |= (Jfull - (uint32_t)ilow) > 248u;
     };
 
     // One step of the recurrence for position i, whose size x is already in a register.
@@ -247,10 +251,7 @@ __global__ __launch_bounds__(kWave) void linear_ring_kernel(const int64_t *__res
                 "s_and_saveexec_b64 %[sv], vcc\n\t"
                 "v_add_u32 %[pt], %[step], %[pt]\n\t"
                 "v_sub_u32 %[Tpt], %[Ac], %[Mc]\n\t"
-                // the candidate's position from its low byte: it lies 1..256 above i
-                "v_subrev_u32 %[Jpt], %[i1], %[Jc]\n\t"
-                "v_and_b32 %[Jpt], 0xff, %[Jpt]\n\t"
-                "v_add_u32 %[Jpt], %[i1], %[Jpt]\n\t"
+                "v_mov_b32 %[Jpt], %[Jc]\n\t"
                 "v_mov_b32 %[Rp], %[Rc]\n\t"
                 "v_mov_b32 %[Ac], -1\n\t"
                 "v_mov_b32 %[Mc], -1\n\t"
@@ -304,7 +305,7 @@ __global__ __launch_bounds__(kWave) void linear_ring_kernel(const int64_t *__res
                   [Jc] "+v"(Jc), [Rc] "+v"(Rc), [ad] "=&v"(ad), [e] "=&v"(e), [t0] "=&v"(t0), [sv] "=&s"(sv),
                   [sv2] "=&s"(sv2), [sv3] "=&s"(sv3)
                 : [Ti] "v"(Ti), [hd] "v"(hd), [di8] "v"(di8), [Ghd] "v"(Ghd), [G1] "v"(G1), [G2] "v"(G2), [G3] "v"(G3),
-                  [lo] "v"(lane_base), [mask] "s"(kSlotMask), [step] "i"(kStep), [i1] "s"((uint32_t)i + 1u)
+                  [lo] "v"(lane_base), [mask] "s"(kSlotMask), [step] "i"(kStep)
                 : "vcc", "memory");
         }
         const uint32_t Upt = Ti + Rp - Tpt;  // U(i, j_pt)
