@@ -118,14 +118,21 @@ int ckpt_solve_cubic(const int64_t *d, const ckpt_layout *layout, uint8_t *mask_
 
 /* The same result as ckpt_solve_cubic, without running the recurrence for
  * budgets that cannot be optimal.  Any cost s + c_s that has been reached
- * bounds the optimum from above (UB), and c_s >= d_0 + d_n for every budget
- * (both ends are checkpoints), so a budget s > UB - d_0 - d_n costs more than
- * UB.  The call first runs one tile in 64 of the sorted budgets, takes UB from
- * them, and then runs only the budgets up to the bound: the optimum, the
- * smallest optimal budget and the canonical set are unchanged (the comparison
- * is strict, so ties are never cut).  Chains whose values need 64-bit
- * arithmetic, and chains of fewer than 2048 layers (where the two extra passes
- * cost more than they save), are solved without pruning.
+ * bounds the optimum from above (UB).  From above: c_s >= d_0 + d_n for every
+ * budget (both ends are checkpoints), so a budget s > UB - d_0 - d_n costs more
+ * than UB.  From below: with m interior checkpoints the other interior layers
+ * form at most m+1 segments of at most s each, so the checkpoints weigh at
+ * least sum(interior) - (m+1) s, and at least the m smallest interior sizes
+ * W(m); c_s - d_0 - d_n >= min_m max(W(m), sum(interior) - (m+1) s), which
+ * does not grow with s, so the budgets for which it exceeds UB - d_0 - d_n are
+ * the ones below some s_lo.  The call takes a first UB from the set with a
+ * checkpoint every ceil(sqrt(n)) layers, runs one tile in 64 of the sorted
+ * budgets inside the bounds, takes UB from them, and then runs the budgets
+ * inside the tightened bounds: the optimum, the smallest optimal budget and
+ * the canonical set are unchanged (both comparisons are strict, so ties are
+ * never cut).  Chains whose values need 64-bit arithmetic, and chains of
+ * fewer than 2048 layers (where the extra passes cost more than they save),
+ * are solved without pruning.
  * evaluated_out [out] `batch` int64 or NULL: the number of budgets whose
  * recurrence was run (sampled ones counted again when they run a second time),
  * times n the recurrence cells actually evaluated; ckpt_solve_cubic always

@@ -127,6 +127,8 @@ struct CubicWs {
     Partial *partial2;    // [batch][kReduceBlocks] second-level partial results (long chains only)
     int32_t *pred;        // [batch][n+1]
     int32_t *prune;       // [batch] budgets above this (normalised) value cannot be optimal; pruned calls only
+    int32_t *prune_lo;    // [batch] ... nor budgets below this one
+    int32_t *wsum;        // [batch][n+1] wsum[m] = sum of the m smallest interior sizes; pruned calls only
     unsigned long long *evaluated;  // [batch] budgets whose recurrence was run; pruned calls only
 };
 
@@ -203,6 +205,8 @@ __host__ CubicWs carve_cubic(void *ws, int64_t batch, int n)
     w.partial2 = (Partial *)p;  p += align_up(B * kReduceBlocks * sizeof(Partial));
     w.pred = (int32_t *)p;      p += align_up(B * n1 * 4);
     w.prune = (int32_t *)p;     p += align_up(B * 4);
+    w.prune_lo = (int32_t *)p;  p += align_up(B * 4);
+    w.wsum = (int32_t *)p;      p += align_up(B * n1 * 4);
     w.evaluated = (unsigned long long *)p; p += align_up(B * 8);
     return w;
 }
@@ -237,6 +241,7 @@ __global__ __launch_bounds__(kWave) void cubic_prologue_kernel(const int64_t *__
     if (c == 0 && lane == 0) *w.redo_count = 0;
     if (lane == 0) {
         w.prune[c] = INT32_MAX;
+        w.prune_lo[c] = 0;
         w.evaluated[c] = 0;
     }
     const int64_t *dp = d + c * cstride;
@@ -786,10 +791,10 @@ __device__ __attribute__((noinline)) SharedLane shared_rare(SharedLane L, const 
 // instead of the waves of their own index.
 // Otherwise workgroup b of a chain takes tile b * tile_stride of the sorted
 // budgets (tile_stride > 1: a sample of the budgets).  mode kSharedAll runs
-// every tile it is given; kSharedCount also adds the budgets it runs to
-// w.evaluated; kSharedPrune in addition skips a wave whose smallest budget is
-// above w.prune[c] (no budget of the wave can then be optimal).
-constexpr int kSharedAll = 0, kSharedCount = 1, kSharedPrune = 2;
+// every tile it is given; kSharedPrune skips a wave whose smallest budget is
+// above w.prune[c] or whose largest is below w.prune_lo[c] (no budget of the
+// wave can then be optimal), and adds the budgets it does run to w.evaluated.
+constexpr int kSharedAll = 0, kSharedPrune = 1;
 
 template <int RING, int BLOCK, bool REDO>
 __global__ __launch_bounds__(BLOCK) void cubic_shared_kernel(int n, int64_t blocks_per_chain, int tile_stride,
@@ -822,8 +827,10 @@ __global__ __launch_bounds__(BLOCK) void cubic_shared_kernel(int n, int64_t bloc
     const V s = live ? w.sorted[c * K + idx] : 0;
     if (!REDO && mode != kSharedAll) {
         const bool first = (tid & (kWave - 1)) == 0;
-        // budgets ascend along the sorted list: the wave's first lane holds its smallest
-        if (mode == kSharedPrune && __builtin_amdgcn_readfirstlane(s) > w.prune[c]) {
+        // budgets ascend along the sorted list: the wave's first lane holds its smallest, its last
+        // lane the largest (lanes past the list count as large)
+        const V s_last = __builtin_amdgcn_readlane(live ? s : std::numeric_limits<V>::max(), kWave - 1);
+        if (__builtin_amdgcn_readfirstlane(s) > w.prune[c] || s_last < w.prune_lo[c]) {
             if (first) {
                 const int64_t slot_id = c * waves_per_chain(n) + wave_in_chain;
                 w.partial[slot_id] = Partial{kInf, (int64_t)s};
@@ -1218,38 +1225,146 @@ constexpr int kSampleStride = 64;  // a pruned call first runs every 64th tile o
 // keeps are the small ones, whose waves run longest: below this length it does not pay.
 constexpr int kPruneFromLayers = 2048;
 
-// From the sampled tiles' results: any s + c_s that was reached bounds the optimum from
-// above, and c_s >= d_0 + d_n for every s, so a budget above UB - d_0 - d_n cannot be
-// optimal (nor tie: the comparison is strict).  One workgroup per chain.
-__global__ __launch_bounds__(256) void cubic_bound_kernel(int n, int64_t blocks_per_chain, int tile_stride,
-                                                          int waves_per_tile, CubicWs w)
+// The two bounds of a pruned call.  One workgroup per chain.
+//
+// Above: any s + c_s that was reached bounds the optimum from above (UB), and
+// c_s >= d_0 + d_n for every s, so a budget above UB - d_0 - d_n cannot be optimal.
+// Below: with m interior checkpoints the other interior layers form at most m+1
+// segments of at most s each, so the checkpoints weigh at least
+// sum(interior) - (m+1) s, and they weigh at least W(m), the m smallest interior
+// sizes; hence c_s - d_0 - d_n >= LB(s) = min_m max(W(m), sum(interior) - (m+1) s),
+// which does not grow with s: the budgets with LB(s) > UB - d_0 - d_n are those
+// below some s_lo and cannot be optimal either.  (Both comparisons are strict, so
+// neither cuts a budget that ties with the optimum.)
+//
+// Stage 0, before anything has run: W from a bitonic sort of the sizes in LDS, and
+// UB from the cost of the set with a checkpoint every ceil(sqrt(n)) layers.
+// Stage 1, after the sampled tiles: UB from their results as well.
+constexpr int kBoundThreads = 256;
+
+__global__ __launch_bounds__(kBoundThreads) void cubic_bound_kernel(int n, int64_t blocks_per_chain,
+                                                                    int tile_stride, int waves_per_tile, int stage,
+                                                                    CubicWs w)
 {
-    __shared__ int64_t part[256];
+    __shared__ int64_t part[kBoundThreads];
+    __shared__ int32_t srt[CKPT_CUBIC_MAX_LAYERS + 1];
     const int64_t c = blockIdx.x;
     const int tid = threadIdx.x;
-    if (c == 0 && tid == 0) *w.redo_count = 0;  // waves the sample flagged are run again anyway
+    if (stage == 1 && c == 0 && tid == 0) *w.redo_count = 0;  // waves the sample flagged are run again anyway
     const ChainMeta meta = w.meta[c];
     if (meta.status != CKPT_OK || !meta.mode32) return;
-    const int64_t wpc = waves_per_chain(n);
-    const int64_t launched = (blocks_per_chain + tile_stride - 1) / tile_stride;
+    const El *el = w.el + (size_t)c * table_len(n);
+    int32_t *W = w.wsum + c * ((int64_t)n + 1);
+    const int m_int = n - 1;  // interior layers 1..n-1
+
     int64_t best = kInf;
-    for (int64_t t = tid; t < launched * waves_per_tile; t += 256) {
-        const int64_t wave = (t / waves_per_tile) * tile_stride * waves_per_tile + t % waves_per_tile;
-        if (wave < wpc) {
-            const int64_t cost = w.partial[c * wpc + wave].cost;
-            best = cost < best ? cost : best;
+    if (stage == 0) {
+        // the interior sizes in ascending order, then their running sums
+        int N = 1;
+        while (N < m_int) N <<= 1;
+        for (int t = tid; t < N; t += kBoundThreads) srt[t] = t < m_int ? el[t + 1].d : INT32_MAX;
+        __syncthreads();
+        for (int k = 2; k <= N; k <<= 1)
+            for (int j = k >> 1; j >= 1; j >>= 1) {
+                for (int t = tid; t < N; t += kBoundThreads) {
+                    const int o = t ^ j;
+                    if (o > t) {
+                        const int32_t a = srt[t], b = srt[o];
+                        const bool up = (t & k) == 0;
+                        if ((a > b) == up) { srt[t] = b; srt[o] = a; }
+                    }
+                }
+                __syncthreads();
+            }
+        // running sums: every thread sums a contiguous piece, one thread chains the pieces
+        const int piece = N / kBoundThreads > 0 ? N / kBoundThreads : 1;
+        const int p0 = tid * piece;
+        int64_t mine = 0;
+        for (int t = p0; t < p0 + piece && t < m_int; ++t) mine += srt[t];
+        part[tid] = mine;
+        __syncthreads();
+        if (tid == 0) {
+            int64_t run = 0;
+            for (int t = 0; t < kBoundThreads; ++t) { const int64_t x = part[t]; part[t] = run; run += x; }
+        }
+        __syncthreads();
+        {
+            int32_t run = (int32_t)part[tid];
+            if (tid == 0) W[0] = 0;
+            for (int t = p0; t < p0 + piece && t < m_int; ++t) { run += srt[t]; W[t + 1] = run; }
+        }
+        __syncthreads();
+        // the cost of a checkpoint every ceil(sqrt(n)) layers, an upper bound to start from: thread g
+        // takes the checkpoint at g * seg_len (position n for the last) and the segment after it
+        int seg_len = 1;
+        while ((int64_t)seg_len * seg_len < n) ++seg_len;
+        int64_t ckpt = 0, seg_max = 0;
+        for (int g = tid; g * seg_len <= n; g += kBoundThreads) {
+            const int k0 = g * seg_len;
+            ckpt += el[k0].d;
+            int64_t seg = 0;
+            for (int k = k0 + 1; k < k0 + seg_len && k < n; ++k) seg += el[k].d;
+            seg_max = seg > seg_max ? seg : seg_max;
+            if (k0 < n && k0 + seg_len > n) ckpt += el[n].d;  // the last, shorter segment ends at n
+        }
+        part[tid] = ckpt;
+        __syncthreads();
+        for (int half = kBoundThreads / 2; half >= 1; half >>= 1) {
+            if (tid < half) part[tid] += part[tid + half];
+            __syncthreads();
+        }
+        const int64_t ckpt_all = part[0];
+        __syncthreads();
+        part[tid] = seg_max;
+        __syncthreads();
+        for (int half = kBoundThreads / 2; half >= 1; half >>= 1) {
+            if (tid < half) part[tid] = part[tid + half] > part[tid] ? part[tid + half] : part[tid];
+            __syncthreads();
+        }
+        if (tid == 0) part[0] = ckpt_all + part[0];
+        __syncthreads();
+    } else {
+        const int64_t wpc = waves_per_chain(n);
+        const int64_t launched = (blocks_per_chain + tile_stride - 1) / tile_stride;
+        for (int64_t t = tid; t < launched * waves_per_tile; t += kBoundThreads) {
+            const int64_t wave = (t / waves_per_tile) * tile_stride * waves_per_tile + t % waves_per_tile;
+            if (wave < wpc) {
+                const int64_t cost = w.partial[c * wpc + wave].cost;
+                best = cost < best ? cost : best;
+            }
+        }
+        part[tid] = best;
+        __syncthreads();
+        for (int half = kBoundThreads / 2; half >= 1; half >>= 1) {
+            if (tid < half) part[tid] = part[tid + half] < part[tid] ? part[tid + half] : part[tid];
+            __syncthreads();
         }
     }
-    part[tid] = best;
-    __syncthreads();
-    for (int half = 128; half >= 1; half >>= 1) {
-        if (tid < half) part[tid] = part[tid + half] < part[tid] ? part[tid + half] : part[tid];
-        __syncthreads();
+    if (tid != 0) return;
+    // UB: this stage's, or the earlier stage's if that was better
+    int64_t room = part[0] == kInf ? (int64_t)INT32_MAX : part[0] - el[0].d - el[n].d;  // UB - d_0 - d_n
+    if (stage == 1 && (int64_t)w.prune[c] < room) room = w.prune[c];
+    if (room >= INT32_MAX) return;
+    w.prune[c] = (int32_t)room;
+    // the smallest s with LB(s) <= room (LB(room) <= room holds: m = 0 gives at most sum - s ... or the
+    // search ends at room + 1, which prunes nothing that the upper bound leaves)
+    const int64_t sum_int = W[m_int];
+    auto lower = [&](int64_t sv) -> int64_t {
+        int lo = 0, hi = m_int;  // smallest m with W(m) >= sum - (m+1) s
+        while (lo < hi) {
+            const int mid = (lo + hi) >> 1;
+            if ((int64_t)W[mid] >= sum_int - (int64_t)(mid + 1) * sv) hi = mid; else lo = mid + 1;
+        }
+        const int64_t a = W[lo];
+        const int64_t b = sum_int - (int64_t)lo * sv;  // the max at m - 1 (for m = 0: no smaller m, a = 0 wins)
+        return lo == 0 ? a : (a < b ? a : b);
+    };
+    int64_t lo = 0, hi = room + 1;
+    while (lo < hi) {
+        const int64_t mid = (lo + hi) >> 1;
+        if (lower(mid) <= room) hi = mid; else lo = mid + 1;
     }
-    if (tid == 0 && part[0] != kInf) {
-        const El *el = w.el + (size_t)c * table_len(n);
-        w.prune[c] = (int32_t)(part[0] - el[0].d - el[n].d);
-    }
+    w.prune_lo[c] = (int32_t)(lo < INT32_MAX ? lo : INT32_MAX);
 }
 
 // All waves with a ring of RING entries per lane (for a pruned call: a sample of them, the
@@ -1262,10 +1377,12 @@ void launch_shared(int n, int64_t batch, bool pruned, CubicWs w, hipStream_t str
     const int64_t blocks_per_chain = (num_budgets(n) + BLOCK - 1) / BLOCK;
     if (pruned) {
         const int64_t sampled = (blocks_per_chain + kSampleStride - 1) / kSampleStride;
+        hipLaunchKernelGGL(cubic_bound_kernel, dim3((unsigned)batch), dim3(kBoundThreads), 0, stream, n,
+                           blocks_per_chain, kSampleStride, BLOCK / kWave, 0, w);
         hipLaunchKernelGGL((cubic_shared_kernel<RING, BLOCK, false>), dim3((unsigned)(sampled * batch)), dim3(BLOCK),
-                           0, stream, n, blocks_per_chain, kSampleStride, kSharedCount, w);
-        hipLaunchKernelGGL(cubic_bound_kernel, dim3((unsigned)batch), dim3(256), 0, stream, n, blocks_per_chain,
-                           kSampleStride, BLOCK / kWave, w);
+                           0, stream, n, blocks_per_chain, kSampleStride, kSharedPrune, w);
+        hipLaunchKernelGGL(cubic_bound_kernel, dim3((unsigned)batch), dim3(kBoundThreads), 0, stream, n,
+                           blocks_per_chain, kSampleStride, BLOCK / kWave, 1, w);
     }
     hipLaunchKernelGGL((cubic_shared_kernel<RING, BLOCK, false>), dim3((unsigned)(blocks_per_chain * batch)),
                        dim3(BLOCK), 0, stream, n, blocks_per_chain, 1, pruned ? kSharedPrune : kSharedAll, w);
@@ -1640,8 +1757,8 @@ size_t cubic_workspace_bytes(int64_t batch, int n)
            align_up(B * step_len(n) * sizeof(Step)) + 2 * align_up(B * (size_t)num_budgets(n) * 4) +
            align_up(sort_tmp_bytes(batch, n)) + 256 + align_up(B * wpc * 8) +
            align_up(B * wpc * sizeof(Partial)) + align_up(B * wpc * 8) +
-           align_up(B * kReduceBlocks * sizeof(Partial)) + align_up(B * n1 * 4) + align_up(B * 4) +
-           align_up(B * 8) + 256;
+           align_up(B * kReduceBlocks * sizeof(Partial)) + align_up(B * n1 * 4) + 2 * align_up(B * 4) +
+           align_up(B * n1 * 4) + align_up(B * 8) + 256;
 }
 
 hipError_t launch_solve_cubic(const int64_t *d, int64_t batch, int n, Strides st, uint8_t *mask_out,
