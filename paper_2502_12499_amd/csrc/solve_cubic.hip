@@ -1795,7 +1795,7 @@ hipError_t launch_solve_cubic(const int64_t *d, int64_t batch, int n, Strides st
         }
     }
     launch_shared<16, 64, 64>(n, batch, pruned, w, stream);
-    launch_budgets<int64_t, 16, 256>(n, batch, w, stream);
+    launch_budgets<int64_t, 16, 64>(n, batch, w, stream);
     const int64_t word_groups = (n_words + kWave - 1) / kWave;
     const unsigned over_grid = (unsigned)(word_groups < 4096 ? word_groups : 4096);
     hipLaunchKernelGGL(cubic_overflow_kernel, dim3(over_grid), dim3(kWave), table_lds, stream, n, n_words, w);
