@@ -21,8 +21,8 @@
 // chunks of kChunk rows held in registers, with the next chunk already loaded
 // and the one after it in flight.  For a chunk it first finds what lies above
 // the chunk's last row (it scans the next chunk's registers up to the first
-// checkpoint; a lane whose next chunk holds no checkpoint reads on from
-// memory, which is rare and hits rows that are about to be loaded anyway),
+// checkpoint; while some lane of the wave has found none, the wave goes on
+// with the rows in flight and then with eight further rows at a time),
 // then sweeps the chunk downwards in registers to get the part above every
 // row, then upwards to write both stages of every row.  Algorithm 3's stages
 // need nothing else, so that objective reads 9(n+1) bytes and writes 16(n+1)
@@ -34,7 +34,7 @@
 namespace ckpt {
 namespace {
 
-constexpr int kBlock = 256;
+constexpr int kBlock = 64;
 constexpr int kChunk = 8;
 
 template <int OBJ>
@@ -95,20 +95,33 @@ __global__ __launch_bounds__(kBlock) void eval_timeline_kernel(const int64_t *__
         }
 
         // what lies above the chunk's last row: d from the next chunk's first row up to (not
-        // including) the first checkpoint there
+        // including) the first checkpoint.  Most lanes find it among the next chunk's rows; as
+        // long as some lane of the wave has not, the whole wave looks at eight more rows: first
+        // the ones already requested for the chunk after next, then further ones, eight loads
+        // at a time (one memory latency per round instead of one per row).
         uint64_t acc = 0;
         bool found = false;
+        auto scan = [&](const int64_t(&dd)[kChunk], const uint8_t(&mm)[kChunk], const int first_row) {
 #pragma unroll
-        for (int u = 0; u < kChunk; ++u) {
-            const bool open = !found && (k0 + kChunk + u) <= n;
-            found |= (k0 + kChunk + u) > n || nxt_m[u] != 0;
-            if (open && nxt_m[u] == 0) acc = join(acc, nxt_d[u]);
-        }
-        for (int k = k0 + 2 * kChunk; !found; ++k) {
-            if (k > n) break;
-            const int64_t x = dp[(int64_t)k * pstride];
-            if (mp[(int64_t)k * pstride]) break;
-            acc = join(acc, x);
+            for (int u = 0; u < kChunk; ++u) {
+                const bool open = !found && (first_row + u) <= n;
+                found |= (first_row + u) > n || mm[u] != 0;
+                if (open && mm[u] == 0) acc = join(acc, dd[u]);
+            }
+        };
+        scan(nxt_d, nxt_m, k0 + kChunk);
+        if (__builtin_amdgcn_ballot_w64(!found) != 0) {
+            scan(far_d, far_m, k0 + 2 * kChunk);
+            for (int kb = k0 + 3 * kChunk; __builtin_amdgcn_ballot_w64(!found) != 0; kb += kChunk) {
+                int64_t more_d[kChunk];
+                uint8_t more_m[kChunk];
+#pragma unroll
+                for (int u = 0; u < kChunk; ++u) {
+                    const int64_t a = (int64_t)min(kb + u, n) * pstride;
+                    more_d[u] = dp[a]; more_m[u] = mp[a];
+                }
+                scan(more_d, more_m, kb);
+            }
         }
 
         // downwards: the part above each row of the chunk (the row itself included)
