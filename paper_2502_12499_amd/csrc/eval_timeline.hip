@@ -180,12 +180,15 @@ __global__ __launch_bounds__(kBlock) void eval_timeline_kernel(const int64_t *__
 
 // Checkpoint sets that do not depend on the sizes: the two ends only, every
 // position, or segments of ceil(sqrt(n)) layers (the sqrt(n) rule of Section
-// 2.1 as Section 5 applies it: n = 24 gives {5,10,15,20,24}).
+// 2.1 as Section 5 applies it: n = 24 gives {5,10,15,20,24}).  The byte of a
+// position is the same for every chain, so with chains next to each other in
+// memory (chain stride 1) a lane writes the bytes of PACK chains as one word.
+template <int PACK>
 __global__ __launch_bounds__(kBlock) void select_baseline_kernel(int64_t batch, int n, int64_t cstride,
                                                                  int64_t pstride, int kind, int seg_len,
                                                                  uint8_t *__restrict__ mask_out)
 {
-    const int64_t c = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+    const int64_t c = ((int64_t)blockIdx.x * kBlock + threadIdx.x) * PACK;
     if (c >= batch) return;
     uint8_t *mp = mask_out + c * cstride;
     int next_multiple = 0;
@@ -195,7 +198,10 @@ __global__ __launch_bounds__(kBlock) void select_baseline_kernel(int64_t batch, 
             on |= kind == CKPT_SELECT_SQRT;
             next_multiple += seg_len;
         }
-        mp[(int64_t)k * pstride] = on ? 1 : 0;
+        if (PACK == 8)
+            __builtin_nontemporal_store(on ? 0x0101010101010101ull : 0ull, (uint64_t *)(mp + (int64_t)k * pstride));
+        else
+            mp[(int64_t)k * pstride] = on ? 1 : 0;
     }
 }
 
@@ -222,9 +228,17 @@ hipError_t launch_select_baseline(int64_t batch, int n, Strides st, int kind, ui
     if (batch == 0) return hipSuccess;
     int seg_len = 1;  // ceil(sqrt(n))
     while ((int64_t)seg_len * seg_len < n) ++seg_len;
-    const unsigned grid = (unsigned)((batch + kBlock - 1) / kBlock);
-    hipLaunchKernelGGL(select_baseline_kernel, dim3(grid), dim3(kBlock), 0, stream, batch, n, st.chain, st.pos,
-                       kind, seg_len, mask_out);
+    // eight chains per lane when every row of eight bytes is contiguous and 8-byte aligned
+    const bool packed = st.chain == 1 && batch % 8 == 0 && st.pos % 8 == 0 && ((uintptr_t)mask_out & 7u) == 0;
+    if (packed) {
+        const unsigned grid = (unsigned)((batch / 8 + kBlock - 1) / kBlock);
+        hipLaunchKernelGGL(select_baseline_kernel<8>, dim3(grid), dim3(kBlock), 0, stream, batch, n, st.chain, st.pos,
+                           kind, seg_len, mask_out);
+    } else {
+        const unsigned grid = (unsigned)((batch + kBlock - 1) / kBlock);
+        hipLaunchKernelGGL(select_baseline_kernel<1>, dim3(grid), dim3(kBlock), 0, stream, batch, n, st.chain, st.pos,
+                           kind, seg_len, mask_out);
+    }
     return hipGetLastError();
 }
 

@@ -103,7 +103,7 @@ def test_timeline_config5_sampled():
         del tl
 
 
-@pytest.mark.parametrize("batch,n", [(1, 1), (1, 24), (5, 15), (300, 64), (70, 1001)])
+@pytest.mark.parametrize("batch,n", [(1, 1), (1, 24), (5, 15), (300, 64), (70, 1001), (64, 33), (4096, 256)])
 def test_select_baseline(batch, n):
     say(f"select_baseline batch={batch} n={n}")
     like = torch.empty((n + 1, batch), dtype=torch.int64, device=DEV)
