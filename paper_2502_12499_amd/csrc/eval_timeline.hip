@@ -65,13 +65,14 @@ __global__ __launch_bounds__(kBlock) void eval_timeline_kernel(const int64_t *__
     }
 
     // rows beyond n re-read row n and are not used
+    // the masks of a chunk that has arrived are kept as one bit per row
     int64_t cur_d[kChunk], nxt_d[kChunk];
-    uint8_t cur_m[kChunk], nxt_m[kChunk];
+    uint32_t cur_m = 0, nxt_m = 0;
 #pragma unroll
     for (int u = 0; u < kChunk; ++u) {
         const int64_t a = (int64_t)min(1 + u, n) * pstride, b = (int64_t)min(1 + kChunk + u, n) * pstride;
-        cur_d[u] = dp[a]; cur_m[u] = mp[a];
-        nxt_d[u] = dp[b]; nxt_m[u] = mp[b];
+        cur_d[u] = dp[a]; cur_m |= (uint32_t)(mp[a] != 0) << u;
+        nxt_d[u] = dp[b]; nxt_m |= (uint32_t)(mp[b] != 0) << u;
     }
 
     bool bad_size = x0 <= 0, ovf = false;
@@ -101,17 +102,24 @@ __global__ __launch_bounds__(kBlock) void eval_timeline_kernel(const int64_t *__
         // at a time (one memory latency per round instead of one per row).
         uint64_t acc = 0;
         bool found = false;
-        auto scan = [&](const int64_t(&dd)[kChunk], const uint8_t(&mm)[kChunk], const int first_row) {
+        auto bits = [](const uint8_t(&mm)[kChunk]) -> uint32_t {
+            uint32_t b = 0;
+#pragma unroll
+            for (int u = 0; u < kChunk; ++u) b |= (uint32_t)(mm[u] != 0) << u;
+            return b;
+        };
+        auto scan = [&](const int64_t(&dd)[kChunk], const uint32_t mm, const int first_row) {
 #pragma unroll
             for (int u = 0; u < kChunk; ++u) {
+                const bool ck = (mm >> u) & 1u;
                 const bool open = !found && (first_row + u) <= n;
-                found |= (first_row + u) > n || mm[u] != 0;
-                if (open && mm[u] == 0) acc = join(acc, dd[u]);
+                found |= (first_row + u) > n || ck;
+                if (open && !ck) acc = join(acc, dd[u]);
             }
         };
         scan(nxt_d, nxt_m, k0 + kChunk);
         if (__builtin_amdgcn_ballot_w64(!found) != 0) {
-            scan(far_d, far_m, k0 + 2 * kChunk);
+            scan(far_d, bits(far_m), k0 + 2 * kChunk);
             for (int kb = k0 + 3 * kChunk; __builtin_amdgcn_ballot_w64(!found) != 0; kb += kChunk) {
                 int64_t more_d[kChunk];
                 uint8_t more_m[kChunk];
@@ -120,7 +128,7 @@ __global__ __launch_bounds__(kBlock) void eval_timeline_kernel(const int64_t *__
                     const int64_t a = (int64_t)min(kb + u, n) * pstride;
                     more_d[u] = dp[a]; more_m[u] = mp[a];
                 }
-                scan(more_d, more_m, kb);
+                scan(more_d, bits(more_m), kb);
             }
         }
 
@@ -128,7 +136,7 @@ __global__ __launch_bounds__(kBlock) void eval_timeline_kernel(const int64_t *__
         uint64_t above[kChunk];
 #pragma unroll
         for (int u = kChunk - 1; u >= 0; --u) {
-            if (k0 + u <= n) acc = cur_m[u] ? 0 : join(acc, cur_d[u]);
+            if (k0 + u <= n) acc = ((cur_m >> u) & 1u) ? 0 : join(acc, cur_d[u]);
             above[u] = acc;
         }
 
@@ -149,7 +157,7 @@ __global__ __launch_bounds__(kBlock) void eval_timeline_kernel(const int64_t *__
             else
                 b = below + seg + (uint64_t)x + ((uint64_t)segmax > above[u] ? (uint64_t)segmax : above[u]);
             __builtin_nontemporal_store((int64_t)b, op + (last - i) * opstride);
-            if (cur_m[u]) {
+            if ((cur_m >> u) & 1u) {
                 below += (uint64_t)x;
                 seg = 0;
                 segmax = x;
@@ -162,9 +170,11 @@ __global__ __launch_bounds__(kBlock) void eval_timeline_kernel(const int64_t *__
         }
 #pragma unroll
         for (int u = 0; u < kChunk; ++u) {
-            cur_d[u] = nxt_d[u]; cur_m[u] = nxt_m[u];
-            nxt_d[u] = far_d[u]; nxt_m[u] = far_m[u];
+            cur_d[u] = nxt_d[u];
+            nxt_d[u] = far_d[u];
         }
+        cur_m = nxt_m;
+        nxt_m = bits(far_m);
     }
     op[last * opstride] = x0;
     ovf |= (total + (uint64_t)dmax) > (uint64_t)INT64_MAX;
