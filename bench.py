@@ -231,8 +231,8 @@ def main():
     # workload only; to be set to None when those kernels change)
     default_workload = (Bn, n, nc) == (1048576, 256, 4096)
     traffic_cubic = 40.0e6 + 8.4e6 if default_workload else None
-    traffic_linear = 2.695e9 + 0.536e9 if default_workload else None
-    traffic_eval = 2.695e9 + 8.4e6 if default_workload else None
+    traffic_linear = 2.487e9 + 0.584e9 if default_workload else None
+    traffic_eval = 2.54e9 + 8.4e6 if default_workload else None
     kernels["eval_static"]["traffic"] = kernels["eval_dynamic"]["traffic"] = traffic_eval
     kernels["solve_linear"]["traffic"] = traffic_linear
     kernels["solve_cubic"]["traffic"] = traffic_cubic

@@ -21,6 +21,18 @@ struct Strides {
 
 inline size_t align_up(size_t x, size_t a = 256) { return (x + a - 1) / a * a; }
 
+// Workgroups are handed to the eight XCDs of the chip in turn, and each XCD has its own L2.  A
+// one-wave workgroup of a lane-per-chain kernel touches 64 bytes of a mask row, half a 128-byte
+// line; its neighbour, which holds the other half, would run on the next XCD and fetch the line
+// again.  This maps the workgroup index so that, within every 16 consecutive workgroups, the two
+// that one XCD receives take neighbouring groups of chains.  A bijection on [0, grid).
+__device__ inline unsigned xcd_paired_block(unsigned b, unsigned grid)
+{
+    constexpr unsigned kXcds = 8;
+    if (b >= grid / (2 * kXcds) * (2 * kXcds)) return b;  // the ragged end keeps its order
+    return (b / (2 * kXcds)) * (2 * kXcds) + (b % kXcds) * 2 + (b / kXcds) % 2;
+}
+
 // ---- eval_peak ---------------------------------------------------------------
 hipError_t launch_eval_peak(const int64_t *d, const uint8_t *mask, int64_t batch, int n, Strides st,
                             int objective, int64_t *peak_out, int32_t *status_out, hipStream_t stream);

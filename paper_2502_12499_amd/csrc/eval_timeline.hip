@@ -44,7 +44,7 @@ __global__ __launch_bounds__(kBlock) void eval_timeline_kernel(const int64_t *__
                                                                int64_t *__restrict__ out, int64_t ocstride,
                                                                int64_t opstride, int32_t *__restrict__ status_out)
 {
-    const int64_t c = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+    const int64_t c = (int64_t)xcd_paired_block(blockIdx.x, gridDim.x) * kBlock + threadIdx.x;
     if (c >= batch) return;
     const int64_t *dp = d + c * cstride;
     const uint8_t *mp = mask + c * cstride;

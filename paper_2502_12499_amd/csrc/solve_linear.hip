@@ -131,7 +131,7 @@ __global__ __launch_bounds__(kWave) void linear_ring_kernel(const int64_t *__res
     static_assert(kPlane == 4096, "plane size and alignment");
 
     const int lane = threadIdx.x;
-    const int64_t c0 = (int64_t)blockIdx.x * kWave;
+    const int64_t c0 = (int64_t)xcd_paired_block(blockIdx.x, gridDim.x) * kWave;
     const int64_t c = c0 + lane;
     const bool live = c < batch;
     const int64_t cc = live ? c : batch - 1;  // idle lanes shadow the last chain and write nothing
