@@ -105,6 +105,16 @@ struct alignas(8) Step {
     int32_t d;      // d_t
     int32_t under;  // depth(t) - 1: the depth the size stack drops to before t goes on it
 };
+// What a wave reads about kGroup consecutive positions g*kGroup .. g*kGroup + kGroup - 1 before it
+// looks at any of them: if no lane's top entry is reached by the smallest size and no lane's
+// head is left behind by the last prefix sum, nothing happens in the whole group.
+constexpr int kGroup = 8;
+struct alignas(16) Group {
+    int32_t dmin;   // smallest d_t of the group
+    int32_t pend;   // P[t] of its last position
+    int32_t umin;   // smallest depth(t) - 1
+    int32_t pad;
+};
 // (P[h], d_h) of the kSnap elements of t's chain that follow t itself; zeros past its end
 struct alignas(64) Snap {
     PD<int32_t> e[kSnap];
@@ -116,6 +126,7 @@ struct CubicWs {
     El *el;               // [batch][table_len(n)], 32-bit chains only
     Snap *snap;           // [batch][table_len(n)], 32-bit chains only
     Step *step;           // [batch][step_len(n)], 32-bit chains only
+    Group *group;         // [batch][group_len(n)], 32-bit chains only
     int32_t *budgets;     // [batch][K] budget values in enumeration order (zeros for other chains) ...
     int32_t *sorted;      // ... and in ascending order per chain: lane i of wave w takes sorted[w*64 + i]
     int32_t *redo_count;  // number of waves whose ring was too small ...
@@ -137,6 +148,10 @@ __host__ __device__ inline int64_t waves_per_chain(int n) { return (num_budgets(
 __host__ __device__ inline size_t table_len(int n) { return ((size_t)n + 1 + kPad + kCells - 1) / kCells * kCells; }
 
 __host__ __device__ inline size_t step_len(int n) { return table_len(n) + 32; }  // read up to two blocks of 16 past n
+// Group g sits in slot g + 1, so that the pair of groups (1, 2), where the loop starts, and every
+// pair after it is 32-byte aligned; the loop reads up to three pairs past the last group it uses.
+__host__ __device__ inline size_t group_slot(int g) { return (size_t)g + 1; }
+__host__ __device__ inline size_t group_len(int n) { return (table_len(n) / kGroup + 10) / 2 * 2; }
 
 template <typename V>
 __device__ inline const PD<V> *chain_table(const CubicWs &w, int64_t c, int n)
@@ -194,6 +209,7 @@ __host__ CubicWs carve_cubic(void *ws, int64_t batch, int n)
     w.el = (El *)p;             p += align_up(B * table_len(n) * sizeof(El));
     w.snap = (Snap *)p;         p += align_up(B * table_len(n) * sizeof(Snap));
     w.step = (Step *)p;         p += align_up(B * step_len(n) * sizeof(Step));
+    w.group = (Group *)p;       p += align_up(B * group_len(n) * sizeof(Group));
     w.budgets = (int32_t *)p;   p += align_up(B * (size_t)num_budgets(n) * 4);
     w.sorted = (int32_t *)p;    p += align_up(B * (size_t)num_budgets(n) * 4);
     w.redo_count = (int32_t *)p; p += 256;
@@ -447,6 +463,21 @@ __global__ __launch_bounds__(kLinksBlock) void cubic_links_kernel(int n, CubicWs
     Step *__restrict__ st = w.step + (size_t)c * step_len(n);
     for (int t = tid; t < (int)step_len(n); t += kLinksBlock)
         st[t] = t < n1 ? Step{dl[t], (int32_t)(link[t] & 0xffffu) - 1} : Step{0, 0};
+    // the groups' summaries; a group that reaches past n is never used as one
+    Group *__restrict__ gr = w.group + (size_t)c * group_len(n);
+    for (int slot = tid; slot < (int)group_len(n); slot += kLinksBlock) {
+        Group G{std::numeric_limits<int32_t>::max(), 0, std::numeric_limits<int32_t>::max(), 0};
+        const int g = slot - 1;
+        const int t_last = g * kGroup + kGroup - 1;
+        if (g >= 0 && t_last < n1) {
+            for (int t = g * kGroup; t <= t_last; ++t) {
+                G.dmin = min(G.dmin, dl[t]);
+                G.umin = min(G.umin, (int32_t)(link[t] & 0xffffu) - 1);
+            }
+            G.pend = pd[t_last + 1].P;
+        }
+        gr[slot] = G;
+    }
 }
 
 // ---- budget index -> (range length, start) ------------------------------------
@@ -819,6 +850,7 @@ __global__ __launch_bounds__(BLOCK) void cubic_shared_kernel(int n, int64_t bloc
     const El *__restrict__ el = w.el + (size_t)c * table_len(n);
     const Snap *__restrict__ snap = w.snap + (size_t)c * table_len(n);
     const Step *__restrict__ st = w.step + (size_t)c * step_len(n);
+    const Group *__restrict__ gr = w.group + (size_t)c * group_len(n);
     const int64_t K = num_budgets(n);
     const int64_t idx = tile * BLOCK + tid;
     const int64_t wave_in_chain = idx / kWave;
@@ -979,14 +1011,22 @@ __global__ __launch_bounds__(BLOCK) void cubic_shared_kernel(int n, int64_t bloc
               "s96", "s97", "s98", "s99"); \
     }
     // ---- the unguarded middle of the chain as one loop in assembly ------------------
-    // Sixteen cells per round from two register sets (s[36:51], s[52:67]: eight
-    // (d, under) pairs each) that are loaded in turn one set ahead.  A cell is
+    // A cell is
     //     P += d;  base = min(base, under);  pop = d <= Xr;  gone = P > hK
     // with Xr = X - hF (so that F(t) = d + hF need not be formed to compare it),
-    // and falls through unless some lane pops or has lost its head; the rare parts
-    // of the sixteen cells sit behind the loop and jump back.
+    // and does nothing else unless some lane pops or has lost its head.  As long as
+    // no cell does more, X, hF and hK stay as they are; so none of kGroup consecutive
+    // cells does exactly when the group's smallest size and last prefix sum do not,
+    // and then the whole group is
+    //     pop = dmin <= Xr;  gone = pend > hK;  base = min(base, umin);  P = pend.
+    // Thirty-two cells per round: four groups, whose summaries come two at a time
+    // into s[36:43] and s[44:51], loaded in turn one pair ahead (the summaries of a
+    // chain are a quarter of its sizes and stay in the scalar cache).  A group that
+    // passes the test loads its eight (d, under) pairs into s[52:67] and takes its
+    // cells one by one; those, and the rare parts of the cells, sit behind the loop
+    // and jump back.
     // Fixed registers: v80 Y, v81 address, v82/v83 entry, v84 count, v85 write
-    // position, v86 old head value; s[68:83] snapshot, s[84:85] stream address,
+    // position, v86 old head value; s[68:83] snapshot, s[84:85] summaries' address,
     // s[86:87] saved exec, s[88:89] lanes whose head left, s[90:91] scratch mask,
     // s92 element counter, s93 offset, s94 next snapshot's position, s95 t of the
     // round's first cell, s96 rounds left.
@@ -1093,51 +1133,73 @@ __global__ __launch_bounds__(BLOCK) void cubic_shared_kernel(int n, int64_t bloc
     "v_cndmask_b32 %[X], %[X], %[vLow], vcc\n\t"             \
     "v_cndmask_b32 %[Xr], %[Xr], %[vLow], vcc\n\t"           \
     "s_branch Lback_" TAG "_%=\n\t"
+#define SH_GROUP(DMIN, PEND, UMIN, TAG)                      \
+    "v_cmp_le_i32 vcc, " DMIN ", %[Xr]\n\t"                  \
+    "v_cmp_gt_i32 s[88:89], " PEND ", %[hK]\n\t"             \
+    "s_or_b64 s[90:91], vcc, s[88:89]\n\t"                  \
+    "s_cbranch_scc1 Lcells_" TAG "_%=\n\t"                  \
+    "v_min_i32 %[base], " UMIN ", %[base]\n\t"              \
+    "s_mov_b32 %[P], " PEND "\n\t"                          \
+    "Lgroup_done_" TAG "_%=:\n\t"
+#define SH_CELLS(TAG, TOFF)                                  \
+    "Lcells_" TAG "_%=:\n\t"                                \
+    "s_add_u32 s93, s95, " TOFF "\n\t"                      \
+    "s_lshl_b32 s93, s93, 3\n\t"                            \
+    "s_load_dwordx16 s[52:67], %[stb], s93\n\t"             \
+    "s_waitcnt lgkmcnt(0)\n\t"                              \
+    SH_FAST("s52", "s53", TAG "c0") SH_FAST("s54", "s55", TAG "c1") SH_FAST("s56", "s57", TAG "c2") \
+    SH_FAST("s58", "s59", TAG "c3") SH_FAST("s60", "s61", TAG "c4") SH_FAST("s62", "s63", TAG "c5") \
+    SH_FAST("s64", "s65", TAG "c6") SH_FAST("s66", "s67", TAG "c7") \
+    "s_branch Lgroup_done_" TAG "_%=\n\t"
+#define SH_RARE8(TAG, T0, T1, T2, T3, T4, T5, T6, T7)       \
+    SH_RARE("s52", "s53", TAG "c0", T0) SH_RARE("s54", "s55", TAG "c1", T1) SH_RARE("s56", "s57", TAG "c2", T2) \
+    SH_RARE("s58", "s59", TAG "c3", T3) SH_RARE("s60", "s61", TAG "c4", T4) SH_RARE("s62", "s63", TAG "c5", T5) \
+    SH_RARE("s64", "s65", TAG "c6", T6) SH_RARE("s66", "s67", TAG "c7", T7)
+    static_assert(kGroup == 8 && sizeof(Group) == 16 && sizeof(Step) == 8, "the loads and shifts below");
     auto middle = [&](const int t_first, const int rounds) {
         V Xr = L.hd == L.tl ? kLow : L.X - L.hF;
-        const uint64_t stream = (uint64_t)(uintptr_t)(st + t_first);
+        const uint64_t summaries = (uint64_t)(uintptr_t)(gr + group_slot(t_first / kGroup));
+        const uint64_t st_base = (uint64_t)(uintptr_t)st;
         asm volatile(
-            "s_mov_b64 s[84:85], %[stream]\n\t"
+            "s_mov_b64 s[84:85], %[summaries]\n\t"
             "s_mov_b32 s95, %[t_first]\n\t"
             "s_mov_b32 s96, %[rounds]\n\t"
-            "s_load_dwordx16 s[36:51], s[84:85], 0x0\n\t"
+            "s_load_dwordx8 s[36:43], s[84:85], 0x0\n\t"
             "Lround_%=:\n\t"
             "s_waitcnt lgkmcnt(0)\n\t"
-            "s_load_dwordx16 s[52:67], s[84:85], 0x40\n\t"
-            SH_FAST("s36", "s37", "a0") SH_FAST("s38", "s39", "a1") SH_FAST("s40", "s41", "a2")
-            SH_FAST("s42", "s43", "a3") SH_FAST("s44", "s45", "a4") SH_FAST("s46", "s47", "a5")
-            SH_FAST("s48", "s49", "a6") SH_FAST("s50", "s51", "a7")
+            "s_load_dwordx8 s[44:51], s[84:85], 0x20\n\t"
+            SH_GROUP("s36", "s37", "s38", "g0") SH_GROUP("s40", "s41", "s42", "g1")
             "s_waitcnt lgkmcnt(0)\n\t"
-            "s_load_dwordx16 s[36:51], s[84:85], 0x80\n\t"
-            SH_FAST("s52", "s53", "b0") SH_FAST("s54", "s55", "b1") SH_FAST("s56", "s57", "b2")
-            SH_FAST("s58", "s59", "b3") SH_FAST("s60", "s61", "b4") SH_FAST("s62", "s63", "b5")
-            SH_FAST("s64", "s65", "b6") SH_FAST("s66", "s67", "b7")
-            "s_add_u32 s84, s84, 0x80\n\t"
+            "s_load_dwordx8 s[36:43], s[84:85], 0x40\n\t"
+            SH_GROUP("s44", "s45", "s46", "g2") SH_GROUP("s48", "s49", "s50", "g3")
+            "s_add_u32 s84, s84, 0x40\n\t"
             "s_addc_u32 s85, s85, 0\n\t"
-            "s_add_u32 s95, s95, 16\n\t"
+            "s_add_u32 s95, s95, 32\n\t"
             "s_sub_u32 s96, s96, 1\n\t"
             "s_cmp_lg_u32 s96, 0\n\t"
             "s_cbranch_scc1 Lround_%=\n\t"
             "s_waitcnt lgkmcnt(0)\n\t"
             "s_branch Lexit_%=\n\t"
-            SH_RARE("s36", "s37", "a0", "0") SH_RARE("s38", "s39", "a1", "1") SH_RARE("s40", "s41", "a2", "2")
-            SH_RARE("s42", "s43", "a3", "3") SH_RARE("s44", "s45", "a4", "4") SH_RARE("s46", "s47", "a5", "5")
-            SH_RARE("s48", "s49", "a6", "6") SH_RARE("s50", "s51", "a7", "7")
-            SH_RARE("s52", "s53", "b0", "8") SH_RARE("s54", "s55", "b1", "9") SH_RARE("s56", "s57", "b2", "10")
-            SH_RARE("s58", "s59", "b3", "11") SH_RARE("s60", "s61", "b4", "12") SH_RARE("s62", "s63", "b5", "13")
-            SH_RARE("s64", "s65", "b6", "14") SH_RARE("s66", "s67", "b7", "15")
+            SH_CELLS("g0", "0") SH_CELLS("g1", "8") SH_CELLS("g2", "16") SH_CELLS("g3", "24")
+            SH_RARE8("g0", "0", "1", "2", "3", "4", "5", "6", "7")
+            SH_RARE8("g1", "8", "9", "10", "11", "12", "13", "14", "15")
+            SH_RARE8("g2", "16", "17", "18", "19", "20", "21", "22", "23")
+            SH_RARE8("g3", "24", "25", "26", "27", "28", "29", "30", "31")
             "Lexit_%=:\n\t"
             : [hd] "+v"(L.hd), [tl] "+v"(L.tl), [hF] "+v"(L.hF), [hK] "+v"(L.hK), [X] "+v"(L.X), [Xr] "+v"(Xr),
               [base] "+v"(L.base), [over] "+v"(L.over), [P] "+s"(P)
-            : [stream] "s"(stream), [t_first] "s"(t_first), [rounds] "s"(rounds), [snapb] "s"(snap_base),
-              [elb] "s"(el_base), [lo] "v"(lane_base), [s] "v"(s), [vLow] "v"(vLow), [mask] "s"(kSlotMask),
-              [step] "i"(kStep), [shift] "i"(kShift), [cap] "i"(RING * kStep)
+            : [summaries] "s"(summaries), [stb] "s"(st_base), [t_first] "s"(t_first), [rounds] "s"(rounds),
+              [snapb] "s"(snap_base), [elb] "s"(el_base), [lo] "v"(lane_base), [s] "v"(s), [vLow] "v"(vLow),
+              [mask] "s"(kSlotMask), [step] "i"(kStep), [shift] "i"(kShift), [cap] "i"(RING * kStep)
             : "vcc", "scc", "memory", "v80", "v81", "v82", "v83", "v84", "v85", "v86", "s36", "s37", "s38", "s39", "s40",
               "s41", "s42", "s43", "s44", "s45", "s46", "s47", "s48", "s49", "s50", "s51", "s52", "s53", "s54", "s55",
               "s56", "s57", "s58", "s59", "s60", "s61", "s62", "s63", "s64", "s65", "s66", "s67", "s68", "s69", "s70",
               "s71", "s72", "s73", "s74", "s75", "s76", "s77", "s78", "s79", "s80", "s81", "s82", "s83", "s84", "s85",
               "s86", "s87", "s88", "s89", "s90", "s91", "s92", "s93", "s94", "s95", "s96");
     };
+#undef SH_GROUP
+#undef SH_CELLS
+#undef SH_RARE8
 #undef SH_FAST
 #undef SH_SNAP_STEP
 #undef SH_RARE
@@ -1181,10 +1243,10 @@ __global__ __launch_bounds__(BLOCK) void cubic_shared_kernel(int n, int64_t bloc
     block(A, B, 0, true);
     int t0 = kBlockCells;
 #if CKPT_CUBIC_ASM_CELL
-    if (last_full - t0 >= 16) {
-        const int rounds = (last_full - t0) / 16;
+    if (last_full - t0 >= 32) {
+        const int rounds = (last_full - t0) / 32;
         middle(t0, rounds);
-        t0 += 16 * rounds;
+        t0 += 32 * rounds;
 #pragma unroll
         for (int u = 0; u < kBlockCells; ++u) B[u] = uniform_load(st, t0 + u);
     }
@@ -1754,7 +1816,7 @@ size_t cubic_workspace_bytes(int64_t batch, int n)
     const size_t n1 = (size_t)n + 1, B = (size_t)batch, wpc = (size_t)waves_per_chain(n);
     return align_up(B * sizeof(ChainMeta)) + align_up(B * table_len(n) * sizeof(PD<int64_t>)) +
            align_up(B * table_len(n) * sizeof(El)) + align_up(B * table_len(n) * sizeof(Snap)) +
-           align_up(B * step_len(n) * sizeof(Step)) + 2 * align_up(B * (size_t)num_budgets(n) * 4) +
+           align_up(B * step_len(n) * sizeof(Step)) + align_up(B * group_len(n) * sizeof(Group)) + 2 * align_up(B * (size_t)num_budgets(n) * 4) +
            align_up(sort_tmp_bytes(batch, n)) + 256 + align_up(B * wpc * 8) +
            align_up(B * wpc * sizeof(Partial)) + align_up(B * wpc * 8) +
            align_up(B * kReduceBlocks * sizeof(Partial)) + align_up(B * n1 * 4) + 2 * align_up(B * 4) +
