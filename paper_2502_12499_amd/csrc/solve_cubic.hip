@@ -542,7 +542,8 @@ __global__ __launch_bounds__(BLOCK) void cubic_budgets_kernel(int n, int64_t blo
     const int64_t wave_in_chain = idx / kWave;   // uniform per wave
     if (wave_in_chain * kWave >= K) return;      // whole wave beyond the list
     const bool live = idx < K;
-    const V s = live ? budget_value<V>(pd, idx, n) : 0;
+    // lanes past the list take the largest budget (all interior layers), the one with the least to do
+    const V s = live ? budget_value<V>(pd, idx, n) : (V)(pd[n].P - pd[1].P);
 
     // LDS byte address of this lane's slot 0 (the ring is aligned to its own size,
     // so a position's address is (pos & kSlotMask) | lane_base)
@@ -856,7 +857,9 @@ __global__ __launch_bounds__(BLOCK) void cubic_shared_kernel(int n, int64_t bloc
     const int64_t wave_in_chain = idx / kWave;
     if (wave_in_chain * kWave >= K) continue;
     const bool live = idx < K;
-    const V s = live ? w.sorted[c * K + idx] : 0;
+    // lanes past the list take the largest budget, whose head never leaves, and are not counted:
+    // a budget of 0 there would make this wave the slowest of the launch, and it starts last
+    const V s = w.sorted[c * K + (live ? idx : K - 1)];
     if (!REDO && mode != kSharedAll) {
         const bool first = (tid & (kWave - 1)) == 0;
         // budgets ascend along the sorted list: the wave's first lane holds its smallest, its last
