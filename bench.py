@@ -23,6 +23,7 @@ if ROOT not in sys.path:
 HBM_PEAK_GBS = 8000.0
 # 256 CUs x 4 SIMDs x 16 lanes x 2.4 GHz: one 32-bit integer lane-op per lane per clock
 INT32_PEAK_TOPS = 256 * 64 * 2.4e9 / 1e12
+CUBIC_VALU_INSTS = 5.81e8  # per launch at n = 4096
 CUBIC_OPS_PER_CELL = 3  # one add and two compare-selects (queue push / pop) per recurrence cell
 
 
@@ -237,10 +238,22 @@ def main():
     kernels["solve_linear"]["traffic"] = traffic_linear
     kernels["solve_cubic"]["traffic"] = traffic_cubic
     dominant = max(names, key=lambda k: ms[k])
+    # Vector instructions that one launch of cubic_shared_kernel executes (rocprofv3 SQ_INSTS_VALU,
+    # profiles/bench_stress_kernel_stats.md; default workload only, None when the kernel changes): with 64
+    # lanes each they give the rate the hardware ran at, beside the algorithmic one.
+    valu_insts_cubic = CUBIC_VALU_INSTS if default_workload else None
+    kernels["solve_cubic"]["executed_TOPs"] = (valu_insts_cubic * 64 / (ms["solve_cubic"] * 1e-3) / 1e12
+                                               if valu_insts_cubic else None)
     if dominant == "solve_cubic":
         roofline = {"kernel": "cubic_shared_kernel (timed as the whole ckpt_solve_cubic call)", "bound": "alu",
                     "achieved": kernels["solve_cubic"]["int32_TOPs"], "peak": INT32_PEAK_TOPS, "unit": "TOP/s",
-                    "frac": kernels["solve_cubic"]["int32_frac"], "traffic": traffic_cubic}
+                    "frac": kernels["solve_cubic"]["int32_frac"], "traffic": traffic_cubic,
+                    "executed_frac": (kernels["solve_cubic"]["executed_TOPs"] / INT32_PEAK_TOPS
+                                      if valu_insts_cubic else None),
+                    "note": "achieved/frac count 3 operations for every cell of the recurrence (the algorithmic "
+                            "rate); the kernel passes over groups of eight cells in which nothing can happen, so "
+                            "it executes fewer and frac can exceed 1; executed_frac = vector instructions "
+                            "executed x 64 lanes / time / peak"}
     else:
         roofline = {"kernel": dominant, "bound": "hbm", "achieved": kernels[dominant]["hbm_GBs"],
                     "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": kernels[dominant]["hbm_frac"], "traffic": None}
