@@ -1144,6 +1144,18 @@ __global__ __launch_bounds__(BLOCK) void cubic_shared_kernel(int n, int64_t bloc
     "v_min_i32 %[base], " UMIN ", %[base]\n\t"              \
     "s_mov_b32 %[P], " PEND "\n\t"                          \
     "Lgroup_done_" TAG "_%=:\n\t"
+// Two groups at once, on the smaller of their smallest sizes and depths and the second one's
+// last prefix sum; the groups one by one, behind the loop, only if that test passes.
+#define SH_PAIR(DMIN0, UMIN0, DMIN1, PEND1, UMIN1, TAG)      \
+    "s_min_i32 s97, " DMIN0 ", " DMIN1 "\n\t"                \
+    "s_min_i32 s98, " UMIN0 ", " UMIN1 "\n\t"                \
+    "v_cmp_le_i32 vcc, s97, %[Xr]\n\t"                      \
+    "v_cmp_gt_i32 s[88:89], " PEND1 ", %[hK]\n\t"           \
+    "s_or_b64 s[90:91], vcc, s[88:89]\n\t"                  \
+    "s_cbranch_scc1 Lpair_open_" TAG "_%=\n\t"              \
+    "v_min_i32 %[base], s98, %[base]\n\t"                   \
+    "s_mov_b32 %[P], " PEND1 "\n\t"                         \
+    "Lpair_done_" TAG "_%=:\n\t"
 #define SH_CELLS(TAG, TOFF)                                  \
     "Lcells_" TAG "_%=:\n\t"                                \
     "s_add_u32 s93, s95, " TOFF "\n\t"                      \
@@ -1171,10 +1183,10 @@ __global__ __launch_bounds__(BLOCK) void cubic_shared_kernel(int n, int64_t bloc
             "Lround_%=:\n\t"
             "s_waitcnt lgkmcnt(0)\n\t"
             "s_load_dwordx8 s[44:51], s[84:85], 0x20\n\t"
-            SH_GROUP("s36", "s37", "s38", "g0") SH_GROUP("s40", "s41", "s42", "g1")
+            SH_PAIR("s36", "s38", "s40", "s41", "s42", "p0")
             "s_waitcnt lgkmcnt(0)\n\t"
             "s_load_dwordx8 s[36:43], s[84:85], 0x40\n\t"
-            SH_GROUP("s44", "s45", "s46", "g2") SH_GROUP("s48", "s49", "s50", "g3")
+            SH_PAIR("s44", "s46", "s48", "s49", "s50", "p1")
             "s_add_u32 s84, s84, 0x40\n\t"
             "s_addc_u32 s85, s85, 0\n\t"
             "s_add_u32 s95, s95, 32\n\t"
@@ -1183,6 +1195,12 @@ __global__ __launch_bounds__(BLOCK) void cubic_shared_kernel(int n, int64_t bloc
             "s_cbranch_scc1 Lround_%=\n\t"
             "s_waitcnt lgkmcnt(0)\n\t"
             "s_branch Lexit_%=\n\t"
+            "Lpair_open_p0_%=:\n\t"
+            SH_GROUP("s36", "s37", "s38", "g0") SH_GROUP("s40", "s41", "s42", "g1")
+            "s_branch Lpair_done_p0_%=\n\t"
+            "Lpair_open_p1_%=:\n\t"
+            SH_GROUP("s44", "s45", "s46", "g2") SH_GROUP("s48", "s49", "s50", "g3")
+            "s_branch Lpair_done_p1_%=\n\t"
             SH_CELLS("g0", "0") SH_CELLS("g1", "8") SH_CELLS("g2", "16") SH_CELLS("g3", "24")
             SH_RARE8("g0", "0", "1", "2", "3", "4", "5", "6", "7")
             SH_RARE8("g1", "8", "9", "10", "11", "12", "13", "14", "15")
@@ -1198,8 +1216,9 @@ __global__ __launch_bounds__(BLOCK) void cubic_shared_kernel(int n, int64_t bloc
               "s41", "s42", "s43", "s44", "s45", "s46", "s47", "s48", "s49", "s50", "s51", "s52", "s53", "s54", "s55",
               "s56", "s57", "s58", "s59", "s60", "s61", "s62", "s63", "s64", "s65", "s66", "s67", "s68", "s69", "s70",
               "s71", "s72", "s73", "s74", "s75", "s76", "s77", "s78", "s79", "s80", "s81", "s82", "s83", "s84", "s85",
-              "s86", "s87", "s88", "s89", "s90", "s91", "s92", "s93", "s94", "s95", "s96");
+              "s86", "s87", "s88", "s89", "s90", "s91", "s92", "s93", "s94", "s95", "s96", "s97", "s98");
     };
+#undef SH_PAIR
 #undef SH_GROUP
 #undef SH_CELLS
 #undef SH_RARE8
