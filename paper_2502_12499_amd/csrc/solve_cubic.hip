@@ -53,6 +53,7 @@
 #include <hipcub/hipcub.hpp>
 
 #include <limits>
+#include <mutex>
 
 #include "ckpt_internal.h"
 
@@ -1845,6 +1846,40 @@ size_t cubic_workspace_bytes(int64_t batch, int n)
            align_up(B * n1 * 4) + align_up(B * 8) + 256;
 }
 
+namespace {
+
+// A side stream per device for work of a call that does not depend on what the caller's stream
+// is doing at the time; it is forked from and joined to the caller's stream with events, so to
+// the caller all work of the call is still on its stream.  Default priority; never destroyed.
+struct SideStream {
+    hipStream_t stream = nullptr;
+    hipEvent_t fork = nullptr, join = nullptr;
+};
+constexpr int kMaxDevices = 64;
+std::mutex side_mutex;
+SideStream side_streams[kMaxDevices];
+
+hipError_t side_stream_of_current_device(SideStream &out)
+{
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+    std::lock_guard<std::mutex> lock(side_mutex);
+    SideStream &s = side_streams[dev];
+    if (s.stream == nullptr) {
+        SideStream t;
+        if ((e = hipStreamCreateWithFlags(&t.stream, hipStreamNonBlocking)) != hipSuccess) return e;
+        if ((e = hipEventCreateWithFlags(&t.fork, hipEventDisableTiming)) != hipSuccess) return e;
+        if ((e = hipEventCreateWithFlags(&t.join, hipEventDisableTiming)) != hipSuccess) return e;
+        s = t;
+    }
+    out = s;
+    return hipSuccess;
+}
+
+}  // namespace
+
 hipError_t launch_solve_cubic(const int64_t *d, int64_t batch, int n, Strides st, uint8_t *mask_out,
                               int64_t *peak_out, int64_t *budget_out, int32_t *status_out, bool pruned,
                               int64_t *evaluated_out, void *ws, hipStream_t stream)
@@ -1857,6 +1892,8 @@ hipError_t launch_solve_cubic(const int64_t *d, int64_t batch, int n, Strides st
     const int64_t n_words = waves_per_chain(n) * batch;
     if (total_blocks > 0x7fffffffLL) return hipErrorInvalidConfiguration;
     const size_t table_lds = ((size_t)n + 1) * 8;
+    const int64_t per = sort_chains_per_call(batch, n);
+    if (per == 0) return hipErrorInvalidConfiguration;
 
     hipLaunchKernelGGL(cubic_prologue_kernel, dim3((unsigned)batch), dim3(kWave), 0, stream, d, batch, n,
                        st.chain, st.pos, w);
@@ -1865,12 +1902,19 @@ hipError_t launch_solve_cubic(const int64_t *d, int64_t batch, int n, Strides st
                                                  hipFuncAttributeMaxDynamicSharedMemorySize, (int)links_lds_bytes(n));
         if (e != hipSuccess) return e;
     }
-    hipLaunchKernelGGL(cubic_links_kernel, dim3((unsigned)batch), dim3(kLinksBlock), links_lds_bytes(n), stream, n, w);
+    // The links (one workgroup per chain, a tenth of a millisecond for a long chain) and the sorted
+    // budget list need only the prologue's tables and not each other: the links go to the side stream.
+    SideStream side;
+    hipError_t e = side_stream_of_current_device(side);
+    if (e != hipSuccess) return e;
+    if ((e = hipEventRecord(side.fork, stream)) != hipSuccess) return e;
+    if ((e = hipStreamWaitEvent(side.stream, side.fork, 0)) != hipSuccess) return e;
+    hipLaunchKernelGGL(cubic_links_kernel, dim3((unsigned)batch), dim3(kLinksBlock), links_lds_bytes(n), side.stream,
+                       n, w);
+    if ((e = hipEventRecord(side.join, side.stream)) != hipSuccess) return e;
     {
         const int64_t vblocks = (K + 255) / 256;
         hipLaunchKernelGGL(cubic_values_kernel, dim3((unsigned)(vblocks * batch)), dim3(256), 0, stream, n, vblocks, w);
-        const int64_t per = sort_chains_per_call(batch, n);
-        if (per == 0) return hipErrorInvalidConfiguration;
         for (int64_t c0 = 0; c0 < batch; c0 += per) {
             size_t bytes = w.sort_tmp_bytes;
             const int64_t chains = batch - c0 < per ? batch - c0 : per;
@@ -1878,6 +1922,7 @@ hipError_t launch_solve_cubic(const int64_t *d, int64_t batch, int n, Strides st
             if (e != hipSuccess) return e;
         }
     }
+    if ((e = hipStreamWaitEvent(stream, side.join, 0)) != hipSuccess) return e;
     launch_shared<16, 64, 64>(n, batch, pruned, w, stream);
     launch_budgets<int64_t, 16, 64>(n, batch, w, stream);
     const int64_t word_groups = (n_words + kWave - 1) / kWave;
