@@ -1025,9 +1025,11 @@ __global__ __launch_bounds__(BLOCK) void cubic_shared_kernel(int n, int64_t bloc
     //     pop = dmin <= Xr;  gone = pend > hK;  base = min(base, umin);  P = pend.
     // Thirty-two cells per round: four groups, whose summaries come two at a time
     // into s[36:43] and s[44:51], loaded in turn one pair ahead (the summaries of a
-    // chain are a quarter of its sizes and stay in the scalar cache).  A group that
-    // passes the test loads its eight (d, under) pairs into s[52:67] and takes its
-    // cells one by one; those, and the rare parts of the cells, sit behind the loop
+    // chain are a quarter of its sizes and stay in the scalar cache).  The two groups
+    // of a load are first tested as one (the smaller dmin and umin, the second pend;
+    // s97, s98), and singly only if that passes.  A group that passes the test loads
+    // its eight (d, under) pairs into s[52:67] and takes its cells one by one; the
+    // single groups, the cells and the rare parts of the cells sit behind the loop
     // and jump back.
     // Fixed registers: v80 Y, v81 address, v82/v83 entry, v84 count, v85 write
     // position, v86 old head value; s[68:83] snapshot, s[84:85] summaries' address,
@@ -1308,7 +1310,7 @@ constexpr int kRedoBlocks = 2048;
 constexpr int kSampleStride = 64;  // a pruned call first runs every 64th tile of the sorted budgets
 // Pruning costs two more passes of at least one wave's running time each, and the budgets it
 // keeps are the small ones, whose waves run longest: below this length it does not pay.
-constexpr int kPruneFromLayers = 2048;
+constexpr int kPruneFromLayers = 4096;
 
 // The two bounds of a pruned call.  One workgroup per chain.
 //

@@ -70,7 +70,7 @@ def check_cubic(d, chain_major=False):
             mask, peak, budget, evaluated, status = B.ckpt_solve_cubic_pruned(x, chain_major=chain_major)
             # at most every budget once plus the sampled tiles (whole tiles) a second time
             assert bool((evaluated >= 1).all()) and bool((evaluated <= K + K // 64 + 512).all()), "evaluated"
-            if n < 2048:
+            if n < 4096:
                 assert bool((evaluated == K).all())
         else:
             mask, peak, budget, status = B.ckpt_solve_cubic(x, chain_major=chain_major)
@@ -267,20 +267,17 @@ def test_solve_cubic_data_errors():
         assert np_(peak)[c] == v and np_(budget)[c] == s and (np_(mask)[:, c] == mk).all()
 
 
-def test_solve_cubic_pruned_runs_few_budgets_on_long_chains():
-    """Where the optimum is far below the sum of the sizes most budgets cannot be optimal."""
+def test_solve_cubic_pruned_runs_every_budget_of_shorter_chains():
+    """Below 4096 layers the extra passes cost more than they save: the call does not prune
+    (a chain of 4096 layers, where it does, is in the full-size tests)."""
     n = 2500
-    say(f"solve_cubic_pruned n={n}: budgets run")
+    say(f"solve_cubic_pruned n={n}")
     d = inputs.config5_single(n)
     K = n * (n - 1) // 2 + 1
     mask, peak, budget, evaluated, status = B.ckpt_solve_cubic_pruned(to_dev(d))
     v, mk, s = oracle.solve_static(d[:, 0])
     assert int(peak[0]) == v and int(budget[0]) == s and (np_(mask)[:, 0] == mk).all()
-    b = oracle.budgets(d[:, 0])
-    below = int((b <= v - d[0, 0] - d[n, 0]).sum())     # what the upper bound alone would leave at best
-    assert 0 < int(evaluated[0]) <= K // 4
-    say(f"  {int(evaluated[0])} of {K} budgets run ({below} lie under the optimum's upper bound)")
-    # shorter chains are solved without pruning
+    assert int(evaluated[0]) == K
     d = inputs.config4()
     _, _, _, evaluated, _ = B.ckpt_solve_cubic_pruned(to_dev(d))
     assert int(evaluated[0]) == 1001 * 1000 // 2 + 1
