@@ -222,6 +222,38 @@ def test_solve_cubic_special_chains(name, d):
     check_cubic(d.reshape(-1, 1))
 
 
+def group_edge_chains():
+    """32-bit chains of lengths around the cubic kernel's units (groups of 8 positions, rounds of 32,
+    the loop starting at position 8), shaped so that queue events fall on and around the groups'
+    first and last positions."""
+    rng = np.random.default_rng(23)
+    out = []
+    for n in (39, 40, 41, 47, 48, 71, 72, 73, 103, 104, 105, 136, 167, 168, 169):
+        k = np.arange(n + 1)
+        shapes = {
+            "random": rng.integers(256, 32769, size=n + 1),
+            "constant": np.full(n + 1, 7),
+            "increasing": 3 + k,
+            "decreasing": 3 + n - k,                       # the size stack grows to n
+            "spike_every_8": np.where(k % 8 == 0, 5000, 9 + k % 5),
+            "spike_before_8": np.where(k % 8 == 7, 5000, 9 + k % 5),
+            "dip_every_8": np.where(k % 8 == 0, 1, 400 + k % 3),
+            "dip_before_32": np.where(k % 32 == 31, 1, 400 + k % 7),
+            "two_values": rng.integers(1, 3, size=n + 1),   # ties everywhere
+        }
+        for kind, d in shapes.items():
+            out.append((f"{kind}_{n}", d.astype(np.int64) * 4096))
+    return out
+
+
+def test_solve_cubic_group_edges():
+    """Every budget of many short chains: one call per length, the shapes side by side as a batch."""
+    chains = group_edge_chains()
+    for n in sorted({len(d) - 1 for _, d in chains}):
+        say(f"solve_cubic group edges n={n}")
+        check_cubic(np.stack([d for _, d in chains if len(d) - 1 == n], axis=1))
+
+
 def test_solve_cubic_single_chain_configs():
     for name, d in (("config1", inputs.config1()), ("config2", inputs.config2())):
         say(f"solve_cubic {name}")
