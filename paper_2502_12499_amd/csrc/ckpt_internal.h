@@ -33,6 +33,58 @@ __device__ inline unsigned xcd_paired_block(unsigned b, unsigned grid)
     return (b / (2 * kXcds)) * (2 * kXcds) + (b % kXcds) * 2 + (b / kXcds) % 2;
 }
 
+// ---- wave reductions on the data-parallel-primitive path (no LDS traffic) --------------------------
+
+constexpr int kDppRowShr1 = 0x111, kDppRowShr2 = 0x112, kDppRowShr4 = 0x114, kDppRowShr8 = 0x118;
+constexpr int kDppRowBcast15 = 0x142, kDppRowBcast31 = 0x143;
+
+// One step of a wave reduction: every lane whose DPP source exists (and whose
+// row is in ROW_MASK) joins its value with the source's; the others keep theirs.
+template <int CTRL, int ROW_MASK>
+__device__ inline uint64_t dpp_min_step_u64(uint64_t v)
+{
+    const uint32_t lo = (uint32_t)v, hi = (uint32_t)(v >> 32);
+    const uint32_t olo = (uint32_t)__builtin_amdgcn_update_dpp((int)lo, (int)lo, CTRL, ROW_MASK, 0xf, false);
+    const uint32_t ohi = (uint32_t)__builtin_amdgcn_update_dpp((int)hi, (int)hi, CTRL, ROW_MASK, 0xf, false);
+    const uint64_t o = ((uint64_t)ohi << 32) | olo;
+    return o < v ? o : v;
+}
+
+template <int CTRL, int ROW_MASK>
+__device__ inline uint32_t dpp_min_step_u32(uint32_t v)
+{
+    const uint32_t o = (uint32_t)__builtin_amdgcn_update_dpp((int)v, (int)v, CTRL, ROW_MASK, 0xf, false);
+    return o < v ? o : v;
+}
+
+// Minimum over the wave, returned to every lane.  Shifts by 1, 2, 4, 8 inside
+// each row of 16 lanes leave the row's minimum in its last lane; lane 15 is
+// then broadcast into row 1 and lane 47 into row 3, lane 31 into rows 2 and 3,
+// and lane 63 holds the minimum of all 64.
+__device__ inline uint64_t wave_min_u64(uint64_t v)
+{
+    v = dpp_min_step_u64<kDppRowShr1, 0xf>(v);
+    v = dpp_min_step_u64<kDppRowShr2, 0xf>(v);
+    v = dpp_min_step_u64<kDppRowShr4, 0xf>(v);
+    v = dpp_min_step_u64<kDppRowShr8, 0xf>(v);
+    v = dpp_min_step_u64<kDppRowBcast15, 0xa>(v);
+    v = dpp_min_step_u64<kDppRowBcast31, 0xc>(v);
+    const uint32_t lo = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)v, 63);
+    const uint32_t hi = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)(v >> 32), 63);
+    return ((uint64_t)hi << 32) | lo;
+}
+
+__device__ inline uint32_t wave_min_u32(uint32_t v)
+{
+    v = dpp_min_step_u32<kDppRowShr1, 0xf>(v);
+    v = dpp_min_step_u32<kDppRowShr2, 0xf>(v);
+    v = dpp_min_step_u32<kDppRowShr4, 0xf>(v);
+    v = dpp_min_step_u32<kDppRowShr8, 0xf>(v);
+    v = dpp_min_step_u32<kDppRowBcast15, 0xa>(v);
+    v = dpp_min_step_u32<kDppRowBcast31, 0xc>(v);
+    return (uint32_t)__builtin_amdgcn_readlane((int)v, 63);
+}
+
 // ---- eval_peak ---------------------------------------------------------------
 hipError_t launch_eval_peak(const int64_t *d, const uint8_t *mask, int64_t batch, int n, Strides st,
                             int objective, int64_t *peak_out, int32_t *status_out, hipStream_t stream);

@@ -234,17 +234,15 @@ __device__ inline int64_t shfl_i64(int64_t v, int src) { return __shfl(v, src, k
 __device__ inline int64_t shfl_xor_i64(int64_t v, int m) { return __shfl_xor(v, m, kWave); }
 __device__ inline int64_t shfl_up_i64(int64_t v, int d) { return __shfl_up(v, d, kWave); }
 
-// Lexicographic minimum of (a, b) over the wave; every lane gets the result.
+// Lexicographic minimum of (a, b) over the wave; every lane gets the result.  Both values are
+// non-negative wherever this is used (costs, budgets, indices, kInf), so they order as unsigned:
+// the smallest a, then the smallest b among the lanes that hold it.
 __device__ inline void wave_min_pair(int64_t &a, int64_t &b)
 {
-#pragma unroll
-    for (int m = kWave / 2; m >= 1; m >>= 1) {
-        const int64_t oa = shfl_xor_i64(a, m);
-        const int64_t ob = shfl_xor_i64(b, m);
-        const bool take = oa < a || (oa == a && ob < b);
-        a = take ? oa : a;
-        b = take ? ob : b;
-    }
+    const uint64_t am = wave_min_u64((uint64_t)a);
+    const uint64_t bm = wave_min_u64((uint64_t)a == am ? (uint64_t)b : ~0ull);
+    a = (int64_t)am;
+    b = (int64_t)bm;
 }
 
 // ---- prologue ---------------------------------------------------------------
