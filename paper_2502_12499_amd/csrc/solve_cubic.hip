@@ -8,7 +8,9 @@
 // the answer is min_s (s + c_s) over the budgets s = 0 and s = P[b] - P[a-1],
 // 1 <= a <= b <= n-1.
 //
-// Kernels, all on the caller's stream:
+// Kernels, all in the caller's stream order (the links kernel runs on a side
+// stream that is forked from the caller's stream after the prologue and joined
+// to it again before the shared kernel):
 //   prologue  one wave per chain: validates the sizes, builds P by a wave scan,
 //             divides everything by the largest common power of two and picks
 //             32-bit arithmetic when sum(d)+max(d) then fits (it does for
@@ -17,7 +19,8 @@
 //   32-bit chains:
 //   links     the monotone stack of the sizes themselves: for every position
 //             the nearest earlier smaller size, the stack depth, and a snapshot
-//             of the stack's next eight entries.
+//             of the stack's next eight entries; for every eight positions their
+//             smallest size and depth and last prefix sum.
 //   values +  the budget values in enumeration order, then sorted per chain
 //   sort      (library radix sort), so that the 64 lanes of a wave hold nearly
 //             equal budgets and meet the same events at the same cells.
@@ -26,7 +29,9 @@
 //             head stays, the part of Algorithm 4's queue that the lane builds
 //             is the stack of the sizes (cut off at a lane-specific depth), the
 //             same for every lane and every budget, so it is not stored at all.
-//             A cell is one min and two compares against wave-uniform values;
+//             A cell is one min and two compares against wave-uniform values,
+//             and eight cells in which no lane's compare can pass are taken as
+//             one such step on their summary;
 //             only when a head leaves does the lane write that part of its queue
 //             out to its ring in LDS (from the snapshot), and only such
 //             written-out entries are ever dropped by value.  See the comment
