@@ -125,10 +125,12 @@ int ckpt_solve_cubic(const int64_t *d, const ckpt_layout *layout, uint8_t *mask_
  * least sum(interior) - (m+1) s, and at least the m smallest interior sizes
  * W(m); c_s - d_0 - d_n >= min_m max(W(m), sum(interior) - (m+1) s), which
  * does not grow with s, so the budgets for which it exceeds UB - d_0 - d_n are
- * the ones below some s_lo.  The call takes a first UB from the set with a
- * checkpoint every ceil(sqrt(n)) layers, runs one tile in 64 of the sorted
- * budgets inside the bounds, takes UB from them, and then runs the budgets
- * inside the tightened bounds: the optimum, the smallest optimal budget and
+ * the ones below some s_lo.  The call takes a first UB from feasible sets it
+ * builds itself (a checkpoint every ceil(sqrt(n)) layers; greedy sets for a
+ * grid of segment limits); if the bounds from that UB still leave more than an
+ * eighth of the budgets it runs one tile in 64 of the sorted budgets inside
+ * them and takes UB from those as well; then it runs the budgets inside the
+ * bounds: the optimum, the smallest optimal budget and
  * the canonical set are unchanged (both comparisons are strict, so ties are
  * never cut).  Chains whose values need 64-bit arithmetic, and chains of
  * fewer than 4096 layers (where the extra passes cost more than they save),

@@ -145,6 +145,7 @@ struct CubicWs {
     int32_t *pred;        // [batch][n+1]
     int32_t *prune;       // [batch] budgets above this (normalised) value cannot be optimal; pruned calls only
     int32_t *prune_lo;    // [batch] ... nor budgets below this one
+    int32_t *skip_sample; // [batch] 1: the first bounds leave so few budgets that no sample is run first
     int32_t *wsum;        // [batch][n+1] wsum[m] = sum of the m smallest interior sizes; pruned calls only
     unsigned long long *evaluated;  // [batch] budgets whose recurrence was run; pruned calls only
 };
@@ -228,6 +229,7 @@ __host__ CubicWs carve_cubic(void *ws, int64_t batch, int n)
     w.pred = (int32_t *)p;      p += align_up(B * n1 * 4);
     w.prune = (int32_t *)p;     p += align_up(B * 4);
     w.prune_lo = (int32_t *)p;  p += align_up(B * 4);
+    w.skip_sample = (int32_t *)p; p += align_up(B * 4);
     w.wsum = (int32_t *)p;      p += align_up(B * n1 * 4);
     w.evaluated = (unsigned long long *)p; p += align_up(B * 8);
     return w;
@@ -261,6 +263,7 @@ __global__ __launch_bounds__(kWave) void cubic_prologue_kernel(const int64_t *__
     if (c == 0 && lane == 0) *w.redo_count = 0;
     if (lane == 0) {
         w.prune[c] = INT32_MAX;
+        w.skip_sample[c] = 0;
         w.prune_lo[c] = 0;
         w.evaluated[c] = 0;
     }
@@ -869,7 +872,8 @@ __global__ __launch_bounds__(BLOCK) void cubic_shared_kernel(int n, int64_t bloc
         // budgets ascend along the sorted list: the wave's first lane holds its smallest, its last
         // lane the largest (lanes past the list count as large)
         const V s_last = __builtin_amdgcn_readlane(live ? s : std::numeric_limits<V>::max(), kWave - 1);
-        if (__builtin_amdgcn_readfirstlane(s) > w.prune[c] || s_last < w.prune_lo[c]) {
+        if (__builtin_amdgcn_readfirstlane(s) > w.prune[c] || s_last < w.prune_lo[c] ||
+            (tile_stride > 1 && w.skip_sample[c] != 0)) {
             if (first) {
                 const int64_t slot_id = c * waves_per_chain(n) + wave_in_chain;
                 w.partial[slot_id] = Partial{kInf, (int64_t)s};
@@ -1327,10 +1331,12 @@ constexpr int kPruneFromLayers = 4096;
 // below some s_lo and cannot be optimal either.  (Both comparisons are strict, so
 // neither cuts a budget that ties with the optimum.)
 //
-// Stage 0, before anything has run: W from a bitonic sort of the sizes in LDS, and
-// UB from the cost of the set with a checkpoint every ceil(sqrt(n)) layers.
-// Stage 1, after the sampled tiles: UB from their results as well.
+// Stage 0, before anything has run: UB from the costs of feasible sets (a checkpoint every
+// ceil(sqrt(n)) layers; one greedy set per thread), W from a bitonic sort of the sizes in
+// LDS, and whether the bounds are tight enough to do without a sample.
+// Stage 1, after the sampled tiles (if they ran): UB from their results as well.
 constexpr int kBoundThreads = 256;
+constexpr int kSkipSampleBelow = 8;  // no sample when the first bounds leave under 1/8 of the budgets
 
 __global__ __launch_bounds__(kBoundThreads) void cubic_bound_kernel(int n, int64_t blocks_per_chain,
                                                                     int tile_stride, int waves_per_tile, int stage,
@@ -1347,12 +1353,36 @@ __global__ __launch_bounds__(kBoundThreads) void cubic_bound_kernel(int n, int64
     int32_t *W = w.wsum + c * ((int64_t)n + 1);
     const int m_int = n - 1;  // interior layers 1..n-1
 
-    int64_t best = kInf;
+    int64_t best = kInf, greedy = kInf;
     if (stage == 0) {
         // the interior sizes in ascending order, then their running sums
         int N = 1;
         while (N < m_int) N <<= 1;
         for (int t = tid; t < N; t += kBoundThreads) srt[t] = t < m_int ? el[t + 1].d : INT32_MAX;
+        __syncthreads();
+        // Upper bounds from greedy sets, before the sizes are put in order: thread t takes a segment
+        // limit on a geometric grid around sqrt(n) mean sizes and walks the chain once, making a
+        // checkpoint of every layer that would take its segment beyond the limit.  The set is
+        // feasible, so its cost (its checkpoints plus its largest segment) bounds the optimum.
+        {
+            int seg_len = 1;
+            while ((int64_t)seg_len * seg_len < n) ++seg_len;
+            const float mean = (float)(el[n].P - el[0].d - el[n].d) / (float)(m_int > 0 ? m_int : 1);
+            const float lim_f = mean * (float)seg_len * exp2f((float)(tid - kBoundThreads / 2) * (1.0f / 24.0f));
+            // 32-bit sums: the chain's total is below 2^30 in this mode, and so is the limit
+            const uint32_t lim = lim_f < 1.0f ? 1u : (lim_f > 1.0e9f ? 1000000000u : (uint32_t)lim_f);
+            uint32_t ck = (uint32_t)el[0].d + (uint32_t)el[n].d, seg = 0, seg_max = 0;
+#pragma unroll 8
+            for (int k = 0; k < m_int; ++k) {
+                const uint32_t x = (uint32_t)srt[k];
+                const bool fits = seg + x <= lim;
+                ck += fits ? 0u : x;
+                seg_max = (!fits && seg > seg_max) ? seg : seg_max;
+                seg = fits ? seg + x : 0u;
+            }
+            seg_max = seg > seg_max ? seg : seg_max;
+            greedy = (int64_t)ck + seg_max;
+        }
         __syncthreads();
         for (int k = 2; k <= N; k <<= 1)
             for (int j = k >> 1; j >= 1; j >>= 1) {
@@ -1411,7 +1441,15 @@ __global__ __launch_bounds__(kBoundThreads) void cubic_bound_kernel(int n, int64
             if (tid < half) part[tid] = part[tid + half] > part[tid] ? part[tid + half] : part[tid];
             __syncthreads();
         }
-        if (tid == 0) part[0] = ckpt_all + part[0];
+        const int64_t sqrt_set = ckpt_all + part[0];
+        __syncthreads();
+        part[tid] = greedy;
+        __syncthreads();
+        for (int half = kBoundThreads / 2; half >= 1; half >>= 1) {
+            if (tid < half) part[tid] = part[tid + half] < part[tid] ? part[tid + half] : part[tid];
+            __syncthreads();
+        }
+        if (tid == 0) part[0] = sqrt_set < part[0] ? sqrt_set : part[0];
         __syncthreads();
     } else {
         const int64_t wpc = waves_per_chain(n);
@@ -1455,6 +1493,14 @@ __global__ __launch_bounds__(kBoundThreads) void cubic_bound_kernel(int n, int64
         if (lower(mid) <= room) hi = mid; else lo = mid + 1;
     }
     w.prune_lo[c] = (int32_t)(lo < INT32_MAX ? lo : INT32_MAX);
+    if (stage == 0) {
+        // About n (room - s_lo) / mean ranges have their sum between the bounds (n starts, and as many
+        // lengths as mean sizes fit the gap).  If that is a small part of all budgets, running them all
+        // costs less than a sample that would only tighten the bounds further.
+        const int64_t mean = sum_int / (m_int > 0 ? m_int : 1) + 1;
+        const int64_t inside = (int64_t)n * ((room - lo) / mean + 1);
+        w.skip_sample[c] = inside <= num_budgets(n) / kSkipSampleBelow ? 1 : 0;
+    }
 }
 
 // All waves with a ring of RING entries per lane (for a pruned call: a sample of them, the
@@ -1465,10 +1511,8 @@ template <int RING, int BLOCK, int REDO_RING>
 void launch_shared(int n, int64_t batch, bool pruned, CubicWs w, hipStream_t stream)
 {
     const int64_t blocks_per_chain = (num_budgets(n) + BLOCK - 1) / BLOCK;
-    if (pruned) {
+    if (pruned) {  // the first bounds (stage 0 of cubic_bound_kernel) have been launched by the caller
         const int64_t sampled = (blocks_per_chain + kSampleStride - 1) / kSampleStride;
-        hipLaunchKernelGGL(cubic_bound_kernel, dim3((unsigned)batch), dim3(kBoundThreads), 0, stream, n,
-                           blocks_per_chain, kSampleStride, BLOCK / kWave, 0, w);
         hipLaunchKernelGGL((cubic_shared_kernel<RING, BLOCK, false>), dim3((unsigned)(sampled * batch)), dim3(BLOCK),
                            0, stream, n, blocks_per_chain, kSampleStride, kSharedPrune, w);
         hipLaunchKernelGGL(cubic_bound_kernel, dim3((unsigned)batch), dim3(kBoundThreads), 0, stream, n,
@@ -1847,7 +1891,7 @@ size_t cubic_workspace_bytes(int64_t batch, int n)
            align_up(B * step_len(n) * sizeof(Step)) + align_up(B * group_len(n) * sizeof(Group)) + 2 * align_up(B * (size_t)num_budgets(n) * 4) +
            align_up(sort_tmp_bytes(batch, n)) + 256 + align_up(B * wpc * 8) +
            align_up(B * wpc * sizeof(Partial)) + align_up(B * wpc * 8) +
-           align_up(B * kReduceBlocks * sizeof(Partial)) + align_up(B * n1 * 4) + 2 * align_up(B * 4) +
+           align_up(B * kReduceBlocks * sizeof(Partial)) + align_up(B * n1 * 4) + 3 * align_up(B * 4) +
            align_up(B * n1 * 4) + align_up(B * 8) + 256;
 }
 
@@ -1916,6 +1960,9 @@ hipError_t launch_solve_cubic(const int64_t *d, int64_t batch, int n, Strides st
     if ((e = hipStreamWaitEvent(side.stream, side.fork, 0)) != hipSuccess) return e;
     hipLaunchKernelGGL(cubic_links_kernel, dim3((unsigned)batch), dim3(kLinksBlock), links_lds_bytes(n), side.stream,
                        n, w);
+    if (pruned)  // the first bounds of a pruned call need the links' tables only: same place
+        hipLaunchKernelGGL(cubic_bound_kernel, dim3((unsigned)batch), dim3(kBoundThreads), 0, side.stream, n,
+                           (num_budgets(n) + kWave - 1) / kWave, kSampleStride, 1, 0, w);
     if ((e = hipEventRecord(side.join, side.stream)) != hipSuccess) return e;
     {
         const int64_t vblocks = (K + 255) / 256;
