@@ -133,7 +133,7 @@ int ckpt_solve_cubic(const int64_t *d, const ckpt_layout *layout, uint8_t *mask_
  * bounds: the optimum, the smallest optimal budget and
  * the canonical set are unchanged (both comparisons are strict, so ties are
  * never cut).  Chains whose values need 64-bit arithmetic, and chains of
- * fewer than 4096 layers (where the extra passes cost more than they save),
+ * fewer than 3072 layers (where pruning costs more than it saves),
  * are solved without pruning.
  * evaluated_out [out] `batch` int64 or NULL: the number of budgets whose
  * recurrence was run (sampled ones counted again when they run a second time),

@@ -1317,7 +1317,7 @@ constexpr int kRedoBlocks = 2048;
 constexpr int kSampleStride = 64;  // a pruned call first runs every 64th tile of the sorted budgets
 // Pruning costs two more passes of at least one wave's running time each, and the budgets it
 // keeps are the small ones, whose waves run longest: below this length it does not pay.
-constexpr int kPruneFromLayers = 4096;
+constexpr int kPruneFromLayers = 3072;
 
 // The two bounds of a pruned call.  One workgroup per chain.
 //

@@ -70,7 +70,7 @@ def check_cubic(d, chain_major=False):
             mask, peak, budget, evaluated, status = B.ckpt_solve_cubic_pruned(x, chain_major=chain_major)
             # at most every budget once plus the sampled tiles (whole tiles) a second time
             assert bool((evaluated >= 1).all()) and bool((evaluated <= K + K // 64 + 512).all()), "evaluated"
-            if n < 4096:
+            if n < 3072:
                 assert bool((evaluated == K).all())
         else:
             mask, peak, budget, status = B.ckpt_solve_cubic(x, chain_major=chain_major)
@@ -300,7 +300,7 @@ def test_solve_cubic_data_errors():
 
 
 def test_solve_cubic_pruned_runs_every_budget_of_shorter_chains():
-    """Below 4096 layers the extra passes cost more than they save: the call does not prune
+    """Below 3072 layers pruning costs more than it saves: the call does not prune
     (a chain of 4096 layers, where it does, is in the full-size tests)."""
     n = 2500
     say(f"solve_cubic_pruned n={n}")
