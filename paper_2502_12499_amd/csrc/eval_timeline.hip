@@ -59,9 +59,13 @@ __global__ __launch_bounds__(kBlock) void eval_timeline_kernel(const int64_t *__
     const int64_t x0 = dp[0];
     uint64_t ckpt_all = 0;  // sum of all checkpoints (Algorithm 2 only)
     if (OBJ == CKPT_OBJ_STATIC) {
-#pragma unroll 8
-        for (int k = 0; k <= n; ++k)
-            if (mp[(int64_t)k * pstride]) ckpt_all += (uint64_t)dp[(int64_t)k * pstride];
+        // both loads of a row are issued whatever the mask says, so that sixteen rows are in flight
+#pragma unroll 16
+        for (int k = 0; k <= n; ++k) {
+            const uint8_t on = mp[(int64_t)k * pstride];
+            const int64_t x = dp[(int64_t)k * pstride];
+            ckpt_all += on ? (uint64_t)x : 0;
+        }
     }
 
     // rows beyond n re-read row n and are not used
