@@ -7,11 +7,16 @@
  * mask over positions 0..n with mask[0] = mask[n] = 1.
  *
  * Memory and ownership.  Every pointer below, except the ckpt_layout itself,
- * is a DEVICE pointer owned by the caller.  The library allocates nothing,
- * keeps nothing between calls and never synchronises: each call validates its
+ * is a DEVICE pointer owned by the caller.  The library allocates no memory,
+ * keeps no data between calls and never synchronises: each call validates its
  * arguments on the host, enqueues its kernels on `hip_stream` (a hipStream_t
  * passed as void*, NULL = the null stream) and returns.  Outputs are valid
- * once the stream has reached the end of the call's work.  `ws` is scratch of
+ * once the stream has reached the end of the call's work.  (The two cubic
+ * calls run one of their kernels on a second stream, which the library
+ * creates with two events the first time they are used on a device and keeps;
+ * it waits for `hip_stream` at the start of that kernel and `hip_stream`
+ * waits for it before the call's later kernels, so to the caller the whole
+ * call is ordered on `hip_stream`.)  `ws` is scratch of
  * at least ckpt_workspace_bytes() bytes, 256-byte aligned, private to the call
  * until it has finished on the stream; its contents need no initialisation.
  *
