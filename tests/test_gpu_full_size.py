@@ -63,6 +63,31 @@ def test_config5_single_chain_cubic_n4096():
     assert int(evaluated.cpu()[0]) < K // 8
 
 
+def test_pruned_cubic_on_long_chains_with_a_few_huge_layers():
+    """Sizes with a heavy tail (one layer in twenty 20 to 200 times the others): the greedy sets that
+    give the pruned call its first upper bound then consist mostly of forced checkpoints, and the
+    lower bound's sorted sizes have a long flat start.  Two chains side by side, so that their bounds
+    and the decision whether to sample are per chain."""
+    n = 3200
+    say(f"solve_cubic_pruned: heavy-tailed sizes, n = {n}, 2 chains")
+    rng = np.random.default_rng(41)
+    d = rng.integers(100, 200, size=(n + 1, 2)) * 1024
+    d = np.where(rng.random((n + 1, 2)) < 0.05, d * rng.integers(20, 200, size=(n + 1, 2)), d)
+    d[:, 1] = inputs.config5_single(n)[:, 0]           # the second chain: the stress distribution
+    d = np.ascontiguousarray(d.astype(np.int64))
+    mask, peak, budget, evaluated, status = B.ckpt_solve_cubic_pruned(torch.from_numpy(d).to(DEV))
+    torch.cuda.synchronize()
+    say("  gpu done, oracle running")
+    K = n * (n - 1) // 2 + 1
+    for c in range(2):
+        v, mk, s = oracle.solve_static(d[:, c])
+        assert int(status.cpu()[c]) == 0
+        assert int(peak.cpu()[c]) == v and int(budget.cpu()[c]) == s
+        assert np.array_equal(mask.cpu().numpy()[:, c], mk)
+        say(f"  chain {c}: {int(evaluated.cpu()[c])} of {K} budgets run")
+        assert 0 < int(evaluated.cpu()[c]) < K
+
+
 def test_config5_full_batch_linear_and_eval():
     batch, n = 1048576, 256
     say("config 5: 1,048,576 chains, n = 256")
