@@ -583,13 +583,27 @@ __global__ __launch_bounds__(BLOCK) void cubic_budgets_kernel(int n, int64_t blo
     //    new value has been stored that loop stops at it at the latest (it fits).
     //  - when some lane's ring is full or has a live hole the whole wave takes
     //    the slow path, which is the same cell with the hole bookkeeping.
+    // The values of the two entries under the tail and the entry after the head are mirrored in
+    // registers as well (read back at the end of every cell, when nothing waits for them), so that
+    // the usual one to three drops and the usual single expiry are decided without a trip to LDS.
+    // What the mirrors hold beyond the head is never looked at: the head's value is below every
+    // new value, so the nested tests stop at it at the latest.
+    V t1F = kLow, t2F = kLow, h1F = kLow, h1K = kLow;
     auto cell_generic = [&](const V Pj1, const V dj) {
-        for (;;) {
-            const bool more = tF >= Fprev;
-            if (__builtin_amdgcn_ballot_w64(more) == 0) break;
-            if (more) {
-                tl -= kStep;
-                tF = slot(tl)[0];
+        const bool p0 = tF >= Fprev;
+        const bool p1 = p0 & (t1F >= Fprev);
+        const bool p2 = p1 & (t2F >= Fprev);
+        tl -= (p0 ? kStep : 0u) + (p1 ? kStep : 0u) + (p2 ? kStep : 0u);
+        tF = p1 ? t2F : (p0 ? t1F : tF);  // the value now at the tail (p2: read below)
+        if (__builtin_amdgcn_ballot_w64(p2) != 0) {
+            if (p2) tF = slot(tl)[0];
+            for (;;) {
+                const bool more = p2 & (tF >= Fprev);
+                if (__builtin_amdgcn_ballot_w64(more) == 0) break;
+                if (more) {
+                    tl -= kStep;
+                    tF = slot(tl)[0];
+                }
             }
         }
         const V key = Pj1 + s;
@@ -610,19 +624,37 @@ __global__ __launch_bounds__(BLOCK) void cubic_budgets_kernel(int n, int64_t blo
             tl += kStep;
             store_entry(tl, Fprev, key);
             tF = Fprev;
+            const bool second = tl == hd + kStep;  // the new entry is the one after the head
+            h1F = second ? Fprev : h1F;
+            h1K = second ? key : h1K;
         }
-        for (;;) {
-            const bool more = (hK < Pj1) & (hd != tl);
-            if (__builtin_amdgcn_ballot_w64(more) == 0) break;
-            if (more) {
+        const bool e0 = (hK < Pj1) & (hd != tl);
+        if (__builtin_amdgcn_ballot_w64(e0) != 0) {
+            if (e0) {
                 hd += kStep;
-                hF = slot(hd)[0];
-                hK = slot(hd)[1];
+                hF = h1F;
+                hK = h1K;
+            }
+            for (;;) {
+                const bool more = e0 & (hK < Pj1) & (hd != tl);
+                if (__builtin_amdgcn_ballot_w64(more) == 0) break;
+                if (more) {
+                    hd += kStep;
+                    hF = slot(hd)[0];
+                    hK = slot(hd)[1];
+                }
             }
         }
         over |= (hK < Pj1) | (hK > holeOld);  // nothing valid left, or the head passed a hole
         hole_lanes = __builtin_amdgcn_ballot_w64(holeOld != kHigh);
         Fprev = dj + hF;
+        {
+            LdsPtr a1 = slot(tl - kStep), a2 = slot(tl - 2 * kStep), b1 = slot(hd + kStep);
+            t1F = a1[0];
+            t2F = a2[0];
+            h1F = b1[0];
+            h1K = b1[1];
+        }
     };
 
     auto cell = [&](const V Pj1, const V dj) { cell_generic(Pj1, dj); };
