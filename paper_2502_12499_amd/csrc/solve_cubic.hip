@@ -40,7 +40,7 @@
 //   64-bit chains:
 //   budgets   one LANE per budget, 64 budgets of equal range length and
 //             consecutive start per wave, the queue kept per lane as a 16-entry
-//             ring in LDS laid out [slot][lane], head entry and tail value
+//             ring in LDS laid out [slot][lane], the entries at its two ends
 //             mirrored in registers, keys stored as P[h] + s so that expiry is
 //             one compare with P[j-1].  A value that finds the ring full is not
 //             stored but remembered as a "hole" (smallest value, oldest and
