@@ -119,7 +119,8 @@ struct alignas(16) Group {
     int32_t dmin;   // smallest d_t of the group
     int32_t pend;   // P[t] of its last position
     int32_t umin;   // smallest depth(t) - 1
-    int32_t pad;
+    int32_t pair;   // for the pair of groups in slots (2k, 2k+1): in the first the smaller of the two dmin,
+                    // in the second the smaller of the two umin
 };
 // (P[h], d_h) of the kSnap elements of t's chain that follow t itself; zeros past its end
 struct alignas(64) Snap {
@@ -472,7 +473,7 @@ __global__ __launch_bounds__(kLinksBlock) void cubic_links_kernel(int n, CubicWs
         st[t] = t < n1 ? Step{dl[t], (int32_t)(link[t] & 0xffffu) - 1} : Step{0, 0};
     // the groups' summaries; a group that reaches past n is never used as one
     Group *__restrict__ gr = w.group + (size_t)c * group_len(n);
-    for (int slot = tid; slot < (int)group_len(n); slot += kLinksBlock) {
+    auto summary = [&](const int slot) -> Group {
         Group G{std::numeric_limits<int32_t>::max(), 0, std::numeric_limits<int32_t>::max(), 0};
         const int g = slot - 1;
         const int t_last = g * kGroup + kGroup - 1;
@@ -483,6 +484,12 @@ __global__ __launch_bounds__(kLinksBlock) void cubic_links_kernel(int n, CubicWs
             }
             G.pend = pd[t_last + 1].P;
         }
+        return G;
+    };
+    for (int slot = tid; slot < (int)group_len(n); slot += kLinksBlock) {  // group_len is even
+        Group G = summary(slot);
+        const Group other = summary(slot ^ 1);
+        G.pair = (slot & 1) == 0 ? min(G.dmin, other.dmin) : min(G.umin, other.umin);
         gr[slot] = G;
     }
 }
@@ -1065,8 +1072,8 @@ __global__ __launch_bounds__(BLOCK) void cubic_shared_kernel(int n, int64_t bloc
     // Thirty-two cells per round: four groups, whose summaries come two at a time
     // into s[36:43] and s[44:51], loaded in turn one pair ahead (the summaries of a
     // chain are a quarter of its sizes and stay in the scalar cache).  The two groups
-    // of a load are first tested as one (the smaller dmin and umin, the second pend;
-    // s97, s98), and singly only if that passes.  A group that passes the test loads
+    // of a load are first tested as one (the smaller dmin and umin, which the
+    // summaries carry as well, and the second pend), and singly only if that passes.  A group that passes the test loads
     // its eight (d, under) pairs into s[52:67] and takes its cells one by one; the
     // single groups, the cells and the rare parts of the cells sit behind the loop
     // and jump back.
@@ -1186,16 +1193,15 @@ __global__ __launch_bounds__(BLOCK) void cubic_shared_kernel(int n, int64_t bloc
     "v_min_i32 %[base], " UMIN ", %[base]\n\t"              \
     "s_mov_b32 %[P], " PEND "\n\t"                          \
     "Lgroup_done_" TAG "_%=:\n\t"
-// Two groups at once, on the smaller of their smallest sizes and depths and the second one's
-// last prefix sum; the groups one by one, behind the loop, only if that test passes.
-#define SH_PAIR(DMIN0, UMIN0, DMIN1, PEND1, UMIN1, TAG)      \
-    "s_min_i32 s97, " DMIN0 ", " DMIN1 "\n\t"                \
-    "s_min_i32 s98, " UMIN0 ", " UMIN1 "\n\t"                \
-    "v_cmp_le_i32 vcc, s97, %[Xr]\n\t"                      \
+// Two groups at once, on the smaller of their smallest sizes and of their smallest depths (kept in
+// the summaries' fourth words) and the second one's last prefix sum; the groups one by one, behind
+// the loop, only if that test passes.
+#define SH_PAIR(DMIN01, PEND1, UMIN01, TAG)                  \
+    "v_cmp_le_i32 vcc, " DMIN01 ", %[Xr]\n\t"               \
     "v_cmp_gt_i32 s[88:89], " PEND1 ", %[hK]\n\t"           \
     "s_or_b64 s[90:91], vcc, s[88:89]\n\t"                  \
     "s_cbranch_scc1 Lpair_open_" TAG "_%=\n\t"              \
-    "v_min_i32 %[base], s98, %[base]\n\t"                   \
+    "v_min_i32 %[base], " UMIN01 ", %[base]\n\t"            \
     "s_mov_b32 %[P], " PEND1 "\n\t"                         \
     "Lpair_done_" TAG "_%=:\n\t"
 #define SH_CELLS(TAG, TOFF)                                  \
@@ -1225,10 +1231,10 @@ __global__ __launch_bounds__(BLOCK) void cubic_shared_kernel(int n, int64_t bloc
             "Lround_%=:\n\t"
             "s_waitcnt lgkmcnt(0)\n\t"
             "s_load_dwordx8 s[44:51], s[84:85], 0x20\n\t"
-            SH_PAIR("s36", "s38", "s40", "s41", "s42", "p0")
+            SH_PAIR("s39", "s41", "s43", "p0")
             "s_waitcnt lgkmcnt(0)\n\t"
             "s_load_dwordx8 s[36:43], s[84:85], 0x40\n\t"
-            SH_PAIR("s44", "s46", "s48", "s49", "s50", "p1")
+            SH_PAIR("s47", "s49", "s51", "p1")
             "s_add_u32 s84, s84, 0x40\n\t"
             "s_addc_u32 s85, s85, 0\n\t"
             "s_add_u32 s95, s95, 32\n\t"
@@ -1258,7 +1264,7 @@ __global__ __launch_bounds__(BLOCK) void cubic_shared_kernel(int n, int64_t bloc
               "s41", "s42", "s43", "s44", "s45", "s46", "s47", "s48", "s49", "s50", "s51", "s52", "s53", "s54", "s55",
               "s56", "s57", "s58", "s59", "s60", "s61", "s62", "s63", "s64", "s65", "s66", "s67", "s68", "s69", "s70",
               "s71", "s72", "s73", "s74", "s75", "s76", "s77", "s78", "s79", "s80", "s81", "s82", "s83", "s84", "s85",
-              "s86", "s87", "s88", "s89", "s90", "s91", "s92", "s93", "s94", "s95", "s96", "s97", "s98");
+              "s86", "s87", "s88", "s89", "s90", "s91", "s92", "s93", "s94", "s95", "s96");
     };
 #undef SH_PAIR
 #undef SH_GROUP
