@@ -23,7 +23,7 @@ if ROOT not in sys.path:
 HBM_PEAK_GBS = 8000.0
 # 256 CUs x 4 SIMDs x 16 lanes x 2.4 GHz: one 32-bit integer lane-op per lane per clock
 INT32_PEAK_TOPS = 256 * 64 * 2.4e9 / 1e12
-CUBIC_VALU_INSTS = 5.02e8  # per launch at n = 4096
+CUBIC_VALU_INSTS = 5.05e8  # per launch at n = 4096
 CUBIC_OPS_PER_CELL = 3  # one add and two compare-selects (queue push / pop) per recurrence cell
 
 
