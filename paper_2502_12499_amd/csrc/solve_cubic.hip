@@ -1945,6 +1945,9 @@ struct SideStream {
 constexpr int kMaxDevices = 64;
 std::mutex side_mutex;
 SideStream side_streams[kMaxDevices];
+// Held while a call enqueues its work: the fork and join events belong to the device, and a wait
+// refers to the event's latest record, so two host threads must not interleave their records and waits.
+std::mutex side_enqueue_mutex;
 
 hipError_t side_stream_of_current_device(SideStream &out)
 {
@@ -1994,6 +1997,7 @@ hipError_t launch_solve_cubic(const int64_t *d, int64_t batch, int n, Strides st
     SideStream side;
     hipError_t e = side_stream_of_current_device(side);
     if (e != hipSuccess) return e;
+    std::lock_guard<std::mutex> enqueue_lock(side_enqueue_mutex);
     if ((e = hipEventRecord(side.fork, stream)) != hipSuccess) return e;
     if ((e = hipStreamWaitEvent(side.stream, side.fork, 0)) != hipSuccess) return e;
     hipLaunchKernelGGL(cubic_links_kernel, dim3((unsigned)batch), dim3(kLinksBlock), links_lds_bytes(n), side.stream,
