@@ -81,3 +81,24 @@ def test_empty_batch_is_a_no_op():
     assert lib.ckpt_select_baseline(ctypes.byref(E), 2, None, None) == 0
     assert lib.ckpt_solve_cubic_pruned(None, ctypes.byref(E), None, None, None, None, None, None, 0, None) == 0
     torch.cuda.synchronize()
+
+
+def test_cubic_calls_in_flight_on_two_streams():
+    """Two callers' streams, each with cubic calls of its own (workspaces apart): the calls share the
+    library's side stream and its events, and every call still finds its own tables finished."""
+    say("solve_cubic on two streams at once")
+    chains = [inputs.config5_single(700), inputs.config4(), inputs.config5_single(1300), inputs.config2()]
+    want = [oracle.solve_static(d[:, 0]) for d in chains]
+    streams = [torch.cuda.Stream(), torch.cuda.Stream()]
+    dev_in = [torch.from_numpy(d).to(DEV) for d in chains]
+    torch.cuda.synchronize()
+    got = [None] * len(chains)
+    for rounds in range(2):                      # the second round finds stream and events in use
+        for k, x in enumerate(dev_in):
+            with torch.cuda.stream(streams[k % 2]):
+                got[k] = (B.ckpt_solve_cubic_pruned(x) if (k + rounds) % 2 else B.ckpt_solve_cubic(x))
+        torch.cuda.synchronize()
+        for k, (v, mk, s) in enumerate(want):
+            mask, peak, budget = got[k][0], got[k][1], got[k][2]
+            assert int(peak.cpu()[0]) == v and int(budget.cpu()[0]) == s
+            assert np.array_equal(mask.cpu().numpy()[:, 0], mk)
