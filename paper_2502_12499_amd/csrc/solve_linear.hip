@@ -432,19 +432,20 @@ __global__ __launch_bounds__(kWave) void linear_ring_kernel(const int64_t *__res
     // forward sweep: replace the parked steps by the mask (once they have all landed)
     asm volatile("s_waitcnt vmcnt(0)" : : : "memory");
     int cur = 0;
-    for (int k0 = 0; k0 <= n; k0 += kChunk) {
-        uint8_t b[kChunk];
+    constexpr int kSweep = 32;  // rows in flight per lane in this sweep, which does nothing but wait for them
+    for (int k0 = 0; k0 <= n; k0 += kSweep) {
+        uint8_t b[kSweep];
 #pragma unroll
-        for (int u = 0; u < kChunk; ++u) b[u] = (k0 + u) <= n ? mp[(int64_t)(k0 + u) * pstride] : 0;
+        for (int u = 0; u < kSweep; ++u) b[u] = (k0 + u) <= n ? mp[(int64_t)(k0 + u) * pstride] : 0;
 #pragma unroll
-        for (int u = 0; u < kChunk; ++u) {
+        for (int u = 0; u < kSweep; ++u) {
             const int k = k0 + u;
             const bool on = k == cur;
             if (on) cur = k + 1 + b[u];
             b[u] = on ? 1 : 0;
         }
 #pragma unroll
-        for (int u = 0; u < kChunk; ++u)
+        for (int u = 0; u < kSweep; ++u)
             if ((k0 + u) <= n) mp[(int64_t)(k0 + u) * pstride] = b[u];
     }
 }
