@@ -531,6 +531,8 @@ struct alignas(2 * sizeof(V)) QueueEntry {
 };
 
 // RING slots per lane, BLOCK lanes per workgroup: RING * BLOCK * sizeof(QueueEntry) bytes of LDS.
+constexpr int64_t kBudgetBlocksPerChain = 4096;
+
 template <typename V, int RING, int BLOCK>
 __global__ __launch_bounds__(BLOCK) void cubic_budgets_kernel(int n, int64_t blocks_per_chain, CubicWs w)
 {
@@ -544,17 +546,20 @@ __global__ __launch_bounds__(BLOCK) void cubic_budgets_kernel(int n, int64_t blo
     constexpr uint32_t kFull = (uint32_t)(RING - 1) * kStep;  // tl - hd at RING entries
     static_assert((kStep & (kStep - 1)) == 0 && (RING & (RING - 1)) == 0, "power-of-two ring");
 
-    const int64_t c = blockIdx.x / blocks_per_chain;
-    const int64_t tile = blockIdx.x % blocks_per_chain;
+    // A chain has at most kBudgetBlocksPerChain workgroups, each taking every so-many-th tile of
+    // its budgets: a chain that is not this kernel's costs a handful of workgroups, not one per tile.
+    const int64_t per_chain = blocks_per_chain < kBudgetBlocksPerChain ? blocks_per_chain : kBudgetBlocksPerChain;
+    const int64_t c = blockIdx.x / per_chain;
     const ChainMeta meta = w.meta[c];
     if (meta.status != CKPT_OK || (meta.mode32 != 0) != (sizeof(V) == 4)) return;
+    for (int64_t tile = blockIdx.x % per_chain; tile < blocks_per_chain; tile += per_chain) {
 
     const int tid = threadIdx.x;
     const PD<V> *__restrict__ pd = chain_table<V>(w, c, n);
     const int64_t K = num_budgets(n);
     const int64_t idx = tile * BLOCK + tid;
     const int64_t wave_in_chain = idx / kWave;   // uniform per wave
-    if (wave_in_chain * kWave >= K) return;      // whole wave beyond the list
+    if (wave_in_chain * kWave >= K) continue;    // whole wave beyond the list
     const bool live = idx < K;
     // lanes past the list take the largest budget (all interior layers), the one with the least to do
     const V s = live ? budget_value<V>(pd, idx, n) : (V)(pd[n].P - pd[1].P);
@@ -696,13 +701,15 @@ __global__ __launch_bounds__(BLOCK) void cubic_budgets_kernel(int n, int64_t blo
         w.partial[slot_id] = Partial{cost, sv};
         w.flags[slot_id] = flag;
     }
+    }
 }
 
 template <typename V, int RING, int BLOCK>
 void launch_budgets(int n, int64_t batch, CubicWs w, hipStream_t stream)
 {
     const int64_t blocks_per_chain = (num_budgets(n) + BLOCK - 1) / BLOCK;
-    hipLaunchKernelGGL((cubic_budgets_kernel<V, RING, BLOCK>), dim3((unsigned)(blocks_per_chain * batch)),
+    const int64_t per_chain = blocks_per_chain < kBudgetBlocksPerChain ? blocks_per_chain : kBudgetBlocksPerChain;
+    hipLaunchKernelGGL((cubic_budgets_kernel<V, RING, BLOCK>), dim3((unsigned)(per_chain * batch)),
                        dim3(BLOCK), 0, stream, n, blocks_per_chain, w);
 }
 

@@ -97,6 +97,7 @@ def special_chains():
         ("sawtooth_97", np.tile(np.array([1, 50, 3, 40, 7], dtype=np.int64), 20)[:98]),
         ("ties_200", rng.integers(1, 4, size=201)),
         ("wide_130", rng.integers(1, 1 << 40, size=131)),                   # 64-bit arithmetic
+        ("wide_900", rng.integers(1, 1 << 36, size=901)),                   # ... and more tiles of budgets than workgroups
         ("odd_bytes_65", rng.integers(1, 1 << 20, size=66) * 2 + 1),        # no common factor
         ("vgg19", inputs.vgg19_chain()[:, 0]),
         ("alexnet", inputs.alexnet_chain()[:, 0]),
