@@ -117,6 +117,57 @@ def time_extras(torch, B, inputs, d, m, d1, ws_cub, Bn, n, reps=3):
     return out
 
 
+def measure_peaks(reps=5):
+    """What the part delivers on kernels of known work (include/ckpt_probe.h): HBM read and copy
+    rates on the stress batch's 2.16 GB, the issue rate of 32-bit integer vector instructions and
+    the LDS instruction rate.  Median of `reps` launches each, HIP events on the launch stream."""
+    import torch
+    from paper_2502_12499_amd import binding as B
+    dev = torch.device("cuda:0")
+    sink = torch.zeros(8, dtype=torch.int64, device=dev)
+
+    def timed(fn):
+        fn()
+        torch.cuda.synchronize()
+        ts = []
+        for _ in range(reps):
+            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            a.record()
+            fn()
+            b.record()
+            torch.cuda.synchronize()
+            ts.append(a.elapsed_time(b))
+        return float(np.median(ts)) * 1e-3
+
+    out = {}
+    nbytes = 1048576 * 257 * 8
+    src = torch.empty(nbytes // 8, dtype=torch.int64, device=dev).random_()
+    dst = torch.empty_like(src)
+    t = timed(lambda: B.ckpt_probe_hbm_read(src, sink))
+    out["hbm_read_GBs"] = nbytes / t / 1e9
+    t = timed(lambda: B.ckpt_probe_hbm_copy(src, dst))
+    out["hbm_copy_GBs_moved"] = 2 * nbytes / t / 1e9
+    del src, dst
+    waves = 256 * 4 * 8  # eight waves per SIMD
+    for name, which in B.PROBE_VALU.items():
+        ops = [0]
+
+        def fn():
+            ops[0] = B.ckpt_probe_valu(which, waves, 256, sink)
+        t = timed(fn)
+        out[name + "_TOPs"] = ops[0] / t / 1e12
+    for name, which in B.PROBE_LDS.items():
+        acc = [0]
+
+        def fn():
+            acc[0] = B.ckpt_probe_lds(which, 256 * 16, 2048, sink)
+        t = timed(fn)
+        out[name + "_T_lane_accesses_per_s"] = acc[0] / t / 1e12
+        out[name + "_bytes_per_clk_per_cu"] = acc[0] * 4 / t / 256 / 2.4e9
+    out["nominal"] = {"hbm_GBs": HBM_PEAK_GBS, "int32_TOPs": INT32_PEAK_TOPS}
+    return out
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -131,7 +182,13 @@ def main():
     ap.add_argument("--copy-probe", action="store_true",
                     help="after the timed steps, copy the batch of sizes once (a plain copy kernel of known size, "
                          "to scale the profiler's memory counters)")
+    ap.add_argument("--peaks", action="store_true",
+                    help="run only the measurement probes (HBM read/copy, integer vector issue rate, LDS rate) "
+                         "and print their JSON line")
     args = ap.parse_args()
+    if args.peaks:
+        print(json.dumps({"peaks": measure_peaks()}), flush=True)
+        return
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this path runs on one GPU only (independent chains and budgets would be split "
               "across GPUs without communication; no multi-GPU figure is produced). Use --gpus 1.",

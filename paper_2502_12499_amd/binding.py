@@ -25,8 +25,11 @@ CALL_EVAL_PEAK, CALL_SOLVE_CUBIC, CALL_SOLVE_LINEAR = 0, 1, 2
 SELECT_ENDS, SELECT_ALL, SELECT_SQRT = 0, 1, 2
 
 EXPORTS = ("ckpt_workspace_bytes", "ckpt_eval_peak", "ckpt_eval_timeline", "ckpt_select_baseline",
-           "ckpt_solve_cubic", "ckpt_solve_cubic_pruned", "ckpt_solve_linear", "ckpt_solve_quadratic", "ckpt_cubic_cells",
-           "ckpt_status_string")
+           "ckpt_solve_cubic", "ckpt_solve_cubic_pruned", "ckpt_solve_linear",
+           "ckpt_solve_quadratic", "ckpt_cubic_cells",
+           "ckpt_status_string",
+           # include/ckpt_probe.h
+           "ckpt_probe_hbm_read", "ckpt_probe_hbm_copy", "ckpt_probe_valu", "ckpt_probe_lds")
 
 
 class Layout(ctypes.Structure):
@@ -67,6 +70,14 @@ def load():
         lib.ckpt_cubic_cells.argtypes = [ctypes.c_int32]
         lib.ckpt_status_string.restype = ctypes.c_char_p
         lib.ckpt_status_string.argtypes = [ctypes.c_int]
+        lib.ckpt_probe_hbm_read.restype = ctypes.c_int
+        lib.ckpt_probe_hbm_read.argtypes = [vp, ctypes.c_size_t, vp, vp]
+        lib.ckpt_probe_hbm_copy.restype = ctypes.c_int
+        lib.ckpt_probe_hbm_copy.argtypes = [vp, vp, ctypes.c_size_t, vp]
+        lib.ckpt_probe_valu.restype = ctypes.c_int
+        lib.ckpt_probe_valu.argtypes = [ctypes.c_int, ctypes.c_int64, ctypes.c_int32, vp, vp]
+        lib.ckpt_probe_lds.restype = ctypes.c_int
+        lib.ckpt_probe_lds.argtypes = [ctypes.c_int, ctypes.c_int64, ctypes.c_int32, vp, vp]
         _lib = lib
     return _lib
 
@@ -237,3 +248,37 @@ def ckpt_solve_quadratic(d, chain_major=False, want_values=True, want_status=Tru
     if rc != CKPT_OK:
         raise CkptError("ckpt_solve_quadratic", rc)
     return mask, peak, values, status
+
+
+# ---- measurement probes (include/ckpt_probe.h) ------------------------------------------------
+
+PROBE_VALU = {"v_add_u32": 0, "v_min_i32": 1, "v_max_u32": 2, "v_cndmask_b32": 3}
+PROBE_LDS = {"ds_read_b32": 0, "ds_write_b32": 1, "ds_max_u32": 2}
+
+
+def _probe(name, rc):
+    if rc != CKPT_OK:
+        raise CkptError(name, rc)
+
+
+def ckpt_probe_hbm_read(src, sink):
+    """Enqueues the read-only streaming kernel over the bytes of ``src``."""
+    _probe("ckpt_probe_hbm_read",
+           load().ckpt_probe_hbm_read(_ptr(src), src.numel() * src.element_size(), _ptr(sink), _stream()))
+
+
+def ckpt_probe_hbm_copy(src, dst):
+    _probe("ckpt_probe_hbm_copy",
+           load().ckpt_probe_hbm_copy(_ptr(src), _ptr(dst), src.numel() * src.element_size(), _stream()))
+
+
+def ckpt_probe_valu(which, waves, iters, sink):
+    """Returns the lane-operations the launch executes."""
+    _probe("ckpt_probe_valu", load().ckpt_probe_valu(int(which), int(waves), int(iters), _ptr(sink), _stream()))
+    return int(waves) * 64 * int(iters) * 256
+
+
+def ckpt_probe_lds(which, waves, iters, sink):
+    """Returns the LDS lane-accesses the launch executes."""
+    _probe("ckpt_probe_lds", load().ckpt_probe_lds(int(which), int(waves), int(iters), _ptr(sink), _stream()))
+    return int(waves) * 64 * int(iters) * 16
