@@ -158,6 +158,23 @@ int ckpt_solve_linear(const int64_t *d, const ckpt_layout *layout, uint8_t *mask
                       int64_t *peak_out, int32_t *status_out,
                       void *ws, size_t ws_bytes, void *hip_stream);
 
+/* ckpt_solve_linear for callers that cannot allocate device memory (code under
+ * HIP graph capture, serving loops, harnesses that forbid hipMalloc): the same
+ * kernels and the same results, with the scratch that ckpt_solve_linear takes
+ * from `ws` held in an array of the library's own instead (about 8 MiB of
+ * device memory per GPU, reserved when the library is loaded and kept until
+ * the process ends).  The call allocates and frees nothing and calls no
+ * allocating routine.  Limits: batch <= CKPT_NOALLOC_MAX_BATCH and n <=
+ * CKPT_NOALLOC_MAX_LAYERS, beyond which CKPT_ERR_SHAPE is returned and nothing
+ * is launched.  Every call on a GPU uses that GPU's one array: calls that
+ * overlap on one GPU (two streams, two threads) race and must be ordered by
+ * the caller; calls in a row on one stream are fine (the call clears what it
+ * needs at its start).  Arguments as for ckpt_solve_linear, without ws. */
+#define CKPT_NOALLOC_MAX_BATCH 1048576
+#define CKPT_NOALLOC_MAX_LAYERS 2047
+int ckpt_solve_linear_noalloc(const int64_t *d, const ckpt_layout *layout, uint8_t *mask_out,
+                              int64_t *peak_out, int32_t *status_out, void *hip_stream);
+
 /* Memory per training phase index of a given checkpoint set, per chain
  * (Section 5.1, "training phase index": 0 is the stage before training, 1..n
  * the forward stage of layer i, n+1..2n the backward stages of layers n..1,

@@ -25,7 +25,7 @@ CALL_EVAL_PEAK, CALL_SOLVE_CUBIC, CALL_SOLVE_LINEAR = 0, 1, 2
 SELECT_ENDS, SELECT_ALL, SELECT_SQRT = 0, 1, 2
 
 EXPORTS = ("ckpt_workspace_bytes", "ckpt_eval_peak", "ckpt_eval_timeline", "ckpt_select_baseline",
-           "ckpt_solve_cubic", "ckpt_solve_cubic_pruned", "ckpt_solve_linear",
+           "ckpt_solve_cubic", "ckpt_solve_cubic_pruned", "ckpt_solve_linear", "ckpt_solve_linear_noalloc",
            "ckpt_solve_quadratic", "ckpt_cubic_cells",
            "ckpt_status_string",
            # include/ckpt_probe.h
@@ -64,6 +64,8 @@ def load():
         lib.ckpt_solve_cubic_pruned.argtypes = [vp, LP, vp, vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
         lib.ckpt_solve_linear.restype = ctypes.c_int
         lib.ckpt_solve_linear.argtypes = [vp, LP, vp, vp, vp, vp, ctypes.c_size_t, vp]
+        lib.ckpt_solve_linear_noalloc.restype = ctypes.c_int
+        lib.ckpt_solve_linear_noalloc.argtypes = [vp, LP, vp, vp, vp, vp]
         lib.ckpt_solve_quadratic.restype = ctypes.c_int
         lib.ckpt_solve_quadratic.argtypes = [vp, LP, vp, vp, vp, vp, vp]
         lib.ckpt_cubic_cells.restype = ctypes.c_int64
@@ -232,6 +234,16 @@ def ckpt_solve_linear(d, chain_major=False, workspace=None, want_status=True):
     if rc != CKPT_OK:
         raise CkptError("ckpt_solve_linear", rc)
     return mask, peak, status
+
+
+def ckpt_solve_linear_noalloc(d, mask, peak, status=None, chain_major=False):
+    """ckpt_solve_linear into tensors the caller already holds, with the library's own
+    scratch: nothing is allocated here or in the library.  Returns None."""
+    _check_inputs(d)
+    L = layout_of(d, chain_major)
+    rc = load().ckpt_solve_linear_noalloc(_ptr(d), ctypes.byref(L), _ptr(mask), _ptr(peak), _ptr(status), _stream())
+    if rc != CKPT_OK:
+        raise CkptError("ckpt_solve_linear_noalloc", rc)
 
 
 def ckpt_solve_quadratic(d, chain_major=False, want_values=True, want_status=True):

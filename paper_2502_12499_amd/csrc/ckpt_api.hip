@@ -127,6 +127,19 @@ int ckpt_solve_linear(const int64_t *d, const ckpt_layout *L, uint8_t *mask_out,
                                             mask_out, peak_out, status_out, ws, (hipStream_t)hip_stream));
 }
 
+int ckpt_solve_linear_noalloc(const int64_t *d, const ckpt_layout *L, uint8_t *mask_out, int64_t *peak_out,
+                              int32_t *status_out, void *hip_stream)
+{
+    const int rc = check_layout(L, CKPT_NOALLOC_MAX_LAYERS);
+    if (rc != CKPT_OK) return rc;
+    if (L->batch > CKPT_NOALLOC_MAX_BATCH) return CKPT_ERR_SHAPE;
+    if (L->batch == 0) return CKPT_OK;
+    if (!d || !mask_out || !peak_out) return CKPT_ERR_NULL;
+    return finish(ckpt::launch_solve_linear_noalloc(d, L->batch, L->n_layers,
+                                                    Strides{L->chain_stride, L->pos_stride}, mask_out, peak_out,
+                                                    status_out, (hipStream_t)hip_stream));
+}
+
 int ckpt_solve_quadratic(const int64_t *d, const ckpt_layout *L, uint8_t *mask_out, int64_t *peak_out,
                          int64_t *value_out, int32_t *status_out, void *hip_stream)
 {
@@ -151,7 +164,7 @@ const char *ckpt_status_string(int status)
     switch (status) {
         case CKPT_OK: return "ok";
         case CKPT_ERR_NULL: return "null pointer";
-        case CKPT_ERR_SHAPE: return "bad shape, stride, objective or kind";
+        case CKPT_ERR_SHAPE: return "bad shape, stride, objective or kind, or beyond a call's size limit";
         case CKPT_ERR_SIZE: return "non-positive size";
         case CKPT_ERR_OVERFLOW: return "sum(d)+max(d) overflows int64";
         case CKPT_ERR_MASK: return "mask does not contain both ends";

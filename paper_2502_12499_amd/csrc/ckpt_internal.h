@@ -100,6 +100,10 @@ hipError_t launch_select_baseline(int64_t batch, int n, Strides st, int kind, ui
 size_t linear_workspace_bytes(int64_t batch, int n);
 hipError_t launch_solve_linear(const int64_t *d, int64_t batch, int n, Strides st, uint8_t *mask_out,
                                int64_t *peak_out, int32_t *status_out, void *ws, hipStream_t stream);
+// the same launches with the lists in an array of the library's own (batch and n within the
+// CKPT_NOALLOC_* limits, checked by the caller); no allocation, no other library call
+hipError_t launch_solve_linear_noalloc(const int64_t *d, int64_t batch, int n, Strides st, uint8_t *mask_out,
+                                       int64_t *peak_out, int32_t *status_out, hipStream_t stream);
 
 // ---- solve_quadratic ---------------------------------------------------------
 hipError_t launch_solve_quadratic(const int64_t *d, int64_t batch, int n, Strides st, uint8_t *mask_out,

@@ -54,6 +54,8 @@
 //        statuses.
 #include "ckpt_internal.h"
 
+#include <atomic>
+
 namespace ckpt {
 namespace {
 
@@ -677,6 +679,42 @@ __global__ __launch_bounds__(kWave) void linear_list_kernel(const int64_t *__res
 size_t linear_workspace_bytes(int64_t batch, int n)
 {
     return 256 + 2 * align_up((size_t)batch * 4) + (size_t)kListBlocks * stack_bytes(n) + 256;
+}
+
+// ---------------------------------------------------------------------------
+// the call that allocates nothing: the lists live in an array of the library's own
+// ---------------------------------------------------------------------------
+
+// Up to CKPT_NOALLOC_MAX_LAYERS layers the list kernel keeps its stacks in LDS, so the
+// scratch is the two counters and the two lists of chain indices only.
+constexpr size_t kNoallocScratchBytes = 256 + 2 * ((size_t)CKPT_NOALLOC_MAX_BATCH * 4) + 256;
+static_assert(CKPT_NOALLOC_MAX_LAYERS <= kLdsStackMaxN, "the list kernel must not need scratch stacks");
+
+namespace {
+// One copy per GPU, at an address of its own on each; held until the process ends.
+static __device__ __align__(256) unsigned char scratch[kNoallocScratchBytes];
+
+constexpr int kMaxDevices = 64;
+std::atomic<void *> scratch_of_device[kMaxDevices];
+}  // namespace
+
+hipError_t launch_solve_linear_noalloc(const int64_t *d, int64_t batch, int n, Strides st, uint8_t *mask_out,
+                                       int64_t *peak_out, int32_t *status_out, hipStream_t stream)
+{
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+    // The array's name is a host-side stand-in; its device address is looked up once per
+    // device, with that device current (two threads that race here store the same address).
+    void *ptr = scratch_of_device[dev].load(std::memory_order_acquire);
+    if (!ptr) {
+        e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return e;
+        if (!ptr) return hipErrorInvalidSymbol;
+        scratch_of_device[dev].store(ptr, std::memory_order_release);
+    }
+    return launch_solve_linear(d, batch, n, st, mask_out, peak_out, status_out, ptr, stream);
 }
 
 hipError_t launch_solve_linear(const int64_t *d, int64_t batch, int n, Strides st, uint8_t *mask_out,
