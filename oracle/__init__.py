@@ -57,6 +57,12 @@ def _load():
             "orc_batch_solve_dynamic": (None, [P, I, N, U, P]),
             "orc_batch_solve_static": (None, [P, I, N, U, P, P]),
             "orc_max_threads": (N, []),
+            "orc_set_threads": (None, [N]),
+            "orc_ragged_peak": (None, [P, U, P, I, N, P]),
+            "orc_ragged_timeline": (None, [P, U, P, I, N, P]),
+            "orc_ragged_solve_dynamic": (None, [P, P, I, U, P]),
+            "orc_ragged_solve_static": (None, [P, P, I, U, P, P]),
+            "orc_static_cs_list": (None, [P, N, P, I, P]),
         }
         for name, (res, args) in sig.items():
             fn = getattr(lib, name)
@@ -77,6 +83,11 @@ def _m(a):
 
 def max_threads():
     return int(_load().orc_max_threads())
+
+
+def set_threads(t):
+    """Threads for the batch and budget loops from now on (t < 1: all processors)."""
+    _load().orc_set_threads(int(t))
 
 
 # ---- objective functions (single chain) ------------------------------------
@@ -236,4 +247,53 @@ def batch_solve_static(d, want_mask=True):
     _load().orc_batch_solve_static(dp, B, n1 - 1,
                                    mask.ctypes.data_as(_u8p) if want_mask else None,
                                    peak.ctypes.data_as(_i64p), s.ctypes.data_as(_i64p))
+    return peak, mask, s
+
+
+def static_cs_list(d, s_list):
+    """c_s (Equation (T), literal recurrence) for every budget of a list."""
+    d, dp = _d(d)
+    sl = np.ascontiguousarray(s_list, dtype=np.int64)
+    out = np.empty(len(sl), dtype=np.int64)
+    _load().orc_static_cs_list(dp, len(d) - 1, sl.ctypes.data_as(_i64p), len(sl), out.ctypes.data_as(_i64p))
+    return out
+
+
+# ---- ragged batches: 1-D d (and mask) with offsets[batch+1]; chain c is d[off[c]:off[c+1]] ----
+
+def _off(offsets):
+    o = np.ascontiguousarray(offsets, dtype=np.int64)
+    return o, o.ctypes.data_as(_i64p)
+
+
+def ragged_peak(d, mask, offsets, objective):
+    d, dp = _d(d); mask, mp = _m(mask); o, op = _off(offsets)
+    out = np.empty(len(o) - 1, dtype=np.int64)
+    _load().orc_ragged_peak(dp, mp, op, len(o) - 1, int(objective), out.ctypes.data_as(_i64p))
+    return out
+
+
+def ragged_timeline(d, mask, offsets, objective):
+    """1-D array; the 2 n_c + 2 phases of chain c start at 2 * offsets[c]."""
+    d, dp = _d(d); mask, mp = _m(mask); o, op = _off(offsets)
+    out = np.empty(2 * len(d), dtype=np.int64)
+    _load().orc_ragged_timeline(dp, mp, op, len(o) - 1, int(objective), out.ctypes.data_as(_i64p))
+    return out
+
+
+def ragged_solve_dynamic(d, offsets):
+    d, dp = _d(d); o, op = _off(offsets)
+    mask = np.zeros(len(d), dtype=np.uint8)
+    peak = np.empty(len(o) - 1, dtype=np.int64)
+    _load().orc_ragged_solve_dynamic(dp, op, len(o) - 1, mask.ctypes.data_as(_u8p), peak.ctypes.data_as(_i64p))
+    return peak, mask
+
+
+def ragged_solve_static(d, offsets):
+    d, dp = _d(d); o, op = _off(offsets)
+    mask = np.zeros(len(d), dtype=np.uint8)
+    peak = np.empty(len(o) - 1, dtype=np.int64)
+    s = np.empty(len(o) - 1, dtype=np.int64)
+    _load().orc_ragged_solve_static(dp, op, len(o) - 1, mask.ctypes.data_as(_u8p), peak.ctypes.data_as(_i64p),
+                                    s.ctypes.data_as(_i64p))
     return peak, mask, s

@@ -539,6 +539,66 @@ void orc_batch_solve_static(const i64 *d, i64 batch, int n, uint8_t *mask_out, i
                                        s_out ? s_out + c : NULL);
 }
 
+/* ------------------------------------------------------------------------ */
+/* Ragged batches: chain c has n_c = off[c+1] - off[c] - 1 layers and         */
+/* occupies d[off[c] .. off[c+1]-1]; masks use the same offsets, timelines   */
+/* (2 n_c + 2 values) start at 2 off[c].  What cutting a network that is not  */
+/* a chain into linear sub-chains produces (the paper's concluding remarks),  */
+/* or one model in plain and in extended specs (Section 5.4).  Each chain is  */
+/* solved on its own by the functions above.                                  */
+/* ------------------------------------------------------------------------ */
+
+void orc_ragged_peak(const i64 *d, const uint8_t *mask, const i64 *off, i64 batch, int objective, i64 *peak_out)
+{
+#pragma omp parallel for schedule(dynamic, 16)
+    for (i64 c = 0; c < batch; c++) {
+        int n = (int)(off[c + 1] - off[c] - 1);
+        peak_out[c] = objective ? orc_peak_dynamic(d + off[c], mask + off[c], n)
+                                : orc_peak_static(d + off[c], mask + off[c], n);
+    }
+}
+
+void orc_ragged_timeline(const i64 *d, const uint8_t *mask, const i64 *off, i64 batch, int objective, i64 *out)
+{
+#pragma omp parallel for schedule(dynamic, 16)
+    for (i64 c = 0; c < batch; c++)
+        orc_timeline(d + off[c], mask + off[c], (int)(off[c + 1] - off[c] - 1), objective, out + 2 * off[c]);
+}
+
+void orc_ragged_solve_dynamic(const i64 *d, const i64 *off, i64 batch, uint8_t *mask_out, i64 *peak_out)
+{
+#pragma omp parallel for schedule(dynamic, 16)
+    for (i64 c = 0; c < batch; c++)
+        peak_out[c] = orc_solve_dynamic(d + off[c], (int)(off[c + 1] - off[c] - 1),
+                                        mask_out ? mask_out + off[c] : NULL, NULL);
+}
+
+void orc_ragged_solve_static(const i64 *d, const i64 *off, i64 batch, uint8_t *mask_out, i64 *peak_out, i64 *s_out)
+{
+    for (i64 c = 0; c < batch; c++)
+        peak_out[c] = orc_solve_static(d + off[c], (int)(off[c + 1] - off[c] - 1),
+                                       mask_out ? mask_out + off[c] : NULL, s_out ? s_out + c : NULL);
+}
+
+/* c_s of Equation (T) for each budget of a list, by the literal recurrence. */
+void orc_static_cs_list(const i64 *d, int n, const i64 *s_list, i64 count, i64 *out)
+{
+#pragma omp parallel for schedule(dynamic, 16)
+    for (i64 t = 0; t < count; t++) out[t] = orc_static_cs(d, n, s_list[t]);
+}
+
+/* Number of threads the batch and budget loops use from now on (t < 1: the default again). */
+void orc_set_threads(int t)
+{
+#ifdef _OPENMP
+    extern void omp_set_num_threads(int);
+    extern int omp_get_num_procs(void);
+    omp_set_num_threads(t >= 1 ? t : omp_get_num_procs());
+#else
+    (void)t;
+#endif
+}
+
 int orc_max_threads(void)
 {
 #ifdef _OPENMP

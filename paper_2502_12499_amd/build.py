@@ -15,6 +15,17 @@ FLAGS = [
 ]
 
 
+def stale():
+    """True when the library is missing or older than a source or header it is built from."""
+    if not os.path.exists(LIB):
+        return True
+    built = os.path.getmtime(LIB)
+    deps = [os.path.join(CSRC, f) for f in os.listdir(CSRC) if f.endswith((".hip", ".h"))]
+    inc = os.path.join(os.path.dirname(HERE), "include")
+    deps += [os.path.join(inc, f) for f in os.listdir(inc) if f.endswith(".h")]
+    return any(os.path.getmtime(f) > built for f in deps)
+
+
 def build(verbose=False):
     """Compile every HIP source for gfx950 and link the shared library."""
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")

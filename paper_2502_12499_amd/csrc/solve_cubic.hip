@@ -71,9 +71,6 @@ constexpr int kPad = 16;   // table entries past n+1, so a fetch never leaves th
 constexpr int kReduceBlocks = 64;      // second-level reduction: workgroups per chain
 constexpr int64_t kReduceFrom = 4096;  // ... used when a chain has more per-wave partial results than this
 
-#ifndef CKPT_CUBIC_ASM_CELL
-#define CKPT_CUBIC_ASM_CELL 1  // 0: use the portable form of the recurrence cell for 32-bit values too
-#endif
 
 struct ChainMeta {
     int32_t status;
@@ -767,21 +764,6 @@ __device__ inline Step uniform_load(const Step *p, int i)
     const i32x2 v = ((const CKPT_CONST_AS i32x2 *)p)[i];
     return Step{v.x, v.y};
 }
-#if !CKPT_CUBIC_ASM_CELL
-__device__ inline El uniform_load(const El *p, int i)
-{
-    const i32x4 v = ((const CKPT_CONST_AS i32x4 *)p)[i];
-    return El{v.x, v.y, v.z, v.w};
-}
-__device__ inline Snap uniform_load(const Snap *p, int i)
-{
-    const i32x16 v = ((const CKPT_CONST_AS i32x16 *)p)[i];
-    Snap s;
-#pragma unroll
-    for (int k = 0; k < kSnap; ++k) s.e[k] = PD<int32_t>{v[2 * k], v[2 * k + 1]};
-    return s;
-}
-#endif
 
 struct SharedLane {
     uint32_t hd, tl;   // the ring holds the written-out entries above the head at positions (hd, tl]
@@ -791,86 +773,6 @@ struct SharedLane {
     uint32_t over;     // the ring was too small at some point: the lane's result is not to be used
 };
 
-#if !CKPT_CUBIC_ASM_CELL
-// The rare part of a cell, kept out of line so that the unrolled cells stay
-// short: drop ring entries not below the incoming value Y, and if the head has
-// left the window write the implicit entries out and take the new head.
-// t, P = P[t], depth = depth(t) describe the position being inserted; every
-// lane of the wave calls this together.
-template <int RING, int BLOCK>
-__device__ __attribute__((noinline)) SharedLane shared_rare(SharedLane L, const uint32_t lane_base, const int32_t s,
-                                                            const El *el, const Snap *snap, const int t_in,
-                                                            const int32_t P_in, const int32_t depth_in,
-                                                            const int32_t Y, bool pop, const bool gone)
-{
-    typedef int32_t V;
-    typedef __attribute__((address_space(3))) V *LdsPtr;
-    constexpr V kLow = std::numeric_limits<V>::min();
-    constexpr uint32_t kStep = (uint32_t)(BLOCK * sizeof(QueueEntry<V>));
-    constexpr uint32_t kSlotMask = (uint32_t)(RING - 1) * kStep;
-    auto slot = [&](uint32_t pos) -> LdsPtr { return (LdsPtr)(uintptr_t)((pos & kSlotMask) | lane_base); };
-    // arguments arrive in vector registers; these are the same in every lane
-    el = (const El *)uniform((int64_t)(uintptr_t)el);
-    snap = (const Snap *)uniform((int64_t)(uintptr_t)snap);
-    const int t = __builtin_amdgcn_readfirstlane(t_in);
-    const int32_t P = __builtin_amdgcn_readfirstlane(P_in);
-    const int32_t depth = __builtin_amdgcn_readfirstlane(depth_in);
-
-    while (__builtin_amdgcn_ballot_w64(pop) != 0) {
-        if (pop) {
-            L.tl -= kStep;
-            L.X = L.tl != L.hd ? slot(L.tl)[0] : kLow;
-            pop = L.X >= Y;
-        }
-    }
-    if (__builtin_amdgcn_ballot_w64(gone) == 0) return L;
-    // the head has left: write the implicit entries out, top (this position) first
-    const int32_t count = gone ? depth - L.base : 0;
-    const V m_old = L.hF;
-    uint32_t wp = L.tl + (uint32_t)count * kStep;
-    if (gone) {
-        L.over |= (wp - L.hd) > (uint32_t)RING * kStep;
-        L.tl = wp;
-        L.base = depth;
-        L.X = Y;
-    }
-    if (gone) {
-        LdsPtr p = slot(wp);
-        p[0] = Y;
-        p[1] = P;
-        wp -= kStep;
-    }
-    int at = t;
-    for (int k0 = 1; __builtin_amdgcn_ballot_w64(k0 < count) != 0; k0 += kSnap) {
-        const Snap sn = uniform_load(snap, at);
-        const int next = uniform_load(el, at).below;
-#pragma unroll
-        for (int u = 0; u < kSnap; ++u) {
-            if (__builtin_amdgcn_ballot_w64(k0 + u < count) == 0) break;
-            if (k0 + u < count) {
-                LdsPtr p = slot(wp);
-                p[0] = sn.e[u].d + m_old;
-                p[1] = sn.e[u].P;
-                wp -= kStep;
-            }
-        }
-        at = next > 0 ? next : 0;
-    }
-    // new head: the lowest entry still inside the window (the top one always is)
-    bool seek = gone;
-    while (__builtin_amdgcn_ballot_w64(seek) != 0) {
-        if (seek) {
-            L.hd += kStep;
-            LdsPtr p = slot(L.hd);
-            L.hF = p[0];
-            L.hK = p[1] + s;
-            seek = (P > L.hK) & (L.hd != L.tl);
-        }
-    }
-    if (gone && L.hd == L.tl) L.X = kLow;
-    return L;
-}
-#endif
 
 // With REDO the workgroups (one wave each) take the waves listed in w.redo
 // instead of the waves of their own index.
@@ -942,7 +844,6 @@ __global__ __launch_bounds__(BLOCK) void cubic_shared_kernel(int n, int64_t bloc
     V P = el[0].P;  // P[t], carried along on the scalar unit
 
     // cell t + 1: insert position t (implicitly), drop ring entries, check the head
-#if CKPT_CUBIC_ASM_CELL
     // Written out: 4 vector instructions when nothing happens; the rare part is
     // the same as shared_rare, with the wave's exec mask narrowed to the lanes
     // concerned.  t = t0 + u with u a literal, so that nothing is computed for the
@@ -1280,18 +1181,6 @@ __global__ __launch_bounds__(BLOCK) void cubic_shared_kernel(int n, int64_t bloc
 #undef SH_FAST
 #undef SH_SNAP_STEP
 #undef SH_RARE
-#else
-#define CKPT_SHARED_CELL(T0, U, E)                                                                    \
-    {                                                                                                 \
-        P += (E).d;                                                                                   \
-        const V Y = (E).d + L.hF; /* F(t) */                                                          \
-        L.base = L.base < (E).under ? L.base : (E).under;                                             \
-        const bool pop = L.X >= Y;                                                                    \
-        const bool gone = P > L.hK;                                                                   \
-        if (__builtin_amdgcn_ballot_w64(pop | gone) != 0)                                             \
-            L = shared_rare<RING, BLOCK>(L, lane_base, s, el, snap, (T0) + (U), P, (E).under + 1, Y, pop, gone); \
-    }
-#endif
 
     // The (d, depth) stream is read a block of kBlockCells positions ahead; two
     // register sets take turns, so nothing is copied.
@@ -1319,7 +1208,6 @@ __global__ __launch_bounds__(BLOCK) void cubic_shared_kernel(int n, int64_t bloc
     const int last_full = n / kBlockCells * kBlockCells;
     block(A, B, 0, true);
     int t0 = kBlockCells;
-#if CKPT_CUBIC_ASM_CELL
     if (last_full - t0 >= 32) {
         const int rounds = (last_full - t0) / 32;
         middle(t0, rounds);
@@ -1327,7 +1215,6 @@ __global__ __launch_bounds__(BLOCK) void cubic_shared_kernel(int n, int64_t bloc
 #pragma unroll
         for (int u = 0; u < kBlockCells; ++u) B[u] = uniform_load(st, t0 + u);
     }
-#endif
     for (; t0 + kBlockCells < last_full; t0 += 2 * kBlockCells) {
         block(B, A, t0, false);
         block(A, B, t0 + kBlockCells, false);

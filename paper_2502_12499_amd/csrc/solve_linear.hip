@@ -308,7 +308,7 @@ __global__ __launch_bounds__(kWave) void linear_ring_kernel(const int64_t *__res
                   [sv2] "=&s"(sv2), [sv3] "=&s"(sv3)
                 : [Ti] "v"(Ti), [hd] "v"(hd), [di8] "v"(di8), [Ghd] "v"(Ghd), [G1] "v"(G1), [G2] "v"(G2), [G3] "v"(G3),
                   [lo] "v"(lane_base), [mask] "s"(kSlotMask), [step] "i"(kStep)
-                : "vcc", "memory");
+                : "vcc", "scc", "memory");  // (s_and_saveexec writes SCC)
         }
         const uint32_t Upt = Ti + Rp - Tpt;  // U(i, j_pt)
         const bool take_cand = Mc <= Upt;    // ties go to the lower index; kNone never wins
@@ -367,7 +367,7 @@ __global__ __launch_bounds__(kWave) void linear_ring_kernel(const int64_t *__res
                     "Lq_done_%=:\n\t"
                     : [hd] "+v"(hd), [Mhd] "+v"(Mhd), [Ghd] "+v"(Ghd), [G] "+v"(Gacc), [ad] "=&v"(ad), [sv] "=&s"(sv)
                     : [Mi] "v"(Mi), [lo] "v"(lane_base), [mask] "s"(kSlotMask), [step] "i"(kStep)
-                    : "vcc", "memory");
+                    : "vcc", "scc", "memory");  // (s_and_saveexec writes SCC)
             }
         }
         // a ring that is full keeps its entries: the chain is deferred and the new entry

@@ -10,10 +10,11 @@ if ROOT not in sys.path:
 
 def pytest_configure(config):
     config.addinivalue_line("markers", "gpu: needs a real MI355X (run with -m gpu)")
-    # The tests load the library that is built; only when there is none do they build it first
-    # (hipcc cross-compiles for gfx950 without a GPU).
+    # The tests load the library that is built; when there is none, or a source or header under
+    # csrc/ or include/ is newer than it, they build it first (hipcc cross-compiles for gfx950
+    # without a GPU), so that an edited kernel is never tested through a stale library.
     from paper_2502_12499_amd import binding, build
-    if not os.path.exists(binding.LIB_PATH):
+    if not os.path.exists(binding.LIB_PATH) or build.stale():
         build.build()
 
 

@@ -473,3 +473,124 @@ def test_paper_alexnet_sets():
     assert oracle.peak_dynamic(d, positions_to_mask(n, ax["set_algorithm4"])) == w   # 1,002 vs 1,003 MiB measured
     assert oracle.peak_dynamic(d, positions_to_mask(n, ax["set_sqrt_n"])) > w
     assert list(np.flatnonzero(oracle.select_baseline(n, oracle.SELECT_SQRT))[1:]) == ax["set_sqrt_n"]
+
+
+# --------------------------------------------------------------------------
+# Canonical static set on tied chains; budget sub-ranges; ragged batches
+# --------------------------------------------------------------------------
+
+def _canonical_static_by_enumeration(d):
+    """The canonical static set from the problem definition alone (Section 3.1, Equation (cost)),
+    without the recurrence: s* is the smallest maximum segment among the optimal sets; among the
+    sets with every segment within s* and the least checkpoint sum, the canonical one takes from
+    position n downwards the smallest predecessor each time, i.e. its checkpoints listed from the
+    top are lexicographically smallest."""
+    d = np.asarray(d, dtype=np.int64)
+    n = len(d) - 1
+    best = None
+    sets = []
+    for bits in range(1 << (n - 1)):
+        pos = [0] + [k for k in range(1, n) if (bits >> (k - 1)) & 1] + [n]
+        seg = max(int(d[a + 1:b].sum()) for a, b in zip(pos[:-1], pos[1:]))
+        csum = int(d[pos].sum())
+        sets.append((csum + seg, seg, csum, pos))
+        if best is None or csum + seg < best:
+            best = csum + seg
+    s_star = min(seg for cost, seg, _, _ in sets if cost == best)
+    within = [(csum, pos) for _, seg, csum, pos in sets if seg <= s_star]
+    least = min(csum for csum, _ in within)
+    assert least + s_star == best
+    top_down = min(tuple(reversed(pos)) for csum, pos in within if csum == least)
+    return best, s_star, positions_to_mask(n, top_down)
+
+
+def test_static_canonical_set_on_tied_chains():
+    """Chains with many equal optima: the set must be the one whose predecessors, taken from n
+    downwards, are the smallest feasible ones of minimal value (a largest-predecessor rule, or a
+    non-strict queue, gives another set on most of these)."""
+    rng = np.random.default_rng(77)
+    chains = [np.ones(k + 1, dtype=np.int64) for k in (5, 8, 9, 12)]
+    chains += [rng.integers(1, 3, size=k + 1) for k in (7, 9, 10, 11, 12, 12)]
+    chains += [np.array([3, 1, 2, 1, 2, 1, 2, 1, 3]), np.array([1, 2, 2, 2, 2, 2, 2, 1])]
+    differs_from_largest_rule = 0
+    for d in chains:
+        want_v, want_s, want_mask = _canonical_static_by_enumeration(d)
+        v, mask, s = oracle.solve_static(d)
+        assert (v, s) == (want_v, want_s)
+        assert np.array_equal(mask, want_mask), d
+        v2, mask2, s2 = oracle.solve_static_literal(d)
+        assert (v2, s2) == (want_v, want_s) and np.array_equal(mask2, want_mask)
+        # how the other tie-break (largest predecessor first) would answer on the same sets
+        n = len(d) - 1
+        least = want_v - want_s
+        alt = max(tuple(reversed(np.nonzero(m)[0])) for m in (_mask_of(bits, n) for bits in range(1 << (n - 1)))
+                  if _static_cost_and_seg(d, m)[0] == least and _static_cost_and_seg(d, m)[1] <= want_s)
+        differs_from_largest_rule += tuple(reversed(np.nonzero(want_mask)[0])) != alt
+    assert differs_from_largest_rule >= 4      # several of these chains tell the two rules apart
+
+
+def _mask_of(bits, n):
+    m = np.zeros(n + 1, dtype=np.uint8)
+    m[0] = m[n] = 1
+    for k in range(1, n):
+        m[k] = (bits >> (k - 1)) & 1
+    return m
+
+
+def _static_cost_and_seg(d, m):
+    pos = np.nonzero(m)[0]
+    seg = max(int(d[a + 1:b].sum()) for a, b in zip(pos[:-1], pos[1:]))
+    return int(d[pos].sum()), seg
+
+
+def test_static_budget_subranges():
+    """Section 3.2's two-step scheme is a minimum over budgets: over a slice of the budget list the
+    solver must return the least s + c_s of that slice (c_s by the literal recurrence of Equation
+    (T)), ties to the smaller s, and the minimum over disjoint slices that cover the list is the
+    full solve."""
+    rng = np.random.default_rng(5)
+    for n, kind in ((9, "ties"), (14, "spiky"), (23, "aligned"), (40, "wide")):
+        d = random_chain(rng, n, kind)
+        K = oracle.num_budgets(n)
+        blist = oracle.budgets(d)
+        cs = oracle.static_cs_list(d, blist)
+        full_v, _, full_s = oracle.solve_static(d)
+        cuts = sorted(set([0, K] + [int(x) for x in rng.integers(0, K + 1, size=5)]))
+        got = []
+        for a, b in zip(cuts[:-1], cuts[1:]):
+            v, s = oracle.solve_static_range(d, a, b - a)
+            want = min((int(blist[t] + cs[t]), int(blist[t])) for t in range(a, b))
+            assert (v, s) == want, (n, kind, a, b)
+            got.append((v, s))
+        assert min(got) == (full_v, full_s)
+        # a slice that runs past the end of the list is cut there; an empty slice has no optimum
+        v, s = oracle.solve_static_range(d, K - 3, 100)
+        assert (v, s) == min((int(blist[t] + cs[t]), int(blist[t])) for t in range(K - 3, K))
+
+
+def test_ragged_batches_are_the_single_chain_results():
+    """A ragged batch (the linear sub-chains of a network cut at its branch points; one model in
+    plain and extended specs, Section 5.4) is solved chain by chain: the worked examples and the
+    paper's VGG-19 chain side by side, each with its own printed or hand-worked answer."""
+    with open(os.path.join(GOLDEN, "worked_examples.json")) as f:
+        worked = json.load(f)["examples"]
+    chains = [np.array(w["d"], dtype=np.int64) for w in worked] + [inputs.vgg19_chain()[:, 0]]
+    d = np.concatenate(chains)
+    off = np.concatenate([[0], np.cumsum([len(c) for c in chains])])
+    peak_dyn, mask_dyn = oracle.ragged_solve_dynamic(d, off)
+    peak_sta, mask_sta, s_sta = oracle.ragged_solve_static(d, off)
+    for c, w in enumerate(worked):
+        assert peak_dyn[c] == w["dynamic"] and peak_sta[c] == w["static"]
+        assert s_sta[c] == w["static_budget"]
+        assert list(np.nonzero(mask_sta[off[c]:off[c + 1]])[0]) == w["static_set"]
+        assert list(np.nonzero(mask_dyn[off[c]:off[c + 1]])[0]) == w["dynamic_canonical"]
+    assert peak_sta[-1] == 3982479360 and peak_dyn[-1] == 5009571840        # Section 5.3, VGG-19
+    # evaluating the returned sets gives the optima back; timelines peak there
+    assert np.array_equal(oracle.ragged_peak(d, mask_dyn, off, 1), peak_dyn)
+    assert np.array_equal(oracle.ragged_peak(d, mask_sta, off, 0), peak_sta)
+    tl = oracle.ragged_timeline(d, mask_dyn, off, 1)
+    for c in range(len(chains)):
+        n = off[c + 1] - off[c] - 1
+        assert np.array_equal(tl[2 * off[c]:2 * off[c] + 2 * n + 2],
+                              oracle.timeline(d[off[c]:off[c + 1]], mask_dyn[off[c]:off[c + 1]], 1))
+        assert tl[2 * off[c] + n + 1:2 * off[c] + 2 * n + 1].max() == peak_dyn[c]
