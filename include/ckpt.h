@@ -11,12 +11,7 @@
  * keeps no data between calls and never synchronises: each call validates its
  * arguments on the host, enqueues its kernels on `hip_stream` (a hipStream_t
  * passed as void*, NULL = the null stream) and returns.  Outputs are valid
- * once the stream has reached the end of the call's work.  (The two cubic
- * calls run one of their kernels on a second stream, which the library
- * creates with two events the first time they are used on a device and keeps;
- * it waits for `hip_stream` at the start of that kernel and `hip_stream`
- * waits for it before the call's later kernels, so to the caller the whole
- * call is ordered on `hip_stream`.)  `ws` is scratch of
+ * once the stream has reached the end of the call's work.  `ws` is scratch of
  * at least ckpt_workspace_bytes() bytes, 256-byte aligned, private to the call
  * until it has finished on the stream; its contents need no initialisation.
  *
@@ -147,6 +142,23 @@ int ckpt_solve_cubic(const int64_t *d, const ckpt_layout *layout, uint8_t *mask_
 int ckpt_solve_cubic_pruned(const int64_t *d, const ckpt_layout *layout, uint8_t *mask_out,
                             int64_t *peak_out, int64_t *budget_out, int64_t *evaluated_out,
                             int32_t *status_out, void *ws, size_t ws_bytes, void *hip_stream);
+
+/* ckpt_solve_cubic that also returns the curve whose minimum the two-step
+ * scheme of Section 3.2 takes: for every candidate budget s of a chain its
+ * cost s + c_s, c_s the least checkpoint memory with every segment within s
+ * (Equation (T)).  budgets_out, costs_out [out]: `batch` x
+ * ckpt_cubic_costs_len(n) int64 each, chain c at offset c x that length.  The
+ * budgets come in the order the kernels take them (grouped by value, 64 to a
+ * wavefront, not sorted), with -1 in both arrays in the unused places at the
+ * end of a chain's list; a chain with a data error leaves its part unwritten.
+ * The n(n-1)/2 + 1 budgets (as a multiset: equal sums of different ranges
+ * appear once each) are 0 and every sum of a contiguous range inside
+ * d_1..d_{n-1}.  Other arguments, results and workspace as ckpt_solve_cubic. */
+int64_t ckpt_cubic_costs_len(int32_t n_layers);
+int ckpt_solve_cubic_costs(const int64_t *d, const ckpt_layout *layout, uint8_t *mask_out,
+                           int64_t *peak_out, int64_t *budget_out, int64_t *budgets_out,
+                           int64_t *costs_out, int32_t *status_out,
+                           void *ws, size_t ws_bytes, void *hip_stream);
 
 /* Optimal checkpoint set under Equation (memory) by the linear-time method of
  * Section 4.2 (Equation (TU), Lemmas 1-4, Algorithm 6, Theorem 3):

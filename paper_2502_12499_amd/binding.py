@@ -25,7 +25,7 @@ CALL_EVAL_PEAK, CALL_SOLVE_CUBIC, CALL_SOLVE_LINEAR = 0, 1, 2
 SELECT_ENDS, SELECT_ALL, SELECT_SQRT = 0, 1, 2
 
 EXPORTS = ("ckpt_workspace_bytes", "ckpt_eval_peak", "ckpt_eval_timeline", "ckpt_select_baseline",
-           "ckpt_solve_cubic", "ckpt_solve_cubic_pruned", "ckpt_solve_linear", "ckpt_solve_linear_noalloc",
+           "ckpt_solve_cubic", "ckpt_solve_cubic_pruned", "ckpt_solve_cubic_costs", "ckpt_cubic_costs_len", "ckpt_solve_linear", "ckpt_solve_linear_noalloc",
            "ckpt_solve_quadratic", "ckpt_cubic_cells",
            "ckpt_status_string",
            # include/ckpt_probe.h
@@ -62,6 +62,10 @@ def load():
         lib.ckpt_solve_cubic.argtypes = [vp, LP, vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
         lib.ckpt_solve_cubic_pruned.restype = ctypes.c_int
         lib.ckpt_solve_cubic_pruned.argtypes = [vp, LP, vp, vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
+        lib.ckpt_solve_cubic_costs.restype = ctypes.c_int
+        lib.ckpt_solve_cubic_costs.argtypes = [vp, LP, vp, vp, vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
+        lib.ckpt_cubic_costs_len.restype = ctypes.c_int64
+        lib.ckpt_cubic_costs_len.argtypes = [ctypes.c_int32]
         lib.ckpt_solve_linear.restype = ctypes.c_int
         lib.ckpt_solve_linear.argtypes = [vp, LP, vp, vp, vp, vp, ctypes.c_size_t, vp]
         lib.ckpt_solve_linear_noalloc.restype = ctypes.c_int
@@ -219,6 +223,27 @@ def ckpt_solve_cubic_pruned(d, chain_major=False, workspace=None, want_status=Tr
     if rc != CKPT_OK:
         raise CkptError("ckpt_solve_cubic_pruned", rc)
     return mask, peak, budget, evaluated, status
+
+
+def ckpt_solve_cubic_costs(d, chain_major=False, workspace=None):
+    """ckpt_solve_cubic plus the cost s + c_s of every candidate budget.  Returns
+    (mask, peak, budget, budgets, costs, status); budgets and costs have shape
+    (batch, ckpt_cubic_costs_len(n)), -1 in the unused places."""
+    _check_inputs(d)
+    L = layout_of(d, chain_major)
+    per = int(load().ckpt_cubic_costs_len(L.n_layers))
+    mask = torch.empty_strided(d.shape, d.stride(), dtype=torch.uint8, device=d.device)
+    peak = torch.empty(L.batch, dtype=torch.int64, device=d.device)
+    budget = torch.empty(L.batch, dtype=torch.int64, device=d.device)
+    budgets = torch.empty((L.batch, per), dtype=torch.int64, device=d.device)
+    costs = torch.empty((L.batch, per), dtype=torch.int64, device=d.device)
+    status = torch.empty(L.batch, dtype=torch.int32, device=d.device)
+    ws, ws_bytes = _workspace(CALL_SOLVE_CUBIC, L, d.device, workspace)
+    rc = load().ckpt_solve_cubic_costs(_ptr(d), ctypes.byref(L), _ptr(mask), _ptr(peak), _ptr(budget),
+                                       _ptr(budgets), _ptr(costs), _ptr(status), _ptr(ws), ws_bytes, _stream())
+    if rc != CKPT_OK:
+        raise CkptError("ckpt_solve_cubic_costs", rc)
+    return mask, peak, budget, budgets, costs, status
 
 
 def ckpt_solve_linear(d, chain_major=False, workspace=None, want_status=True):

@@ -28,7 +28,7 @@ int finish(hipError_t e) { return e == hipSuccess ? CKPT_OK : CKPT_ERR_DEVICE; }
 // ckpt_solve_cubic and ckpt_solve_cubic_pruned: the same checks and launches
 int solve_cubic(const int64_t *d, const ckpt_layout *L, uint8_t *mask_out, int64_t *peak_out, int64_t *budget_out,
                 int32_t *status_out, bool pruned, int64_t *evaluated_out, void *ws, size_t ws_bytes,
-                void *hip_stream)
+                void *hip_stream, int64_t *trace_s = nullptr, int64_t *trace_cost = nullptr)
 {
     const int rc = check_layout(L, CKPT_CUBIC_MAX_LAYERS);
     if (rc != CKPT_OK) return rc;
@@ -37,8 +37,8 @@ int solve_cubic(const int64_t *d, const ckpt_layout *L, uint8_t *mask_out, int64
     if (((uintptr_t)ws & 255u) != 0 || ws_bytes < ckpt::cubic_workspace_bytes(L->batch, L->n_layers))
         return CKPT_ERR_WORKSPACE;
     return finish(ckpt::launch_solve_cubic(d, L->batch, L->n_layers, Strides{L->chain_stride, L->pos_stride},
-                                           mask_out, peak_out, budget_out, status_out, pruned, evaluated_out, ws,
-                                           (hipStream_t)hip_stream));
+                                           mask_out, peak_out, budget_out, status_out, pruned, evaluated_out,
+                                           trace_s, trace_cost, ws, (hipStream_t)hip_stream));
 }
 
 }  // namespace
@@ -112,6 +112,21 @@ int ckpt_solve_cubic_pruned(const int64_t *d, const ckpt_layout *L, uint8_t *mas
 {
     return solve_cubic(d, L, mask_out, peak_out, budget_out, status_out, true, evaluated_out, ws, ws_bytes,
                        hip_stream);
+}
+
+int64_t ckpt_cubic_costs_len(int32_t n_layers)
+{
+    if (n_layers < 1 || n_layers > CKPT_CUBIC_MAX_LAYERS) return 0;
+    return ckpt::cubic_trace_len(n_layers);
+}
+
+int ckpt_solve_cubic_costs(const int64_t *d, const ckpt_layout *L, uint8_t *mask_out, int64_t *peak_out,
+                           int64_t *budget_out, int64_t *budgets_out, int64_t *costs_out, int32_t *status_out,
+                           void *ws, size_t ws_bytes, void *hip_stream)
+{
+    if (L && L->batch > 0 && (!budgets_out || !costs_out)) return CKPT_ERR_NULL;
+    return solve_cubic(d, L, mask_out, peak_out, budget_out, status_out, false, nullptr, ws, ws_bytes, hip_stream,
+                       budgets_out, costs_out);
 }
 
 int ckpt_solve_linear(const int64_t *d, const ckpt_layout *L, uint8_t *mask_out, int64_t *peak_out,

@@ -114,8 +114,12 @@ hipError_t launch_solve_quadratic(const int64_t *d, int64_t batch, int n, Stride
 size_t cubic_workspace_bytes(int64_t batch, int n);
 // pruned: budgets that a sample of the budgets shows cannot be optimal are skipped (same results);
 // evaluated_out (may be null) receives the number of budgets whose recurrence was run, per chain
+// trace_s, trace_cost (may be null): per budget lane, the budget and its cost s + c_s in bytes
 hipError_t launch_solve_cubic(const int64_t *d, int64_t batch, int n, Strides st, uint8_t *mask_out,
                               int64_t *peak_out, int64_t *budget_out, int32_t *status_out, bool pruned,
-                              int64_t *evaluated_out, void *ws, hipStream_t stream);
+                              int64_t *evaluated_out, int64_t *trace_s, int64_t *trace_cost, void *ws,
+                              hipStream_t stream);
+// entries per chain of the two trace arrays: one per lane of the chain's waves of 64 budgets
+int64_t cubic_trace_len(int n);
 
 }  // namespace ckpt

@@ -55,10 +55,9 @@
 //             partial results (the smallest optimal budget value s*), then the
 //             predecessors for s* (smallest minimal predecessor of every j) and
 //             the walk back from n that writes the mask.
-#include <hipcub/hipcub.hpp>
 
 #include <limits>
-#include <mutex>
+#include <atomic>
 
 #include "ckpt_internal.h"
 
@@ -131,12 +130,11 @@ struct CubicWs {
     Snap *snap;           // [batch][table_len(n)], 32-bit chains only
     Step *step;           // [batch][step_len(n)], 32-bit chains only
     Group *group;         // [batch][group_len(n)], 32-bit chains only
-    int32_t *budgets;     // [batch][K] budget values in enumeration order (zeros for other chains) ...
-    int32_t *sorted;      // ... and in ascending order per chain: lane i of wave w takes sorted[w*64 + i]
+    int32_t *sorted;      // [batch][K] the budget values, slice after slice: lane i of wave w takes sorted[w*64 + i]
     int32_t *redo_count;  // number of waves whose ring was too small ...
     int64_t *redo;        // [batch * waves_per_chain] ... and their slots, for a second run with a larger ring
-    void *sort_tmp;       // scratch of the sort
-    size_t sort_tmp_bytes;
+    int64_t *trace_s;     // [batch][waves_per_chain][64] or null: every lane's budget in bytes (-1: lane past the list) ...
+    int64_t *trace_cost;  // ... and its cost s + c_s in bytes (Equation (T)); set by ckpt_solve_cubic_costs only
     Partial *partial;     // [batch][waves_per_chain]
     uint64_t *flags;      // [batch][waves_per_chain] lanes to recompute
     Partial *partial2;    // [batch][kReduceBlocks] second-level partial results (long chains only)
@@ -164,44 +162,39 @@ __device__ inline const PD<V> *chain_table(const CubicWs &w, int64_t c, int n)
     return (const PD<V> *)(w.pd + (size_t)c * table_len(n) * sizeof(PD<int64_t>));
 }
 
-// ---- sorting the budget values ---------------------------------------------------
+// ---- ordering the budget values --------------------------------------------------
 //
-// Lanes of a wave that hold nearly equal budgets see the same head leave at the
-// same cell, so the rare part of a cell runs once for all of them.
-
-struct SegmentStart {
-    int64_t K;
-    __host__ __device__ int operator()(int c) const { return (int)(c * K); }
-};
-typedef hipcub::TransformInputIterator<int, SegmentStart, hipcub::CountingInputIterator<int>> SegmentIter;
-
-// chains sorted per call: the segmented sort counts items in an int
-__host__ inline int64_t sort_chains_per_call(int64_t batch, int n)
-{
-    const int64_t fit = 0x7fffffffLL / num_budgets(n);
-    return fit < 1 ? 0 : (fit < batch ? fit : batch);
-}
-
-// Sorts chains [0, chains) of `in` into `out`, or with tmp == nullptr only sets tmp_bytes.
-__host__ inline hipError_t sort_budgets(void *tmp, size_t &tmp_bytes, const int32_t *in, int32_t *out,
-                                         int64_t chains, int n, hipStream_t stream)
+// Lanes of a wave that hold nearly equal budgets see the same head leave at the same cell, so the
+// rare part of a cell runs once for all of them.  That needs no total order, only that the 64
+// budgets of a wave lie close together: the budgets of a 32-bit chain are laid out by slices of
+// the value range, slices in ascending order, any order inside a slice.  A slice is 2^w wide, w
+// chosen so that a slice holds 32 to 128 budgets on average: narrower than most layer sizes, so
+// the lanes of a wave nearly always agree on which prefix sum their head's key lies behind.
+// The budgets are the differences Q[x] - Q[a] of the prefix sums Q (1 <= a < x <= n) and 0, so
+// for a fixed start a they ascend with x: the budgets of a below a bound are found by bisection.
+// One workgroup lays out a group of kSliceGroup consecutive slices: the number of budgets below
+// the group's lower bound (a sum over the starts) is where the group begins in the list; the
+// budgets of each start inside the group's range are counted per slice in LDS, the counts scanned,
+// and the budgets written to their slices' places.  No pass over the whole list, no global counters.
+constexpr int kSliceGroup = 256;     // slices per workgroup
+__host__ __device__ inline int slices_log2(int n)
 {
     const int64_t K = num_budgets(n);
-    if (chains == 1) return hipcub::DeviceRadixSort::SortKeys(tmp, tmp_bytes, in, out, (int)K, 0, 31, stream);
-    const SegmentIter begin(hipcub::CountingInputIterator<int>(0), SegmentStart{K});
-    const SegmentIter end(hipcub::CountingInputIterator<int>(1), SegmentStart{K});
-    return hipcub::DeviceSegmentedRadixSort::SortKeys(tmp, tmp_bytes, in, out, (int)(chains * K), (int)chains, begin,
-                                                      end, 0, 31, stream);
+    int b = 0;
+    while (b < 20 && ((int64_t)64 << b) <= K) ++b;
+    return b;
 }
-
-__host__ inline size_t sort_tmp_bytes(int64_t batch, int n)
+// log2 of the slice width for a chain whose largest budget is smax: at most 2^slices_log2(n) slices.
+__device__ inline int slice_shift(int32_t smax, int n)
 {
-    const int64_t per = sort_chains_per_call(batch, n);
-    if (per == 0) return 0;
-    size_t a = 0, b = 0;
-    (void)sort_budgets(nullptr, a, nullptr, nullptr, per, n, nullptr);
-    if (batch % per) (void)sort_budgets(nullptr, b, nullptr, nullptr, batch % per, n, nullptr);
-    return a > b ? a : b;
+    const int bits = 32 - __clz(smax | 1);  // smax < 2^bits
+    const int sh = bits - slices_log2(n);
+    return sh > 0 ? sh : 0;
+}
+// Workgroups per chain: enough groups for the most slices a chain of n layers can have.
+__host__ __device__ inline int64_t slice_groups(int n)
+{
+    return (((int64_t)1 << slices_log2(n)) + kSliceGroup - 1) / kSliceGroup;
 }
 
 __host__ CubicWs carve_cubic(void *ws, int64_t batch, int n)
@@ -215,12 +208,11 @@ __host__ CubicWs carve_cubic(void *ws, int64_t batch, int n)
     w.snap = (Snap *)p;         p += align_up(B * table_len(n) * sizeof(Snap));
     w.step = (Step *)p;         p += align_up(B * step_len(n) * sizeof(Step));
     w.group = (Group *)p;       p += align_up(B * group_len(n) * sizeof(Group));
-    w.budgets = (int32_t *)p;   p += align_up(B * (size_t)num_budgets(n) * 4);
     w.sorted = (int32_t *)p;    p += align_up(B * (size_t)num_budgets(n) * 4);
     w.redo_count = (int32_t *)p; p += 256;
     w.redo = (int64_t *)p;      p += align_up(B * wpc * 8);
-    w.sort_tmp_bytes = sort_tmp_bytes(batch, n);
-    w.sort_tmp = p;             p += align_up(w.sort_tmp_bytes);
+    w.trace_s = nullptr;
+    w.trace_cost = nullptr;
     w.partial = (Partial *)p;   p += align_up(B * wpc * sizeof(Partial));
     w.flags = (uint64_t *)p;    p += align_up(B * wpc * 8);
     w.partial2 = (Partial *)p;  p += align_up(B * kReduceBlocks * sizeof(Partial));
@@ -692,6 +684,12 @@ __global__ __launch_bounds__(BLOCK) void cubic_budgets_kernel(int n, int64_t blo
     const uint64_t flag = __ballot(redo);
     int64_t cost = (live && !over) ? (int64_t)s + (int64_t)Fprev : kInf;
     int64_t sv = (int64_t)s;
+    if (w.trace_s) {  // (a flagged lane's cost is written when it is computed again)
+        const int64_t at = (c * waves_per_chain(n) + wave_in_chain) * kWave + (tid & (kWave - 1));
+        const int shift = w.meta[c].shift;
+        w.trace_s[at] = live ? (int64_t)((uint64_t)sv << shift) : -1;
+        w.trace_cost[at] = (live && !over) ? (int64_t)((uint64_t)cost << shift) : -1;
+    }
     wave_min_pair(cost, sv);
     if ((tid & (kWave - 1)) == 0) {
         const int64_t slot_id = c * waves_per_chain(n) + wave_in_chain;
@@ -710,17 +708,141 @@ void launch_budgets(int n, int64_t batch, CubicWs w, hipStream_t stream)
                        dim3(BLOCK), 0, stream, n, blocks_per_chain, w);
 }
 
-// ---- budget values of the 32-bit chains, in enumeration order ------------------------------
-__global__ __launch_bounds__(256) void cubic_values_kernel(int n, int64_t blocks_per_chain, CubicWs w)
+// ---- budget values of the 32-bit chains, laid out by slices of the value range -----------------
+extern __shared__ __align__(16) unsigned char order_lds[];
+
+constexpr int kBisect = 8;  // starts whose bisections a thread runs side by side
+
+// For kBisect starts a[j] at once: x[j] = the largest x in [a[j], n] with Q[x] - Q[a[j]] < bound
+// (Q ascending; bound >= 1).  The reads of the kBisect searches are independent of each other,
+// so their LDS latencies overlap.  A start a >= n gets x = a.
+__device__ inline void ends_below(const int32_t *Q, int n, const int (&a)[kBisect], int64_t bound, int (&x)[kBisect])
 {
-    const int64_t c = blockIdx.x / blocks_per_chain;
-    const int64_t idx = (blockIdx.x % blocks_per_chain) * 256 + threadIdx.x;
-    const int64_t K = num_budgets(n);
-    if (idx >= K) return;
+    int lo[kBisect], hi[kBisect];
+#pragma unroll
+    for (int j = 0; j < kBisect; ++j) {
+        lo[j] = a[j];
+        hi[j] = a[j] < n ? n : a[j];
+    }
+    for (int span = n; span > 0; span >>= 1) {  // hi - lo at most halves (rounded down) each turn
+        int32_t q[kBisect];
+        int mid[kBisect];
+#pragma unroll
+        for (int j = 0; j < kBisect; ++j) {
+            mid[j] = (lo[j] + hi[j] + 1) >> 1;
+            q[j] = Q[mid[j] <= n ? mid[j] : n];
+        }
+#pragma unroll
+        for (int j = 0; j < kBisect; ++j) {
+            if (lo[j] < hi[j]) {
+                const int32_t qa = Q[a[j] <= n ? a[j] : n];
+                if ((int64_t)q[j] - qa < bound) lo[j] = mid[j]; else hi[j] = mid[j] - 1;
+            }
+        }
+    }
+#pragma unroll
+    for (int j = 0; j < kBisect; ++j) x[j] = lo[j];
+}
+
+// One workgroup per group of kSliceGroup slices of a chain.
+__global__ __launch_bounds__(256) void cubic_slice_kernel(int n, CubicWs w)
+{
+    __shared__ int32_t tally[kSliceGroup];   // budgets per slice, then each slice's next free place
+    __shared__ int32_t below;                // budgets below the group's range
+    const int64_t groups = slice_groups(n);
+    const int64_t c = blockIdx.x / groups;
+    const int64_t g = blockIdx.x % groups;
     const ChainMeta meta = w.meta[c];
-    int32_t s = 0;
-    if (meta.status == CKPT_OK && meta.mode32) s = budget_value<int32_t>(chain_table<int32_t>(w, c, n), idx, n);
-    w.budgets[c * K + idx] = s;
+    if (meta.status != CKPT_OK || !meta.mode32) return;
+    const PD<int32_t> *pd = chain_table<int32_t>(w, c, n);
+    int32_t *Q = (int32_t *)order_lds;  // Q[j] = P[j-1], j = 0..n
+    const int tid = threadIdx.x;
+    const int32_t smax = pd[n].P - pd[1].P;   // the largest budget: every interior layer
+    const int wshift = slice_shift(smax, n);
+    const int64_t lo = (g * kSliceGroup) << wshift, hi = ((g + 1) * kSliceGroup) << wshift;  // lo <= s < hi
+    if (lo > smax) return;                   // (the same for the whole workgroup)
+    for (int j = tid; j <= n; j += 256) Q[j] = pd[j].P;
+    if (tid < kSliceGroup) tally[tid] = 0;
+    if (tid == 0) below = lo > 0 ? 1 : 0;    // the empty range, s = 0
+    __syncthreads();
+    int32_t *out = w.sorted + c * num_budgets(n);
+
+    // pass 1: the ends of every start's budgets inside the range; counts
+    int32_t mine_below = 0;
+    for (int a0 = 1 + tid; a0 < n; a0 += 256 * kBisect) {
+        int a[kBisect], x0[kBisect], x1[kBisect];
+#pragma unroll
+        for (int j = 0; j < kBisect; ++j) a[j] = a0 + 256 * j;
+        if (lo > 0) {
+            ends_below(Q, n, a, lo, x0);
+        } else {
+#pragma unroll
+            for (int j = 0; j < kBisect; ++j) x0[j] = a[j];
+        }
+        ends_below(Q, n, a, hi, x1);
+#pragma unroll
+        for (int j = 0; j < kBisect; ++j) {
+            if (a[j] < n) {
+                mine_below += x0[j] - a[j];
+                const int32_t qa = Q[a[j]];
+                for (int x = x0[j] + 1; x <= x1[j]; ++x)
+                    atomicAdd(&tally[((Q[x] - qa) >> wshift) - (int)(g * kSliceGroup)], 1);
+            }
+        }
+    }
+    if (tid == 0 && lo == 0) atomicAdd(&tally[0], 1);  // the empty range lies in slice 0
+#pragma unroll
+    for (int m = kWave / 2; m >= 1; m >>= 1) mine_below += __shfl_xor(mine_below, m, kWave);
+    if ((tid & (kWave - 1)) == 0) atomicAdd(&below, mine_below);
+    __syncthreads();
+    // exclusive scan of the slice counts (one wave, four slices to a lane), offset by the group's
+    // place in the list
+    if (tid < kWave) {
+        int32_t v[4], sum = 0;
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            v[k] = tally[4 * tid + k];
+            sum += v[k];
+        }
+        int32_t incl = sum;
+#pragma unroll
+        for (int dlt = 1; dlt < kWave; dlt <<= 1) {
+            const int32_t o = __shfl_up(incl, dlt, kWave);
+            if (tid >= dlt) incl += o;
+        }
+        int32_t run = below + incl - sum;
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            tally[4 * tid + k] = run;
+            run += v[k];
+        }
+    }
+    static_assert(kSliceGroup == 4 * kWave, "one wave scans the counts, four to a lane");
+    __syncthreads();
+    // pass 2: the same budgets again, to their places
+    if (tid == 0 && lo == 0) out[atomicAdd(&tally[0], 1)] = 0;
+    for (int a0 = 1 + tid; a0 < n; a0 += 256 * kBisect) {
+        int a[kBisect], x0[kBisect], x1[kBisect];
+#pragma unroll
+        for (int j = 0; j < kBisect; ++j) a[j] = a0 + 256 * j;
+        if (lo > 0) {
+            ends_below(Q, n, a, lo, x0);
+        } else {
+#pragma unroll
+            for (int j = 0; j < kBisect; ++j) x0[j] = a[j];
+        }
+        ends_below(Q, n, a, hi, x1);
+#pragma unroll
+        for (int j = 0; j < kBisect; ++j) {
+            if (a[j] < n) {
+                const int32_t qa = Q[a[j]];
+                for (int x = x0[j] + 1; x <= x1[j]; ++x) {
+                    const int32_t sv = Q[x] - qa;
+                    out[atomicAdd(&tally[(sv >> wshift) - (int)(g * kSliceGroup)], 1)] = sv;
+                }
+            }
+        }
+    }
 }
 
 // ---- budgets kernel for 32-bit chains: the queue's shared part factored out -------------
@@ -817,10 +939,11 @@ __global__ __launch_bounds__(BLOCK) void cubic_shared_kernel(int n, int64_t bloc
     const V s = w.sorted[c * K + (live ? idx : K - 1)];
     if (!REDO && mode != kSharedAll) {
         const bool first = (tid & (kWave - 1)) == 0;
-        // budgets ascend along the sorted list: the wave's first lane holds its smallest, its last
-        // lane the largest (lanes past the list count as large)
-        const V s_last = __builtin_amdgcn_readlane(live ? s : std::numeric_limits<V>::max(), kWave - 1);
-        if (__builtin_amdgcn_readfirstlane(s) > w.prune[c] || s_last < w.prune_lo[c] ||
+        // the wave's smallest and largest budget (slices ascend along the list, inside a slice any
+        // order; lanes past the list hold a large budget and count as large)
+        const V s_first = (V)wave_min_u32((uint32_t)s);
+        const V s_last = (V)~wave_min_u32(~(uint32_t)(live ? s : std::numeric_limits<V>::max()));
+        if (s_first > w.prune[c] || s_last < w.prune_lo[c] ||
             (tile_stride > 1 && w.skip_sample[c] != 0)) {
             if (first) {
                 const int64_t slot_id = c * waves_per_chain(n) + wave_in_chain;
@@ -1234,6 +1357,11 @@ __global__ __launch_bounds__(BLOCK) void cubic_shared_kernel(int n, int64_t bloc
     const uint64_t flag = __ballot(redo);
     int64_t cost = (live && !over) ? (int64_t)s + (int64_t)Fn : kInf;
     int64_t sv = (int64_t)s;
+    if (w.trace_s) {  // (a flagged lane's cost is written when it is computed again)
+        const int64_t at = (c * waves_per_chain(n) + wave_in_chain) * kWave + (tid & (kWave - 1));
+        w.trace_s[at] = live ? (int64_t)((uint64_t)sv << meta.shift) : -1;
+        w.trace_cost[at] = (live && !over) ? (int64_t)((uint64_t)cost << meta.shift) : -1;
+    }
     wave_min_pair(cost, sv);
     if ((tid & (kWave - 1)) == 0) {
         const int64_t slot_id = c * waves_per_chain(n) + wave_in_chain;
@@ -1707,6 +1835,7 @@ __global__ __launch_bounds__(kWave) void cubic_overflow_kernel(int n, int64_t n_
                     cost = s64 + wave_budget_table<int64_t>(pd, n, s64, (int64_t *)dyn_lds, nullptr);
                 }
                 if (cost < best.cost || (cost == best.cost && s64 < best.s)) best = Partial{cost, s64};
+                if (w.trace_s && lane == 0) w.trace_cost[word * kWave + bit] = (int64_t)((uint64_t)cost << meta.shift);
                 __syncthreads();
             }
             if (lane == 0) w.partial[word] = best;
@@ -1820,53 +1949,39 @@ size_t cubic_workspace_bytes(int64_t batch, int n)
     const size_t n1 = (size_t)n + 1, B = (size_t)batch, wpc = (size_t)waves_per_chain(n);
     return align_up(B * sizeof(ChainMeta)) + align_up(B * table_len(n) * sizeof(PD<int64_t>)) +
            align_up(B * table_len(n) * sizeof(El)) + align_up(B * table_len(n) * sizeof(Snap)) +
-           align_up(B * step_len(n) * sizeof(Step)) + align_up(B * group_len(n) * sizeof(Group)) + 2 * align_up(B * (size_t)num_budgets(n) * 4) +
-           align_up(sort_tmp_bytes(batch, n)) + 256 + align_up(B * wpc * 8) +
+           align_up(B * step_len(n) * sizeof(Step)) + align_up(B * group_len(n) * sizeof(Group)) + align_up(B * (size_t)num_budgets(n) * 4) + 256 + align_up(B * wpc * 8) +
            align_up(B * wpc * sizeof(Partial)) + align_up(B * wpc * 8) +
            align_up(B * kReduceBlocks * sizeof(Partial)) + align_up(B * n1 * 4) + 3 * align_up(B * 4) +
            align_up(B * n1 * 4) + align_up(B * 8) + 256;
 }
 
+int64_t cubic_trace_len(int n) { return waves_per_chain(n) * kWave; }
+
 namespace {
 
-// A side stream per device for work of a call that does not depend on what the caller's stream
-// is doing at the time; it is forked from and joined to the caller's stream with events, so to
-// the caller all work of the call is still on its stream.  Default priority; never destroyed.
-struct SideStream {
-    hipStream_t stream = nullptr;
-    hipEvent_t fork = nullptr, join = nullptr;
-};
+// Once per device: the links kernel of long chains needs more dynamic LDS than the default limit.
 constexpr int kMaxDevices = 64;
-std::mutex side_mutex;
-SideStream side_streams[kMaxDevices];
-// Held while a call enqueues its work: the fork and join events belong to the device, and a wait
-// refers to the event's latest record, so two host threads must not interleave their records and waits.
-std::mutex side_enqueue_mutex;
+std::atomic<bool> links_lds_raised[kMaxDevices];
 
-hipError_t side_stream_of_current_device(SideStream &out)
+hipError_t raise_links_lds_limit()
 {
     int dev = 0;
     hipError_t e = hipGetDevice(&dev);
     if (e != hipSuccess) return e;
     if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
-    std::lock_guard<std::mutex> lock(side_mutex);
-    SideStream &s = side_streams[dev];
-    if (s.stream == nullptr) {
-        SideStream t;
-        if ((e = hipStreamCreateWithFlags(&t.stream, hipStreamNonBlocking)) != hipSuccess) return e;
-        if ((e = hipEventCreateWithFlags(&t.fork, hipEventDisableTiming)) != hipSuccess) return e;
-        if ((e = hipEventCreateWithFlags(&t.join, hipEventDisableTiming)) != hipSuccess) return e;
-        s = t;
-    }
-    out = s;
-    return hipSuccess;
+    if (links_lds_raised[dev].load(std::memory_order_acquire)) return hipSuccess;
+    e = hipFuncSetAttribute((const void *)cubic_links_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
+                            (int)links_lds_bytes(CKPT_CUBIC_MAX_LAYERS));
+    if (e == hipSuccess) links_lds_raised[dev].store(true, std::memory_order_release);
+    return e;
 }
 
 }  // namespace
 
 hipError_t launch_solve_cubic(const int64_t *d, int64_t batch, int n, Strides st, uint8_t *mask_out,
                               int64_t *peak_out, int64_t *budget_out, int32_t *status_out, bool pruned,
-                              int64_t *evaluated_out, void *ws, hipStream_t stream)
+                              int64_t *evaluated_out, int64_t *trace_s, int64_t *trace_cost, void *ws,
+                              hipStream_t stream)
 {
     if (batch == 0) return hipSuccess;
     pruned = pruned && n >= kPruneFromLayers;
@@ -1876,41 +1991,23 @@ hipError_t launch_solve_cubic(const int64_t *d, int64_t batch, int n, Strides st
     const int64_t n_words = waves_per_chain(n) * batch;
     if (total_blocks > 0x7fffffffLL) return hipErrorInvalidConfiguration;
     const size_t table_lds = ((size_t)n + 1) * 8;
-    const int64_t per = sort_chains_per_call(batch, n);
-    if (per == 0) return hipErrorInvalidConfiguration;
+    w.trace_s = trace_s;
+    w.trace_cost = trace_cost;
 
     hipLaunchKernelGGL(cubic_prologue_kernel, dim3((unsigned)batch), dim3(kWave), 0, stream, d, batch, n,
                        st.chain, st.pos, w);
     if (links_lds_bytes(n) > 65536) {  // beyond the default limit for dynamic LDS
-        const hipError_t e = hipFuncSetAttribute((const void *)cubic_links_kernel,
-                                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)links_lds_bytes(n));
+        const hipError_t e = raise_links_lds_limit();
         if (e != hipSuccess) return e;
     }
-    // The links (one workgroup per chain, a tenth of a millisecond for a long chain) and the sorted
-    // budget list need only the prologue's tables and not each other: the links go to the side stream.
-    SideStream side;
-    hipError_t e = side_stream_of_current_device(side);
-    if (e != hipSuccess) return e;
-    std::lock_guard<std::mutex> enqueue_lock(side_enqueue_mutex);
-    if ((e = hipEventRecord(side.fork, stream)) != hipSuccess) return e;
-    if ((e = hipStreamWaitEvent(side.stream, side.fork, 0)) != hipSuccess) return e;
-    hipLaunchKernelGGL(cubic_links_kernel, dim3((unsigned)batch), dim3(kLinksBlock), links_lds_bytes(n), side.stream,
-                       n, w);
-    if (pruned)  // the first bounds of a pruned call need the links' tables only: same place
-        hipLaunchKernelGGL(cubic_bound_kernel, dim3((unsigned)batch), dim3(kBoundThreads), 0, side.stream, n,
+    // Everything runs on the caller's stream, in this order: the tables of the size stack, the
+    // first bounds of a pruned call (they need those tables only), the budgets grouped by value.
+    hipLaunchKernelGGL(cubic_links_kernel, dim3((unsigned)batch), dim3(kLinksBlock), links_lds_bytes(n), stream, n, w);
+    if (pruned)
+        hipLaunchKernelGGL(cubic_bound_kernel, dim3((unsigned)batch), dim3(kBoundThreads), 0, stream, n,
                            (num_budgets(n) + kWave - 1) / kWave, kSampleStride, 1, 0, w);
-    if ((e = hipEventRecord(side.join, side.stream)) != hipSuccess) return e;
-    {
-        const int64_t vblocks = (K + 255) / 256;
-        hipLaunchKernelGGL(cubic_values_kernel, dim3((unsigned)(vblocks * batch)), dim3(256), 0, stream, n, vblocks, w);
-        for (int64_t c0 = 0; c0 < batch; c0 += per) {
-            size_t bytes = w.sort_tmp_bytes;
-            const int64_t chains = batch - c0 < per ? batch - c0 : per;
-            const hipError_t e = sort_budgets(w.sort_tmp, bytes, w.budgets + c0 * K, w.sorted + c0 * K, chains, n, stream);
-            if (e != hipSuccess) return e;
-        }
-    }
-    if ((e = hipStreamWaitEvent(stream, side.join, 0)) != hipSuccess) return e;
+    hipLaunchKernelGGL(cubic_slice_kernel, dim3((unsigned)(slice_groups(n) * batch)), dim3(256), ((size_t)n + 1) * 4,
+                       stream, n, w);
     launch_shared<16, 64, 64>(n, batch, pruned, w, stream);
     launch_budgets<int64_t, 16, 64>(n, batch, w, stream);
     const int64_t word_groups = (n_words + kWave - 1) / kWave;

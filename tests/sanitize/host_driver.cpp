@@ -1,0 +1,89 @@
+// The host side of the C ABI (csrc/ckpt_api.hip: argument checks, workspace sizes, layout
+// arithmetic) built for the CPU alone under AddressSanitizer and UndefinedBehaviorSanitizer by
+// tests/test_sanitizers.py.  The kernel launchers are replaced by stubs that only record the
+// call, so every path of the shim runs without a GPU: extreme strides and batch sizes must be
+// rejected before any 64-bit product can wrap.
+#include <hip/hip_runtime.h>
+
+#include <cstdint>
+#include <cstdio>
+#include <cstdlib>
+
+#include "../../include/ckpt.h"
+
+namespace ckpt {
+struct Strides {
+    int64_t chain;
+    int64_t pos;
+};
+static int launches = 0;
+hipError_t launch_eval_peak(const int64_t *, const uint8_t *, int64_t, int, Strides, int, int64_t *, int32_t *,
+                            hipStream_t) { ++launches; return hipSuccess; }
+hipError_t launch_eval_timeline(const int64_t *, const uint8_t *, int64_t, int, Strides, int, int64_t *, Strides,
+                                int32_t *, hipStream_t) { ++launches; return hipSuccess; }
+hipError_t launch_select_baseline(int64_t, int, Strides, int, uint8_t *, hipStream_t) { ++launches; return hipSuccess; }
+size_t linear_workspace_bytes(int64_t batch, int n) { return 256 + (size_t)batch * 8 + (size_t)n * 64; }
+hipError_t launch_solve_linear(const int64_t *, int64_t, int, Strides, uint8_t *, int64_t *, int32_t *, void *,
+                               hipStream_t) { ++launches; return hipSuccess; }
+hipError_t launch_solve_linear_noalloc(const int64_t *, int64_t, int, Strides, uint8_t *, int64_t *, int32_t *,
+                                       hipStream_t) { ++launches; return hipSuccess; }
+hipError_t launch_solve_quadratic(const int64_t *, int64_t, int, Strides, uint8_t *, int64_t *, int64_t *, int32_t *,
+                                  hipStream_t) { ++launches; return hipSuccess; }
+size_t cubic_workspace_bytes(int64_t batch, int n) { return 4096 + (size_t)batch * (size_t)n * (size_t)n * 4; }
+hipError_t launch_solve_cubic(const int64_t *, int64_t, int, Strides, uint8_t *, int64_t *, int64_t *, int32_t *, bool,
+                              int64_t *, int64_t *, int64_t *, void *, hipStream_t) { ++launches; return hipSuccess; }
+int64_t cubic_trace_len(int n) { return ((int64_t)n * (n - 1) / 2 + 1 + 63) / 64 * 64; }
+}  // namespace ckpt
+
+#define CHECK(c) do { if (!(c)) { std::fprintf(stderr, "host_driver: %s failed at line %d\n", #c, __LINE__); std::exit(1); } } while (0)
+
+int main()
+{
+    alignas(256) static unsigned char buf[1 << 16];
+    int64_t *d = (int64_t *)buf, *out = (int64_t *)(buf + 4096);
+    uint8_t *mask = buf + 8192;
+    void *ws = buf + 16384;
+    const int64_t big = INT64_MAX;
+    // layouts that must be refused before anything is multiplied out of range
+    const ckpt_layout bad[] = {
+        {-1, 8, 1, 4}, {4, 0, 1, 4}, {4, 65536, 1, 4}, {4, 8, 0, 4}, {4, 8, 1, 0}, {4, 8, -3, 4},
+        {2147483647, 65535, big / 2, big / 2}, {2147483647, 8, big, 1}, {3, 65535, 1, big / 8},
+        {(int64_t)1 << 40, 8, 1, 1},
+    };
+    for (const ckpt_layout &L : bad) {
+        CHECK(ckpt_workspace_bytes(CKPT_CALL_SOLVE_LINEAR, &L) == 0);
+        CHECK(ckpt_eval_peak(d, mask, &L, 0, out, nullptr, nullptr, 0, nullptr) == CKPT_ERR_SHAPE);
+        CHECK(ckpt_solve_linear(d, &L, mask, out, nullptr, ws, 1 << 15, nullptr) == CKPT_ERR_SHAPE);
+        CHECK(ckpt_solve_cubic(d, &L, mask, out, nullptr, nullptr, ws, 1 << 15, nullptr) == CKPT_ERR_SHAPE);
+        CHECK(ckpt_eval_timeline(d, mask, &L, 1, out, 1, 4, nullptr, nullptr) == CKPT_ERR_SHAPE);
+        CHECK(ckpt_select_baseline(&L, 0, mask, nullptr) == CKPT_ERR_SHAPE);
+        CHECK(ckpt_solve_quadratic(d, &L, mask, out, nullptr, nullptr, nullptr) == CKPT_ERR_SHAPE);
+        CHECK(ckpt_solve_linear_noalloc(d, &L, mask, out, nullptr, nullptr) == CKPT_ERR_SHAPE);
+    }
+    CHECK(ckpt::launches == 0);
+    const ckpt_layout ok = {4, 8, 1, 4};
+    CHECK(ckpt_eval_timeline(d, mask, &ok, 1, out, big / 2, big / 2, nullptr, nullptr) == CKPT_ERR_SHAPE);
+    CHECK(ckpt_eval_peak(d, mask, &ok, 7, out, nullptr, nullptr, 0, nullptr) == CKPT_ERR_SHAPE);
+    CHECK(ckpt_eval_peak(nullptr, mask, &ok, 0, out, nullptr, nullptr, 0, nullptr) == CKPT_ERR_NULL);
+    CHECK(ckpt_solve_linear(d, &ok, mask, out, nullptr, ws, 8, nullptr) == CKPT_ERR_WORKSPACE);
+    CHECK(ckpt_solve_linear(d, &ok, mask, out, nullptr, (char *)ws + 8, 1 << 15, nullptr) == CKPT_ERR_WORKSPACE);
+    CHECK(ckpt_solve_linear_noalloc(d, nullptr, mask, out, nullptr, nullptr) == CKPT_ERR_NULL);
+    CHECK(ckpt::launches == 0);
+    // and the calls that are in order reach their launcher exactly once each
+    CHECK(ckpt_eval_peak(d, mask, &ok, 1, out, nullptr, nullptr, 0, nullptr) == CKPT_OK);
+    CHECK(ckpt_eval_timeline(d, mask, &ok, 0, out, 1, 4, nullptr, nullptr) == CKPT_OK);
+    CHECK(ckpt_select_baseline(&ok, 2, mask, nullptr) == CKPT_OK);
+    CHECK(ckpt_solve_linear(d, &ok, mask, out, nullptr, ws, 1 << 15, nullptr) == CKPT_OK);
+    CHECK(ckpt_solve_linear_noalloc(d, &ok, mask, out, nullptr, nullptr) == CKPT_OK);
+    CHECK(ckpt_solve_quadratic(d, &ok, mask, out, nullptr, nullptr, nullptr) == CKPT_OK);
+    CHECK(ckpt_solve_cubic(d, &ok, mask, out, nullptr, nullptr, ws, 1 << 15, nullptr) == CKPT_OK);
+    CHECK(ckpt_solve_cubic_pruned(d, &ok, mask, out, nullptr, nullptr, nullptr, ws, 1 << 15, nullptr) == CKPT_OK);
+    CHECK(ckpt_solve_cubic_costs(d, &ok, mask, out, nullptr, nullptr, out, nullptr, ws, 1 << 15, nullptr) == CKPT_ERR_NULL);
+    CHECK(ckpt_solve_cubic_costs(d, &ok, mask, out, nullptr, out, out, nullptr, ws, 1 << 15, nullptr) == CKPT_OK);
+    CHECK(ckpt_cubic_costs_len(8) == 64 && ckpt_cubic_costs_len(12) == 128 && ckpt_cubic_costs_len(0) == 0);
+    CHECK(ckpt::launches == 9);
+    CHECK(ckpt_cubic_cells(8191) == ((int64_t)8191 * 8190 / 2 + 1) * 8191 && ckpt_cubic_cells(0) == 0);
+    for (int s = -1; s < 10; ++s) CHECK(ckpt_status_string(s) != nullptr);
+    std::printf("host_driver ok\n");
+    return 0;
+}

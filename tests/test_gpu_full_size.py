@@ -88,7 +88,7 @@ def test_pruned_cubic_on_long_chains_with_a_few_huge_layers():
         assert 0 < int(evaluated.cpu()[c]) < K
 
 
-def test_config5_full_batch_linear_and_eval():
+def test_config5_batch_properties_of_every_chain():
     batch, n = 1048576, 256
     say("config 5: 1,048,576 chains, n = 256")
     d, m = inputs.config5_batch(batch, n)

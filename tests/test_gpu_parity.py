@@ -314,3 +314,90 @@ def test_solve_cubic_pruned_runs_every_budget_of_shorter_chains():
     d = inputs.config4()
     _, _, _, evaluated, _ = B.ckpt_solve_cubic_pruned(to_dev(d))
     assert int(evaluated[0]) == 1001 * 1000 // 2 + 1
+
+
+# ---------------------------------------------------------------------------
+# the n = 12 configuration: every checkpoint set; the cost of every budget
+# ---------------------------------------------------------------------------
+
+def test_config1_every_subset_and_the_solvers_sets():
+    """All 4096 masks over positions 1..12 with the ends forced (2048 distinct sets, each twice),
+    evaluated in one call per objective against the oracle's objective functions; the least of
+    them is what the two solvers return, and their sets evaluate to it."""
+    d = inputs.config1()                                   # (13, 1)
+    n = d.shape[0] - 1
+    masks = np.zeros((n + 1, 4096), dtype=np.uint8)
+    for bits in range(4096):
+        for k in range(1, n + 1):
+            masks[k, bits] = (bits >> (k - 1)) & 1
+    masks[0, :] = 1
+    masks[n, :] = 1
+    dd = np.repeat(d, 4096, axis=1)
+    best = {}
+    for obj in (B.OBJ_STATIC, B.OBJ_DYNAMIC):
+        peak, status = B.ckpt_eval_peak(to_dev(dd), to_dev(masks), obj)
+        want = oracle.batch_peak(inputs.chain_major(dd), inputs.chain_major(masks), obj)
+        assert (np_(status) == 0).all() and np.array_equal(np_(peak), want)
+        best[obj] = int(np_(peak).min())
+    smask, speak, sbudget, _ = B.ckpt_solve_cubic(to_dev(d))
+    lmask, lpeak, _ = B.ckpt_solve_linear(to_dev(d))
+    assert int(speak[0]) == best[B.OBJ_STATIC] and int(lpeak[0]) == best[B.OBJ_DYNAMIC]
+    assert int(B.ckpt_eval_peak(to_dev(d), smask, B.OBJ_STATIC)[0][0]) == best[B.OBJ_STATIC]
+    assert int(B.ckpt_eval_peak(to_dev(d), lmask, B.OBJ_DYNAMIC)[0][0]) == best[B.OBJ_DYNAMIC]
+    assert int(speak[0]) == oracle.peak_static(d[:, 0], np_(smask)[:, 0])
+    assert int(lpeak[0]) == oracle.peak_dynamic(d[:, 0], np_(lmask)[:, 0])
+
+
+def check_budget_costs(d):
+    """Every budget's cost s + c_s from the kernels that ckpt_solve_cubic runs, against the
+    literal recurrence of Equation (T): the budgets must be the oracle's list as a multiset."""
+    dc = inputs.chain_major(d)
+    mask, peak, budget, budgets, costs, status = B.ckpt_solve_cubic_costs(to_dev(d))
+    torch.cuda.synchronize()
+    assert (np_(status) == 0).all()
+    want_peak, want_mask, want_s = oracle.batch_solve_static(dc)
+    assert np.array_equal(np_(peak), want_peak) and np.array_equal(np_(budget), want_s)
+    assert np.array_equal(np_(mask).T, want_mask)
+    gb, gc = np_(budgets), np_(costs)
+    for c in range(dc.shape[0]):
+        used = gb[c] >= 0
+        assert (gc[c][~used] == -1).all()
+        s, cost = gb[c][used], gc[c][used]
+        order = np.argsort(s, kind="stable")
+        want_list = np.sort(oracle.budgets(dc[c]))
+        assert np.array_equal(s[order], want_list), f"chain {c}: budget list"
+        # equal budgets have equal costs, so the order among them does not matter
+        want_cost = want_list + oracle.static_cs_list(dc[c], want_list)
+        assert np.array_equal(cost[order], want_cost), f"chain {c}: costs"
+        assert int(cost.min()) == want_peak[c]
+
+
+def test_cubic_cost_of_every_budget():
+    say("cost of every budget: configs 1, 2, 4 and the group-edge chains")
+    check_budget_costs(inputs.config1())
+    check_budget_costs(inputs.config2())
+    chains = group_edge_chains()
+    for n in (40, 73, 105, 168):
+        check_budget_costs(np.stack([d for _, d in chains if len(d) - 1 == n], axis=1))
+    # chains that need 64-bit values, and a mixed batch
+    check_budget_costs(inputs.log_uniform_chains(21, 33, 5))
+    mixed = inputs.uniform_aligned_chains(22, 50, 6, 256, 32768)
+    mixed[:, 1] += 1
+    mixed[:, 4] = inputs.log_uniform_chains(23, 50, 1)[:, 0]
+    check_budget_costs(mixed)
+
+
+def test_cubic_cost_of_every_budget_resnet1001():
+    say("cost of every budget: config 4 (n = 1001), a sample of 20,000 budgets against Equation (T)")
+    d = inputs.config4()
+    mask, peak, budget, budgets, costs, status = B.ckpt_solve_cubic_costs(to_dev(d))
+    torch.cuda.synchronize()
+    gb, gc = np_(budgets)[0], np_(costs)[0]
+    used = gb >= 0
+    assert int(used.sum()) == 1001 * 1000 // 2 + 1
+    assert np.array_equal(np.sort(gb[used]), np.sort(oracle.budgets(d[:, 0])))
+    rng = np.random.default_rng(3)
+    pick = rng.choice(np.nonzero(used)[0], size=20000, replace=False)
+    want = gb[pick] + oracle.static_cs_list(d[:, 0], gb[pick])
+    assert np.array_equal(gc[pick], want)
+    assert int(gc[used].min()) == int(peak[0])
