@@ -6,8 +6,9 @@
  * the output, and both are always checkpoints.  A checkpoint set C is a byte
  * mask over positions 0..n with mask[0] = mask[n] = 1.
  *
- * Memory and ownership.  Every pointer below, except the ckpt_layout itself,
- * is a DEVICE pointer owned by the caller.  The library allocates no memory,
+ * Memory and ownership.  Every pointer below, except the ckpt_layout itself
+ * and the offsets_host of the ragged calls, is a DEVICE pointer owned by the
+ * caller.  The library allocates no memory,
  * keeps no data between calls and never synchronises: each call validates its
  * arguments on the host, enqueues its kernels on `hip_stream` (a hipStream_t
  * passed as void*, NULL = the null stream) and returns.  Outputs are valid
@@ -68,7 +69,12 @@ typedef enum {
     CKPT_SELECT_SQRT = 2  /* segments of ceil(sqrt(n)) layers (Section 2.1) */
 } ckpt_baseline;
 
-typedef enum { CKPT_CALL_EVAL_PEAK = 0, CKPT_CALL_SOLVE_CUBIC = 1, CKPT_CALL_SOLVE_LINEAR = 2 } ckpt_call;
+typedef enum {
+    CKPT_CALL_EVAL_PEAK = 0,
+    CKPT_CALL_SOLVE_CUBIC = 1,
+    CKPT_CALL_SOLVE_LINEAR = 2,
+    CKPT_CALL_EVAL_TIMELINE = 3
+} ckpt_call;
 
 /* Largest n accepted by ckpt_eval_peak and ckpt_solve_linear, and by
  * ckpt_solve_cubic (whose work grows as n^3). */
@@ -234,6 +240,43 @@ int ckpt_select_baseline(const ckpt_layout *layout, int kind, uint8_t *mask_out,
 int ckpt_solve_quadratic(const int64_t *d, const ckpt_layout *layout, uint8_t *mask_out,
                          int64_t *peak_out, int64_t *value_out, int32_t *status_out,
                          void *hip_stream);
+
+/* Ragged batches: chains of different n in one call.  The networks of Section 5
+ * have n = 15 (AlexNet), 24 (VGG-19), 152, 257 and 1001 layers; a caller who
+ * plans checkpoints for several of them (or for variants of one) hands all
+ * chains over at once.  Chain c has n_c = offsets[c+1] - offsets[c] - 1 layers
+ * (1 <= n_c <= the call's limit) and its sizes d_0..d_{n_c} are the elements
+ * offsets[c] .. offsets[c+1]-1 of the flat device array d; flat masks (input
+ * or output) use the same offsets in bytes, and the flat timeline has the
+ * 2 n_c + 2 phases of chain c from element 2 offsets[c] on.  peak_out,
+ * budget_out and status_out hold one value per chain, as in the equal-length
+ * calls, whose results each chain gets exactly (same equations, same canonical
+ * sets, same per-chain errors).
+ *   offsets_host [in] batch + 1 non-decreasing element offsets in HOST memory
+ *       (the caller built the batch and knows them; the library plans its
+ *       launches from them).  It is read during the call only.
+ *   ws: ckpt_ragged_workspace_bytes(which, offsets_host, batch) bytes, 256-byte
+ *       aligned; it receives a device copy of the offsets, the chain indices
+ *       grouped by length, and room to run the largest group in the
+ *       position-major layout.
+ * Unlike the other calls these wait once on the stream, for the copy of the
+ * offsets and the grouping into ws, before they enqueue the kernels: they
+ * cannot be captured into a HIP graph.  A bad offset (decreasing, n_c < 1 or
+ * beyond the limit) returns CKPT_ERR_SHAPE and launches nothing; batch = 0
+ * does nothing.  ckpt_ragged_workspace_bytes returns 0 for such input. */
+size_t ckpt_ragged_workspace_bytes(int which, const int64_t *offsets_host, int64_t batch);
+int ckpt_ragged_eval_peak(const int64_t *d, const uint8_t *mask, const int64_t *offsets_host,
+                          int64_t batch, int objective, int64_t *peak_out, int32_t *status_out,
+                          void *ws, size_t ws_bytes, void *hip_stream);
+int ckpt_ragged_eval_timeline(const int64_t *d, const uint8_t *mask, const int64_t *offsets_host,
+                              int64_t batch, int objective, int64_t *timeline_out,
+                              int32_t *status_out, void *ws, size_t ws_bytes, void *hip_stream);
+int ckpt_ragged_solve_linear(const int64_t *d, const int64_t *offsets_host, int64_t batch,
+                             uint8_t *mask_out, int64_t *peak_out, int32_t *status_out,
+                             void *ws, size_t ws_bytes, void *hip_stream);
+int ckpt_ragged_solve_cubic(const int64_t *d, const int64_t *offsets_host, int64_t batch,
+                            uint8_t *mask_out, int64_t *peak_out, int64_t *budget_out,
+                            int32_t *status_out, void *ws, size_t ws_bytes, void *hip_stream);
 
 /* Number of recurrence cells one ckpt_solve_cubic call evaluates per chain:
  * (n(n-1)/2 + 1) budgets times n positions.  Host-only. */

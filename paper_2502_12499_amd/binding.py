@@ -20,7 +20,7 @@ LIB_PATH = os.path.join(_HERE, "libckpt_hip.so")
 
 CKPT_OK = 0
 OBJ_STATIC, OBJ_DYNAMIC = 0, 1
-CALL_EVAL_PEAK, CALL_SOLVE_CUBIC, CALL_SOLVE_LINEAR = 0, 1, 2
+CALL_EVAL_PEAK, CALL_SOLVE_CUBIC, CALL_SOLVE_LINEAR, CALL_EVAL_TIMELINE = 0, 1, 2, 3
 
 SELECT_ENDS, SELECT_ALL, SELECT_SQRT = 0, 1, 2
 
@@ -28,6 +28,8 @@ EXPORTS = ("ckpt_workspace_bytes", "ckpt_eval_peak", "ckpt_eval_timeline", "ckpt
            "ckpt_solve_cubic", "ckpt_solve_cubic_pruned", "ckpt_solve_cubic_costs", "ckpt_cubic_costs_len", "ckpt_solve_linear", "ckpt_solve_linear_noalloc",
            "ckpt_solve_quadratic", "ckpt_cubic_cells",
            "ckpt_status_string",
+           "ckpt_ragged_workspace_bytes", "ckpt_ragged_eval_peak", "ckpt_ragged_eval_timeline",
+           "ckpt_ragged_solve_linear", "ckpt_ragged_solve_cubic",
            # include/ckpt_probe.h
            "ckpt_probe_hbm_read", "ckpt_probe_hbm_copy", "ckpt_probe_valu", "ckpt_probe_lds")
 
@@ -76,6 +78,17 @@ def load():
         lib.ckpt_cubic_cells.argtypes = [ctypes.c_int32]
         lib.ckpt_status_string.restype = ctypes.c_char_p
         lib.ckpt_status_string.argtypes = [ctypes.c_int]
+        i64 = ctypes.c_int64
+        lib.ckpt_ragged_workspace_bytes.restype = ctypes.c_size_t
+        lib.ckpt_ragged_workspace_bytes.argtypes = [ctypes.c_int, vp, i64]
+        lib.ckpt_ragged_eval_peak.restype = ctypes.c_int
+        lib.ckpt_ragged_eval_peak.argtypes = [vp, vp, vp, i64, ctypes.c_int, vp, vp, vp, ctypes.c_size_t, vp]
+        lib.ckpt_ragged_eval_timeline.restype = ctypes.c_int
+        lib.ckpt_ragged_eval_timeline.argtypes = [vp, vp, vp, i64, ctypes.c_int, vp, vp, vp, ctypes.c_size_t, vp]
+        lib.ckpt_ragged_solve_linear.restype = ctypes.c_int
+        lib.ckpt_ragged_solve_linear.argtypes = [vp, vp, i64, vp, vp, vp, vp, ctypes.c_size_t, vp]
+        lib.ckpt_ragged_solve_cubic.restype = ctypes.c_int
+        lib.ckpt_ragged_solve_cubic.argtypes = [vp, vp, i64, vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
         lib.ckpt_probe_hbm_read.restype = ctypes.c_int
         lib.ckpt_probe_hbm_read.argtypes = [vp, ctypes.c_size_t, vp, vp]
         lib.ckpt_probe_hbm_copy.restype = ctypes.c_int
@@ -285,6 +298,86 @@ def ckpt_solve_quadratic(d, chain_major=False, want_values=True, want_status=Tru
     if rc != CKPT_OK:
         raise CkptError("ckpt_solve_quadratic", rc)
     return mask, peak, values, status
+
+
+# ---- ragged batches: chains of different n in one flat array ------------------------------------
+
+def _ragged_args(d, offsets, mask=None):
+    """(offsets as a contiguous host int64 array, its pointer, batch) after the type checks."""
+    import numpy as np
+    if d.dtype != torch.int64 or not d.is_cuda or d.dim() != 1 or not d.is_contiguous():
+        raise TypeError("d must be a flat contiguous int64 tensor on the GPU")
+    if mask is not None and (mask.dtype != torch.uint8 or not mask.is_cuda or mask.shape != d.shape
+                             or not mask.is_contiguous()):
+        raise TypeError("mask must be a flat uint8 tensor on the GPU, as long as d")
+    off = np.ascontiguousarray(offsets.numpy() if isinstance(offsets, torch.Tensor) else offsets, dtype=np.int64)
+    if off.ndim != 1 or off.size < 1:
+        raise ValueError("offsets must hold batch + 1 values")
+    if int(off[-1]) > d.numel():
+        raise ValueError("offsets reach past the end of d")
+    return off, ctypes.c_void_p(off.ctypes.data), off.size - 1
+
+
+def _ragged_workspace(which, off_ptr, batch, device, workspace):
+    need = load().ckpt_ragged_workspace_bytes(int(which), off_ptr, batch)
+    if workspace is None or workspace.numel() < need:
+        workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=device)
+    return workspace, workspace.numel()
+
+
+def ckpt_ragged_eval_peak(d, mask, offsets, objective, workspace=None):
+    """Peak memory of each chain's set; chain c is d[offsets[c]:offsets[c+1]].  Returns (peak, status)."""
+    off, off_ptr, batch = _ragged_args(d, offsets, mask)
+    peak = torch.empty(batch, dtype=torch.int64, device=d.device)
+    status = torch.empty(batch, dtype=torch.int32, device=d.device)
+    ws, ws_bytes = _ragged_workspace(CALL_EVAL_PEAK, off_ptr, batch, d.device, workspace)
+    rc = load().ckpt_ragged_eval_peak(_ptr(d), _ptr(mask), off_ptr, batch, int(objective), _ptr(peak), _ptr(status),
+                                      _ptr(ws), ws_bytes, _stream())
+    if rc != CKPT_OK:
+        raise CkptError("ckpt_ragged_eval_peak", rc)
+    return peak, status
+
+
+def ckpt_ragged_eval_timeline(d, mask, offsets, objective, workspace=None):
+    """Memory per phase of each chain, flat: chain c from element 2*offsets[c].  Returns (timeline, status)."""
+    off, off_ptr, batch = _ragged_args(d, offsets, mask)
+    out = torch.empty(2 * d.numel(), dtype=torch.int64, device=d.device)
+    status = torch.empty(batch, dtype=torch.int32, device=d.device)
+    ws, ws_bytes = _ragged_workspace(CALL_EVAL_TIMELINE, off_ptr, batch, d.device, workspace)
+    rc = load().ckpt_ragged_eval_timeline(_ptr(d), _ptr(mask), off_ptr, batch, int(objective), _ptr(out),
+                                          _ptr(status), _ptr(ws), ws_bytes, _stream())
+    if rc != CKPT_OK:
+        raise CkptError("ckpt_ragged_eval_timeline", rc)
+    return out, status
+
+
+def ckpt_ragged_solve_linear(d, offsets, workspace=None):
+    """Optimal sets under the dynamic objective.  Returns (flat mask, peak, status)."""
+    off, off_ptr, batch = _ragged_args(d, offsets)
+    mask = torch.empty(d.numel(), dtype=torch.uint8, device=d.device)
+    peak = torch.empty(batch, dtype=torch.int64, device=d.device)
+    status = torch.empty(batch, dtype=torch.int32, device=d.device)
+    ws, ws_bytes = _ragged_workspace(CALL_SOLVE_LINEAR, off_ptr, batch, d.device, workspace)
+    rc = load().ckpt_ragged_solve_linear(_ptr(d), off_ptr, batch, _ptr(mask), _ptr(peak), _ptr(status),
+                                         _ptr(ws), ws_bytes, _stream())
+    if rc != CKPT_OK:
+        raise CkptError("ckpt_ragged_solve_linear", rc)
+    return mask, peak, status
+
+
+def ckpt_ragged_solve_cubic(d, offsets, workspace=None):
+    """Optimal sets under the static objective.  Returns (flat mask, peak, budget, status)."""
+    off, off_ptr, batch = _ragged_args(d, offsets)
+    mask = torch.empty(d.numel(), dtype=torch.uint8, device=d.device)
+    peak = torch.empty(batch, dtype=torch.int64, device=d.device)
+    budget = torch.empty(batch, dtype=torch.int64, device=d.device)
+    status = torch.empty(batch, dtype=torch.int32, device=d.device)
+    ws, ws_bytes = _ragged_workspace(CALL_SOLVE_CUBIC, off_ptr, batch, d.device, workspace)
+    rc = load().ckpt_ragged_solve_cubic(_ptr(d), off_ptr, batch, _ptr(mask), _ptr(peak), _ptr(budget), _ptr(status),
+                                        _ptr(ws), ws_bytes, _stream())
+    if rc != CKPT_OK:
+        raise CkptError("ckpt_ragged_solve_cubic", rc)
+    return mask, peak, budget, status
 
 
 # ---- measurement probes (include/ckpt_probe.h) ------------------------------------------------

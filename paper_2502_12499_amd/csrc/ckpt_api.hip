@@ -47,10 +47,11 @@ extern "C" {
 
 size_t ckpt_workspace_bytes(int which, const ckpt_layout *L)
 {
-    if (which < CKPT_CALL_EVAL_PEAK || which > CKPT_CALL_SOLVE_LINEAR) return 0;
+    if (which < CKPT_CALL_EVAL_PEAK || which > CKPT_CALL_EVAL_TIMELINE) return 0;
     if (check_layout(L, max_layers_of(which)) != CKPT_OK) return 0;
     switch (which) {
-        case CKPT_CALL_EVAL_PEAK: return 256;
+        case CKPT_CALL_EVAL_PEAK:
+        case CKPT_CALL_EVAL_TIMELINE: return 256;
         case CKPT_CALL_SOLVE_CUBIC: return ckpt::cubic_workspace_bytes(L->batch, L->n_layers);
         default: return ckpt::linear_workspace_bytes(L->batch, L->n_layers);
     }
@@ -165,6 +166,45 @@ int ckpt_solve_quadratic(const int64_t *d, const ckpt_layout *L, uint8_t *mask_o
     return finish(ckpt::launch_solve_quadratic(d, L->batch, L->n_layers, Strides{L->chain_stride, L->pos_stride},
                                                mask_out, peak_out, value_out, status_out,
                                                (hipStream_t)hip_stream));
+}
+
+size_t ckpt_ragged_workspace_bytes(int which, const int64_t *offsets_host, int64_t batch)
+{
+    if (which < CKPT_CALL_EVAL_PEAK || which > CKPT_CALL_EVAL_TIMELINE) return 0;
+    return ckpt::ragged_workspace_bytes(which, offsets_host, batch);
+}
+
+int ckpt_ragged_eval_peak(const int64_t *d, const uint8_t *mask, const int64_t *offsets_host, int64_t batch,
+                          int objective, int64_t *peak_out, int32_t *status_out, void *ws, size_t ws_bytes,
+                          void *hip_stream)
+{
+    if (objective != CKPT_OBJ_STATIC && objective != CKPT_OBJ_DYNAMIC) return CKPT_ERR_SHAPE;
+    return ckpt::launch_ragged(CKPT_CALL_EVAL_PEAK, d, mask, offsets_host, batch, objective, nullptr, peak_out,
+                               nullptr, nullptr, status_out, ws, ws_bytes, (hipStream_t)hip_stream);
+}
+
+int ckpt_ragged_eval_timeline(const int64_t *d, const uint8_t *mask, const int64_t *offsets_host, int64_t batch,
+                              int objective, int64_t *timeline_out, int32_t *status_out, void *ws, size_t ws_bytes,
+                              void *hip_stream)
+{
+    if (objective != CKPT_OBJ_STATIC && objective != CKPT_OBJ_DYNAMIC) return CKPT_ERR_SHAPE;
+    return ckpt::launch_ragged(CKPT_CALL_EVAL_TIMELINE, d, mask, offsets_host, batch, objective, nullptr, nullptr,
+                               nullptr, timeline_out, status_out, ws, ws_bytes, (hipStream_t)hip_stream);
+}
+
+int ckpt_ragged_solve_linear(const int64_t *d, const int64_t *offsets_host, int64_t batch, uint8_t *mask_out,
+                             int64_t *peak_out, int32_t *status_out, void *ws, size_t ws_bytes, void *hip_stream)
+{
+    return ckpt::launch_ragged(CKPT_CALL_SOLVE_LINEAR, d, nullptr, offsets_host, batch, 0, mask_out, peak_out,
+                               nullptr, nullptr, status_out, ws, ws_bytes, (hipStream_t)hip_stream);
+}
+
+int ckpt_ragged_solve_cubic(const int64_t *d, const int64_t *offsets_host, int64_t batch, uint8_t *mask_out,
+                            int64_t *peak_out, int64_t *budget_out, int32_t *status_out, void *ws, size_t ws_bytes,
+                            void *hip_stream)
+{
+    return ckpt::launch_ragged(CKPT_CALL_SOLVE_CUBIC, d, nullptr, offsets_host, batch, 0, mask_out, peak_out,
+                               budget_out, nullptr, status_out, ws, ws_bytes, (hipStream_t)hip_stream);
 }
 
 int64_t ckpt_cubic_cells(int32_t n_layers)

@@ -75,6 +75,28 @@ def chain_major(x):
     return np.ascontiguousarray(x.T)
 
 
+def ragged_batch(seed, lengths, lo_units=256, hi_units=32768, unit=4096, p=0.25, named=()):
+    """Chains of different n in one flat array: (d, mask, offsets).  Chain c has lengths[c] layers,
+    sizes unit * U{lo_units..hi_units} drawn as chain c of `uniform_aligned_chains` with its own n,
+    and a `bernoulli_masks` mask; d[offsets[c]:offsets[c+1]] are its sizes d_0..d_n.  `named` is a
+    list of (index, column) pairs: those chains take the given sizes instead (their lengths must
+    agree), e.g. the chains built from the paper's layer lists."""
+    lengths = np.asarray(lengths, dtype=np.int64)
+    offsets = np.zeros(len(lengths) + 1, dtype=np.int64)
+    np.cumsum(lengths + 1, out=offsets[1:])
+    d = np.empty(int(offsets[-1]), dtype=np.int64)
+    m = np.empty(int(offsets[-1]), dtype=np.uint8)
+    for n in np.unique(lengths):
+        for c in np.nonzero(lengths == n)[0]:
+            d[offsets[c]:offsets[c + 1]] = uniform_aligned_chains(seed, int(n), 1, lo_units, hi_units, unit, chain0=int(c))[:, 0]
+            m[offsets[c]:offsets[c + 1]] = bernoulli_masks(seed, int(n), 1, p, chain0=int(c))[:, 0]
+    for c, col in named:
+        col = np.asarray(col, dtype=np.int64).reshape(-1)
+        assert col.size == lengths[c] + 1
+        d[offsets[c]:offsets[c + 1]] = col
+    return d, m, offsets
+
+
 def _column(sizes):
     return np.asarray(sizes, dtype=np.int64).reshape(-1, 1)
 

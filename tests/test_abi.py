@@ -96,3 +96,29 @@ def test_binding_refuses_cpu_tensors():
     d = torch.ones(5, 3, dtype=torch.int64)
     with pytest.raises(TypeError):
         B.ckpt_solve_linear(d)
+
+
+def test_ragged_host_checks():
+    import numpy as np
+    lib = B.load()
+    off = np.array([0, 16, 41, 43], dtype=np.int64)       # n = 15, 24, 1
+    ptr = ctypes.c_void_p(off.ctypes.data)
+    sizes = [lib.ckpt_ragged_workspace_bytes(w, ptr, 3) for w in
+             (B.CALL_EVAL_PEAK, B.CALL_SOLVE_CUBIC, B.CALL_SOLVE_LINEAR, B.CALL_EVAL_TIMELINE)]
+    assert all(s > 0 and s % 256 == 0 for s in sizes)
+    assert sizes[3] > sizes[0]                              # the timeline stages 2n+2 phases per chain
+    assert lib.ckpt_ragged_workspace_bytes(B.CALL_SOLVE_LINEAR, ptr, 0) == 0
+    assert lib.ckpt_ragged_workspace_bytes(4, ptr, 3) == 0
+    for bad in ([0, 16, 15, 43], [0, 1, 41, 43], [-2, 16, 41, 43]):
+        b = np.array(bad, dtype=np.int64)
+        assert lib.ckpt_ragged_workspace_bytes(B.CALL_SOLVE_LINEAR, ctypes.c_void_p(b.ctypes.data), 3) == 0
+    # the cubic solver's limit on n applies per chain
+    long = np.array([0, 8193], dtype=np.int64)
+    assert lib.ckpt_ragged_workspace_bytes(B.CALL_SOLVE_CUBIC, ctypes.c_void_p(long.ctypes.data), 1) == 0
+    assert lib.ckpt_ragged_workspace_bytes(B.CALL_SOLVE_LINEAR, ctypes.c_void_p(long.ctypes.data), 1) > 0
+    fake = ctypes.c_void_p(4096)        # never dereferenced: validation fails first
+    assert lib.ckpt_ragged_solve_linear(fake, ptr, 3, fake, fake, None, fake, 16, None) == 6
+    assert lib.ckpt_ragged_solve_linear(fake, ptr, 3, None, fake, None, fake, 1 << 30, None) == 1
+    assert lib.ckpt_ragged_solve_linear(fake, None, 3, fake, fake, None, fake, 1 << 30, None) == 1
+    assert lib.ckpt_ragged_eval_peak(fake, fake, ptr, 3, 2, fake, None, fake, 1 << 30, None) == 2
+    assert lib.ckpt_ragged_solve_cubic(None, ptr, 0, None, None, None, None, None, 0, None) == 0

@@ -1,0 +1,132 @@
+"""Ragged batches (chains of different n in one call) through the C ABI against the oracle's
+per-chain loops: every chain must get exactly what it gets on its own."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2502_12499_amd import binding as B
+from paper_2502_12499_amd import inputs
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+
+def to_dev(x):
+    return torch.from_numpy(np.ascontiguousarray(x)).to(DEV)
+
+
+def np_(t):
+    return t.cpu().numpy()
+
+
+def say(msg):
+    print(msg, flush=True)
+
+
+def check_eval(d, m, off):
+    dd, md = to_dev(d), to_dev(m)
+    for obj in (B.OBJ_STATIC, B.OBJ_DYNAMIC):
+        peak, status = B.ckpt_ragged_eval_peak(dd, md, off, obj)
+        line, status2 = B.ckpt_ragged_eval_timeline(dd, md, off, obj)
+        torch.cuda.synchronize()
+        assert (np_(status) == 0).all() and (np_(status2) == 0).all()
+        assert np.array_equal(np_(peak), oracle.ragged_peak(d, m, off, obj)), f"objective {obj}"
+        assert np.array_equal(np_(line), oracle.ragged_timeline(d, m, off, obj)), f"objective {obj}"
+
+
+def check_linear(d, off):
+    mask, peak, status = B.ckpt_ragged_solve_linear(to_dev(d), off)
+    torch.cuda.synchronize()
+    want_peak, want_mask = oracle.ragged_solve_dynamic(d, off)
+    assert (np_(status) == 0).all()
+    assert np.array_equal(np_(peak), want_peak)
+    assert np.array_equal(np_(mask), want_mask)
+
+
+def check_cubic(d, off):
+    mask, peak, budget, status = B.ckpt_ragged_solve_cubic(to_dev(d), off)
+    torch.cuda.synchronize()
+    want_peak, want_mask, want_s = oracle.ragged_solve_static(d, off)
+    assert (np_(status) == 0).all()
+    assert np.array_equal(np_(peak), want_peak)
+    assert np.array_equal(np_(budget), want_s)
+    assert np.array_equal(np_(mask), want_mask)
+
+
+def test_networks_of_the_paper_in_one_batch():
+    """One chain each of n = 1, 15, 24, 152, 257 and 1001 (Section 5's depths), the named ones with
+    the layer lists' sizes, in an order that is not sorted by length."""
+    lengths = [152, 1, 1001, 24, 257, 15]
+    named = [(0, inputs.resnet152_chain()), (2, inputs.resnet1001_chain()), (3, inputs.vgg19_chain()),
+             (5, inputs.alexnet_chain())]
+    d, m, off = inputs.ragged_batch(11, lengths, named=named)
+    say(f"ragged zoo: lengths {lengths}")
+    check_eval(d, m, off)
+    check_linear(d, off)
+    check_cubic(d, off)
+
+
+def test_many_short_chains_of_mixed_length():
+    rng = np.random.default_rng(5)
+    lengths = rng.choice([1, 2, 3, 15, 24, 63, 64, 65, 152, 257], size=6000)
+    d, m, off = inputs.ragged_batch(12, lengths)
+    say(f"ragged mixed: {len(lengths)} chains, {len(d)} sizes")
+    check_eval(d, m, off)
+    check_linear(d, off)
+
+
+def test_cubic_on_mixed_lengths():
+    rng = np.random.default_rng(6)
+    lengths = rng.choice([1, 2, 3, 12, 15, 24, 63, 64, 65, 100], size=400)
+    d, m, off = inputs.ragged_batch(13, lengths, lo_units=1, hi_units=4096)
+    say(f"ragged cubic: {len(lengths)} chains")
+    check_cubic(d, off)
+
+
+def test_one_large_group_beside_small_ones():
+    """A group of 70,001 chains spans many transposition tiles and leaves a ragged last tile."""
+    lengths = np.full(70004, 24)
+    lengths[[0, 35000, 70003]] = [257, 1, 64]
+    d, m, off = inputs.ragged_batch(14, lengths)
+    say("ragged large group")
+    check_eval(d, m, off)
+    check_linear(d, off)
+
+
+def test_chain_with_a_bad_size_is_reported_alone():
+    lengths = [15, 24, 15, 3]
+    d, m, off = inputs.ragged_batch(15, lengths)
+    good_peak, good_mask = oracle.ragged_solve_dynamic(d, off)
+    bad = d.copy()
+    bad[off[1] + 7] = 0
+    mask, peak, status = B.ckpt_ragged_solve_linear(to_dev(bad), off)
+    cmask, cpeak, cbudget, cstatus = B.ckpt_ragged_solve_cubic(to_dev(bad), off)
+    epeak, estatus = B.ckpt_ragged_eval_peak(to_dev(bad), to_dev(m), off, B.OBJ_DYNAMIC)
+    torch.cuda.synchronize()
+    for st in (status, cstatus, estatus):
+        assert np_(st).tolist() == [0, 3, 0, 0]
+    assert np_(peak)[1] == -1 and np_(cpeak)[1] == -1 and np_(epeak)[1] == -1
+    assert not np_(mask)[off[1]:off[2]].any() and not np_(cmask)[off[1]:off[2]].any()
+    keep = np.ones(len(d), dtype=bool)
+    keep[off[1]:off[2]] = False
+    assert np.array_equal(np_(mask)[keep], good_mask[keep])
+    assert np.array_equal(np_(peak)[[0, 2, 3]], good_peak[[0, 2, 3]])
+
+
+def test_host_checks_and_the_empty_batch():
+    d, m, off = inputs.ragged_batch(16, [4, 5])
+    dd = to_dev(d)
+    for bad in ([0, 5, 4], [0, 1, 11], [-1, 5, 11]):
+        with pytest.raises(B.CkptError) as e:
+            B.ckpt_ragged_solve_linear(dd, np.array(bad, dtype=np.int64))
+        assert e.value.code == 2
+    with pytest.raises(ValueError):
+        B.ckpt_ragged_solve_linear(dd, np.array([0, 5, 12], dtype=np.int64))
+    mask, peak, status = B.ckpt_ragged_solve_linear(dd[:0], np.array([0], dtype=np.int64))
+    torch.cuda.synchronize()
+    assert peak.numel() == 0 and mask.numel() == 0
+    lib = B.load()
+    assert lib.ckpt_ragged_workspace_bytes(B.CALL_SOLVE_LINEAR, None, 3) == 0
+    assert lib.ckpt_ragged_workspace_bytes(9, off.ctypes.data, 2) == 0
+    assert lib.ckpt_ragged_workspace_bytes(B.CALL_SOLVE_CUBIC, off.ctypes.data, 2) > 0
