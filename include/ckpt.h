@@ -241,9 +241,12 @@ int ckpt_solve_quadratic(const int64_t *d, const ckpt_layout *layout, uint8_t *m
                          int64_t *peak_out, int64_t *value_out, int32_t *status_out,
                          void *hip_stream);
 
-/* Ragged batches: chains of different n in one call.  The networks of Section 5
- * have n = 15 (AlexNet), 24 (VGG-19), 152, 257 and 1001 layers; a caller who
- * plans checkpoints for several of them (or for variants of one) hands all
+/* Ragged batches: chains of different n in one call.  Section 6 (Conclusion and
+ * Future Work) proposes cutting an arbitrary computation graph into many
+ * linear sub-models, which yields chains of many different lengths, and
+ * Section 5.4 solves one network at two granularities of its specs (AlexNet
+ * as a chain of 12 and of 15 layers); the networks of Section 5 range from
+ * these to VGG-19's 24 layers.  A caller with such a set hands all
  * chains over at once.  Chain c has n_c = offsets[c+1] - offsets[c] - 1 layers
  * (1 <= n_c <= the call's limit) and its sizes d_0..d_{n_c} are the elements
  * offsets[c] .. offsets[c+1]-1 of the flat device array d; flat masks (input

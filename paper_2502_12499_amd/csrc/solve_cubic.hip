@@ -58,6 +58,7 @@
 
 #include <limits>
 #include <atomic>
+#include <cstddef>
 
 #include "ckpt_internal.h"
 
@@ -1250,6 +1251,14 @@ __global__ __launch_bounds__(BLOCK) void cubic_shared_kernel(int n, int64_t bloc
     SH_RARE("s58", "s59", TAG "c3", T3) SH_RARE("s60", "s61", TAG "c4", T4) SH_RARE("s62", "s63", TAG "c5", T5) \
     SH_RARE("s64", "s65", TAG "c6", T6) SH_RARE("s66", "s67", TAG "c7", T7)
     static_assert(kGroup == 8 && sizeof(Group) == 16 && sizeof(Step) == 8, "the loads and shifts below");
+    // What the assembly hard-codes: a snapshot is 64 bytes (position << 6), an El 16 bytes with the
+    // link to the next snapshot at byte 8 (position << 4, + 8), a ring entry two words written by
+    // one ds_write2_b32, a ring aligned to its own size so that an entry's address is
+    // (position & mask) | lane base, and 32-bit table offsets (positions stay below 2^13 + padding).
+    static_assert(sizeof(Snap) == 64 && sizeof(El) == 16 && offsetof(El, below) == 8, "snapshot and link offsets");
+    static_assert(sizeof(QueueEntry<V>) == 8 && offsetof(QueueEntry<V>, K) == 4, "ring entry layout");
+    static_assert(sizeof(ring) == (size_t)RING * BLOCK * 8 && alignof(decltype(ring)) >= 8, "ring size");
+    static_assert(((size_t)CKPT_CUBIC_MAX_LAYERS + 64) * sizeof(Snap) < ((size_t)1 << 31), "32-bit table offsets");
     auto middle = [&](const int t_first, const int rounds) {
         V Xr = L.hd == L.tl ? kLow : L.X - L.hF;
         const uint64_t summaries = (uint64_t)(uintptr_t)(gr + group_slot(t_first / kGroup));
@@ -1990,6 +1999,15 @@ hipError_t launch_solve_cubic(const int64_t *d, int64_t batch, int n, Strides st
     const int64_t total_blocks = (K + kWave - 1) / kWave * batch;  // the largest grid: one wave per workgroup
     const int64_t n_words = waves_per_chain(n) * batch;
     if (total_blocks > 0x7fffffffLL) return hipErrorInvalidConfiguration;
+    {
+        // The shared kernel's loop reads group summaries up to three pairs past the last group it uses
+        // and (d, depth) pairs up to 15 positions past n - 1: the tables are padded for that.
+        const int last_full = n / 8 * 8;
+        const int rounds = last_full - 8 >= 32 ? (last_full - 8) / 32 : 0;
+        if (group_slot(1) + 4 * (size_t)rounds + 2 > group_len(n) || (size_t)n + 15 > step_len(n) ||
+            (size_t)n + 1 + kSnap > table_len(n))
+            return hipErrorInvalidValue;
+    }
     const size_t table_lds = ((size_t)n + 1) * 8;
     w.trace_s = trace_s;
     w.trace_cost = trace_cost;

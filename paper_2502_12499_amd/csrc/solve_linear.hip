@@ -131,6 +131,12 @@ __global__ __launch_bounds__(kWave) void linear_ring_kernel(const int64_t *__res
     constexpr int kA = kPlaneA * (int)(kPlane / 4), kGJ = kPlaneGJ * (int)(kPlane / 4);  // in words
     constexpr uint32_t kNone = 0xffffffffu;  // "no candidate": never passes a test
     static_assert(kPlane == 4096, "plane size and alignment");
+    // What the assembly hard-codes: the literal plane offsets 4096 and 8192 of its LDS reads, a
+    // ring aligned to a plane so that an address is (position & mask) | lane base, steps and
+    // positions that fit the low byte of a GJ word, and lane offsets of the rows that fit 31 bits.
+    static_assert(kPlanes == 3 && kRing == 16 && kWave == 64 && kStep == 256, "ring geometry in the assembly");
+    static_assert(sizeof(ring) == 3 * 4096 && (kSlotMask & (kStep - 1)) == 0, "ring size and slot mask");
+    static_assert(63 * kRingMaxChainStride * 8 < ((int64_t)1 << 31), "32-bit lane offsets");
 
     const int lane = threadIdx.x;
     const int64_t c0 = (int64_t)xcd_paired_block(blockIdx.x, gridDim.x) * kWave;
