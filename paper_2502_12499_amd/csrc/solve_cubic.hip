@@ -337,16 +337,15 @@ extern __shared__ __align__(16) unsigned char dyn_lds[];
 
 constexpr int kLinksBlock = 1024;
 
-__host__ __device__ inline size_t links_lds_bytes(int n) { return ((size_t)n + 2) * 10 + 16; }
+__host__ __device__ constexpr size_t links_lds_bytes(int n) { return ((size_t)n + 2) * 10 + 16; }
 
 // One workgroup per chain.  below(t) comes from a stack pass over 64 contiguous
 // pieces (one per lane of the first wave) and, for the positions whose answer
 // lies in an earlier piece, a search through the pieces' minima and final
 // stacks; depth(t) from below(t) by pointer jumping; then every position's
 // snapshot.  LDS: 10 bytes per position.
-__global__ __launch_bounds__(kLinksBlock) void cubic_links_kernel(int n, CubicWs w)
+__device__ inline void links_chain(int n, const CubicWs &w, int64_t c)
 {
-    const int64_t c = blockIdx.x;
     const ChainMeta meta = w.meta[c];
     if (meta.status != CKPT_OK || !meta.mode32) return;
     const int tid = threadIdx.x;
@@ -483,6 +482,8 @@ __global__ __launch_bounds__(kLinksBlock) void cubic_links_kernel(int n, CubicWs
         gr[slot] = G;
     }
 }
+
+__global__ __launch_bounds__(kLinksBlock) void cubic_links_kernel(int n, CubicWs w) { links_chain(n, w, blockIdx.x); }
 
 // ---- budget index -> (range length, start) ------------------------------------
 
@@ -712,11 +713,12 @@ void launch_budgets(int n, int64_t batch, CubicWs w, hipStream_t stream)
 // ---- budget values of the 32-bit chains, laid out by slices of the value range -----------------
 extern __shared__ __align__(16) unsigned char order_lds[];
 
-constexpr int kBisect = 8;  // starts whose bisections a thread runs side by side
+// kBisect: starts whose bisections a thread runs side by side
 
 // For kBisect starts a[j] at once: x[j] = the largest x in [a[j], n] with Q[x] - Q[a[j]] < bound
 // (Q ascending; bound >= 1).  The reads of the kBisect searches are independent of each other,
 // so their LDS latencies overlap.  A start a >= n gets x = a.
+template <int kBisect>
 __device__ inline void ends_below(const int32_t *Q, int n, const int (&a)[kBisect], int64_t bound, int (&x)[kBisect])
 {
     int lo[kBisect], hi[kBisect];
@@ -745,14 +747,18 @@ __device__ inline void ends_below(const int32_t *Q, int n, const int (&a)[kBisec
     for (int j = 0; j < kBisect; ++j) x[j] = lo[j];
 }
 
-// One workgroup per group of kSliceGroup slices of a chain.
-__global__ __launch_bounds__(256) void cubic_slice_kernel(int n, CubicWs w)
+// One workgroup of THREADS threads per group of kSliceGroup slices of a chain.  A long chain has
+// few groups (256 at n = 4096, one per CU): with 1024 threads a CU holds four waves per SIMD, whose
+// bisections and scattered stores hide each other's latency; a short chain has fewer starts than
+// that many threads could take.
+template <int THREADS, int kBisect>
+__device__ inline void slice_group(int n, const CubicWs &w, int64_t block)
 {
     __shared__ int32_t tally[kSliceGroup];   // budgets per slice, then each slice's next free place
     __shared__ int32_t below;                // budgets below the group's range
     const int64_t groups = slice_groups(n);
-    const int64_t c = blockIdx.x / groups;
-    const int64_t g = blockIdx.x % groups;
+    const int64_t c = block / groups;
+    const int64_t g = block % groups;
     const ChainMeta meta = w.meta[c];
     if (meta.status != CKPT_OK || !meta.mode32) return;
     const PD<int32_t> *pd = chain_table<int32_t>(w, c, n);
@@ -762,7 +768,7 @@ __global__ __launch_bounds__(256) void cubic_slice_kernel(int n, CubicWs w)
     const int wshift = slice_shift(smax, n);
     const int64_t lo = (g * kSliceGroup) << wshift, hi = ((g + 1) * kSliceGroup) << wshift;  // lo <= s < hi
     if (lo > smax) return;                   // (the same for the whole workgroup)
-    for (int j = tid; j <= n; j += 256) Q[j] = pd[j].P;
+    for (int j = tid; j <= n; j += THREADS) Q[j] = pd[j].P;
     if (tid < kSliceGroup) tally[tid] = 0;
     if (tid == 0) below = lo > 0 ? 1 : 0;    // the empty range, s = 0
     __syncthreads();
@@ -770,17 +776,17 @@ __global__ __launch_bounds__(256) void cubic_slice_kernel(int n, CubicWs w)
 
     // pass 1: the ends of every start's budgets inside the range; counts
     int32_t mine_below = 0;
-    for (int a0 = 1 + tid; a0 < n; a0 += 256 * kBisect) {
+    for (int a0 = 1 + tid; a0 < n; a0 += THREADS * kBisect) {
         int a[kBisect], x0[kBisect], x1[kBisect];
 #pragma unroll
-        for (int j = 0; j < kBisect; ++j) a[j] = a0 + 256 * j;
+        for (int j = 0; j < kBisect; ++j) a[j] = a0 + THREADS * j;
         if (lo > 0) {
-            ends_below(Q, n, a, lo, x0);
+            ends_below<kBisect>(Q, n, a, lo, x0);
         } else {
 #pragma unroll
             for (int j = 0; j < kBisect; ++j) x0[j] = a[j];
         }
-        ends_below(Q, n, a, hi, x1);
+        ends_below<kBisect>(Q, n, a, hi, x1);
 #pragma unroll
         for (int j = 0; j < kBisect; ++j) {
             if (a[j] < n) {
@@ -822,17 +828,17 @@ __global__ __launch_bounds__(256) void cubic_slice_kernel(int n, CubicWs w)
     __syncthreads();
     // pass 2: the same budgets again, to their places
     if (tid == 0 && lo == 0) out[atomicAdd(&tally[0], 1)] = 0;
-    for (int a0 = 1 + tid; a0 < n; a0 += 256 * kBisect) {
+    for (int a0 = 1 + tid; a0 < n; a0 += THREADS * kBisect) {
         int a[kBisect], x0[kBisect], x1[kBisect];
 #pragma unroll
-        for (int j = 0; j < kBisect; ++j) a[j] = a0 + 256 * j;
+        for (int j = 0; j < kBisect; ++j) a[j] = a0 + THREADS * j;
         if (lo > 0) {
-            ends_below(Q, n, a, lo, x0);
+            ends_below<kBisect>(Q, n, a, lo, x0);
         } else {
 #pragma unroll
             for (int j = 0; j < kBisect; ++j) x0[j] = a[j];
         }
-        ends_below(Q, n, a, hi, x1);
+        ends_below<kBisect>(Q, n, a, hi, x1);
 #pragma unroll
         for (int j = 0; j < kBisect; ++j) {
             if (a[j] < n) {
@@ -844,6 +850,29 @@ __global__ __launch_bounds__(256) void cubic_slice_kernel(int n, CubicWs w)
             }
         }
     }
+}
+
+constexpr int kSliceLongFrom = 1024;  // chains from this length on take the 1024-thread form
+
+static_assert(links_lds_bytes(kSliceLongFrom) >= ((size_t)kSliceLongFrom + 1) * 4, "the links' LDS covers the prefix sums");
+
+template <int THREADS, int kBisect>
+__global__ __launch_bounds__(THREADS) void cubic_slice_kernel(int n, CubicWs w)
+{
+    slice_group<THREADS, kBisect>(n, w, blockIdx.x);
+}
+
+// Long chains: the links of the size stack and the layout of the budgets need the prologue's table
+// and nothing of each other, and a single long chain fills the chip with neither (one workgroup, and
+// one workgroup per CU).  One launch runs both: the first `batch` workgroups take the links of a
+// chain each (they run longest, so they start first), the others a group of slices each.
+static_assert(kLinksBlock == 1024, "the two parts share a launch of 1024 threads");
+__global__ __launch_bounds__(kLinksBlock) void cubic_prepare_kernel(int n, int64_t batch, CubicWs w)
+{
+    if ((int64_t)blockIdx.x < batch)
+        links_chain(n, w, blockIdx.x);
+    else
+        slice_group<kLinksBlock, 4>(n, w, (int64_t)blockIdx.x - batch);
 }
 
 // ---- budgets kernel for 32-bit chains: the queue's shared part factored out -------------
@@ -1981,6 +2010,9 @@ hipError_t raise_links_lds_limit()
     if (links_lds_raised[dev].load(std::memory_order_acquire)) return hipSuccess;
     e = hipFuncSetAttribute((const void *)cubic_links_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
                             (int)links_lds_bytes(CKPT_CUBIC_MAX_LAYERS));
+    if (e == hipSuccess)
+        e = hipFuncSetAttribute((const void *)cubic_prepare_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                (int)links_lds_bytes(CKPT_CUBIC_MAX_LAYERS));
     if (e == hipSuccess) links_lds_raised[dev].store(true, std::memory_order_release);
     return e;
 }
@@ -2018,14 +2050,23 @@ hipError_t launch_solve_cubic(const int64_t *d, int64_t batch, int n, Strides st
         const hipError_t e = raise_links_lds_limit();
         if (e != hipSuccess) return e;
     }
-    // Everything runs on the caller's stream, in this order: the tables of the size stack, the
-    // first bounds of a pruned call (they need those tables only), the budgets grouped by value.
-    hipLaunchKernelGGL(cubic_links_kernel, dim3((unsigned)batch), dim3(kLinksBlock), links_lds_bytes(n), stream, n, w);
+    // Everything runs on the caller's stream: the tables of the size stack and the budgets grouped by
+    // value (one launch for long chains, two for short ones), then the first bounds of a pruned call
+    // (they need those tables only).
+    if (n >= kSliceLongFrom) {
+        const int64_t blocks = (slice_groups(n) + 1) * batch;
+        if (blocks > 0x7fffffffLL) return hipErrorInvalidConfiguration;
+        hipLaunchKernelGGL(cubic_prepare_kernel, dim3((unsigned)blocks), dim3(kLinksBlock), links_lds_bytes(n), stream,
+                           n, batch, w);
+    } else {
+        hipLaunchKernelGGL(cubic_links_kernel, dim3((unsigned)batch), dim3(kLinksBlock), links_lds_bytes(n), stream, n,
+                           w);
+        hipLaunchKernelGGL((cubic_slice_kernel<256, 8>), dim3((unsigned)(slice_groups(n) * batch)), dim3(256),
+                           ((size_t)n + 1) * 4, stream, n, w);
+    }
     if (pruned)
         hipLaunchKernelGGL(cubic_bound_kernel, dim3((unsigned)batch), dim3(kBoundThreads), 0, stream, n,
                            (num_budgets(n) + kWave - 1) / kWave, kSampleStride, 1, 0, w);
-    hipLaunchKernelGGL(cubic_slice_kernel, dim3((unsigned)(slice_groups(n) * batch)), dim3(256), ((size_t)n + 1) * 4,
-                       stream, n, w);
     launch_shared<16, 64, 64>(n, batch, pruned, w, stream);
     launch_budgets<int64_t, 16, 64>(n, batch, w, stream);
     const int64_t word_groups = (n_words + kWave - 1) / kWave;
