@@ -1759,10 +1759,21 @@ __device__ bool epoch_budget_pred(const PD<V> *__restrict__ pd, int n, V s_in, u
     V *dl = Pl + n1 + 1;                     // [n1]
     pred16 = STAGED ? (uint16_t *)(dl + n1) : (uint16_t *)(F + n1);
     if (STAGED) {
-        for (int j = lane; j <= n1; j += kWave) {
-            const PD<V> x = pd[j];
-            Pl[j] = x.P;
-            if (j < n1) dl[j] = x.d;
+        // eight loads in flight per lane (the table is padded past n+1, so a clamped index is enough)
+        constexpr int kAhead = 8;
+        for (int j0 = lane; j0 <= n1; j0 += kWave * kAhead) {
+            PD<V> x[kAhead];
+#pragma unroll
+            for (int u = 0; u < kAhead; ++u) {
+                const int j = j0 + u * kWave;
+                x[u] = pd[j <= n1 ? j : n1];
+            }
+#pragma unroll
+            for (int u = 0; u < kAhead; ++u) {
+                const int j = j0 + u * kWave;
+                if (j <= n1) Pl[j] = x[u].P;
+                if (j < n1) dl[j] = x[u].d;
+            }
         }
         __syncthreads();
     }
@@ -1796,6 +1807,36 @@ __device__ bool epoch_budget_pred(const PD<V> *__restrict__ pd, int n, V s_in, u
         __syncthreads();
         // window of e: indices i in (h, e-1] with P[e-1] - P[i] <= s; its start is near h
         const V Pe = P_at(e);
+        {
+            // Usual case, the window is shorter than a wave: the lanes take i = e-1, e-2, .. (the
+            // window is a prefix of them), one reduction gives the minimum, and the highest lane
+            // that holds it is the smallest index; its P[i] is the new head's key.
+            const int i = e - 1 - lane;
+            const bool valid = i > h;
+            const int ic = valid ? i : e - 1;
+            const V pi = P_at(ic + 1);  // P[ic]
+            const V fi = F[ic];
+            const bool in = valid && Pe - pi <= s;
+            if (__builtin_amdgcn_ballot_w64(in) != ~0ull) {
+                const V vmax = std::numeric_limits<V>::max();
+                const V v = in ? fi : vmax;  // (values are positive: they order as unsigned)
+                V mn;
+                if constexpr (sizeof(V) == 4)
+                    mn = (V)wave_min_u32((uint32_t)v);
+                else
+                    mn = (V)wave_min_u64((uint64_t)v);
+                const uint64_t eq = __builtin_amdgcn_ballot_w64(in && v == mn);
+                const int sel = 63 - __clzll((unsigned long long)eq);
+                h = e - 1 - sel;
+                m = mn;
+                if constexpr (sizeof(V) == 4)
+                    limit = (V)__builtin_amdgcn_readlane((int)pi, sel) + s;
+                else
+                    limit = (V)shfl_i64((int64_t)pi, sel) + s;
+                t = e;
+                continue;
+            }
+        }
         int l = e - 1;
         for (int i0 = h + 1; i0 <= e - 1; i0 += kWave) {
             const int i = i0 + lane;
