@@ -279,6 +279,29 @@ def test_solve_cubic_batches(batch, n, kind):
     check_cubic(d, chain_major=True)
 
 
+def test_solve_cubic_batch_of_long_chains():
+    """Chains long enough for the launch that lays out the budgets and builds the size stack's
+    links together: several 32-bit chains, one that needs 64-bit arithmetic, one with a bad size."""
+    n, batch = 1100, 5
+    say(f"solve_cubic batch={batch} n={n} mixed")
+    d = inputs.uniform_aligned_chains(7, n, batch, 256, 32768)
+    d[:, 1] = inputs.log_uniform_chains(7, n, 1)[:, 0]
+    d[700, 3] = -5
+    good = [0, 1, 2, 4]
+    want_peak, want_mask, want_s = oracle.batch_solve_static(inputs.chain_major(d[:, good]))
+    for pruned in (False, True):
+        if pruned:
+            mask, peak, budget, evaluated, status = B.ckpt_solve_cubic_pruned(to_dev(d))
+        else:
+            mask, peak, budget, status = B.ckpt_solve_cubic(to_dev(d))
+        torch.cuda.synchronize()
+        assert np_(status).tolist() == [0, 0, 0, 3, 0]
+        assert np_(peak)[3] == -1 and not np_(mask)[:, 3].any()
+        assert np.array_equal(np_(peak)[good], want_peak), f"pruned={pruned}"
+        assert np.array_equal(np_(budget)[good], want_s), f"pruned={pruned}"
+        assert np.array_equal(np_(mask)[:, good].T, want_mask), f"pruned={pruned}"
+
+
 def test_solve_cubic_data_errors():
     n, batch = 12, 4
     d = inputs.uniform_aligned_chains(3, n, batch, 1, 100, unit=1)
