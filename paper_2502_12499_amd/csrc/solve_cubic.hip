@@ -267,13 +267,23 @@ __global__ __launch_bounds__(kWave) void cubic_prologue_kernel(const int64_t *__
     uint64_t sum = 0, bits = 0;
     int64_t mx = 0;
     bool bad = false, ovf = false;
-    for (int k = k0; k < k1; ++k) {
-        const int64_t x = dp[(int64_t)k * pstride];
-        bad |= x <= 0;
-        bits |= (uint64_t)x;
-        mx = x > mx ? x : mx;
-        sum += (uint64_t)x;
-        ovf |= sum > (uint64_t)INT64_MAX;
+    // (eight loads in flight per lane; positions past the lane's part repeat its last one and are not used)
+    constexpr int kAhead = 8;
+    for (int kb = k0; kb < k1; kb += kAhead) {
+        int64_t xs[kAhead];
+#pragma unroll
+        for (int u = 0; u < kAhead; ++u) xs[u] = dp[(int64_t)min(kb + u, k1 - 1) * pstride];
+#pragma unroll
+        for (int u = 0; u < kAhead; ++u) {
+            if (kb + u < k1) {
+                const int64_t x = xs[u];
+                bad |= x <= 0;
+                bits |= (uint64_t)x;
+                mx = x > mx ? x : mx;
+                sum += (uint64_t)x;
+                ovf |= sum > (uint64_t)INT64_MAX;
+            }
+        }
     }
     // inclusive scan of the lane sums (all terms positive: any wrap shows as > INT64_MAX first)
     uint64_t incl = sum;
@@ -313,13 +323,21 @@ __global__ __launch_bounds__(kWave) void cubic_prologue_kernel(const int64_t *__
     uint64_t run = incl - sum;  // P[k0-1]
     PD<int64_t> *pd64 = (PD<int64_t> *)chain_table<int64_t>(w, c, n);
     PD<int32_t> *pd32 = (PD<int32_t> *)pd64;
-    for (int k = k0; k < k1; ++k) {
-        const uint64_t x = (uint64_t)dp[(int64_t)k * pstride];
-        if (meta.mode32)
-            pd32[k] = PD<int32_t>{(int32_t)(run >> meta.shift), (int32_t)(x >> meta.shift)};
-        else
-            pd64[k] = PD<int64_t>{(int64_t)(run >> meta.shift), (int64_t)(x >> meta.shift)};
-        run += x;
+    for (int kb = k0; kb < k1; kb += kAhead) {
+        uint64_t xs[kAhead];
+#pragma unroll
+        for (int u = 0; u < kAhead; ++u) xs[u] = (uint64_t)dp[(int64_t)min(kb + u, k1 - 1) * pstride];
+#pragma unroll
+        for (int u = 0; u < kAhead; ++u) {
+            const int k = kb + u;
+            if (k < k1) {
+                if (meta.mode32)
+                    pd32[k] = PD<int32_t>{(int32_t)(run >> meta.shift), (int32_t)(xs[u] >> meta.shift)};
+                else
+                    pd64[k] = PD<int64_t>{(int64_t)(run >> meta.shift), (int64_t)(xs[u] >> meta.shift)};
+                run += xs[u];
+            }
+        }
     }
     const int len = (int)table_len(n);
     for (int k = n1 + lane; k < len; k += kWave) {
@@ -339,11 +357,10 @@ constexpr int kLinksBlock = 1024;
 
 __host__ __device__ constexpr size_t links_lds_bytes(int n) { return ((size_t)n + 2) * 10 + 16; }
 
-// One workgroup per chain.  below(t) comes from a stack pass over 64 contiguous
-// pieces (one per lane of the first wave) and, for the positions whose answer
-// lies in an earlier piece, a search through the pieces' minima and final
-// stacks; depth(t) from below(t) by pointer jumping; then every position's
-// snapshot.  LDS: 10 bytes per position.
+// One workgroup per chain.  below(t) comes from a backward search per position (its own block
+// of 64 positions, then the blocks' minima, then the block that answers); depth(t) from below(t)
+// by pointer jumping; then every position's snapshot.  LDS: 10 bytes per position.
+template <int THREADS>
 __device__ inline void links_chain(int n, const CubicWs &w, int64_t c)
 {
     const ChainMeta meta = w.meta[c];
@@ -358,64 +375,67 @@ __device__ inline void links_chain(int n, const CubicWs &w, int64_t c)
     // end), dist the number of chain elements from t (inclusive) to jump (exclusive)
     uint32_t *link = (uint32_t *)dyn_lds;              // [n1 + 1]
     int32_t *dl = (int32_t *)(link + n1 + 1);          // [n1] the sizes
-    uint16_t *stk = (uint16_t *)(dl + n1);             // [n1 + 1] the pieces' stacks, later below(t)
-    __shared__ int32_t piece_min[kWave];                // smallest size of each piece
-    __shared__ int32_t pieces_min[kWave];               // ... of pieces 0..q
-    __shared__ int32_t piece_sp[kWave];                 // final stack height of each piece
+    uint16_t *stk = (uint16_t *)(dl + n1);             // [n1 + 1] below(t)
+    constexpr int kBlk = 64;                            // positions per block of the search below
+    constexpr int kMaxBlks = (CKPT_CUBIC_MAX_LAYERS + 1 + kBlk - 1) / kBlk;
+    __shared__ int32_t blk_min[kMaxBlks];               // smallest size of each block
+    __shared__ int32_t blks_min[kMaxBlks];              // ... of blocks 0..b
     const uint32_t kEnd = (uint32_t)n1;
 
-    for (int t = tid; t < n1; t += kLinksBlock) dl[t] = pd[t].d;
+    for (int t = tid; t < n1; t += THREADS) dl[t] = pd[t].d;
     __syncthreads();
-
-    const int piece = (n1 + kWave - 1) / kWave;
-    const int k0 = min(tid * piece, n1), k1 = min(k0 + piece, n1);
-    if (tid < kWave) {
-        // pass 1: stack pass inside the piece (top of the stack mirrored in registers)
-        int sp = 0;
-        int32_t top_d = 0, low = INT32_MAX;
-        for (int t = k0; t < k1; ++t) {
-            const int32_t x = dl[t];
-            while (sp > 0 && top_d >= x) {
-                --sp;
-                if (sp > 0) top_d = dl[stk[k0 + sp - 1]];
-            }
-            link[t] = ((sp > 0 ? (uint32_t)stk[k0 + sp - 1] : kEnd) << 16) | 1u;  // kEnd for now: not in this piece
-            stk[k0 + sp] = (uint16_t)t;
-            ++sp;
-            top_d = x;
-            low = x < low ? x : low;
-        }
-        piece_min[tid] = low;
-        piece_sp[tid] = sp;
+    const int nblk = (n1 + kBlk - 1) / kBlk;
+    for (int q = tid; q < nblk; q += THREADS) {
+        int32_t low = INT32_MAX;
+        const int t1 = min((q + 1) * kBlk, n1);
+        for (int t = q * kBlk; t < t1; ++t) low = min(low, dl[t]);
+        blk_min[q] = low;
     }
     __syncthreads();
     if (tid == 0) {
         int32_t run = INT32_MAX;
-        for (int q = 0; q < kWave; ++q) {
-            run = piece_min[q] < run ? piece_min[q] : run;
-            pieces_min[q] = run;
+        for (int q = 0; q < nblk; ++q) {
+            run = min(run, blk_min[q]);
+            blks_min[q] = run;
         }
         link[n1] = kEnd << 16;
     }
     __syncthreads();
-    if (tid < kWave) {
-        // pass 2: positions with nothing smaller before them in their own piece (their sizes
-        // do not increase, so the piece that answers only moves towards the front)
-        int q = tid - 1;
-        for (int t = k0; t < k1; ++t) {
-            if ((link[t] >> 16) != kEnd) continue;
-            const int32_t x = dl[t];
-            if (q < 0 || pieces_min[q] >= x) break;  // nothing smaller anywhere before; the same holds for the rest
-            while (piece_min[q] >= x) --q;           // stops: pieces_min[q] < x
-            const int q0 = min(q * piece, n1);
-            int h = piece_sp[q] - 1;                 // topmost stack entry below x; the bottom one is the piece's minimum
-            while (dl[stk[q0 + h]] >= x) --h;
-            link[t] = ((uint32_t)stk[q0 + h] << 16) | 1u;
+    // below(t), every position on its own: backwards through its block; if nothing smaller is
+    // there, backwards over the blocks' minima to the nearest block that holds something smaller
+    // (none if even the minimum of all earlier blocks is not), then backwards through that block.
+    // The nearest smaller size is a few positions away for most positions of most chains; the
+    // worst case is two blocks' lengths plus the number of blocks.
+    static_assert(kBlk == kWave && THREADS % kWave == 0, "a wave holds one block");
+    const int lane = tid & (kWave - 1);
+    for (int t0 = tid - lane; t0 < n1; t0 += THREADS) {  // the same trip count for the whole wave
+        const int t = t0 + lane;
+        const int32_t x = t < n1 ? dl[t] : INT32_MAX;
+        // inside the block the sizes are the wave's own registers: the nearest lower lane with a
+        // smaller size (ascending j, so the last hit stays)
+        int near = -1;
+        for (int j = 0; j < kWave - 1; ++j) {
+            const int32_t v = __builtin_amdgcn_readlane(x, j);
+            near = (j < lane && v < x) ? j : near;
         }
+        if (t >= n1) continue;
+        uint32_t found = kEnd;
+        if (near >= 0) {
+            found = (uint32_t)(t0 + near);
+        } else {
+            int q = t0 / kBlk - 1;
+            if (q >= 0 && blks_min[q] < x) {
+                while (blk_min[q] >= x) --q;  // stops: some block up to q holds a smaller size
+                int h = (q + 1) * kBlk - 1;   // (q is not the last block: it is a full one)
+                while (dl[h] >= x) --h;       // stops inside block q
+                found = (uint32_t)h;
+            }
+        }
+        link[t] = (found << 16) | 1u;
     }
     __syncthreads();
-    // below(t) is final; it replaces the stacks
-    for (int t = tid; t <= n1; t += kLinksBlock) stk[t] = (uint16_t)(link[t] >> 16);  // link[n1] points at itself
+    // below(t) on its own, as 16-bit positions
+    for (int t = tid; t <= n1; t += THREADS) stk[t] = (uint16_t)(link[t] >> 16);  // link[n1] points at itself
     uint16_t *below = stk;
     __syncthreads();
 
@@ -423,7 +443,7 @@ __device__ inline void links_chain(int n, const CubicWs &w, int64_t c)
     // (a word is read and written whole, so any mix of old and new words is consistent)
     for (;;) {
         int moved = 0;
-        for (int t = tid; t < n1; t += kLinksBlock) {
+        for (int t = tid; t < n1; t += THREADS) {
             const uint32_t a = link[t];
             if ((a >> 16) == kEnd) continue;
             const uint32_t b = link[a >> 16];
@@ -433,7 +453,7 @@ __device__ inline void links_chain(int n, const CubicWs &w, int64_t c)
         if (!__syncthreads_or(moved)) break;
     }
 
-    for (int t = tid; t < (int)table_len(n); t += kLinksBlock) {
+    for (int t = tid; t < (int)table_len(n); t += THREADS) {
         El e;
         Snap sn;
         if (t < n1) {
@@ -458,7 +478,7 @@ __device__ inline void links_chain(int n, const CubicWs &w, int64_t c)
         snap[t] = sn;
     }
     Step *__restrict__ st = w.step + (size_t)c * step_len(n);
-    for (int t = tid; t < (int)step_len(n); t += kLinksBlock)
+    for (int t = tid; t < (int)step_len(n); t += THREADS)
         st[t] = t < n1 ? Step{dl[t], (int32_t)(link[t] & 0xffffu) - 1} : Step{0, 0};
     // the groups' summaries; a group that reaches past n is never used as one
     Group *__restrict__ gr = w.group + (size_t)c * group_len(n);
@@ -475,7 +495,7 @@ __device__ inline void links_chain(int n, const CubicWs &w, int64_t c)
         }
         return G;
     };
-    for (int slot = tid; slot < (int)group_len(n); slot += kLinksBlock) {  // group_len is even
+    for (int slot = tid; slot < (int)group_len(n); slot += THREADS) {  // group_len is even
         Group G = summary(slot);
         const Group other = summary(slot ^ 1);
         G.pair = (slot & 1) == 0 ? min(G.dmin, other.dmin) : min(G.umin, other.umin);
@@ -483,7 +503,12 @@ __device__ inline void links_chain(int n, const CubicWs &w, int64_t c)
     }
 }
 
-__global__ __launch_bounds__(kLinksBlock) void cubic_links_kernel(int n, CubicWs w) { links_chain(n, w, blockIdx.x); }
+// (short chains: a smaller workgroup, most of a large one would sit idle at the barriers)
+constexpr int kLinksShortBlock = 256;
+__global__ __launch_bounds__(kLinksShortBlock) void cubic_links_kernel(int n, CubicWs w)
+{
+    links_chain<kLinksShortBlock>(n, w, blockIdx.x);
+}
 
 // ---- budget index -> (range length, start) ------------------------------------
 
@@ -870,7 +895,7 @@ static_assert(kLinksBlock == 1024, "the two parts share a launch of 1024 threads
 __global__ __launch_bounds__(kLinksBlock) void cubic_prepare_kernel(int n, int64_t batch, CubicWs w)
 {
     if ((int64_t)blockIdx.x < batch)
-        links_chain(n, w, blockIdx.x);
+        links_chain<kLinksBlock>(n, w, blockIdx.x);
     else
         slice_group<kLinksBlock, 4>(n, w, (int64_t)blockIdx.x - batch);
 }
@@ -2100,8 +2125,8 @@ hipError_t launch_solve_cubic(const int64_t *d, int64_t batch, int n, Strides st
         hipLaunchKernelGGL(cubic_prepare_kernel, dim3((unsigned)blocks), dim3(kLinksBlock), links_lds_bytes(n), stream,
                            n, batch, w);
     } else {
-        hipLaunchKernelGGL(cubic_links_kernel, dim3((unsigned)batch), dim3(kLinksBlock), links_lds_bytes(n), stream, n,
-                           w);
+        hipLaunchKernelGGL(cubic_links_kernel, dim3((unsigned)batch), dim3(kLinksShortBlock), links_lds_bytes(n), stream,
+                           n, w);
         hipLaunchKernelGGL((cubic_slice_kernel<256, 8>), dim3((unsigned)(slice_groups(n) * batch)), dim3(256),
                            ((size_t)n + 1) * 4, stream, n, w);
     }
