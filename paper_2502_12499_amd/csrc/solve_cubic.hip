@@ -794,7 +794,7 @@ __device__ inline void slice_group(int n, const CubicWs &w, int64_t block)
     const int64_t lo = (g * kSliceGroup) << wshift, hi = ((g + 1) * kSliceGroup) << wshift;  // lo <= s < hi
     if (lo > smax) return;                   // (the same for the whole workgroup)
     for (int j = tid; j <= n; j += THREADS) Q[j] = pd[j].P;
-    if (tid < kSliceGroup) tally[tid] = 0;
+    for (int k = tid; k < kSliceGroup; k += THREADS) tally[k] = 0;
     if (tid == 0) below = lo > 0 ? 1 : 0;    // the empty range, s = 0
     __syncthreads();
     int32_t *out = w.sorted + c * num_budgets(n);
@@ -878,6 +878,7 @@ __device__ inline void slice_group(int n, const CubicWs &w, int64_t block)
 }
 
 constexpr int kSliceLongFrom = 1024;  // chains from this length on take the 1024-thread form
+constexpr int kSliceShortUpTo = 128;  // chains up to this length have no more starts than two per lane of one wave
 
 static_assert(links_lds_bytes(kSliceLongFrom) >= ((size_t)kSliceLongFrom + 1) * 4, "the links' LDS covers the prefix sums");
 
@@ -2127,8 +2128,12 @@ hipError_t launch_solve_cubic(const int64_t *d, int64_t batch, int n, Strides st
     } else {
         hipLaunchKernelGGL(cubic_links_kernel, dim3((unsigned)batch), dim3(kLinksShortBlock), links_lds_bytes(n), stream,
                            n, w);
-        hipLaunchKernelGGL((cubic_slice_kernel<256, 8>), dim3((unsigned)(slice_groups(n) * batch)), dim3(256),
-                           ((size_t)n + 1) * 4, stream, n, w);
+        if (n <= kSliceShortUpTo)
+            hipLaunchKernelGGL((cubic_slice_kernel<64, 2>), dim3((unsigned)(slice_groups(n) * batch)), dim3(64),
+                               ((size_t)n + 1) * 4, stream, n, w);
+        else
+            hipLaunchKernelGGL((cubic_slice_kernel<256, 8>), dim3((unsigned)(slice_groups(n) * batch)), dim3(256),
+                               ((size_t)n + 1) * 4, stream, n, w);
     }
     if (pruned)
         hipLaunchKernelGGL(cubic_bound_kernel, dim3((unsigned)batch), dim3(kBoundThreads), 0, stream, n,
