@@ -1592,7 +1592,13 @@ __global__ __launch_bounds__(kBoundThreads) void cubic_bound_kernel(int n, int64
             __syncthreads();
         }
     }
+    // The search below reads the running sums W a few hundred times, one read after the other:
+    // from LDS (the sorted sizes are no longer needed), not from the workspace.
+    __syncthreads();
+    for (int t = tid; t <= m_int; t += kBoundThreads) srt[t] = W[t];
+    __syncthreads();
     if (tid != 0) return;
+    const int32_t *Wl = srt;
     // UB: this stage's, or the earlier stage's if that was better
     int64_t room = part[0] == kInf ? (int64_t)INT32_MAX : part[0] - el[0].d - el[n].d;  // UB - d_0 - d_n
     if (stage == 1 && (int64_t)w.prune[c] < room) room = w.prune[c];
@@ -1600,14 +1606,14 @@ __global__ __launch_bounds__(kBoundThreads) void cubic_bound_kernel(int n, int64
     w.prune[c] = (int32_t)room;
     // the smallest s with LB(s) <= room (LB(room) <= room holds: m = 0 gives at most sum - s ... or the
     // search ends at room + 1, which prunes nothing that the upper bound leaves)
-    const int64_t sum_int = W[m_int];
+    const int64_t sum_int = Wl[m_int];
     auto lower = [&](int64_t sv) -> int64_t {
         int lo = 0, hi = m_int;  // smallest m with W(m) >= sum - (m+1) s
         while (lo < hi) {
             const int mid = (lo + hi) >> 1;
-            if ((int64_t)W[mid] >= sum_int - (int64_t)(mid + 1) * sv) hi = mid; else lo = mid + 1;
+            if ((int64_t)Wl[mid] >= sum_int - (int64_t)(mid + 1) * sv) hi = mid; else lo = mid + 1;
         }
-        const int64_t a = W[lo];
+        const int64_t a = Wl[lo];
         const int64_t b = sum_int - (int64_t)lo * sv;  // the max at m - 1 (for m = 0: no smaller m, a = 0 wins)
         return lo == 0 ? a : (a < b ? a : b);
     };
