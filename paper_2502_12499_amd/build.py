@@ -7,7 +7,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libckpt_hip.so")
 SOURCES = ["ckpt_api.hip", "eval_peak.hip", "eval_timeline.hip", "solve_linear.hip", "solve_quadratic.hip", "probe.hip",
-           "ragged.hip", "solve_cubic.hip"]
+           "ragged.hip", "ragged_host.hip", "solve_cubic.hip"]
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall",
     # keep the compiler from forming packed fp32 instructions

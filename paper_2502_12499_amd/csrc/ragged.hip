@@ -5,87 +5,13 @@
 // brings the group's chains into the position-major layout, the group runs through the same
 // kernels as an equal-length batch, and a second transposition puts the results where the flat
 // layout wants them.  Everything is enqueued on the caller's stream.
-#include <algorithm>
-#include <vector>
-
-#include "ckpt_internal.h"
+#include "ragged_plan.h"
 
 namespace ckpt {
 namespace {
 
 constexpr int kTile = 64;         // chains and positions per transposition tile
 constexpr int kTileThreads = 256; // four waves
-
-struct Group {
-    int n;
-    int64_t first;  // index into perm of the group's first chain
-    int64_t count;
-};
-
-struct Plan {
-    std::vector<Group> groups;
-    std::vector<int32_t> perm;  // chain indices, grouped by length, ascending index inside a group
-};
-
-int64_t pitch_of(int64_t count) { return (count + 31) / 32 * 32; }  // rows of the staging start on 256 bytes
-
-// Validates the offsets and groups the chains by length.
-int make_plan(const int64_t *off, int64_t batch, int max_layers, Plan &p)
-{
-    if (batch < 0 || batch > INT32_MAX) return CKPT_ERR_SHAPE;
-    if (batch == 0) return CKPT_OK;
-    if (!off) return CKPT_ERR_NULL;
-    if (off[0] < 0) return CKPT_ERR_SHAPE;
-    int longest = 0;
-    for (int64_t c = 0; c < batch; ++c) {
-        const int64_t len = off[c + 1] - off[c];
-        if (off[c + 1] < off[c] || len < 2 || len - 1 > max_layers) return CKPT_ERR_SHAPE;
-        if ((int)(len - 1) > longest) longest = (int)(len - 1);
-    }
-    if (off[batch] > INT64_MAX / 32) return CKPT_ERR_SHAPE;
-    std::vector<int64_t> start((size_t)longest + 2, 0);
-    for (int64_t c = 0; c < batch; ++c) ++start[(size_t)(off[c + 1] - off[c] - 1) + 1];
-    for (int n = 1; n <= longest; ++n) {
-        if (start[(size_t)n + 1] > 0) p.groups.push_back(Group{n, start[(size_t)n], start[(size_t)n + 1]});
-        start[(size_t)n + 1] += start[(size_t)n];
-    }
-    p.perm.resize((size_t)batch);
-    for (int64_t c = 0; c < batch; ++c) p.perm[(size_t)start[(size_t)(off[c + 1] - off[c] - 1)]++] = (int32_t)c;
-    return CKPT_OK;
-}
-
-struct Workspace {
-    size_t off = 0, perm = 0, d = 0, mask = 0, wide = 0, peak = 0, budget = 0, status = 0, inner = 0, total = 0;
-};
-
-// Staging is sized for the group that needs most of each part.
-Workspace layout_ws(int which, const Plan &p, int64_t batch)
-{
-    size_t d = 0, mask = 0, wide = 0, vec = 0, inner = 0;
-    for (const Group &g : p.groups) {
-        const size_t pitch = (size_t)pitch_of(g.count), rows = (size_t)g.n + 1;
-        d = std::max(d, rows * pitch * 8);
-        mask = std::max(mask, rows * pitch);
-        vec = std::max(vec, pitch * 8);
-        if (which == CKPT_CALL_EVAL_TIMELINE) wide = std::max(wide, 2 * rows * pitch * 8);
-        if (which == CKPT_CALL_SOLVE_LINEAR) inner = std::max(inner, linear_workspace_bytes(g.count, g.n));
-        if (which == CKPT_CALL_SOLVE_CUBIC) inner = std::max(inner, cubic_workspace_bytes(g.count, g.n));
-    }
-    Workspace w;
-    size_t at = 0;
-    auto take = [&at](size_t bytes) { const size_t here = at; at += align_up(bytes); return here; };
-    w.off = take((size_t)(batch + 1) * 8);
-    w.perm = take((size_t)batch * 4);
-    w.d = take(d);
-    w.mask = take(mask);
-    w.wide = take(wide);
-    w.peak = take(vec);
-    w.budget = take(vec);
-    w.status = take(vec);
-    w.inner = take(inner);
-    w.total = at;
-    return w;
-}
 
 // Flat -> position-major for one group.  Element k of chain c is src[mult*off[c] + k], k < rows;
 // it goes to stage[k*pitch + j], j the chain's place in the group.  Reads run along a chain,
@@ -160,23 +86,23 @@ struct Device {
 };
 
 template <typename T>
-void gather(const T *src, const Device &dv, const Group &g, int rows, int mult, T *stage, hipStream_t s)
+void gather(const T *src, const Device &dv, const RaggedGroup &g, int rows, int mult, T *stage, hipStream_t s)
 {
     const dim3 grid((unsigned)((g.count + kTile - 1) / kTile), (unsigned)((rows + kTile - 1) / kTile));
     hipLaunchKernelGGL(ragged_gather_kernel<T>, grid, dim3(kTileThreads), 0, s, src, dv.off, dv.perm, g.first, g.count,
-                       rows, mult, pitch_of(g.count), stage);
+                       rows, mult, ragged_pitch(g.count), stage);
 }
 
 template <typename T>
-void scatter(const T *stage, const Device &dv, const Group &g, int rows, int mult, T *dst, hipStream_t s)
+void scatter(const T *stage, const Device &dv, const RaggedGroup &g, int rows, int mult, T *dst, hipStream_t s)
 {
     const dim3 grid((unsigned)((g.count + kTile - 1) / kTile), (unsigned)((rows + kTile - 1) / kTile));
     hipLaunchKernelGGL(ragged_scatter_kernel<T>, grid, dim3(kTileThreads), 0, s, stage, dv.off, dv.perm, g.first,
-                       g.count, rows, mult, pitch_of(g.count), dst);
+                       g.count, rows, mult, ragged_pitch(g.count), dst);
 }
 
 template <typename T>
-void scatter_value(const T *stage, const Device &dv, const Group &g, T *dst, hipStream_t s)
+void scatter_value(const T *stage, const Device &dv, const RaggedGroup &g, T *dst, hipStream_t s)
 {
     if (!dst) return;
     hipLaunchKernelGGL(ragged_scatter_value_kernel<T>, dim3((unsigned)((g.count + kTileThreads - 1) / kTileThreads)),
@@ -185,28 +111,11 @@ void scatter_value(const T *stage, const Device &dv, const Group &g, T *dst, hip
 
 }  // namespace
 
-size_t ragged_workspace_bytes(int which, const int64_t *offsets_host, int64_t batch)
+int ragged_run(int which, const int64_t *d, const uint8_t *mask_in, const int64_t *offsets_host, int64_t batch,
+               int objective, uint8_t *mask_out, int64_t *peak_out, int64_t *budget_out, int64_t *timeline_out,
+               int32_t *status_out, const RaggedPlan &p, const RaggedWorkspace &w, void *ws, hipStream_t stream)
 {
-    Plan p;
-    const int max_layers = which == CKPT_CALL_SOLVE_CUBIC ? CKPT_CUBIC_MAX_LAYERS : CKPT_MAX_LAYERS;
-    if (make_plan(offsets_host, batch, max_layers, p) != CKPT_OK || batch == 0) return 0;
-    return layout_ws(which, p, batch).total;
-}
-
-int launch_ragged(int which, const int64_t *d, const uint8_t *mask_in, const int64_t *offsets_host, int64_t batch,
-                  int objective, uint8_t *mask_out, int64_t *peak_out, int64_t *budget_out, int64_t *timeline_out,
-                  int32_t *status_out, void *ws, size_t ws_bytes, hipStream_t stream)
-{
-    Plan p;
-    const int max_layers = which == CKPT_CALL_SOLVE_CUBIC ? CKPT_CUBIC_MAX_LAYERS : CKPT_MAX_LAYERS;
-    const int rc = make_plan(offsets_host, batch, max_layers, p);
-    if (rc != CKPT_OK) return rc;
-    if (batch == 0) return CKPT_OK;
     const bool eval = which == CKPT_CALL_EVAL_PEAK || which == CKPT_CALL_EVAL_TIMELINE;
-    if (!d || !ws || (eval && !mask_in) || (!eval && !mask_out)) return CKPT_ERR_NULL;
-    if (which == CKPT_CALL_EVAL_TIMELINE ? !timeline_out : !peak_out) return CKPT_ERR_NULL;
-    const Workspace w = layout_ws(which, p, batch);
-    if (((uintptr_t)ws & 255u) != 0 || ws_bytes < w.total) return CKPT_ERR_WORKSPACE;
     char *base = (char *)ws;
     Device dv{(const int64_t *)(base + w.off), (const int32_t *)(base + w.perm), (int64_t *)(base + w.d),
               (int64_t *)(base + w.wide),      (int64_t *)(base + w.peak),       (int64_t *)(base + w.budget),
@@ -217,9 +126,9 @@ int launch_ragged(int which, const int64_t *d, const uint8_t *mask_in, const int
         hipMemcpyAsync(base + w.perm, p.perm.data(), (size_t)batch * 4, hipMemcpyHostToDevice, stream) != hipSuccess ||
         hipStreamSynchronize(stream) != hipSuccess)
         return CKPT_ERR_DEVICE;
-    for (const Group &g : p.groups) {
+    for (const RaggedGroup &g : p.groups) {
         const int rows = g.n + 1;
-        const Strides st{1, pitch_of(g.count)};
+        const Strides st{1, ragged_pitch(g.count)};
         hipError_t e = hipSuccess;
         gather(d, dv, g, rows, 1, dv.d, stream);
         if (eval) gather(mask_in, dv, g, rows, 1, dv.mask, stream);

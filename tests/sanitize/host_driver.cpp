@@ -8,14 +8,13 @@
 #include <cstdint>
 #include <cstdio>
 #include <cstdlib>
+#include <initializer_list>
 
 #include "../../include/ckpt.h"
 
+#include "../../paper_2502_12499_amd/csrc/ckpt_internal.h"
+
 namespace ckpt {
-struct Strides {
-    int64_t chain;
-    int64_t pos;
-};
 static int launches = 0;
 hipError_t launch_eval_peak(const int64_t *, const uint8_t *, int64_t, int, Strides, int, int64_t *, int32_t *,
                             hipStream_t) { ++launches; return hipSuccess; }
@@ -33,6 +32,30 @@ size_t cubic_workspace_bytes(int64_t batch, int n) { return 4096 + (size_t)batch
 hipError_t launch_solve_cubic(const int64_t *, int64_t, int, Strides, uint8_t *, int64_t *, int64_t *, int32_t *, bool,
                               int64_t *, int64_t *, int64_t *, void *, hipStream_t) { ++launches; return hipSuccess; }
 int64_t cubic_trace_len(int n) { return ((int64_t)n * (n - 1) / 2 + 1 + 63) / 64 * 64; }
+}  // namespace ckpt
+
+// the device side of the ragged calls (csrc/ragged.hip); the plan and the layout it is handed are
+// checked here for what the kernels rely on
+#include "../../paper_2502_12499_amd/csrc/ragged_plan.h"
+namespace ckpt {
+static int ragged_runs = 0;
+int ragged_run(int, const int64_t *, const uint8_t *, const int64_t *off, int64_t batch, int, uint8_t *, int64_t *,
+               int64_t *, int64_t *, int32_t *, const RaggedPlan &plan, const RaggedWorkspace &w, void *, hipStream_t)
+{
+    ++ragged_runs;
+    int64_t seen = 0;
+    for (const RaggedGroup &g : plan.groups) {
+        if (g.first != seen || g.count <= 0) return CKPT_ERR_DEVICE;
+        for (int64_t j = 0; j < g.count; ++j) {
+            const int32_t c = plan.perm[(size_t)(g.first + j)];
+            if (c < 0 || c >= batch || off[c + 1] - off[c] - 1 != g.n) return CKPT_ERR_DEVICE;
+            if (j > 0 && plan.perm[(size_t)(g.first + j - 1)] >= c) return CKPT_ERR_DEVICE;
+        }
+        seen += g.count;
+    }
+    if (seen != batch || w.total % 256 != 0 || w.inner > w.total) return CKPT_ERR_DEVICE;
+    return CKPT_OK;
+}
 }  // namespace ckpt
 
 #define CHECK(c) do { if (!(c)) { std::fprintf(stderr, "host_driver: %s failed at line %d\n", #c, __LINE__); std::exit(1); } } while (0)
@@ -83,6 +106,52 @@ int main()
     CHECK(ckpt_cubic_costs_len(8) == 64 && ckpt_cubic_costs_len(12) == 128 && ckpt_cubic_costs_len(0) == 0);
     CHECK(ckpt::launches == 9);
     CHECK(ckpt_cubic_cells(8191) == ((int64_t)8191 * 8190 / 2 + 1) * 8191 && ckpt_cubic_cells(0) == 0);
+    // ragged batches: the grouping by length and the workspace layout are host code (csrc/ragged.hip);
+    // only calls that end before any device work are made here
+    {
+        const int64_t off[] = {0, 16, 41, 43, 59, 1061};  // n = 15, 24, 1, 15, 1001
+        const int calls[] = {CKPT_CALL_EVAL_PEAK, CKPT_CALL_SOLVE_CUBIC, CKPT_CALL_SOLVE_LINEAR, CKPT_CALL_EVAL_TIMELINE};
+        for (const int which : calls) {
+            const size_t need = ckpt_ragged_workspace_bytes(which, off, 5);
+            CHECK(need > 0 && need % 256 == 0);
+            CHECK(ckpt_ragged_workspace_bytes(which, off, 0) == 0);
+            CHECK(ckpt_ragged_workspace_bytes(which, nullptr, 5) == 0);
+        }
+        CHECK(ckpt_ragged_workspace_bytes(9, off, 5) == 0);
+        const int64_t dec[] = {0, 16, 10}, tiny[] = {0, 1, 17}, neg[] = {-4, 16, 32}, huge[] = {0, big / 16, big / 8};
+        const int64_t longc[] = {0, 8193};
+        for (const int64_t *bad_off : {dec, tiny, neg, huge}) {
+            CHECK(ckpt_ragged_workspace_bytes(CKPT_CALL_SOLVE_LINEAR, bad_off, 2) == 0);
+            CHECK(ckpt_ragged_solve_linear(d, bad_off, 2, mask, out, nullptr, ws, 1 << 15, nullptr) == CKPT_ERR_SHAPE);
+            CHECK(ckpt_ragged_eval_peak(d, mask, bad_off, 2, 0, out, nullptr, ws, 1 << 15, nullptr) == CKPT_ERR_SHAPE);
+        }
+        CHECK(ckpt_ragged_workspace_bytes(CKPT_CALL_SOLVE_CUBIC, longc, 1) == 0);
+        CHECK(ckpt_ragged_workspace_bytes(CKPT_CALL_SOLVE_LINEAR, longc, 1) > 0);
+        CHECK(ckpt_ragged_solve_cubic(d, longc, 1, mask, out, nullptr, nullptr, ws, 1 << 15, nullptr) == CKPT_ERR_SHAPE);
+        CHECK(ckpt_ragged_solve_linear(d, off, -1, mask, out, nullptr, ws, 1 << 15, nullptr) == CKPT_ERR_SHAPE);
+        CHECK(ckpt_ragged_solve_linear(d, off, 5, nullptr, out, nullptr, ws, 1 << 15, nullptr) == CKPT_ERR_NULL);
+        CHECK(ckpt_ragged_solve_linear(d, off, 5, mask, out, nullptr, ws, 64, nullptr) == CKPT_ERR_WORKSPACE);
+        CHECK(ckpt_ragged_eval_timeline(d, mask, off, 5, 3, out, nullptr, ws, 1 << 15, nullptr) == CKPT_ERR_SHAPE);
+        CHECK(ckpt_ragged_eval_timeline(d, mask, off, 5, 1, nullptr, nullptr, ws, 1 << 15, nullptr) == CKPT_ERR_NULL);
+        CHECK(ckpt_ragged_solve_cubic(nullptr, off, 0, nullptr, nullptr, nullptr, nullptr, nullptr, 0, nullptr) == CKPT_OK);
+        CHECK(ckpt::ragged_runs == 0);
+        // calls in order reach the device side once each, with a plan that covers every chain once
+        CHECK(ckpt_ragged_solve_linear(d, off, 5, mask, out, nullptr, ws, 1 << 15, nullptr) == CKPT_ERR_WORKSPACE);
+        static unsigned char big_ws[1 << 22] __attribute__((aligned(256)));
+        CHECK(ckpt_ragged_solve_linear(d, off, 5, mask, out, nullptr, big_ws, sizeof(big_ws), nullptr) == CKPT_OK);
+        CHECK(ckpt_ragged_eval_peak(d, mask, off, 5, 1, out, nullptr, big_ws, sizeof(big_ws), nullptr) == CKPT_OK);
+        CHECK(ckpt_ragged_eval_timeline(d, mask, off, 5, 0, out, nullptr, big_ws, sizeof(big_ws), nullptr) == CKPT_OK);
+        CHECK(ckpt::ragged_runs == 3);
+        // a large batch of mixed lengths: the plan's counting sort and the sizes it adds up
+        const int64_t many = 200000;
+        int64_t *offs = (int64_t *)std::malloc((size_t)(many + 1) * sizeof(int64_t));
+        CHECK(offs != nullptr);
+        offs[0] = 0;
+        for (int64_t c = 0; c < many; ++c) offs[c + 1] = offs[c] + 2 + (c * 7919) % 300;
+        CHECK(ckpt_ragged_workspace_bytes(CKPT_CALL_EVAL_TIMELINE, offs, many) > (size_t)many * 12);
+        std::free(offs);
+        CHECK(ckpt::launches == 9);
+    }
     for (int s = -1; s < 10; ++s) CHECK(ckpt_status_string(s) != nullptr);
     std::printf("host_driver ok\n");
     return 0;

@@ -39,6 +39,7 @@ def test_host_side_of_the_abi_under_asan_and_ubsan(tmp_path):
         flags += ["-Xarch_host", f] if f.startswith("-fsanitize") or f.startswith("-fno-sanitize") else [f]
     run([hipcc, "--cuda-host-only", "-x", "hip", "-O1", "-std=c++17", *flags, "-o", exe,
          os.path.join(ROOT, "tests", "sanitize", "host_driver.cpp"),
-         os.path.join(ROOT, "paper_2502_12499_amd", "csrc", "ckpt_api.hip")])
+         os.path.join(ROOT, "paper_2502_12499_amd", "csrc", "ckpt_api.hip"),
+         os.path.join(ROOT, "paper_2502_12499_amd", "csrc", "ragged_host.hip")])
     out = run([exe], env=ENV)
     assert "host_driver ok" in out
