@@ -115,6 +115,14 @@ constexpr int64_t kRingMaxChainStride = (int64_t)1 << 22;
 //        255 positions (checked per chunk), and a byte is what gets stored of it.
 constexpr int kPlaneM = 0, kPlaneA = 1, kPlaneGJ = 2, kPlanes = 3;
 
+// LOG_REGS (chains of at most kLogMaxLayers layers): the chosen step of every position is kept as a
+// byte in 64 vector registers per lane (two per chunk of eight positions, written and read with a
+// wave-uniform register index) instead of being parked in the caller's mask array: nothing but
+// the sizes is read and nothing but the mask written.
+constexpr int kLogMaxLayers = 256;
+typedef uint32_t u32x32 __attribute__((ext_vector_type(32)));
+
+template <bool LOG_REGS>
 __global__ __launch_bounds__(kWave) void linear_ring_kernel(const int64_t *__restrict__ d, int64_t batch, int n,
                                                             int64_t cstride, int64_t pstride,
                                                             uint8_t *__restrict__ mask_out,
@@ -235,8 +243,10 @@ __global__ __launch_bounds__(kWave) void linear_ring_kernel(const int64_t *__res
         defer |= (Jfull - (uint32_t)ilow) > 248u;
     };
 
-    // One step of the recurrence for position i, whose size x is already in a register.
-    auto step_fn = [&](const int i, const int64_t x) {
+    u32x32 logA = {}, logB = {};   // LOG_REGS: the steps of chunk k as bytes of logA[k] (u = 0..3) and logB[k] (u = 4..7)
+    uint32_t acc0 = 0, acc1 = 0;   // ... of the chunk under way
+    // One step of the recurrence for position i = ihi - u, whose size x is already in a register.
+    auto step_fn = [&](const int i, const int64_t x, const int u) {
         const uint32_t di = __builtin_amdgcn_alignbit((uint32_t)((uint64_t)x >> 32), (uint32_t)x, (uint32_t)sh);
         const uint32_t di8 = di << 8;  // as a GJ word
         Ti += dnext;
@@ -325,7 +335,14 @@ __global__ __launch_bounds__(kWave) void linear_ring_kernel(const int64_t *__res
         // Parked with a store the compiler does not count, so that its waits on the
         // rows fetched ahead stay partial (a counted store would make it wait for
         // everything in flight; an uncounted one can only lengthen a wait).
-        if (live) {
+        if constexpr (LOG_REGS) {
+            // the step's low byte into byte u % 4 of the chunk's word (u is a literal once unrolled)
+            const uint32_t sel = 0x03020100u ^ ((0x04u ^ (uint32_t)(u & 3)) << (8 * (u & 3)));
+            if (u < 4)
+                acc0 = __builtin_amdgcn_perm(step, acc0, sel);
+            else
+                acc1 = __builtin_amdgcn_perm(step, acc1, sel);
+        } else if (live) {
             const uint64_t rowbase = scalar((uint64_t)(uintptr_t)(mbase + (int64_t)i * pstride));
             // The compiler may form the scalar base with v_readfirstlane right before this
             // statement; a vector memory instruction must not read such a register within five
@@ -407,7 +424,8 @@ __global__ __launch_bounds__(kWave) void linear_ring_kernel(const int64_t *__res
     int64_t rows[kChunk], ahead[kChunk];
 #pragma unroll
     for (int u = 0; u < kChunk; ++u) rows[u] = row(max(n - 1 - u, 0));
-    for (int ihi = n - 1; ihi >= 0; ihi -= kChunk) {
+    int chunk = 0;
+    for (int ihi = n - 1; ihi >= 0; ihi -= kChunk, ++chunk) {
 #pragma unroll
         for (int u = 0; u < kChunk; ++u)  // rows below 0 re-read row 0 and are not used
             ahead[u] = row(max(ihi - kChunk - u, 0));
@@ -423,7 +441,14 @@ __global__ __launch_bounds__(kWave) void linear_ring_kernel(const int64_t *__res
         if (!defer) {
 #pragma unroll
             for (int u = 0; u < kChunk; ++u)
-                if (ihi - u >= 0) step_fn(ihi - u, rows[u]);
+                if (ihi - u >= 0) step_fn(ihi - u, rows[u], u);
+            if constexpr (LOG_REGS) {
+                const int k = __builtin_amdgcn_readfirstlane(chunk);
+                logA[k] = acc0;
+                logB[k] = acc1;
+                acc0 = 0;
+                acc1 = 0;
+            }
         }
 #pragma unroll
         for (int u = 0; u < kChunk; ++u) rows[u] = ahead[u];
@@ -437,6 +462,25 @@ __global__ __launch_bounds__(kWave) void linear_ring_kernel(const int64_t *__res
     }
     peak_out[c] = (int64_t)((uint64_t)Mi << sh);
     if (status_out) status_out[c] = CKPT_OK;
+    if constexpr (LOG_REGS) {
+        // forward sweep over the steps in the registers: position i = n-1 - (8k + u), ascending
+        int cur = 0;
+        for (int k = chunk - 1; k >= 0; --k) {
+            const int ks = __builtin_amdgcn_readfirstlane(k);
+            const uint32_t w0 = logA[ks], w1 = logB[ks];
+#pragma unroll
+            for (int u = kChunk - 1; u >= 0; --u) {
+                const int i = n - 1 - (kChunk * ks + u);
+                if (i < 0) continue;
+                const uint32_t step = ((u < 4 ? w0 : w1) >> (8 * (u & 3))) & 255u;
+                const bool on = i == cur;
+                if (on) cur = i + 1 + (int)step;
+                mp[(int64_t)i * pstride] = on ? 1 : 0;
+            }
+        }
+        mp[(int64_t)n * pstride] = 1;
+        return;
+    }
     // forward sweep: replace the parked steps by the mask (once they have all landed)
     asm volatile("s_waitcnt vmcnt(0)" : : : "memory");
     int cur = 0;
@@ -731,8 +775,12 @@ hipError_t launch_solve_linear(const int64_t *d, int64_t batch, int n, Strides s
     const unsigned grid = (unsigned)((batch + kWave - 1) / kWave);
     hipLaunchKernelGGL(linear_reset_kernel, dim3(1), dim3(1), 0, stream, w);
     if (st.chain <= kRingMaxChainStride)
-        hipLaunchKernelGGL(linear_ring_kernel, dim3(grid), dim3(kWave), 0, stream, d, batch, n, st.chain, st.pos,
-                           mask_out, peak_out, status_out, w);
+        if (n <= kLogMaxLayers)
+            hipLaunchKernelGGL(linear_ring_kernel<true>, dim3(grid), dim3(kWave), 0, stream, d, batch, n, st.chain,
+                               st.pos, mask_out, peak_out, status_out, w);
+        else
+            hipLaunchKernelGGL(linear_ring_kernel<false>, dim3(grid), dim3(kWave), 0, stream, d, batch, n, st.chain,
+                               st.pos, mask_out, peak_out, status_out, w);
     else
         hipLaunchKernelGGL(linear_defer_all_kernel, dim3((unsigned)((batch + 255) / 256)), dim3(256), 0, stream,
                            batch, w);
