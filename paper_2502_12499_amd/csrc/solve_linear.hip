@@ -298,7 +298,9 @@ __global__ __launch_bounds__(kWave) void linear_ring_kernel(const int64_t *__res
                 "v_cmp_le_u32 vcc, 4*%[step], %[t0]\n\t"
                 "s_and_b64 exec, exec, vcc\n\t"
                 "v_max_u32 %[Rc], %[Rc], %[G3]\n\t"
-                // more than four entries above it: the rest from the ring
+                // more than four entries above it (rare: one test for the whole wave): the rest from the ring
+                "v_cmp_le_u32 vcc, 5*%[step], %[t0]\n\t"
+                "s_cbranch_vccz Lg_done_%=\n\t"
                 "v_subrev_u32 %[e], 3*%[step], %[hd]\n\t"
                 "Lg_%=:\n\t"
                 "v_subrev_u32 %[e], %[step], %[e]\n\t"
@@ -463,21 +465,27 @@ __global__ __launch_bounds__(kWave) void linear_ring_kernel(const int64_t *__res
     peak_out[c] = (int64_t)((uint64_t)Mi << sh);
     if (status_out) status_out[c] = CKPT_OK;
     if constexpr (LOG_REGS) {
-        // forward sweep over the steps in the registers: position i = n-1 - (8k + u), ascending
+        // forward sweep over the steps in the registers: position i = n-1 - (8k + u), ascending.
+        // Rows are addressed by a scalar base that moves up one row per position, plus the lane's
+        // offset; only the first chunk taken (the last one filled) can reach below position 0.
         int cur = 0;
-        for (int k = chunk - 1; k >= 0; --k) {
-            const int ks = __builtin_amdgcn_readfirstlane(k);
+        auto sweep_chunk = [&](const int ks, const bool guarded) {
             const uint32_t w0 = logA[ks], w1 = logB[ks];
+            const int ilow = n - 1 - (kChunk * ks + kChunk - 1);  // the chunk's lowest position (below 0 if guarded)
+            uint8_t *rowp = mbase + (int64_t)ilow * pstride;      // wave-uniform; one row up per position
 #pragma unroll
-            for (int u = kChunk - 1; u >= 0; --u) {
-                const int i = n - 1 - (kChunk * ks + u);
-                if (i < 0) continue;
+            for (int u = kChunk - 1; u >= 0; --u, rowp += pstride) {
+                const int i = ilow + (kChunk - 1 - u);
+                if (guarded && i < 0) continue;
                 const uint32_t step = ((u < 4 ? w0 : w1) >> (8 * (u & 3))) & 255u;
                 const bool on = i == cur;
-                if (on) cur = i + 1 + (int)step;
-                mp[(int64_t)i * pstride] = on ? 1 : 0;
+                cur = on ? i + 1 + (int)step : cur;
+                rowp[moff] = on ? 1 : 0;
             }
-        }
+        };
+        int k = chunk - 1;
+        if (k >= 0) sweep_chunk(__builtin_amdgcn_readfirstlane(k), true);
+        for (--k; k >= 0; --k) sweep_chunk(__builtin_amdgcn_readfirstlane(k), false);
         mp[(int64_t)n * pstride] = 1;
         return;
     }
