@@ -125,8 +125,9 @@ def test_config5_batch_properties_of_every_chain():
 def test_cubic_largest_chain_n8191():
     """The longest chain the cubic solver takes.  The oracle needs minutes for it, so: a chain of
     equal sizes against the closed form (gaps of at most k layers need ceil(n/(k+1))-1 interior
-    checkpoints, cost (k + ceil(n/(k+1)) + 1) d), and a random chain through properties: the set
-    returned costs what is reported, the reported budget attains it, no sampled budget does better."""
+    checkpoints, cost (k + ceil(n/(k+1)) + 1) d), and a random chain through properties (the set
+    returned costs what is reported, the reported budget attains it, no sampled budget does better)
+    and through the per-budget costs: the complete list of budgets and a random sample of costs."""
     n = 8191  # CKPT_CUBIC_MAX_LAYERS
     say(f"cubic, n = {n}: equal sizes")
     unit = 3 << 20
@@ -157,3 +158,17 @@ def test_cubic_largest_chain_n8191():
     for first in [0, K - 4096] + [int(x) for x in rng.integers(0, K - 4096, 6)]:
         cost, _ = oracle.solve_static_range(d[:, 0], first, 4096)
         assert cost >= v
+    # the cost of every budget as the kernels computed it: the list of budgets is the oracle's as a
+    # multiset, and 1,500 of the costs, drawn at random, are the literal recurrence's (Equation (T))
+    say("  per-budget costs: the whole list of budgets, 1500 sampled costs")
+    mask2, peak2, budget2, budgets, costs, status = B.ckpt_solve_cubic_costs(torch.from_numpy(d).to(DEV))
+    torch.cuda.synchronize()
+    assert int(peak2.cpu()[0]) == v and int(budget2.cpu()[0]) == s and bool((mask2 == mask).all())
+    gb, gc = budgets.cpu().numpy()[0], costs.cpu().numpy()[0]
+    used = gb >= 0
+    assert int(used.sum()) == K and (gc[~used] == -1).all()
+    assert np.array_equal(np.sort(gb[used]), np.sort(oracle.budgets(d[:, 0])))
+    assert int(gc[used].min()) == v
+    pick = rng.choice(np.nonzero(used)[0], size=1500, replace=False)
+    want = gb[pick] + oracle.static_cs_list(d[:, 0], gb[pick])
+    assert np.array_equal(gc[pick], want)
