@@ -447,23 +447,31 @@ def time_extras(torch, B, inputs, W, reps=3):
     t, _ = timed_ms(torch, lambda: B.ckpt_solve_quadratic(d4, want_values=False, want_status=False), reps)
     out["solve_quadratic_n1001"] = {"ms": t, "instances_per_s": 1.0 / (t * 1e-3),
                                     "candidates_per_s": n4 * (n4 + 1) / 2 / (t * 1e-3)}
-    # ragged: the depths of the paper's networks mixed in one call
-    lengths = np.tile(np.array([15, 24, 152, 257], dtype=np.int64), 16384)
-    lengths[::4096] = 1001
-    rd, rm, off = inputs.ragged_batch(3, lengths)
-    rdd, rmd = torch.from_numpy(rd).to(W.d.device), torch.from_numpy(rm).to(W.d.device)
-    rbytes = 9 * len(rd) + 8 * len(lengths)
-    for name, which, fn in (
-            ("ragged_solve_linear", B.CALL_SOLVE_LINEAR, lambda ws: B.ckpt_ragged_solve_linear(rdd, off, workspace=ws)),
-            ("ragged_eval_peak_dynamic", B.CALL_EVAL_PEAK,
-             lambda ws: B.ckpt_ragged_eval_peak(rdd, rmd, off, B.OBJ_DYNAMIC, workspace=ws))):
-        ws = torch.empty(B.load().ckpt_ragged_workspace_bytes(which, off.ctypes.data, len(lengths)), dtype=torch.uint8,
-                         device=W.d.device)
-        t, _ = timed_ms(torch, lambda: fn(ws), reps)
-        out[name] = {"ms": t, "chains": len(lengths), "lengths": "15, 24, 152, 257 in turn, sixteen of 1001",
-                     "instances_per_s": len(lengths) / (t * 1e-3), "hbm_GBs": rbytes / (t * 1e-3) / 1e9,
-                     "hbm_frac": rbytes / (t * 1e-3) / 1e9 / HBM_PEAK_GBS,
-                     "note": "includes the host's grouping by length and one wait on the stream"}
+    # ragged: the depths of the paper's networks mixed in one call; a small batch (a call is then
+    # bound by its launches and by the latency of its small groups) and a large one
+    for tag, copies, long_every in (("ragged", 16384, 4096), ("ragged_large", 131072, 0)):
+        lengths = np.tile(np.array([15, 24, 152, 257], dtype=np.int64), copies)
+        if long_every:
+            lengths[::long_every] = 1001
+        rd, rm, off = inputs.ragged_batch(3, lengths)
+        rdd, rmd = torch.from_numpy(rd).to(W.d.device), torch.from_numpy(rm).to(W.d.device)
+        offd = torch.from_numpy(off).to(W.d.device)  # the caller keeps the offsets on the device as well
+        rbytes = 9 * len(rd) + 8 * len(lengths)
+        for name, which, fn in (
+                (tag + "_solve_linear", B.CALL_SOLVE_LINEAR,
+                 lambda ws: B.ckpt_ragged_solve_linear(rdd, off, workspace=ws, offsets_dev=offd)),
+                (tag + "_eval_peak_dynamic", B.CALL_EVAL_PEAK,
+                 lambda ws: B.ckpt_ragged_eval_peak(rdd, rmd, off, B.OBJ_DYNAMIC, workspace=ws, offsets_dev=offd))):
+            ws = torch.empty(B.load().ckpt_ragged_workspace_bytes(which, off.ctypes.data, len(lengths)),
+                             dtype=torch.uint8, device=W.d.device)
+            t, _ = timed_ms(torch, lambda: fn(ws), reps)
+            out[name] = {"ms": t, "chains": len(lengths),
+                         "lengths": "15, 24, 152, 257 in turn" + (", sixteen of 1001" if long_every else ""),
+                         "instances_per_s": len(lengths) / (t * 1e-3), "hbm_GBs": rbytes / (t * 1e-3) / 1e9,
+                         "hbm_frac": rbytes / (t * 1e-3) / 1e9 / HBM_PEAK_GBS,
+                         "note": "includes the host's count of the lengths and one wait on the stream"}
+            del ws
+        del rdd, rmd
     small = min(Bn, 4096)
     ds = W.d[:, :small].contiguous()
     t, _ = timed_ms(torch, lambda: B.ckpt_solve_quadratic(ds, want_values=False, want_status=False), reps)

@@ -258,26 +258,35 @@ int ckpt_solve_quadratic(const int64_t *d, const ckpt_layout *layout, uint8_t *m
  *   offsets_host [in] batch + 1 non-decreasing element offsets in HOST memory
  *       (the caller built the batch and knows them; the library plans its
  *       launches from them).  It is read during the call only.
+ *   offsets_dev [in] the same offsets in DEVICE memory, or NULL: the call then
+ *       copies offsets_host into the workspace itself (from pageable host
+ *       memory that is the slowest part of a call on a large batch).
  *   ws: ckpt_ragged_workspace_bytes(which, offsets_host, batch) bytes, 256-byte
- *       aligned; it receives a device copy of the offsets, the chain indices
- *       grouped by length, and room to run the largest group in the
- *       position-major layout.
+ *       aligned; it receives the table of lengths, the chains' places grouped
+ *       by length (handed out on the device: the order inside a group differs
+ *       from call to call, the results do not), a copy of the offsets, and
+ *       room to run the largest group in the position-major layout.
  * Unlike the other calls these wait once on the stream, for the copy of the
- * offsets and the grouping into ws, before they enqueue the kernels: they
- * cannot be captured into a HIP graph.  A bad offset (decreasing, n_c < 1 or
- * beyond the limit) returns CKPT_ERR_SHAPE and launches nothing; batch = 0
- * does nothing.  ckpt_ragged_workspace_bytes returns 0 for such input. */
+ * table of lengths (and of the offsets) into ws, before they enqueue the
+ * kernels: work already on the stream finishes first, and they cannot be
+ * captured into a HIP graph.  A bad offset (decreasing, n_c < 1 or beyond the
+ * limit) returns CKPT_ERR_SHAPE and launches nothing; batch = 0 does nothing.
+ * ckpt_ragged_workspace_bytes returns 0 for such input. */
 size_t ckpt_ragged_workspace_bytes(int which, const int64_t *offsets_host, int64_t batch);
 int ckpt_ragged_eval_peak(const int64_t *d, const uint8_t *mask, const int64_t *offsets_host,
-                          int64_t batch, int objective, int64_t *peak_out, int32_t *status_out,
+                          const int64_t *offsets_dev, int64_t batch, int objective,
+                          int64_t *peak_out, int32_t *status_out,
                           void *ws, size_t ws_bytes, void *hip_stream);
 int ckpt_ragged_eval_timeline(const int64_t *d, const uint8_t *mask, const int64_t *offsets_host,
-                              int64_t batch, int objective, int64_t *timeline_out,
-                              int32_t *status_out, void *ws, size_t ws_bytes, void *hip_stream);
-int ckpt_ragged_solve_linear(const int64_t *d, const int64_t *offsets_host, int64_t batch,
+                              const int64_t *offsets_dev, int64_t batch, int objective,
+                              int64_t *timeline_out, int32_t *status_out,
+                              void *ws, size_t ws_bytes, void *hip_stream);
+int ckpt_ragged_solve_linear(const int64_t *d, const int64_t *offsets_host,
+                             const int64_t *offsets_dev, int64_t batch,
                              uint8_t *mask_out, int64_t *peak_out, int32_t *status_out,
                              void *ws, size_t ws_bytes, void *hip_stream);
-int ckpt_ragged_solve_cubic(const int64_t *d, const int64_t *offsets_host, int64_t batch,
+int ckpt_ragged_solve_cubic(const int64_t *d, const int64_t *offsets_host,
+                            const int64_t *offsets_dev, int64_t batch,
                             uint8_t *mask_out, int64_t *peak_out, int64_t *budget_out,
                             int32_t *status_out, void *ws, size_t ws_bytes, void *hip_stream);
 

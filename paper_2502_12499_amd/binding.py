@@ -82,13 +82,13 @@ def load():
         lib.ckpt_ragged_workspace_bytes.restype = ctypes.c_size_t
         lib.ckpt_ragged_workspace_bytes.argtypes = [ctypes.c_int, vp, i64]
         lib.ckpt_ragged_eval_peak.restype = ctypes.c_int
-        lib.ckpt_ragged_eval_peak.argtypes = [vp, vp, vp, i64, ctypes.c_int, vp, vp, vp, ctypes.c_size_t, vp]
+        lib.ckpt_ragged_eval_peak.argtypes = [vp, vp, vp, vp, i64, ctypes.c_int, vp, vp, vp, ctypes.c_size_t, vp]
         lib.ckpt_ragged_eval_timeline.restype = ctypes.c_int
-        lib.ckpt_ragged_eval_timeline.argtypes = [vp, vp, vp, i64, ctypes.c_int, vp, vp, vp, ctypes.c_size_t, vp]
+        lib.ckpt_ragged_eval_timeline.argtypes = [vp, vp, vp, vp, i64, ctypes.c_int, vp, vp, vp, ctypes.c_size_t, vp]
         lib.ckpt_ragged_solve_linear.restype = ctypes.c_int
-        lib.ckpt_ragged_solve_linear.argtypes = [vp, vp, i64, vp, vp, vp, vp, ctypes.c_size_t, vp]
+        lib.ckpt_ragged_solve_linear.argtypes = [vp, vp, vp, i64, vp, vp, vp, vp, ctypes.c_size_t, vp]
         lib.ckpt_ragged_solve_cubic.restype = ctypes.c_int
-        lib.ckpt_ragged_solve_cubic.argtypes = [vp, vp, i64, vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
+        lib.ckpt_ragged_solve_cubic.argtypes = [vp, vp, vp, i64, vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
         lib.ckpt_probe_hbm_read.restype = ctypes.c_int
         lib.ckpt_probe_hbm_read.argtypes = [vp, ctypes.c_size_t, vp, vp]
         lib.ckpt_probe_hbm_copy.restype = ctypes.c_int
@@ -302,8 +302,9 @@ def ckpt_solve_quadratic(d, chain_major=False, want_values=True, want_status=Tru
 
 # ---- ragged batches: chains of different n in one flat array ------------------------------------
 
-def _ragged_args(d, offsets, mask=None):
-    """(offsets as a contiguous host int64 array, its pointer, batch) after the type checks."""
+def _ragged_args(d, offsets, mask=None, offsets_dev=None):
+    """(offsets as a contiguous host int64 array, its pointer, batch) after the type checks.
+    offsets_dev, if given, is the caller's copy of the offsets on the GPU."""
     import numpy as np
     if d.dtype != torch.int64 or not d.is_cuda or d.dim() != 1 or not d.is_contiguous():
         raise TypeError("d must be a flat contiguous int64 tensor on the GPU")
@@ -315,6 +316,9 @@ def _ragged_args(d, offsets, mask=None):
         raise ValueError("offsets must hold batch + 1 values")
     if int(off[-1]) > d.numel():
         raise ValueError("offsets reach past the end of d")
+    if offsets_dev is not None and (offsets_dev.dtype != torch.int64 or not offsets_dev.is_cuda
+                                    or offsets_dev.numel() != off.size or not offsets_dev.is_contiguous()):
+        raise TypeError("offsets_dev must be the offsets as a contiguous int64 tensor on the GPU")
     return off, ctypes.c_void_p(off.ctypes.data), off.size - 1
 
 
@@ -325,55 +329,55 @@ def _ragged_workspace(which, off_ptr, batch, device, workspace):
     return workspace, workspace.numel()
 
 
-def ckpt_ragged_eval_peak(d, mask, offsets, objective, workspace=None):
+def ckpt_ragged_eval_peak(d, mask, offsets, objective, workspace=None, offsets_dev=None):
     """Peak memory of each chain's set; chain c is d[offsets[c]:offsets[c+1]].  Returns (peak, status)."""
-    off, off_ptr, batch = _ragged_args(d, offsets, mask)
+    off, off_ptr, batch = _ragged_args(d, offsets, mask, offsets_dev)
     peak = torch.empty(batch, dtype=torch.int64, device=d.device)
     status = torch.empty(batch, dtype=torch.int32, device=d.device)
     ws, ws_bytes = _ragged_workspace(CALL_EVAL_PEAK, off_ptr, batch, d.device, workspace)
-    rc = load().ckpt_ragged_eval_peak(_ptr(d), _ptr(mask), off_ptr, batch, int(objective), _ptr(peak), _ptr(status),
+    rc = load().ckpt_ragged_eval_peak(_ptr(d), _ptr(mask), off_ptr, _ptr(offsets_dev), batch, int(objective), _ptr(peak), _ptr(status),
                                       _ptr(ws), ws_bytes, _stream())
     if rc != CKPT_OK:
         raise CkptError("ckpt_ragged_eval_peak", rc)
     return peak, status
 
 
-def ckpt_ragged_eval_timeline(d, mask, offsets, objective, workspace=None):
+def ckpt_ragged_eval_timeline(d, mask, offsets, objective, workspace=None, offsets_dev=None):
     """Memory per phase of each chain, flat: chain c from element 2*offsets[c].  Returns (timeline, status)."""
-    off, off_ptr, batch = _ragged_args(d, offsets, mask)
+    off, off_ptr, batch = _ragged_args(d, offsets, mask, offsets_dev)
     out = torch.empty(2 * d.numel(), dtype=torch.int64, device=d.device)
     status = torch.empty(batch, dtype=torch.int32, device=d.device)
     ws, ws_bytes = _ragged_workspace(CALL_EVAL_TIMELINE, off_ptr, batch, d.device, workspace)
-    rc = load().ckpt_ragged_eval_timeline(_ptr(d), _ptr(mask), off_ptr, batch, int(objective), _ptr(out),
+    rc = load().ckpt_ragged_eval_timeline(_ptr(d), _ptr(mask), off_ptr, _ptr(offsets_dev), batch, int(objective), _ptr(out),
                                           _ptr(status), _ptr(ws), ws_bytes, _stream())
     if rc != CKPT_OK:
         raise CkptError("ckpt_ragged_eval_timeline", rc)
     return out, status
 
 
-def ckpt_ragged_solve_linear(d, offsets, workspace=None):
+def ckpt_ragged_solve_linear(d, offsets, workspace=None, offsets_dev=None):
     """Optimal sets under the dynamic objective.  Returns (flat mask, peak, status)."""
-    off, off_ptr, batch = _ragged_args(d, offsets)
+    off, off_ptr, batch = _ragged_args(d, offsets, None, offsets_dev)
     mask = torch.empty(d.numel(), dtype=torch.uint8, device=d.device)
     peak = torch.empty(batch, dtype=torch.int64, device=d.device)
     status = torch.empty(batch, dtype=torch.int32, device=d.device)
     ws, ws_bytes = _ragged_workspace(CALL_SOLVE_LINEAR, off_ptr, batch, d.device, workspace)
-    rc = load().ckpt_ragged_solve_linear(_ptr(d), off_ptr, batch, _ptr(mask), _ptr(peak), _ptr(status),
+    rc = load().ckpt_ragged_solve_linear(_ptr(d), off_ptr, _ptr(offsets_dev), batch, _ptr(mask), _ptr(peak), _ptr(status),
                                          _ptr(ws), ws_bytes, _stream())
     if rc != CKPT_OK:
         raise CkptError("ckpt_ragged_solve_linear", rc)
     return mask, peak, status
 
 
-def ckpt_ragged_solve_cubic(d, offsets, workspace=None):
+def ckpt_ragged_solve_cubic(d, offsets, workspace=None, offsets_dev=None):
     """Optimal sets under the static objective.  Returns (flat mask, peak, budget, status)."""
-    off, off_ptr, batch = _ragged_args(d, offsets)
+    off, off_ptr, batch = _ragged_args(d, offsets, None, offsets_dev)
     mask = torch.empty(d.numel(), dtype=torch.uint8, device=d.device)
     peak = torch.empty(batch, dtype=torch.int64, device=d.device)
     budget = torch.empty(batch, dtype=torch.int64, device=d.device)
     status = torch.empty(batch, dtype=torch.int32, device=d.device)
     ws, ws_bytes = _ragged_workspace(CALL_SOLVE_CUBIC, off_ptr, batch, d.device, workspace)
-    rc = load().ckpt_ragged_solve_cubic(_ptr(d), off_ptr, batch, _ptr(mask), _ptr(peak), _ptr(budget), _ptr(status),
+    rc = load().ckpt_ragged_solve_cubic(_ptr(d), off_ptr, _ptr(offsets_dev), batch, _ptr(mask), _ptr(peak), _ptr(budget), _ptr(status),
                                         _ptr(ws), ws_bytes, _stream())
     if rc != CKPT_OK:
         raise CkptError("ckpt_ragged_solve_cubic", rc)

@@ -174,36 +174,38 @@ size_t ckpt_ragged_workspace_bytes(int which, const int64_t *offsets_host, int64
     return ckpt::ragged_workspace_bytes(which, offsets_host, batch);
 }
 
-int ckpt_ragged_eval_peak(const int64_t *d, const uint8_t *mask, const int64_t *offsets_host, int64_t batch,
-                          int objective, int64_t *peak_out, int32_t *status_out, void *ws, size_t ws_bytes,
+int ckpt_ragged_eval_peak(const int64_t *d, const uint8_t *mask, const int64_t *offsets_host,
+                          const int64_t *offsets_dev, int64_t batch, int objective, int64_t *peak_out, int32_t *status_out, void *ws, size_t ws_bytes,
                           void *hip_stream)
 {
     if (objective != CKPT_OBJ_STATIC && objective != CKPT_OBJ_DYNAMIC) return CKPT_ERR_SHAPE;
-    return ckpt::launch_ragged(CKPT_CALL_EVAL_PEAK, d, mask, offsets_host, batch, objective, nullptr, peak_out,
+    return ckpt::launch_ragged(CKPT_CALL_EVAL_PEAK, d, mask, offsets_host, offsets_dev, batch, objective, nullptr, peak_out,
                                nullptr, nullptr, status_out, ws, ws_bytes, (hipStream_t)hip_stream);
 }
 
-int ckpt_ragged_eval_timeline(const int64_t *d, const uint8_t *mask, const int64_t *offsets_host, int64_t batch,
-                              int objective, int64_t *timeline_out, int32_t *status_out, void *ws, size_t ws_bytes,
+int ckpt_ragged_eval_timeline(const int64_t *d, const uint8_t *mask, const int64_t *offsets_host,
+                              const int64_t *offsets_dev, int64_t batch, int objective, int64_t *timeline_out, int32_t *status_out, void *ws, size_t ws_bytes,
                               void *hip_stream)
 {
     if (objective != CKPT_OBJ_STATIC && objective != CKPT_OBJ_DYNAMIC) return CKPT_ERR_SHAPE;
-    return ckpt::launch_ragged(CKPT_CALL_EVAL_TIMELINE, d, mask, offsets_host, batch, objective, nullptr, nullptr,
+    return ckpt::launch_ragged(CKPT_CALL_EVAL_TIMELINE, d, mask, offsets_host, offsets_dev, batch, objective, nullptr, nullptr,
                                nullptr, timeline_out, status_out, ws, ws_bytes, (hipStream_t)hip_stream);
 }
 
-int ckpt_ragged_solve_linear(const int64_t *d, const int64_t *offsets_host, int64_t batch, uint8_t *mask_out,
+int ckpt_ragged_solve_linear(const int64_t *d, const int64_t *offsets_host, const int64_t *offsets_dev,
+                             int64_t batch, uint8_t *mask_out,
                              int64_t *peak_out, int32_t *status_out, void *ws, size_t ws_bytes, void *hip_stream)
 {
-    return ckpt::launch_ragged(CKPT_CALL_SOLVE_LINEAR, d, nullptr, offsets_host, batch, 0, mask_out, peak_out,
+    return ckpt::launch_ragged(CKPT_CALL_SOLVE_LINEAR, d, nullptr, offsets_host, offsets_dev, batch, 0, mask_out, peak_out,
                                nullptr, nullptr, status_out, ws, ws_bytes, (hipStream_t)hip_stream);
 }
 
-int ckpt_ragged_solve_cubic(const int64_t *d, const int64_t *offsets_host, int64_t batch, uint8_t *mask_out,
+int ckpt_ragged_solve_cubic(const int64_t *d, const int64_t *offsets_host, const int64_t *offsets_dev,
+                            int64_t batch, uint8_t *mask_out,
                             int64_t *peak_out, int64_t *budget_out, int32_t *status_out, void *ws, size_t ws_bytes,
                             void *hip_stream)
 {
-    return ckpt::launch_ragged(CKPT_CALL_SOLVE_CUBIC, d, nullptr, offsets_host, batch, 0, mask_out, peak_out,
+    return ckpt::launch_ragged(CKPT_CALL_SOLVE_CUBIC, d, nullptr, offsets_host, offsets_dev, batch, 0, mask_out, peak_out,
                                budget_out, nullptr, status_out, ws, ws_bytes, (hipStream_t)hip_stream);
 }
 

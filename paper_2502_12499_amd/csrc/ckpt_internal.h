@@ -125,9 +125,10 @@ int64_t cubic_trace_len(int n);
 // ---- ragged batches ----------------------------------------------------------
 // which: a ckpt_call; offsets_host: batch + 1 element offsets in host memory
 size_t ragged_workspace_bytes(int which, const int64_t *offsets_host, int64_t batch);
-// Returns a ckpt_status.  Copies the offsets and the grouping to the workspace and waits for
-// those two copies; everything else is enqueued on the stream.
-int launch_ragged(int which, const int64_t *d, const uint8_t *mask_in, const int64_t *offsets_host, int64_t batch,
+// Returns a ckpt_status.  Copies the group table (and the offsets, if offsets_dev is null) to the
+// workspace and waits for the copies; everything else is enqueued on the stream.
+int launch_ragged(int which, const int64_t *d, const uint8_t *mask_in, const int64_t *offsets_host,
+                  const int64_t *offsets_dev, int64_t batch,
                   int objective, uint8_t *mask_out, int64_t *peak_out, int64_t *budget_out, int64_t *timeline_out,
                   int32_t *status_out, void *ws, size_t ws_bytes, hipStream_t stream);
 

@@ -1,5 +1,5 @@
-// Ragged batches, host side (see ragged_plan.h): checks, the counting sort of the chain indices by
-// length (launch planning: none of the method's arithmetic) and the workspace layout.
+// Ragged batches, host side (see ragged_plan.h): checks, the count of the chains of every length
+// (launch planning: none of the method's arithmetic) and the workspace layout.
 #include <algorithm>
 
 #include "ragged_plan.h"
@@ -12,22 +12,21 @@ int ragged_make_plan(const int64_t *off, int64_t batch, int max_layers, RaggedPl
     if (batch == 0) return CKPT_OK;
     if (!off) return CKPT_ERR_NULL;
     if (off[0] < 0) return CKPT_ERR_SHAPE;
-    int longest = 0;
+    // one pass: every length checked and counted
+    std::vector<int64_t> count((size_t)max_layers + 2, 0);
     for (int64_t c = 0; c < batch; ++c) {
         if (off[c + 1] < off[c]) return CKPT_ERR_SHAPE;
         const int64_t len = off[c + 1] - off[c];  // (both are non-negative here: no wrap)
         if (len < 2 || len - 1 > max_layers) return CKPT_ERR_SHAPE;
-        if ((int)(len - 1) > longest) longest = (int)(len - 1);
+        ++count[(size_t)(len - 1)];
     }
     if (off[batch] > INT64_MAX / 32) return CKPT_ERR_SHAPE;
-    std::vector<int64_t> start((size_t)longest + 2, 0);
-    for (int64_t c = 0; c < batch; ++c) ++start[(size_t)(off[c + 1] - off[c] - 1) + 1];
-    for (int n = 1; n <= longest; ++n) {
-        if (start[(size_t)n + 1] > 0) p.groups.push_back(RaggedGroup{n, start[(size_t)n], start[(size_t)n + 1]});
-        start[(size_t)n + 1] += start[(size_t)n];
-    }
-    p.perm.resize((size_t)batch);
-    for (int64_t c = 0; c < batch; ++c) p.perm[(size_t)start[(size_t)(off[c + 1] - off[c] - 1)]++] = (int32_t)c;
+    int64_t first = 0;
+    for (int n = 1; n <= max_layers; ++n)
+        if (count[(size_t)n] > 0) {
+            p.groups.push_back(RaggedGroup{n, first, count[(size_t)n]});
+            first += count[(size_t)n];
+        }
     return CKPT_OK;
 }
 
@@ -48,6 +47,8 @@ RaggedWorkspace ragged_layout(int which, const RaggedPlan &p, int64_t batch)
     auto take = [&at](size_t bytes) { const size_t here = at; at += align_up(bytes); return here; };
     w.off = take((size_t)(batch + 1) * 8);
     w.perm = take((size_t)batch * 4);
+    w.groups = take(p.groups.size() * sizeof(RaggedGroupDev));
+    w.cursor = take(p.groups.size() * 4);
     w.d = take(d);
     w.mask = take(mask);
     w.wide = take(wide);
@@ -67,7 +68,8 @@ size_t ragged_workspace_bytes(int which, const int64_t *offsets_host, int64_t ba
     return ragged_layout(which, p, batch).total;
 }
 
-int launch_ragged(int which, const int64_t *d, const uint8_t *mask_in, const int64_t *offsets_host, int64_t batch,
+int launch_ragged(int which, const int64_t *d, const uint8_t *mask_in, const int64_t *offsets_host,
+                  const int64_t *offsets_dev, int64_t batch,
                   int objective, uint8_t *mask_out, int64_t *peak_out, int64_t *budget_out, int64_t *timeline_out,
                   int32_t *status_out, void *ws, size_t ws_bytes, hipStream_t stream)
 {
@@ -81,7 +83,7 @@ int launch_ragged(int which, const int64_t *d, const uint8_t *mask_in, const int
     if (which == CKPT_CALL_EVAL_TIMELINE ? !timeline_out : !peak_out) return CKPT_ERR_NULL;
     const RaggedWorkspace w = ragged_layout(which, p, batch);
     if (((uintptr_t)ws & 255u) != 0 || ws_bytes < w.total) return CKPT_ERR_WORKSPACE;
-    return ragged_run(which, d, mask_in, offsets_host, batch, objective, mask_out, peak_out, budget_out, timeline_out,
+    return ragged_run(which, d, mask_in, offsets_host, offsets_dev, batch, objective, mask_out, peak_out, budget_out, timeline_out,
                       status_out, p, w, ws, stream);
 }
 

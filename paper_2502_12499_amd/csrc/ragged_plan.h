@@ -18,13 +18,19 @@ struct RaggedGroup {
 };
 
 struct RaggedPlan {
-    std::vector<RaggedGroup> groups;
-    std::vector<int32_t> perm;  // chain indices, grouped by length, ascending index inside a group
+    std::vector<RaggedGroup> groups;  // ascending length; group g's chains take places first .. first + count - 1
+};
+
+// What the device is told about a group (the places themselves are handed out on the device).
+struct RaggedGroupDev {
+    int32_t n;
+    int32_t first;
 };
 
 // Byte offsets of the parts of a ragged call's workspace.
 struct RaggedWorkspace {
-    size_t off = 0, perm = 0, d = 0, mask = 0, wide = 0, peak = 0, budget = 0, status = 0, inner = 0, total = 0;
+    size_t off = 0, perm = 0, groups = 0, cursor = 0, d = 0, mask = 0, wide = 0, peak = 0, budget = 0, status = 0,
+           inner = 0, total = 0;
 };
 
 // rows of the staging start on 256 bytes
@@ -35,9 +41,12 @@ int ragged_make_plan(const int64_t *offsets_host, int64_t batch, int max_layers,
 // Staging is sized for the group that needs most of each part.
 RaggedWorkspace ragged_layout(int which, const RaggedPlan &plan, int64_t batch);
 
-// The device side (ragged.hip): copies the plan into the workspace, waits for the copies, and
-// enqueues gather, the equal-length kernels and scatter for every group.  Returns a ckpt_status.
-int ragged_run(int which, const int64_t *d, const uint8_t *mask_in, const int64_t *offsets_host, int64_t batch,
+// The device side (ragged.hip): copies the group table (and the offsets, unless the caller has
+// them on the device already) into the workspace, waits for the copies, hands out the chains'
+// places, and enqueues gather, the equal-length kernels and scatter for every group.  Returns a
+// ckpt_status.
+int ragged_run(int which, const int64_t *d, const uint8_t *mask_in, const int64_t *offsets_host,
+               const int64_t *offsets_dev, int64_t batch,
                int objective, uint8_t *mask_out, int64_t *peak_out, int64_t *budget_out, int64_t *timeline_out,
                int32_t *status_out, const RaggedPlan &plan, const RaggedWorkspace &w, void *ws, hipStream_t stream);
 

@@ -33,20 +33,23 @@ def _mix(z):
     return z ^ (z >> np.uint64(31))
 
 
-def random_u64(seed, stream, n_pos, batch, chain0=0):
+def random_u64(seed, stream, n_pos, batch, chain0=0, chains=None):
     """uint64 array (n_pos, batch): element (k, c) depends only on
-    (seed, stream, chain0 + c, k)."""
+    (seed, stream, chain0 + c, k); with `chains` (an array of `batch` chain
+    numbers) on (seed, stream, chains[c], k) instead."""
     with np.errstate(over="ignore"):
         key = _mix(np.array([(int(seed) << 8) ^ int(stream)], dtype=np.uint64))
-        chain = (np.arange(batch, dtype=np.uint64) + np.uint64(chain0)) << np.uint64(20)
+        ids = np.arange(batch, dtype=np.uint64) + np.uint64(chain0) if chains is None \
+            else np.asarray(chains, dtype=np.uint64)
+        chain = ids << np.uint64(20)
         pos = np.arange(n_pos, dtype=np.uint64)
         ctr = chain[None, :] | pos[:, None]
         return _mix(_mix(ctr ^ key))
 
 
-def uniform_aligned_chains(seed, n_layers, batch, lo_units, hi_units, unit=4096, chain0=0):
+def uniform_aligned_chains(seed, n_layers, batch, lo_units, hi_units, unit=4096, chain0=0, chains=None):
     """Sizes unit * U{lo_units..hi_units}, shape (n_layers+1, batch)."""
-    r = random_u64(seed, 0, n_layers + 1, batch, chain0)
+    r = random_u64(seed, 0, n_layers + 1, batch, chain0, chains)
     span = np.uint64(hi_units - lo_units + 1)
     return ((r % span).astype(np.int64) + np.int64(lo_units)) * np.int64(unit)
 
@@ -59,10 +62,10 @@ def log_uniform_chains(seed, n_layers, batch, lo_log2=16.0, hi_log2=28.0, chain0
     return np.maximum(d, 1)
 
 
-def bernoulli_masks(seed, n_layers, batch, p=0.25, chain0=0):
+def bernoulli_masks(seed, n_layers, batch, p=0.25, chain0=0, chains=None):
     """Checkpoint masks: interior positions set with probability p, both ends
     forced to 1.  Shape (n_layers+1, batch), uint8."""
-    r = random_u64(seed, 1, n_layers + 1, batch, chain0)
+    r = random_u64(seed, 1, n_layers + 1, batch, chain0, chains)
     thresh = np.uint64(min(int(p * 2.0 ** 64), 2 ** 64 - 1))
     m = (r < thresh).astype(np.uint8)
     m[0, :] = 1
@@ -87,9 +90,10 @@ def ragged_batch(seed, lengths, lo_units=256, hi_units=32768, unit=4096, p=0.25,
     d = np.empty(int(offsets[-1]), dtype=np.int64)
     m = np.empty(int(offsets[-1]), dtype=np.uint8)
     for n in np.unique(lengths):
-        for c in np.nonzero(lengths == n)[0]:
-            d[offsets[c]:offsets[c + 1]] = uniform_aligned_chains(seed, int(n), 1, lo_units, hi_units, unit, chain0=int(c))[:, 0]
-            m[offsets[c]:offsets[c + 1]] = bernoulli_masks(seed, int(n), 1, p, chain0=int(c))[:, 0]
+        idx = np.nonzero(lengths == n)[0]          # all chains of this length at once
+        at = offsets[idx][None, :] + np.arange(int(n) + 1, dtype=np.int64)[:, None]
+        d[at] = uniform_aligned_chains(seed, int(n), len(idx), lo_units, hi_units, unit, chains=idx)
+        m[at] = bernoulli_masks(seed, int(n), len(idx), p, chains=idx)
     for c, col in named:
         col = np.asarray(col, dtype=np.int64).reshape(-1)
         assert col.size == lengths[c] + 1

@@ -39,21 +39,24 @@ int64_t cubic_trace_len(int n) { return ((int64_t)n * (n - 1) / 2 + 1 + 63) / 64
 #include "../../paper_2502_12499_amd/csrc/ragged_plan.h"
 namespace ckpt {
 static int ragged_runs = 0;
-int ragged_run(int, const int64_t *, const uint8_t *, const int64_t *off, int64_t batch, int, uint8_t *, int64_t *,
-               int64_t *, int64_t *, int32_t *, const RaggedPlan &plan, const RaggedWorkspace &w, void *, hipStream_t)
+int ragged_run(int, const int64_t *, const uint8_t *, const int64_t *off, const int64_t *, int64_t batch, int,
+               uint8_t *, int64_t *, int64_t *, int64_t *, int32_t *, const RaggedPlan &plan, const RaggedWorkspace &w,
+               void *, hipStream_t)
 {
     ++ragged_runs;
+    // the groups ascend in length, follow each other without gaps and hold every chain of their length
     int64_t seen = 0;
+    int last_n = 0;
     for (const RaggedGroup &g : plan.groups) {
-        if (g.first != seen || g.count <= 0) return CKPT_ERR_DEVICE;
-        for (int64_t j = 0; j < g.count; ++j) {
-            const int32_t c = plan.perm[(size_t)(g.first + j)];
-            if (c < 0 || c >= batch || off[c + 1] - off[c] - 1 != g.n) return CKPT_ERR_DEVICE;
-            if (j > 0 && plan.perm[(size_t)(g.first + j - 1)] >= c) return CKPT_ERR_DEVICE;
-        }
+        if (g.first != seen || g.count <= 0 || g.n <= last_n) return CKPT_ERR_DEVICE;
+        int64_t have = 0;
+        for (int64_t c = 0; c < batch; ++c) have += off[c + 1] - off[c] - 1 == g.n;
+        if (have != g.count) return CKPT_ERR_DEVICE;
         seen += g.count;
+        last_n = g.n;
     }
-    if (seen != batch || w.total % 256 != 0 || w.inner > w.total) return CKPT_ERR_DEVICE;
+    if (seen != batch || w.total % 256 != 0 || w.inner > w.total || w.groups < w.perm + (size_t)batch * 4)
+        return CKPT_ERR_DEVICE;
     return CKPT_OK;
 }
 }  // namespace ckpt
@@ -122,25 +125,25 @@ int main()
         const int64_t longc[] = {0, 8193};
         for (const int64_t *bad_off : {dec, tiny, neg, huge}) {
             CHECK(ckpt_ragged_workspace_bytes(CKPT_CALL_SOLVE_LINEAR, bad_off, 2) == 0);
-            CHECK(ckpt_ragged_solve_linear(d, bad_off, 2, mask, out, nullptr, ws, 1 << 15, nullptr) == CKPT_ERR_SHAPE);
-            CHECK(ckpt_ragged_eval_peak(d, mask, bad_off, 2, 0, out, nullptr, ws, 1 << 15, nullptr) == CKPT_ERR_SHAPE);
+            CHECK(ckpt_ragged_solve_linear(d, bad_off, nullptr, 2, mask, out, nullptr, ws, 1 << 15, nullptr) == CKPT_ERR_SHAPE);
+            CHECK(ckpt_ragged_eval_peak(d, mask, bad_off, nullptr, 2, 0, out, nullptr, ws, 1 << 15, nullptr) == CKPT_ERR_SHAPE);
         }
         CHECK(ckpt_ragged_workspace_bytes(CKPT_CALL_SOLVE_CUBIC, longc, 1) == 0);
         CHECK(ckpt_ragged_workspace_bytes(CKPT_CALL_SOLVE_LINEAR, longc, 1) > 0);
-        CHECK(ckpt_ragged_solve_cubic(d, longc, 1, mask, out, nullptr, nullptr, ws, 1 << 15, nullptr) == CKPT_ERR_SHAPE);
-        CHECK(ckpt_ragged_solve_linear(d, off, -1, mask, out, nullptr, ws, 1 << 15, nullptr) == CKPT_ERR_SHAPE);
-        CHECK(ckpt_ragged_solve_linear(d, off, 5, nullptr, out, nullptr, ws, 1 << 15, nullptr) == CKPT_ERR_NULL);
-        CHECK(ckpt_ragged_solve_linear(d, off, 5, mask, out, nullptr, ws, 64, nullptr) == CKPT_ERR_WORKSPACE);
-        CHECK(ckpt_ragged_eval_timeline(d, mask, off, 5, 3, out, nullptr, ws, 1 << 15, nullptr) == CKPT_ERR_SHAPE);
-        CHECK(ckpt_ragged_eval_timeline(d, mask, off, 5, 1, nullptr, nullptr, ws, 1 << 15, nullptr) == CKPT_ERR_NULL);
-        CHECK(ckpt_ragged_solve_cubic(nullptr, off, 0, nullptr, nullptr, nullptr, nullptr, nullptr, 0, nullptr) == CKPT_OK);
+        CHECK(ckpt_ragged_solve_cubic(d, longc, nullptr, 1, mask, out, nullptr, nullptr, ws, 1 << 15, nullptr) == CKPT_ERR_SHAPE);
+        CHECK(ckpt_ragged_solve_linear(d, off, nullptr, -1, mask, out, nullptr, ws, 1 << 15, nullptr) == CKPT_ERR_SHAPE);
+        CHECK(ckpt_ragged_solve_linear(d, off, nullptr, 5, nullptr, out, nullptr, ws, 1 << 15, nullptr) == CKPT_ERR_NULL);
+        CHECK(ckpt_ragged_solve_linear(d, off, nullptr, 5, mask, out, nullptr, ws, 64, nullptr) == CKPT_ERR_WORKSPACE);
+        CHECK(ckpt_ragged_eval_timeline(d, mask, off, nullptr, 5, 3, out, nullptr, ws, 1 << 15, nullptr) == CKPT_ERR_SHAPE);
+        CHECK(ckpt_ragged_eval_timeline(d, mask, off, nullptr, 5, 1, nullptr, nullptr, ws, 1 << 15, nullptr) == CKPT_ERR_NULL);
+        CHECK(ckpt_ragged_solve_cubic(nullptr, off, nullptr, 0, nullptr, nullptr, nullptr, nullptr, nullptr, 0, nullptr) == CKPT_OK);
         CHECK(ckpt::ragged_runs == 0);
         // calls in order reach the device side once each, with a plan that covers every chain once
-        CHECK(ckpt_ragged_solve_linear(d, off, 5, mask, out, nullptr, ws, 1 << 15, nullptr) == CKPT_ERR_WORKSPACE);
+        CHECK(ckpt_ragged_solve_linear(d, off, nullptr, 5, mask, out, nullptr, ws, 1 << 15, nullptr) == CKPT_ERR_WORKSPACE);
         static unsigned char big_ws[1 << 22] __attribute__((aligned(256)));
-        CHECK(ckpt_ragged_solve_linear(d, off, 5, mask, out, nullptr, big_ws, sizeof(big_ws), nullptr) == CKPT_OK);
-        CHECK(ckpt_ragged_eval_peak(d, mask, off, 5, 1, out, nullptr, big_ws, sizeof(big_ws), nullptr) == CKPT_OK);
-        CHECK(ckpt_ragged_eval_timeline(d, mask, off, 5, 0, out, nullptr, big_ws, sizeof(big_ws), nullptr) == CKPT_OK);
+        CHECK(ckpt_ragged_solve_linear(d, off, nullptr, 5, mask, out, nullptr, big_ws, sizeof(big_ws), nullptr) == CKPT_OK);
+        CHECK(ckpt_ragged_eval_peak(d, mask, off, nullptr, 5, 1, out, nullptr, big_ws, sizeof(big_ws), nullptr) == CKPT_OK);
+        CHECK(ckpt_ragged_eval_timeline(d, mask, off, nullptr, 5, 0, out, nullptr, big_ws, sizeof(big_ws), nullptr) == CKPT_OK);
         CHECK(ckpt::ragged_runs == 3);
         // a large batch of mixed lengths: the plan's counting sort and the sizes it adds up
         const int64_t many = 200000;

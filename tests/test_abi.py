@@ -117,8 +117,8 @@ def test_ragged_host_checks():
     assert lib.ckpt_ragged_workspace_bytes(B.CALL_SOLVE_CUBIC, ctypes.c_void_p(long.ctypes.data), 1) == 0
     assert lib.ckpt_ragged_workspace_bytes(B.CALL_SOLVE_LINEAR, ctypes.c_void_p(long.ctypes.data), 1) > 0
     fake = ctypes.c_void_p(4096)        # never dereferenced: validation fails first
-    assert lib.ckpt_ragged_solve_linear(fake, ptr, 3, fake, fake, None, fake, 16, None) == 6
-    assert lib.ckpt_ragged_solve_linear(fake, ptr, 3, None, fake, None, fake, 1 << 30, None) == 1
-    assert lib.ckpt_ragged_solve_linear(fake, None, 3, fake, fake, None, fake, 1 << 30, None) == 1
-    assert lib.ckpt_ragged_eval_peak(fake, fake, ptr, 3, 2, fake, None, fake, 1 << 30, None) == 2
-    assert lib.ckpt_ragged_solve_cubic(None, ptr, 0, None, None, None, None, None, 0, None) == 0
+    assert lib.ckpt_ragged_solve_linear(fake, ptr, None, 3, fake, fake, None, fake, 16, None) == 6
+    assert lib.ckpt_ragged_solve_linear(fake, ptr, fake, 3, None, fake, None, fake, 1 << 30, None) == 1
+    assert lib.ckpt_ragged_solve_linear(fake, None, fake, 3, fake, fake, None, fake, 1 << 30, None) == 1
+    assert lib.ckpt_ragged_eval_peak(fake, fake, ptr, None, 3, 2, fake, None, fake, 1 << 30, None) == 2
+    assert lib.ckpt_ragged_solve_cubic(None, ptr, None, 0, None, None, None, None, None, 0, None) == 0

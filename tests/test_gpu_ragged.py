@@ -26,9 +26,10 @@ def say(msg):
 
 def check_eval(d, m, off):
     dd, md = to_dev(d), to_dev(m)
+    off_dev = to_dev(off)
     for obj in (B.OBJ_STATIC, B.OBJ_DYNAMIC):
-        peak, status = B.ckpt_ragged_eval_peak(dd, md, off, obj)
-        line, status2 = B.ckpt_ragged_eval_timeline(dd, md, off, obj)
+        peak, status = B.ckpt_ragged_eval_peak(dd, md, off, obj, offsets_dev=off_dev if obj else None)
+        line, status2 = B.ckpt_ragged_eval_timeline(dd, md, off, obj, offsets_dev=None if obj else off_dev)
         torch.cuda.synchronize()
         assert (np_(status) == 0).all() and (np_(status2) == 0).all()
         assert np.array_equal(np_(peak), oracle.ragged_peak(d, m, off, obj)), f"objective {obj}"
@@ -36,12 +37,13 @@ def check_eval(d, m, off):
 
 
 def check_linear(d, off):
-    mask, peak, status = B.ckpt_ragged_solve_linear(to_dev(d), off)
-    torch.cuda.synchronize()
     want_peak, want_mask = oracle.ragged_solve_dynamic(d, off)
-    assert (np_(status) == 0).all()
-    assert np.array_equal(np_(peak), want_peak)
-    assert np.array_equal(np_(mask), want_mask)
+    for off_dev in (None, to_dev(off)):  # the library's own copy of the offsets, then the caller's
+        mask, peak, status = B.ckpt_ragged_solve_linear(to_dev(d), off, offsets_dev=off_dev)
+        torch.cuda.synchronize()
+        assert (np_(status) == 0).all()
+        assert np.array_equal(np_(peak), want_peak)
+        assert np.array_equal(np_(mask), want_mask)
 
 
 def check_cubic(d, off):
@@ -112,6 +114,23 @@ def test_chain_with_a_bad_size_is_reported_alone():
     keep[off[1]:off[2]] = False
     assert np.array_equal(np_(mask)[keep], good_mask[keep])
     assert np.array_equal(np_(peak)[[0, 2, 3]], good_peak[[0, 2, 3]])
+
+
+def test_many_distinct_lengths_and_repeated_calls():
+    """Every chain a group of its own next to large groups, twice in a row into one workspace: the
+    places inside a group may differ between the calls, the results may not."""
+    rng = np.random.default_rng(8)
+    lengths = np.concatenate([np.arange(1, 200), rng.choice([7, 31, 64], size=5000)])
+    rng.shuffle(lengths)
+    d, m, off = inputs.ragged_batch(17, lengths)
+    want_peak, want_mask = oracle.ragged_solve_dynamic(d, off)
+    dd = to_dev(d)
+    ws = torch.empty(B.load().ckpt_ragged_workspace_bytes(B.CALL_SOLVE_LINEAR, off.ctypes.data, len(lengths)),
+                     dtype=torch.uint8, device=DEV)
+    for _ in range(2):
+        mask, peak, status = B.ckpt_ragged_solve_linear(dd, off, workspace=ws, offsets_dev=to_dev(off))
+        torch.cuda.synchronize()
+        assert np.array_equal(np_(peak), want_peak) and np.array_equal(np_(mask), want_mask)
 
 
 def test_host_checks_and_the_empty_batch():
