@@ -86,6 +86,15 @@ def test_cubic_on_mixed_lengths():
     check_cubic(d, off)
 
 
+def test_cubic_with_long_chains_in_the_batch():
+    """Chains long enough for the cubic solver's launch that lays out the budgets and builds the size
+    stack's links together, as a group of three inside a ragged batch (padded staging rows)."""
+    lengths = [1100, 24, 1100, 15, 1100, 1030]
+    d, m, off = inputs.ragged_batch(18, lengths)
+    say(f"ragged cubic, long chains: lengths {lengths}")
+    check_cubic(d, off)
+
+
 def test_one_large_group_beside_small_ones():
     """A group of 70,001 chains spans many transposition tiles and leaves a ragged last tile."""
     lengths = np.full(70004, 24)
