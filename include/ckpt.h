@@ -8,10 +8,12 @@
  *
  * Memory and ownership.  Every pointer below, except the ckpt_layout itself
  * and the offsets_host of the ragged calls, is a DEVICE pointer owned by the
- * caller.  The library allocates no memory,
- * keeps no data between calls and never synchronises: each call validates its
- * arguments on the host, enqueues its kernels on `hip_stream` (a hipStream_t
- * passed as void*, NULL = the null stream) and returns.  Outputs are valid
+ * caller.  The library allocates no memory, keeps no data, streams or events
+ * between calls and does not synchronise: each call validates its arguments on
+ * the host, enqueues its kernels on `hip_stream` (a hipStream_t passed as
+ * void*, NULL = the null stream) and returns.  (Two exceptions, stated where
+ * they are declared: the ragged calls wait once for a small copy, and
+ * ckpt_solve_linear_noalloc uses a device array of the library's own.)  Outputs are valid
  * once the stream has reached the end of the call's work.  `ws` is scratch of
  * at least ckpt_workspace_bytes() bytes, 256-byte aligned, private to the call
  * until it has finished on the stream; its contents need no initialisation.
@@ -134,7 +136,7 @@ int ckpt_solve_cubic(const int64_t *d, const ckpt_layout *layout, uint8_t *mask_
  * the ones below some s_lo.  The call takes a first UB from feasible sets it
  * builds itself (a checkpoint every ceil(sqrt(n)) layers; greedy sets for a
  * grid of segment limits); if the bounds from that UB still leave more than an
- * eighth of the budgets it runs one tile in 64 of the sorted budgets inside
+ * eighth of the budgets it runs one tile in 64 of the budgets (ordered by value) inside
  * them and takes UB from those as well; then it runs the budgets inside the
  * bounds: the optimum, the smallest optimal budget and
  * the canonical set are unchanged (both comparisons are strict, so ties are

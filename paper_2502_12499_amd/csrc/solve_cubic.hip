@@ -8,9 +8,8 @@
 // the answer is min_s (s + c_s) over the budgets s = 0 and s = P[b] - P[a-1],
 // 1 <= a <= b <= n-1.
 //
-// Kernels, all in the caller's stream order (the links kernel runs on a side
-// stream that is forked from the caller's stream after the prologue and joined
-// to it again before the shared kernel):
+// Kernels, all on the caller's stream, in this order (from 1024 layers on, links
+// and slices share one launch: neither needs the other):
 //   prologue  one wave per chain: validates the sizes, builds P by a wave scan,
 //             divides everything by the largest common power of two and picks
 //             32-bit arithmetic when sum(d)+max(d) then fits (it does for
@@ -21,8 +20,8 @@
 //             the nearest earlier smaller size, the stack depth, and a snapshot
 //             of the stack's next eight entries; for every eight positions their
 //             smallest size and depth and last prefix sum.
-//   values +  the budget values in enumeration order, then sorted per chain
-//   sort      (library radix sort), so that the 64 lanes of a wave hold nearly
+//   slices    the budget values laid out by slices of their value range (any
+//             order inside a slice), so that the 64 lanes of a wave hold nearly
 //             equal budgets and meet the same events at the same cells.
 //   shared    one LANE per budget, all lanes walking j together.  F_s(j) is
 //             d_j + m with m the value at the window's head; as long as a lane's
@@ -954,7 +953,7 @@ struct SharedLane {
 
 // With REDO the workgroups (one wave each) take the waves listed in w.redo
 // instead of the waves of their own index.
-// Otherwise workgroup b of a chain takes tile b * tile_stride of the sorted
+// Otherwise workgroup b of a chain takes tile b * tile_stride of the laid-out
 // budgets (tile_stride > 1: a sample of the budgets).  mode kSharedAll runs
 // every tile it is given; kSharedPrune skips a wave whose smallest budget is
 // above w.prune[c] or whose largest is below w.prune_lo[c] (no budget of the
@@ -1438,7 +1437,7 @@ __global__ __launch_bounds__(BLOCK) void cubic_shared_kernel(int n, int64_t bloc
 
 constexpr int kRedoBlocks = 2048;
 
-constexpr int kSampleStride = 64;  // a pruned call first runs every 64th tile of the sorted budgets
+constexpr int kSampleStride = 64;  // a pruned call first runs every 64th tile of the laid-out budgets
 // Pruning costs two more passes of at least one wave's running time each, and the budgets it
 // keeps are the small ones, whose waves run longest: below this length it does not pay.
 constexpr int kPruneFromLayers = 3072;

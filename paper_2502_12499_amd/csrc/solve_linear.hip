@@ -38,8 +38,10 @@
 //        [slot][lane].  Values are held as 32-bit multiples of
 //        2^sh, sh the number of trailing zero bits common to the sizes read so
 //        far (stored values are shifted left when a size with fewer trailing
-//        zeros arrives).  nxt(i) - i - 1 is parked as a byte in the chain's
-//        mask_out slot i and replaced by the mask in a final forward sweep.
+//        zeros arrives).  nxt(i) - i - 1 is a byte: chains of up to 256 layers
+//        keep these bytes in vector registers (the same register for every
+//        lane, indexed by the wave-uniform position); longer chains park them in
+//        the chain's mask_out slot i.  A final forward sweep turns them into the mask.
 //        A lane defers its chain when a ring fills, the values outgrow 30 bits,
 //        a step exceeds 255 positions, or a size is not positive: it appends
 //        the chain to a list in the workspace.
