@@ -178,6 +178,28 @@ def test_solve_linear_batches(batch, n, kind):
         check_linear(d, chain_major=True)
 
 
+@pytest.mark.parametrize("n", [1, 2, 3, 7, 8, 9, 15, 16, 17, 63, 64, 65, 247, 248, 249, 255, 256, 257, 258, 264])
+def test_solve_linear_lengths_around_the_chunk_and_register_limits(n):
+    """Chains of up to 256 layers keep their steps in registers, eight positions to a pair of them, longer
+    ones park them in the mask: lengths on both sides of every such boundary, with a ragged last wave,
+    aligned sizes, tied sizes and sizes whose common power of two shrinks along the chain."""
+    batch = 130
+    say(f"solve_linear n={n}")
+    check_linear(inputs.uniform_aligned_chains(30 + n, n, batch, 256, 32768))
+    check_linear(inputs.uniform_aligned_chains(31 + n, n, batch, 1, 3, unit=1))
+    d = inputs.uniform_aligned_chains(32 + n, n, batch, 256, 32768)
+    d[n // 2, ::2] += 12
+    d[0, 1::4] += 1
+    check_linear(d)
+    # long steps (every interior size tiny against the ends) and a ring that fills: these chains are
+    # deferred to the other kernels, their neighbours are not
+    d = inputs.uniform_aligned_chains(33 + n, n, batch, 256, 32768)
+    d[:, 3] = 1
+    d[n, 3] = 1000
+    d[n, 64] = 10 ** 13
+    check_linear(d)
+
+
 def test_solve_linear_mixed_alignment_and_deferred_chains():
     # sizes whose common power of two shrinks as the chain is read, chains that
     # need 64-bit values, deep queues and long steps, all in one batch
