@@ -123,6 +123,61 @@ hipError_t launch_solve_cubic(const int64_t *d, int64_t batch, int n, Strides st
 int64_t cubic_trace_len(int n);
 
 // ---- ragged batches ----------------------------------------------------------
+// What the kernels are told about the chains of one length (a "group") when all groups of a call
+// are staged side by side and taken by one launch.  Groups ascend in n; their chains have the
+// places first .. first + count - 1, their waves of 64 chains the numbers wave_first .., their
+// transposition tiles the numbers tile_first ..; the group's staging (position-major, `pitch`
+// elements from one position to the next) starts stage_off elements into the staging arrays.
+struct RaggedGroupDev {
+    int32_t n;
+    int32_t count;
+    int32_t first;
+    int32_t wave_first;
+    int64_t tile_first;
+    int64_t stage_off;
+    int64_t pitch;
+    int32_t tiles_x;  // tiles across the chains: ceil(count / 64)
+    int32_t pad;
+};
+
+// The group that holds wave `wave`, place `place` or tile `tile` (each exists).
+__device__ inline int ragged_group_of_wave(const RaggedGroupDev *g, int n_groups, int64_t wave)
+{
+    int lo = 0, hi = n_groups - 1;
+    while (lo < hi) {
+        const int mid = (lo + hi + 1) >> 1;
+        if ((int64_t)g[mid].wave_first <= wave) lo = mid; else hi = mid - 1;
+    }
+    return lo;
+}
+__device__ inline int ragged_group_of_place(const RaggedGroupDev *g, int n_groups, int64_t place)
+{
+    int lo = 0, hi = n_groups - 1;
+    while (lo < hi) {
+        const int mid = (lo + hi + 1) >> 1;
+        if ((int64_t)g[mid].first <= place) lo = mid; else hi = mid - 1;
+    }
+    return lo;
+}
+__device__ inline int ragged_group_of_tile(const RaggedGroupDev *g, int n_groups, int64_t tile)
+{
+    int lo = 0, hi = n_groups - 1;
+    while (lo < hi) {
+        const int mid = (lo + hi + 1) >> 1;
+        if (g[mid].tile_first <= tile) lo = mid; else hi = mid - 1;
+    }
+    return lo;
+}
+
+// All groups of a ragged call in one launch each (the staging arrays hold every group).
+hipError_t launch_eval_peak_ragged(const int64_t *d_stage, const uint8_t *mask_stage, const RaggedGroupDev *groups,
+                                   int n_groups, int64_t waves, int objective, int64_t *peak_stage,
+                                   int32_t *status_stage, hipStream_t stream);
+// batch: chains in all groups; max_layers: the longest chain.  ws as for launch_solve_linear(batch, max_layers).
+hipError_t launch_solve_linear_ragged(const int64_t *d_stage, const RaggedGroupDev *groups, int n_groups,
+                                      int64_t waves, int64_t batch, int max_layers, uint8_t *mask_stage,
+                                      int64_t *peak_stage, int32_t *status_stage, void *ws, hipStream_t stream);
+
 // which: a ckpt_call; offsets_host: batch + 1 element offsets in host memory
 size_t ragged_workspace_bytes(int which, const int64_t *offsets_host, int64_t batch);
 // Returns a ckpt_status.  Copies the group table (and the offsets, if offsets_dev is null) to the

@@ -13,15 +13,13 @@ namespace {
 
 constexpr int kBlock = 64;
 
+// The evaluation of chain c of a batch laid out by (cstride, pstride).
 template <int OBJ>
-__global__ __launch_bounds__(kBlock) void eval_peak_kernel(const int64_t *__restrict__ d,
-                                                           const uint8_t *__restrict__ mask,
-                                                           int64_t batch, int n, int64_t cstride,
-                                                           int64_t pstride,
-                                                           int64_t *__restrict__ peak_out,
-                                                           int32_t *__restrict__ status_out)
+__device__ __forceinline__ void eval_peak_chain(const int64_t *__restrict__ d, const uint8_t *__restrict__ mask,
+                                       int64_t batch, int n, int64_t cstride, int64_t pstride,
+                                       int64_t *__restrict__ peak_out, int32_t *__restrict__ status_out,
+                                       const int64_t c)
 {
-    const int64_t c = (int64_t)xcd_paired_block(blockIdx.x, gridDim.x) * kBlock + threadIdx.x;
     if (c >= batch) return;
     const int64_t *dp = d + c * cstride;
     const uint8_t *mp = mask + c * cstride;
@@ -77,6 +75,33 @@ __global__ __launch_bounds__(kBlock) void eval_peak_kernel(const int64_t *__rest
     if (status_out) status_out[c] = status;
 }
 
+template <int OBJ>
+__global__ __launch_bounds__(kBlock) void eval_peak_kernel(const int64_t *__restrict__ d,
+                                                           const uint8_t *__restrict__ mask,
+                                                           int64_t batch, int n, int64_t cstride,
+                                                           int64_t pstride,
+                                                           int64_t *__restrict__ peak_out,
+                                                           int32_t *__restrict__ status_out)
+{
+    const int64_t c = (int64_t)xcd_paired_block(blockIdx.x, gridDim.x) * kBlock + threadIdx.x;
+    eval_peak_chain<OBJ>(d, mask, batch, n, cstride, pstride, peak_out, status_out, c);
+}
+
+// Every group of a ragged call in one launch: a wave looks up the group its 64 chains belong to
+// and evaluates them where that group is staged; results go to the chains' places.
+template <int OBJ>
+__global__ __launch_bounds__(kBlock) void eval_peak_ragged_kernel(const int64_t *__restrict__ d_stage,
+                                                                  const uint8_t *__restrict__ mask_stage,
+                                                                  const RaggedGroupDev *__restrict__ groups,
+                                                                  int n_groups, int64_t *__restrict__ peak_stage,
+                                                                  int32_t *__restrict__ status_stage)
+{
+    const RaggedGroupDev g = groups[ragged_group_of_wave(groups, n_groups, blockIdx.x)];
+    const int64_t c = ((int64_t)blockIdx.x - g.wave_first) * kBlock + threadIdx.x;
+    eval_peak_chain<OBJ>(d_stage + g.stage_off, mask_stage + g.stage_off, g.count, g.n, 1, g.pitch,
+                         peak_stage + g.first, status_stage + g.first, c);
+}
+
 }  // namespace
 
 hipError_t launch_eval_peak(const int64_t *d, const uint8_t *mask, int64_t batch, int n, Strides st,
@@ -90,6 +115,21 @@ hipError_t launch_eval_peak(const int64_t *d, const uint8_t *mask, int64_t batch
     else
         hipLaunchKernelGGL(eval_peak_kernel<CKPT_OBJ_DYNAMIC>, dim3(grid), dim3(kBlock), 0, stream, d, mask,
                            batch, n, st.chain, st.pos, peak_out, status_out);
+    return hipGetLastError();
+}
+
+hipError_t launch_eval_peak_ragged(const int64_t *d_stage, const uint8_t *mask_stage, const RaggedGroupDev *groups,
+                                   int n_groups, int64_t waves, int objective, int64_t *peak_stage,
+                                   int32_t *status_stage, hipStream_t stream)
+{
+    if (waves == 0) return hipSuccess;
+    static_assert(kBlock == kWave, "a workgroup is one of the groups' waves");
+    if (objective == CKPT_OBJ_STATIC)
+        hipLaunchKernelGGL(eval_peak_ragged_kernel<CKPT_OBJ_STATIC>, dim3((unsigned)waves), dim3(kBlock), 0, stream,
+                           d_stage, mask_stage, groups, n_groups, peak_stage, status_stage);
+    else
+        hipLaunchKernelGGL(eval_peak_ragged_kernel<CKPT_OBJ_DYNAMIC>, dim3((unsigned)waves), dim3(kBlock), 0, stream,
+                           d_stage, mask_stage, groups, n_groups, peak_stage, status_stage);
     return hipGetLastError();
 }
 

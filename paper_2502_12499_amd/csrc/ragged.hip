@@ -1,11 +1,12 @@
 // Ragged batches: chains of different lengths in one call (the networks of Section 5 range from
 // n = 15 to n = 1001 layers).  Chain c occupies elements offsets[c] .. offsets[c+1]-1 of one flat
 // array.  The host counts the chains of every length (launch planning, no arithmetic of the
-// method) and a kernel hands every chain a place in its length's group; for each group a tiled
-// transposition through LDS
-// brings the group's chains into the position-major layout, the group runs through the same
-// kernels as an equal-length batch, and a second transposition puts the results where the flat
-// layout wants them.  Everything is enqueued on the caller's stream.
+// method) and decides where each length's group is staged; a kernel hands every chain a place in
+// its group; a tiled transposition through LDS brings all groups into position-major staging at
+// once; eval_peak and solve_linear then take every group in one launch (a wave looks up the group
+// its chains belong to), the timelines and the cubic solver group by group; a second
+// transposition puts the results where the flat layout wants them.  Everything is enqueued on
+// the caller's stream.
 #include <vector>
 
 #include "ragged_plan.h"
@@ -81,33 +82,89 @@ __global__ void ragged_clear_kernel(int32_t *cursor, int n_groups)
     if (g < n_groups) cursor[g] = 0;
 }
 
-// Flat -> position-major for one group.  Element k of chain c is src[mult*off[c] + k], k < rows;
-// it goes to stage[k*pitch + j], j the chain's place in the group.  Reads run along a chain,
-// writes along the chains: both are contiguous per wave.
+// Flat -> position-major, every group in one launch.  A workgroup takes one tile of 64 chains x 64
+// rows of one group (found from the tile's number).  Element k of chain c is src[mult*off[c] + k],
+// k < rows = mult * (n + 1); it goes to stage[mult*stage_off + k*pitch + j], j the chain's place
+// in its group.  Reads run along a chain (several short chains to a wave), writes along the
+// chains: both are contiguous per wave.
+struct TileAt {
+    RaggedGroupDev g;
+    int64_t j0;  // first chain of the tile within the group
+    int k0;      // first row
+    int rows;
+};
+
+__device__ inline TileAt tile_at(const RaggedGroupDev *groups, const int64_t *tile_first2, int n_groups, int mult)
+{
+    TileAt t;
+    int gi;
+    int64_t local;
+    if (mult == 1) {
+        gi = ragged_group_of_tile(groups, n_groups, blockIdx.x);
+        local = (int64_t)blockIdx.x - groups[gi].tile_first;
+    } else {  // the tiles of the arrays with 2n+2 rows per chain are numbered on their own
+        int lo = 0, hi = n_groups - 1;
+        while (lo < hi) {
+            const int mid = (lo + hi + 1) >> 1;
+            if (tile_first2[mid] <= (int64_t)blockIdx.x) lo = mid; else hi = mid - 1;
+        }
+        gi = lo;
+        local = (int64_t)blockIdx.x - tile_first2[gi];
+    }
+    t.g = groups[gi];
+    t.rows = mult * (t.g.n + 1);
+    t.j0 = (local % t.g.tiles_x) * kTile;
+    t.k0 = (int)(local / t.g.tiles_x) * kTile;
+    return t;
+}
+
+// Where the tile's part of each of its 64 chains starts in the flat array (element index), looked
+// up once per tile; the caller synchronises before use.
+__device__ inline void tile_chains(const TileAt &t, const int64_t *__restrict__ off, const int32_t *__restrict__ perm,
+                                   int mult, int64_t *chain_at)
+{
+    if (threadIdx.x < kTile) {
+        const int64_t j = t.j0 + threadIdx.x;
+        chain_at[threadIdx.x] = j < t.g.count ? (int64_t)mult * off[perm[t.g.first + j]] + t.k0 : 0;
+    }
+}
+
+// The workgroup's threads laid along the chains of a tile `width` rows wide (1..64): a thread keeps
+// one row k of the tile and walks the chains; width is rounded up to a power of two so that a
+// thread's chain and row are a shift and a mask away.
+struct AlongChain {
+    int shift, width;
+    __device__ explicit AlongChain(int w) : shift(w > 1 ? 32 - __builtin_clz((unsigned)w - 1u) : 0), width(w) {}
+    __device__ int k() const { return (int)threadIdx.x & ((1 << shift) - 1); }
+    __device__ bool active() const { return k() < width; }
+    __device__ int first_chain() const { return (int)threadIdx.x >> shift; }
+    __device__ int chains_per_pass() const { return kTileThreads >> shift; }
+};
+
 template <typename T>
 __global__ __launch_bounds__(kTileThreads) void ragged_gather_kernel(const T *__restrict__ src,
                                                                      const int64_t *__restrict__ off,
-                                                                     const int32_t *__restrict__ perm, int64_t first,
-                                                                     int64_t count, int rows, int mult, int64_t pitch,
-                                                                     T *__restrict__ stage)
+                                                                     const int32_t *__restrict__ perm,
+                                                                     const RaggedGroupDev *__restrict__ groups,
+                                                                     const int64_t *__restrict__ tile_first2,
+                                                                     int n_groups, int mult, T *__restrict__ stage)
 {
     __shared__ T tile[kTile][kTile + 1];
+    __shared__ int64_t chain_at[kTile];
+    const TileAt t = tile_at(groups, tile_first2, n_groups, mult);
     const int lane = threadIdx.x % kWave, wave = threadIdx.x / kWave;
-    const int64_t j0 = (int64_t)blockIdx.x * kTile;
-    const int k0 = (int)blockIdx.y * kTile;
-    // the tile's elements in chain order, as many chains to a wave as fit its 64 lanes when the
-    // rows are few (a chain of 16 sizes would otherwise use a quarter of a wave's load)
-    const int width = min(kTile, rows - k0);  // positions of this tile
-    for (int e = threadIdx.x; e < kTile * width; e += kTileThreads) {
-        const int r = e / width, k = e - r * width;
-        const int64_t j = j0 + r;
-        if (j < count) tile[r][k] = src[(int64_t)mult * off[perm[first + j]] + k0 + k];
-    }
+    const int64_t count = t.g.count;
+    tile_chains(t, off, perm, mult, chain_at);
     __syncthreads();
+    const AlongChain a(min(kTile, t.rows - t.k0));
+    for (int r = a.first_chain(); r < kTile; r += a.chains_per_pass())
+        if (a.active() && t.j0 + r < count) tile[r][a.k()] = src[chain_at[r] + a.k()];
+    __syncthreads();
+    T *out = stage + (int64_t)mult * t.g.stage_off;
     for (int r = wave; r < kTile; r += kTileThreads / kWave) {
-        const int k = k0 + r;
-        const int64_t j = j0 + lane;
-        if (k < rows && j < count) stage[(int64_t)k * pitch + j] = tile[lane][r];
+        const int k = t.k0 + r;
+        const int64_t j = t.j0 + lane;
+        if (k < t.rows && j < count) out[(int64_t)k * t.g.pitch + j] = tile[lane][r];
     }
 }
 
@@ -115,134 +172,120 @@ __global__ __launch_bounds__(kTileThreads) void ragged_gather_kernel(const T *__
 template <typename T>
 __global__ __launch_bounds__(kTileThreads) void ragged_scatter_kernel(const T *__restrict__ stage,
                                                                       const int64_t *__restrict__ off,
-                                                                      const int32_t *__restrict__ perm, int64_t first,
-                                                                      int64_t count, int rows, int mult, int64_t pitch,
-                                                                      T *__restrict__ dst)
+                                                                      const int32_t *__restrict__ perm,
+                                                                      const RaggedGroupDev *__restrict__ groups,
+                                                                      const int64_t *__restrict__ tile_first2,
+                                                                      int n_groups, int mult, T *__restrict__ dst)
 {
     __shared__ T tile[kTile][kTile + 1];
+    __shared__ int64_t chain_at[kTile];
+    const TileAt t = tile_at(groups, tile_first2, n_groups, mult);
     const int lane = threadIdx.x % kWave, wave = threadIdx.x / kWave;
-    const int64_t j0 = (int64_t)blockIdx.x * kTile;
-    const int k0 = (int)blockIdx.y * kTile;
+    const int64_t count = t.g.count;
+    tile_chains(t, off, perm, mult, chain_at);
+    const T *in = stage + (int64_t)mult * t.g.stage_off;
     for (int r = wave; r < kTile; r += kTileThreads / kWave) {
-        const int k = k0 + r;
-        const int64_t j = j0 + lane;
-        if (k < rows && j < count) tile[lane][r] = stage[(int64_t)k * pitch + j];
+        const int k = t.k0 + r;
+        const int64_t j = t.j0 + lane;
+        if (k < t.rows && j < count) tile[lane][r] = in[(int64_t)k * t.g.pitch + j];
     }
     __syncthreads();
-    const int width = min(kTile, rows - k0);
-    for (int e = threadIdx.x; e < kTile * width; e += kTileThreads) {
-        const int r = e / width, k = e - r * width;
-        const int64_t j = j0 + r;
-        if (j < count) dst[(int64_t)mult * off[perm[first + j]] + k0 + k] = tile[r][k];
-    }
+    const AlongChain a(min(kTile, t.rows - t.k0));
+    for (int r = a.first_chain(); r < kTile; r += a.chains_per_pass())
+        if (a.active() && t.j0 + r < count) dst[chain_at[r] + a.k()] = tile[r][a.k()];
 }
 
-// One value per chain back to the chain's own index.
+// One value per chain from its place back to the chain's own index, all groups at once.
 template <typename T>
 __global__ __launch_bounds__(kTileThreads) void ragged_scatter_value_kernel(const T *__restrict__ stage,
                                                                             const int32_t *__restrict__ perm,
-                                                                            int64_t first, int64_t count,
-                                                                            T *__restrict__ dst)
+                                                                            int64_t batch, T *__restrict__ dst)
 {
-    const int64_t j = (int64_t)blockIdx.x * kTileThreads + threadIdx.x;
-    if (j < count) dst[perm[first + j]] = stage[j];
-}
-
-struct Device {
-    const int64_t *off;
-    const int32_t *perm;
-    int64_t *d, *wide, *peak, *budget;
-    uint8_t *mask;
-    int32_t *status;
-    void *inner;
-};
-
-template <typename T>
-void gather(const T *src, const Device &dv, const RaggedGroup &g, int rows, int mult, T *stage, hipStream_t s)
-{
-    const dim3 grid((unsigned)((g.count + kTile - 1) / kTile), (unsigned)((rows + kTile - 1) / kTile));
-    hipLaunchKernelGGL(ragged_gather_kernel<T>, grid, dim3(kTileThreads), 0, s, src, dv.off, dv.perm, g.first, g.count,
-                       rows, mult, ragged_pitch(g.count), stage);
+    const int64_t p = (int64_t)blockIdx.x * kTileThreads + threadIdx.x;
+    if (p < batch) dst[perm[p]] = stage[p];
 }
 
 template <typename T>
-void scatter(const T *stage, const Device &dv, const RaggedGroup &g, int rows, int mult, T *dst, hipStream_t s)
-{
-    const dim3 grid((unsigned)((g.count + kTile - 1) / kTile), (unsigned)((rows + kTile - 1) / kTile));
-    hipLaunchKernelGGL(ragged_scatter_kernel<T>, grid, dim3(kTileThreads), 0, s, stage, dv.off, dv.perm, g.first,
-                       g.count, rows, mult, ragged_pitch(g.count), dst);
-}
-
-template <typename T>
-void scatter_value(const T *stage, const Device &dv, const RaggedGroup &g, T *dst, hipStream_t s)
+void scatter_value(const T *stage, const int32_t *perm, int64_t batch, T *dst, hipStream_t s)
 {
     if (!dst) return;
-    hipLaunchKernelGGL(ragged_scatter_value_kernel<T>, dim3((unsigned)((g.count + kTileThreads - 1) / kTileThreads)),
-                       dim3(kTileThreads), 0, s, stage, dv.perm, g.first, g.count, dst);
+    hipLaunchKernelGGL(ragged_scatter_value_kernel<T>, dim3((unsigned)((batch + kTileThreads - 1) / kTileThreads)),
+                       dim3(kTileThreads), 0, s, stage, perm, batch, dst);
 }
 
 }  // namespace
 
 int ragged_run(int which, const int64_t *d, const uint8_t *mask_in, const int64_t *offsets_host,
-               const int64_t *offsets_dev, int64_t batch, int objective, uint8_t *mask_out, int64_t *peak_out, int64_t *budget_out, int64_t *timeline_out,
-               int32_t *status_out, const RaggedPlan &p, const RaggedWorkspace &w, void *ws, hipStream_t stream)
+               const int64_t *offsets_dev, int64_t batch, int objective, uint8_t *mask_out, int64_t *peak_out,
+               int64_t *budget_out, int64_t *timeline_out, int32_t *status_out, const RaggedPlan &p,
+               const RaggedWorkspace &w, void *ws, hipStream_t stream)
 {
     const bool eval = which == CKPT_CALL_EVAL_PEAK || which == CKPT_CALL_EVAL_TIMELINE;
     char *base = (char *)ws;
-    Device dv{offsets_dev ? offsets_dev : (const int64_t *)(base + w.off),
-              (const int32_t *)(base + w.perm), (int64_t *)(base + w.d),
-              (int64_t *)(base + w.wide),      (int64_t *)(base + w.peak),       (int64_t *)(base + w.budget),
-              (uint8_t *)(base + w.mask),      (int32_t *)(base + w.status),     base + w.inner};
-    // The table of lengths lives in host memory that ends with this call (and the caller's offsets
-    // may end with it too): wait until the copies have read them.
-    std::vector<RaggedGroupDev> table;
-    table.reserve(p.groups.size());
-    for (const RaggedGroup &g : p.groups) table.push_back(RaggedGroupDev{(int32_t)g.n, (int32_t)g.first});
-    const int n_groups = (int)table.size();
-    if (hipMemcpyAsync(base + w.groups, table.data(), table.size() * sizeof(RaggedGroupDev), hipMemcpyHostToDevice,
+    const int64_t *off = offsets_dev ? offsets_dev : (const int64_t *)(base + w.off);
+    int32_t *perm = (int32_t *)(base + w.perm);
+    const RaggedGroupDev *groups = (const RaggedGroupDev *)(base + w.groups);
+    const int64_t *tile_first2 = (const int64_t *)(base + w.tiles2);
+    int32_t *cursor = (int32_t *)(base + w.cursor);
+    int64_t *sd = (int64_t *)(base + w.d), *swide = (int64_t *)(base + w.wide);
+    int64_t *speak = (int64_t *)(base + w.peak), *sbudget = (int64_t *)(base + w.budget);
+    uint8_t *smask = (uint8_t *)(base + w.mask);
+    int32_t *sstatus = (int32_t *)(base + w.status);
+    const int n_groups = (int)p.groups.size();
+    // The group table lives in host memory that ends with this call (and the caller's offsets may
+    // end with it too): wait until the copies have read them.
+    if (hipMemcpyAsync(base + w.groups, p.groups.data(), p.groups.size() * sizeof(RaggedGroupDev),
+                       hipMemcpyHostToDevice, stream) != hipSuccess ||
+        hipMemcpyAsync(base + w.tiles2, p.tile_first2.data(), p.tile_first2.size() * 8, hipMemcpyHostToDevice,
                        stream) != hipSuccess)
         return CKPT_ERR_DEVICE;
     if (!offsets_dev && hipMemcpyAsync(base + w.off, offsets_host, (size_t)(batch + 1) * 8, hipMemcpyHostToDevice,
                                        stream) != hipSuccess)
         return CKPT_ERR_DEVICE;
     if (hipStreamSynchronize(stream) != hipSuccess) return CKPT_ERR_DEVICE;
-    int32_t *cursor = (int32_t *)(base + w.cursor);
     hipLaunchKernelGGL(ragged_clear_kernel, dim3((unsigned)((n_groups + 255) / 256)), dim3(256), 0, stream, cursor,
                        n_groups);
     hipLaunchKernelGGL(ragged_perm_kernel, dim3((unsigned)((batch + kPermThreads - 1) / kPermThreads)),
-                       dim3(kPermThreads), 0, stream, dv.off, batch, (const RaggedGroupDev *)(base + w.groups), n_groups,
-                       cursor, (int32_t *)(base + w.perm));
-    for (const RaggedGroup &g : p.groups) {
-        const int rows = g.n + 1;
-        const Strides st{1, ragged_pitch(g.count)};
-        hipError_t e = hipSuccess;
-        gather(d, dv, g, rows, 1, dv.d, stream);
-        if (eval) gather(mask_in, dv, g, rows, 1, dv.mask, stream);
-        switch (which) {
-            case CKPT_CALL_EVAL_PEAK:
-                e = launch_eval_peak(dv.d, dv.mask, g.count, g.n, st, objective, dv.peak, dv.status, stream);
-                break;
-            case CKPT_CALL_EVAL_TIMELINE:
-                e = launch_eval_timeline(dv.d, dv.mask, g.count, g.n, st, objective, dv.wide, st, dv.status, stream);
-                break;
-            case CKPT_CALL_SOLVE_LINEAR:
-                e = launch_solve_linear(dv.d, g.count, g.n, st, dv.mask, dv.peak, dv.status, dv.inner, stream);
-                break;
-            default:
-                e = launch_solve_cubic(dv.d, g.count, g.n, st, dv.mask, dv.peak, dv.budget, dv.status, false, nullptr,
-                                       nullptr, nullptr, dv.inner, stream);
-                break;
+                       dim3(kPermThreads), 0, stream, off, batch, groups, n_groups, cursor, perm);
+    // every group's chains into the position-major staging
+    hipLaunchKernelGGL(ragged_gather_kernel<int64_t>, dim3((unsigned)p.tiles), dim3(kTileThreads), 0, stream, d, off, perm,
+                       groups, tile_first2, n_groups, 1, sd);
+    if (eval)
+        hipLaunchKernelGGL(ragged_gather_kernel<uint8_t>, dim3((unsigned)p.tiles), dim3(kTileThreads), 0, stream, mask_in,
+                           off, perm, groups, tile_first2, n_groups, 1, smask);
+    hipError_t e = hipSuccess;
+    if (which == CKPT_CALL_EVAL_PEAK) {
+        e = launch_eval_peak_ragged(sd, smask, groups, n_groups, p.waves, objective, speak, sstatus, stream);
+    } else if (which == CKPT_CALL_SOLVE_LINEAR) {
+        e = launch_solve_linear_ragged(sd, groups, n_groups, p.waves, batch, p.max_layers, smask, speak, sstatus,
+                                       base + w.inner, stream);
+    } else {
+        // the per-phase timelines and the cubic solver take the groups one after the other, each where
+        // it is staged (the cubic solver's tables are sized by the group's length)
+        for (const RaggedGroupDev &g : p.groups) {
+            const Strides st{1, g.pitch};
+            if (which == CKPT_CALL_EVAL_TIMELINE)
+                e = launch_eval_timeline(sd + g.stage_off, smask + g.stage_off, g.count, g.n, st, objective,
+                                         swide + 2 * g.stage_off, st, sstatus + g.first, stream);
+            else
+                e = launch_solve_cubic(sd + g.stage_off, g.count, g.n, st, smask + g.stage_off, speak + g.first,
+                                       sbudget + g.first, sstatus + g.first, false, nullptr, nullptr, nullptr,
+                                       base + w.inner, stream);
+            if (e != hipSuccess) return CKPT_ERR_DEVICE;
         }
-        if (e != hipSuccess) return CKPT_ERR_DEVICE;
-        if (which == CKPT_CALL_EVAL_TIMELINE) {
-            scatter(dv.wide, dv, g, 2 * rows, 2, timeline_out, stream);
-        } else {
-            if (!eval) scatter(dv.mask, dv, g, rows, 1, mask_out, stream);
-            scatter_value(dv.peak, dv, g, peak_out, stream);
-            if (which == CKPT_CALL_SOLVE_CUBIC) scatter_value(dv.budget, dv, g, budget_out, stream);
-        }
-        scatter_value(dv.status, dv, g, status_out, stream);
     }
+    if (e != hipSuccess) return CKPT_ERR_DEVICE;
+    if (which == CKPT_CALL_EVAL_TIMELINE) {
+        hipLaunchKernelGGL(ragged_scatter_kernel<int64_t>, dim3((unsigned)p.tiles2), dim3(kTileThreads), 0, stream, swide,
+                           off, perm, groups, tile_first2, n_groups, 2, timeline_out);
+    } else {
+        if (!eval)
+            hipLaunchKernelGGL(ragged_scatter_kernel<uint8_t>, dim3((unsigned)p.tiles), dim3(kTileThreads), 0, stream,
+                               smask, off, perm, groups, tile_first2, n_groups, 1, mask_out);
+        scatter_value(speak, perm, batch, peak_out, stream);
+        if (which == CKPT_CALL_SOLVE_CUBIC) scatter_value(sbudget, perm, batch, budget_out, stream);
+    }
+    scatter_value(sstatus, perm, batch, status_out, stream);
     return hipGetLastError() == hipSuccess ? CKPT_OK : CKPT_ERR_DEVICE;
 }
 

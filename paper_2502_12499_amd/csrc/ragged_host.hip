@@ -1,5 +1,6 @@
 // Ragged batches, host side (see ragged_plan.h): checks, the count of the chains of every length
-// (launch planning: none of the method's arithmetic) and the workspace layout.
+// and where each length's group is staged (launch planning: none of the method's arithmetic), and
+// the workspace layout.
 #include <algorithm>
 
 #include "ragged_plan.h"
@@ -20,41 +21,58 @@ int ragged_make_plan(const int64_t *off, int64_t batch, int max_layers, RaggedPl
         if (len < 2 || len - 1 > max_layers) return CKPT_ERR_SHAPE;
         ++count[(size_t)(len - 1)];
     }
-    if (off[batch] > INT64_MAX / 32) return CKPT_ERR_SHAPE;
+    if (off[batch] > INT64_MAX / 64) return CKPT_ERR_SHAPE;
     int64_t first = 0;
-    for (int n = 1; n <= max_layers; ++n)
-        if (count[(size_t)n] > 0) {
-            p.groups.push_back(RaggedGroup{n, first, count[(size_t)n]});
-            first += count[(size_t)n];
-        }
+    for (int n = 1; n <= max_layers; ++n) {
+        const int64_t many = count[(size_t)n];
+        if (many == 0) continue;
+        RaggedGroupDev g;
+        g.n = n;
+        g.count = (int32_t)many;
+        g.first = (int32_t)first;
+        g.wave_first = (int32_t)p.waves;
+        g.tile_first = p.tiles;
+        g.stage_off = p.staged;
+        g.pitch = ragged_pitch(many);
+        g.tiles_x = (int32_t)((many + 63) / 64);
+        g.pad = 0;
+        p.tile_first2.push_back(p.tiles2);
+        p.groups.push_back(g);
+        first += many;
+        p.waves += (many + 63) / 64;
+        p.tiles += (int64_t)g.tiles_x * ((n + 1 + 63) / 64);
+        p.tiles2 += (int64_t)g.tiles_x * ((2 * n + 2 + 63) / 64);
+        p.staged += ((int64_t)(n + 1) * g.pitch + 31) / 32 * 32;  // the next group starts on 256 bytes
+        p.max_layers = n;
+    }
+    // a padded staging is at most 8 times the sizes themselves (one chain to a group everywhere);
+    // launches are 32-bit
+    if (p.staged > INT64_MAX / 64 || p.tiles2 > 0x7fffffffLL || p.waves > 0x7fffffffLL) return CKPT_ERR_SHAPE;
     return CKPT_OK;
 }
 
 RaggedWorkspace ragged_layout(int which, const RaggedPlan &p, int64_t batch)
 {
-    size_t d = 0, mask = 0, wide = 0, vec = 0, inner = 0;
-    for (const RaggedGroup &g : p.groups) {
-        const size_t pitch = (size_t)ragged_pitch(g.count), rows = (size_t)g.n + 1;
-        d = std::max(d, rows * pitch * 8);
-        mask = std::max(mask, rows * pitch);
-        vec = std::max(vec, pitch * 8);
-        if (which == CKPT_CALL_EVAL_TIMELINE) wide = std::max(wide, 2 * rows * pitch * 8);
-        if (which == CKPT_CALL_SOLVE_LINEAR) inner = std::max(inner, linear_workspace_bytes(g.count, g.n));
-        if (which == CKPT_CALL_SOLVE_CUBIC) inner = std::max(inner, cubic_workspace_bytes(g.count, g.n));
-    }
+    size_t inner = 0;
+    if (which == CKPT_CALL_SOLVE_LINEAR) inner = linear_workspace_bytes(batch, p.max_layers);
+    if (which == CKPT_CALL_SOLVE_CUBIC)
+        for (const RaggedGroupDev &g : p.groups) inner = std::max(inner, cubic_workspace_bytes(g.count, g.n));
+    const bool eval = which == CKPT_CALL_EVAL_PEAK || which == CKPT_CALL_EVAL_TIMELINE;
+    (void)eval;
     RaggedWorkspace w;
     size_t at = 0;
     auto take = [&at](size_t bytes) { const size_t here = at; at += align_up(bytes); return here; };
     w.off = take((size_t)(batch + 1) * 8);
     w.perm = take((size_t)batch * 4);
     w.groups = take(p.groups.size() * sizeof(RaggedGroupDev));
+    w.tiles2 = take(p.groups.size() * 8);
     w.cursor = take(p.groups.size() * 4);
-    w.d = take(d);
-    w.mask = take(mask);
-    w.wide = take(wide);
-    w.peak = take(vec);
-    w.budget = take(vec);
-    w.status = take(vec);
+    w.d = take((size_t)p.staged * 8);
+    w.mask = take((size_t)p.staged);
+    w.wide = take(which == CKPT_CALL_EVAL_TIMELINE ? (size_t)p.staged * 16 : 0);
+    w.peak = take((size_t)batch * 8);
+    w.budget = take(which == CKPT_CALL_SOLVE_CUBIC ? (size_t)batch * 8 : 0);
+    w.status = take((size_t)batch * 4);
     w.inner = take(inner);
     w.total = at;
     return w;

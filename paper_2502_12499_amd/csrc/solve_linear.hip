@@ -124,12 +124,15 @@ constexpr int kPlaneM = 0, kPlaneA = 1, kPlaneGJ = 2, kPlanes = 3;
 constexpr int kLogMaxLayers = 256;
 typedef uint32_t u32x32 __attribute__((ext_vector_type(32)));
 
+// `block` of `grid`: which 64 chains of the batch the wave takes; `list_base` is added to a
+// chain's number when it goes on the deferred list (the place of the batch's first chain among
+// all chains of a ragged call, else 0).
 template <bool LOG_REGS>
-__global__ __launch_bounds__(kWave) void linear_ring_kernel(const int64_t *__restrict__ d, int64_t batch, int n,
-                                                            int64_t cstride, int64_t pstride,
-                                                            uint8_t *__restrict__ mask_out,
-                                                            int64_t *__restrict__ peak_out,
-                                                            int32_t *__restrict__ status_out, LinearWs w)
+__device__ __forceinline__ void linear_ring_wave(const int64_t *__restrict__ d, int64_t batch, int n, int64_t cstride,
+                                        int64_t pstride, uint8_t *__restrict__ mask_out,
+                                        int64_t *__restrict__ peak_out, int32_t *__restrict__ status_out,
+                                        const LinearWs &w, const unsigned block, const unsigned grid,
+                                        const int64_t list_base)
 {
     // Ring positions are kept pre-multiplied by the byte stride of a slot, so
     // the LDS address of a position is one AND-OR away (the ring is aligned to
@@ -149,7 +152,7 @@ __global__ __launch_bounds__(kWave) void linear_ring_kernel(const int64_t *__res
     static_assert(63 * kRingMaxChainStride * 8 < ((int64_t)1 << 31), "32-bit lane offsets");
 
     const int lane = threadIdx.x;
-    const int64_t c0 = (int64_t)xcd_paired_block(blockIdx.x, gridDim.x) * kWave;
+    const int64_t c0 = (int64_t)xcd_paired_block(block, grid) * kWave;
     const int64_t c = c0 + lane;
     const bool live = c < batch;
     const int64_t cc = live ? c : batch - 1;  // idle lanes shadow the last chain and write nothing
@@ -461,7 +464,7 @@ __global__ __launch_bounds__(kWave) void linear_ring_kernel(const int64_t *__res
     if (!live) return;
     if (defer) {
         const int slot = atomicAdd(w.count, 1);
-        w.list[slot] = (int32_t)c;
+        w.list[slot] = (int32_t)(c + list_base);
         return;
     }
     peak_out[c] = (int64_t)((uint64_t)Mi << sh);
@@ -512,6 +515,35 @@ __global__ __launch_bounds__(kWave) void linear_ring_kernel(const int64_t *__res
     }
 }
 
+template <bool LOG_REGS>
+__global__ __launch_bounds__(kWave) void linear_ring_kernel(const int64_t *__restrict__ d, int64_t batch, int n,
+                                                            int64_t cstride, int64_t pstride,
+                                                            uint8_t *__restrict__ mask_out,
+                                                            int64_t *__restrict__ peak_out,
+                                                            int32_t *__restrict__ status_out, LinearWs w)
+{
+    linear_ring_wave<LOG_REGS>(d, batch, n, cstride, pstride, mask_out, peak_out, status_out, w, blockIdx.x,
+                               gridDim.x, 0);
+}
+
+// Every group of a ragged call in one launch: a wave looks up the group its 64 chains belong to
+// and solves them where that group is staged; the launch with LOG_REGS takes the groups of up to
+// kLogMaxLayers layers, the other one the rest.  Results go to the chains' places.
+template <bool LOG_REGS>
+__global__ __launch_bounds__(kWave) void linear_ring_ragged_kernel(const int64_t *__restrict__ d_stage,
+                                                                   const RaggedGroupDev *__restrict__ groups,
+                                                                   int n_groups, uint8_t *__restrict__ mask_stage,
+                                                                   int64_t *__restrict__ peak_stage,
+                                                                   int32_t *__restrict__ status_stage, LinearWs w)
+{
+    const RaggedGroupDev g = groups[ragged_group_of_wave(groups, n_groups, blockIdx.x)];
+    if ((g.n <= kLogMaxLayers) != LOG_REGS) return;
+    const unsigned waves = (unsigned)((g.count + kWave - 1) / kWave);
+    linear_ring_wave<LOG_REGS>(d_stage + g.stage_off, g.count, g.n, 1, g.pitch, mask_stage + g.stage_off,
+                               peak_stage + g.first, status_stage + g.first, w, blockIdx.x - (unsigned)g.wave_first,
+                               waves, g.first);
+}
+
 // ---------------------------------------------------------------------------
 // wide kernel: one lane per chain deferred by the ring kernel, 64-bit values
 // ---------------------------------------------------------------------------
@@ -531,19 +563,32 @@ constexpr int kWideBlocks = 2048;
 // take listed chains and walk i together.  A chain with a size that is not
 // positive, with sums beyond 64 bits, with more than kRing live entries or with
 // a step beyond 255 positions goes on to the list kernel.
-__global__ __launch_bounds__(kWave) void linear_wide_kernel(const int64_t *__restrict__ d, int n, int64_t cstride,
-                                                            int64_t pstride, uint8_t *__restrict__ mask_out,
+// With `groups` (a ragged call) a listed number is a chain's place among all chains: its group
+// gives the length, where the chain is staged and where its results go, per lane.
+__global__ __launch_bounds__(kWave) void linear_wide_kernel(const int64_t *__restrict__ d, int n_all,
+                                                            int64_t cstride, int64_t pstride_all,
+                                                            uint8_t *__restrict__ mask_out,
                                                             int64_t *__restrict__ peak_out,
-                                                            int32_t *__restrict__ status_out, LinearWs w)
+                                                            int32_t *__restrict__ status_out, LinearWs w,
+                                                            const RaggedGroupDev *__restrict__ groups, int n_groups)
 {
     __shared__ WideEntry ring[kRing][kWave];
     const int lane = threadIdx.x;
     const int count = w.count[0];
     for (int item0 = blockIdx.x * kWave; item0 < count; item0 += gridDim.x * kWave) {
         const bool live = item0 + lane < count;
-        const int64_t c = w.list[live ? item0 + lane : count - 1];
+        const int64_t c = w.list[live ? item0 + lane : count - 1];  // the number results are filed under
+        int n = n_all;
+        int64_t pstride = pstride_all;
         const int64_t *dp = d + c * cstride;
         uint8_t *mp = mask_out + c * cstride;
+        if (groups) {
+            const RaggedGroupDev g = groups[ragged_group_of_place(groups, n_groups, c)];
+            n = g.n;
+            pstride = g.pitch;
+            dp = d + g.stage_off + (c - g.first);
+            mp = mask_out + g.stage_off + (c - g.first);
+        }
         auto at = [&](int pos) -> WideEntry & { return ring[pos & (kRing - 1)][lane]; };
 
         int64_t x = dp[(int64_t)n * pstride];
@@ -633,15 +678,19 @@ __global__ __launch_bounds__(kWave) void linear_wide_kernel(const int64_t *__res
 
 extern __shared__ __align__(16) unsigned char lin_lds[];
 
+// n_all: the chains' length, or in a ragged call (`groups`) the longest one, for which the stacks
+// are laid out; a listed number is then a chain's place among all chains, as in the wide kernel.
 template <bool LDS_STACKS>
-__global__ __launch_bounds__(kWave) void linear_list_kernel(const int64_t *__restrict__ d, int n, int64_t cstride,
-                                                            int64_t pstride, uint8_t *__restrict__ mask_out,
+__global__ __launch_bounds__(kWave) void linear_list_kernel(const int64_t *__restrict__ d, int n_all,
+                                                            int64_t cstride, int64_t pstride_all,
+                                                            uint8_t *__restrict__ mask_out,
                                                             int64_t *__restrict__ peak_out,
-                                                            int32_t *__restrict__ status_out, LinearWs w)
+                                                            int32_t *__restrict__ status_out, LinearWs w,
+                                                            const RaggedGroupDev *__restrict__ groups, int n_groups)
 {
     const int count = w.count[1];
-    const size_t n1 = (size_t)n + 1;
-    char *base = w.scratch + (size_t)blockIdx.x * stack_bytes(n);
+    const size_t n1 = (size_t)n_all + 1;
+    char *base = w.scratch + (size_t)blockIdx.x * stack_bytes(n_all);
     int32_t *nxt = (int32_t *)(base + n1 * 32);
     if (LDS_STACKS) base = (char *)lin_lds;
     int64_t *qM = (int64_t *)base;
@@ -653,8 +702,17 @@ __global__ __launch_bounds__(kWave) void linear_list_kernel(const int64_t *__res
     for (int item = blockIdx.x; item < count; item += gridDim.x) {
         if (threadIdx.x != 0) continue;
         const int64_t c = w.list2[item];
+        int n = n_all;
+        int64_t pstride = pstride_all;
         const int64_t *dp = d + c * cstride;
         uint8_t *mp = mask_out + c * cstride;
+        if (groups) {
+            const RaggedGroupDev g = groups[ragged_group_of_place(groups, n_groups, c)];
+            n = g.n;
+            pstride = g.pitch;
+            dp = d + g.stage_off + (c - g.first);
+            mp = mask_out + g.stage_off + (c - g.first);
+        }
 
         int64_t x = dp[(int64_t)n * pstride];
         bool bad_size = x <= 0;
@@ -796,14 +854,41 @@ hipError_t launch_solve_linear(const int64_t *d, int64_t batch, int n, Strides s
                            batch, w);
     const int64_t wide_blocks = (batch + kWave - 1) / kWave;
     hipLaunchKernelGGL(linear_wide_kernel, dim3((unsigned)(wide_blocks < kWideBlocks ? wide_blocks : kWideBlocks)),
-                       dim3(kWave), 0, stream, d, n, st.chain, st.pos, mask_out, peak_out, status_out, w);
+                       dim3(kWave), 0, stream, d, n, st.chain, st.pos, mask_out, peak_out, status_out, w,
+                       (const RaggedGroupDev *)nullptr, 0);
     const unsigned lgrid = (unsigned)(batch < kListBlocks ? batch : kListBlocks);
     if (n <= kLdsStackMaxN)
         hipLaunchKernelGGL(linear_list_kernel<true>, dim3(lgrid), dim3(kWave), lds_stack_bytes(n), stream, d, n,
-                           st.chain, st.pos, mask_out, peak_out, status_out, w);
+                           st.chain, st.pos, mask_out, peak_out, status_out, w, (const RaggedGroupDev *)nullptr, 0);
     else
         hipLaunchKernelGGL(linear_list_kernel<false>, dim3(lgrid), dim3(kWave), 0, stream, d, n, st.chain, st.pos,
-                           mask_out, peak_out, status_out, w);
+                           mask_out, peak_out, status_out, w, (const RaggedGroupDev *)nullptr, 0);
+    return hipGetLastError();
+}
+
+hipError_t launch_solve_linear_ragged(const int64_t *d_stage, const RaggedGroupDev *groups, int n_groups,
+                                      int64_t waves, int64_t batch, int max_layers, uint8_t *mask_stage,
+                                      int64_t *peak_stage, int32_t *status_stage, void *ws, hipStream_t stream)
+{
+    if (batch == 0) return hipSuccess;
+    LinearWs w = carve_linear(ws, batch, max_layers);
+    hipLaunchKernelGGL(linear_reset_kernel, dim3(1), dim3(1), 0, stream, w);
+    hipLaunchKernelGGL(linear_ring_ragged_kernel<true>, dim3((unsigned)waves), dim3(kWave), 0, stream, d_stage, groups,
+                       n_groups, mask_stage, peak_stage, status_stage, w);
+    if (max_layers > kLogMaxLayers)
+        hipLaunchKernelGGL(linear_ring_ragged_kernel<false>, dim3((unsigned)waves), dim3(kWave), 0, stream, d_stage,
+                           groups, n_groups, mask_stage, peak_stage, status_stage, w);
+    const int64_t wide_blocks = (batch + kWave - 1) / kWave;
+    hipLaunchKernelGGL(linear_wide_kernel, dim3((unsigned)(wide_blocks < kWideBlocks ? wide_blocks : kWideBlocks)),
+                       dim3(kWave), 0, stream, d_stage, max_layers, 1, 0, mask_stage, peak_stage, status_stage, w,
+                       groups, n_groups);
+    const unsigned lgrid = (unsigned)(batch < kListBlocks ? batch : kListBlocks);
+    if (max_layers <= kLdsStackMaxN)
+        hipLaunchKernelGGL(linear_list_kernel<true>, dim3(lgrid), dim3(kWave), lds_stack_bytes(max_layers), stream,
+                           d_stage, max_layers, 1, 0, mask_stage, peak_stage, status_stage, w, groups, n_groups);
+    else
+        hipLaunchKernelGGL(linear_list_kernel<false>, dim3(lgrid), dim3(kWave), 0, stream, d_stage, max_layers, 1, 0,
+                           mask_stage, peak_stage, status_stage, w, groups, n_groups);
     return hipGetLastError();
 }
 

@@ -44,18 +44,32 @@ int ragged_run(int, const int64_t *, const uint8_t *, const int64_t *off, const 
                void *, hipStream_t)
 {
     ++ragged_runs;
-    // the groups ascend in length, follow each other without gaps and hold every chain of their length
-    int64_t seen = 0;
+    // the groups ascend in length, follow each other without gaps (places, waves, tiles, staging)
+    // and hold every chain of their length
+    int64_t seen = 0, waves = 0, tiles = 0, tiles2 = 0, staged = 0;
     int last_n = 0;
-    for (const RaggedGroup &g : plan.groups) {
+    size_t gi = 0;
+    for (const RaggedGroupDev &g : plan.groups) {
         if (g.first != seen || g.count <= 0 || g.n <= last_n) return CKPT_ERR_DEVICE;
+        if (g.wave_first != waves || g.tile_first != tiles || plan.tile_first2[gi] != tiles2) return CKPT_ERR_DEVICE;
+        if (g.stage_off < staged || g.stage_off % 32 != 0 || g.pitch < g.count || g.tiles_x != (g.count + 63) / 64)
+            return CKPT_ERR_DEVICE;
         int64_t have = 0;
         for (int64_t c = 0; c < batch; ++c) have += off[c + 1] - off[c] - 1 == g.n;
         if (have != g.count) return CKPT_ERR_DEVICE;
         seen += g.count;
+        waves += (g.count + 63) / 64;
+        tiles += (int64_t)g.tiles_x * ((g.n + 1 + 63) / 64);
+        tiles2 += (int64_t)g.tiles_x * ((2 * g.n + 2 + 63) / 64);
+        staged = g.stage_off + (int64_t)(g.n + 1) * g.pitch;
         last_n = g.n;
+        ++gi;
     }
-    if (seen != batch || w.total % 256 != 0 || w.inner > w.total || w.groups < w.perm + (size_t)batch * 4)
+    if (seen != batch || waves != plan.waves || tiles != plan.tiles || tiles2 != plan.tiles2 || staged > plan.staged ||
+        last_n != plan.max_layers)
+        return CKPT_ERR_DEVICE;
+    if (w.total % 256 != 0 || w.inner > w.total || w.groups < w.perm + (size_t)batch * 4 ||
+        w.mask < w.d + (size_t)plan.staged * 8)
         return CKPT_ERR_DEVICE;
     return CKPT_OK;
 }
