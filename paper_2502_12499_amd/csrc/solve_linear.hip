@@ -126,18 +126,17 @@ typedef uint32_t u32x32 __attribute__((ext_vector_type(32)));
 
 // `block` of `grid`: which 64 chains of the batch the wave takes; `list_base` is added to a
 // chain's number when it goes on the deferred list (the place of the batch's first chain among
-// all chains of a ragged call, else 0).
+// all chains of a ragged call, else 0); `ring`: the wave's 12 KB of LDS.
 template <bool LOG_REGS>
 __device__ __forceinline__ void linear_ring_wave(const int64_t *__restrict__ d, int64_t batch, int n, int64_t cstride,
                                         int64_t pstride, uint8_t *__restrict__ mask_out,
                                         int64_t *__restrict__ peak_out, int32_t *__restrict__ status_out,
                                         const LinearWs &w, const unsigned block, const unsigned grid,
-                                        const int64_t list_base)
+                                        const int64_t list_base, uint32_t (&ring)[kPlanes][kRing][kWave])
 {
     // Ring positions are kept pre-multiplied by the byte stride of a slot, so
     // the LDS address of a position is one AND-OR away (the ring is aligned to
-    // its own size).
-    __shared__ __attribute__((aligned(4096))) uint32_t ring[kPlanes][kRing][kWave];
+    // its own size; the kernel declares it, aligned to 4096 bytes, and hands it in).
     constexpr uint32_t kStep = (uint32_t)(kWave * sizeof(uint32_t));  // bytes from a slot to the next
     constexpr uint32_t kSlotMask = (uint32_t)(kRing - 1) * kStep;
     constexpr uint32_t kPlane = (uint32_t)kRing * kStep;              // bytes from a plane to the next
@@ -522,26 +521,31 @@ __global__ __launch_bounds__(kWave) void linear_ring_kernel(const int64_t *__res
                                                             int64_t *__restrict__ peak_out,
                                                             int32_t *__restrict__ status_out, LinearWs w)
 {
+    __shared__ __attribute__((aligned(4096))) uint32_t ring[kPlanes][kRing][kWave];
     linear_ring_wave<LOG_REGS>(d, batch, n, cstride, pstride, mask_out, peak_out, status_out, w, blockIdx.x,
-                               gridDim.x, 0);
+                               gridDim.x, 0, ring);
 }
 
 // Every group of a ragged call in one launch: a wave looks up the group its 64 chains belong to
-// and solves them where that group is staged; the launch with LOG_REGS takes the groups of up to
-// kLogMaxLayers layers, the other one the rest.  Results go to the chains' places.
-template <bool LOG_REGS>
+// and solves them where that group is staged, with the step log in registers if the group's
+// chains have up to kLogMaxLayers layers (a wave-uniform branch: long and short groups run side by
+// side on the chip).  Results go to the chains' places.
 __global__ __launch_bounds__(kWave) void linear_ring_ragged_kernel(const int64_t *__restrict__ d_stage,
                                                                    const RaggedGroupDev *__restrict__ groups,
                                                                    int n_groups, uint8_t *__restrict__ mask_stage,
                                                                    int64_t *__restrict__ peak_stage,
                                                                    int32_t *__restrict__ status_stage, LinearWs w)
 {
+    __shared__ __attribute__((aligned(4096))) uint32_t ring[kPlanes][kRing][kWave];
     const RaggedGroupDev g = groups[ragged_group_of_wave(groups, n_groups, blockIdx.x)];
-    if ((g.n <= kLogMaxLayers) != LOG_REGS) return;
     const unsigned waves = (unsigned)((g.count + kWave - 1) / kWave);
-    linear_ring_wave<LOG_REGS>(d_stage + g.stage_off, g.count, g.n, 1, g.pitch, mask_stage + g.stage_off,
-                               peak_stage + g.first, status_stage + g.first, w, blockIdx.x - (unsigned)g.wave_first,
-                               waves, g.first);
+    const unsigned block = blockIdx.x - (unsigned)g.wave_first;
+    if (g.n <= kLogMaxLayers)
+        linear_ring_wave<true>(d_stage + g.stage_off, g.count, g.n, 1, g.pitch, mask_stage + g.stage_off,
+                               peak_stage + g.first, status_stage + g.first, w, block, waves, g.first, ring);
+    else
+        linear_ring_wave<false>(d_stage + g.stage_off, g.count, g.n, 1, g.pitch, mask_stage + g.stage_off,
+                                peak_stage + g.first, status_stage + g.first, w, block, waves, g.first, ring);
 }
 
 // ---------------------------------------------------------------------------
@@ -873,11 +877,8 @@ hipError_t launch_solve_linear_ragged(const int64_t *d_stage, const RaggedGroupD
     if (batch == 0) return hipSuccess;
     LinearWs w = carve_linear(ws, batch, max_layers);
     hipLaunchKernelGGL(linear_reset_kernel, dim3(1), dim3(1), 0, stream, w);
-    hipLaunchKernelGGL(linear_ring_ragged_kernel<true>, dim3((unsigned)waves), dim3(kWave), 0, stream, d_stage, groups,
+    hipLaunchKernelGGL(linear_ring_ragged_kernel, dim3((unsigned)waves), dim3(kWave), 0, stream, d_stage, groups,
                        n_groups, mask_stage, peak_stage, status_stage, w);
-    if (max_layers > kLogMaxLayers)
-        hipLaunchKernelGGL(linear_ring_ragged_kernel<false>, dim3((unsigned)waves), dim3(kWave), 0, stream, d_stage,
-                           groups, n_groups, mask_stage, peak_stage, status_stage, w);
     const int64_t wide_blocks = (batch + kWave - 1) / kWave;
     hipLaunchKernelGGL(linear_wide_kernel, dim3((unsigned)(wide_blocks < kWideBlocks ? wide_blocks : kWideBlocks)),
                        dim3(kWave), 0, stream, d_stage, max_layers, 1, 0, mask_stage, peak_stage, status_stage, w,
