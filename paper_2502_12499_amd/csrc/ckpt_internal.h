@@ -173,6 +173,9 @@ __device__ inline int ragged_group_of_tile(const RaggedGroupDev *g, int n_groups
 hipError_t launch_eval_peak_ragged(const int64_t *d_stage, const uint8_t *mask_stage, const RaggedGroupDev *groups,
                                    int n_groups, int64_t waves, int objective, int64_t *peak_stage,
                                    int32_t *status_stage, hipStream_t stream);
+hipError_t launch_eval_timeline_ragged(const int64_t *d_stage, const uint8_t *mask_stage,
+                                       const RaggedGroupDev *groups, int n_groups, int64_t waves, int objective,
+                                       int64_t *wide_stage, int32_t *status_stage, hipStream_t stream);
 // batch: chains in all groups; max_layers: the longest chain.  ws as for launch_solve_linear(batch, max_layers).
 hipError_t launch_solve_linear_ragged(const int64_t *d_stage, const RaggedGroupDev *groups, int n_groups,
                                       int64_t waves, int64_t batch, int max_layers, uint8_t *mask_stage,

@@ -37,14 +37,13 @@ namespace {
 constexpr int kBlock = 64;
 constexpr int kChunk = 8;
 
+// The timeline of chain c of a batch laid out by the strides (the lanes of a wave call it together).
 template <int OBJ>
-__global__ __launch_bounds__(kBlock) void eval_timeline_kernel(const int64_t *__restrict__ d,
-                                                               const uint8_t *__restrict__ mask, int64_t batch,
-                                                               int n, int64_t cstride, int64_t pstride,
-                                                               int64_t *__restrict__ out, int64_t ocstride,
-                                                               int64_t opstride, int32_t *__restrict__ status_out)
+__device__ __forceinline__ void eval_timeline_chain(const int64_t *__restrict__ d, const uint8_t *__restrict__ mask,
+                                                    int64_t batch, int n, int64_t cstride, int64_t pstride,
+                                                    int64_t *__restrict__ out, int64_t ocstride, int64_t opstride,
+                                                    int32_t *__restrict__ status_out, const int64_t c)
 {
-    const int64_t c = (int64_t)xcd_paired_block(blockIdx.x, gridDim.x) * kBlock + threadIdx.x;
     if (c >= batch) return;
     const int64_t *dp = d + c * cstride;
     const uint8_t *mp = mask + c * cstride;
@@ -192,6 +191,33 @@ __global__ __launch_bounds__(kBlock) void eval_timeline_kernel(const int64_t *__
         for (int64_t t = 0; t <= last; ++t) op[t * opstride] = -1;
 }
 
+template <int OBJ>
+__global__ __launch_bounds__(kBlock) void eval_timeline_kernel(const int64_t *__restrict__ d,
+                                                               const uint8_t *__restrict__ mask, int64_t batch,
+                                                               int n, int64_t cstride, int64_t pstride,
+                                                               int64_t *__restrict__ out, int64_t ocstride,
+                                                               int64_t opstride, int32_t *__restrict__ status_out)
+{
+    const int64_t c = (int64_t)xcd_paired_block(blockIdx.x, gridDim.x) * kBlock + threadIdx.x;
+    eval_timeline_chain<OBJ>(d, mask, batch, n, cstride, pstride, out, ocstride, opstride, status_out, c);
+}
+
+// Every group of a ragged call in one launch: a wave looks up the group its 64 chains belong to and
+// writes their timelines (2n+2 rows, position-major) where the group's share of the wide staging
+// lies, which is twice as far in as in the staging of the sizes.
+template <int OBJ>
+__global__ __launch_bounds__(kBlock) void eval_timeline_ragged_kernel(const int64_t *__restrict__ d_stage,
+                                                                      const uint8_t *__restrict__ mask_stage,
+                                                                      const RaggedGroupDev *__restrict__ groups,
+                                                                      int n_groups, int64_t *__restrict__ wide_stage,
+                                                                      int32_t *__restrict__ status_stage)
+{
+    const RaggedGroupDev g = groups[ragged_group_of_wave(groups, n_groups, blockIdx.x)];
+    const int64_t c = ((int64_t)blockIdx.x - g.wave_first) * kBlock + threadIdx.x;
+    eval_timeline_chain<OBJ>(d_stage + g.stage_off, mask_stage + g.stage_off, g.count, g.n, 1, g.pitch,
+                             wide_stage + 2 * g.stage_off, 1, g.pitch, status_stage + g.first, c);
+}
+
 // Checkpoint sets that do not depend on the sizes: the two ends only, every
 // position, or segments of ceil(sqrt(n)) layers (the sqrt(n) rule of Section
 // 2.1 as Section 5 applies it: n = 24 gives {5,10,15,20,24}).  The byte of a
@@ -233,6 +259,21 @@ hipError_t launch_eval_timeline(const int64_t *d, const uint8_t *mask, int64_t b
     else
         hipLaunchKernelGGL(eval_timeline_kernel<CKPT_OBJ_DYNAMIC>, dim3(grid), dim3(kBlock), 0, stream, d, mask,
                            batch, n, st.chain, st.pos, out, out_st.chain, out_st.pos, status_out);
+    return hipGetLastError();
+}
+
+hipError_t launch_eval_timeline_ragged(const int64_t *d_stage, const uint8_t *mask_stage,
+                                       const RaggedGroupDev *groups, int n_groups, int64_t waves, int objective,
+                                       int64_t *wide_stage, int32_t *status_stage, hipStream_t stream)
+{
+    if (waves == 0) return hipSuccess;
+    static_assert(kBlock == kWave, "a workgroup is one of the groups' waves");
+    if (objective == CKPT_OBJ_STATIC)
+        hipLaunchKernelGGL(eval_timeline_ragged_kernel<CKPT_OBJ_STATIC>, dim3((unsigned)waves), dim3(kBlock), 0, stream,
+                           d_stage, mask_stage, groups, n_groups, wide_stage, status_stage);
+    else
+        hipLaunchKernelGGL(eval_timeline_ragged_kernel<CKPT_OBJ_DYNAMIC>, dim3((unsigned)waves), dim3(kBlock), 0, stream,
+                           d_stage, mask_stage, groups, n_groups, wide_stage, status_stage);
     return hipGetLastError();
 }
 

@@ -3,8 +3,8 @@
 // array.  The host counts the chains of every length (launch planning, no arithmetic of the
 // method) and decides where each length's group is staged; a kernel hands every chain a place in
 // its group; a tiled transposition through LDS brings all groups into position-major staging at
-// once; eval_peak and solve_linear then take every group in one launch (a wave looks up the group
-// its chains belong to), the timelines and the cubic solver group by group; a second
+// once; eval_peak, eval_timeline and solve_linear then take every group in one launch (a wave looks
+// up the group its chains belong to), the cubic solver group by group; a second
 // transposition puts the results where the flat layout wants them.  Everything is enqueued on
 // the caller's stream.
 #include <vector>
@@ -259,18 +259,15 @@ int ragged_run(int which, const int64_t *d, const uint8_t *mask_in, const int64_
     } else if (which == CKPT_CALL_SOLVE_LINEAR) {
         e = launch_solve_linear_ragged(sd, groups, n_groups, p.waves, batch, p.max_layers, smask, speak, sstatus,
                                        base + w.inner, stream);
+    } else if (which == CKPT_CALL_EVAL_TIMELINE) {
+        e = launch_eval_timeline_ragged(sd, smask, groups, n_groups, p.waves, objective, swide, sstatus, stream);
     } else {
-        // the per-phase timelines and the cubic solver take the groups one after the other, each where
-        // it is staged (the cubic solver's tables are sized by the group's length)
+        // the cubic solver takes the groups one after the other, each where it is staged (its tables
+        // and launches are sized by the group's length)
         for (const RaggedGroupDev &g : p.groups) {
-            const Strides st{1, g.pitch};
-            if (which == CKPT_CALL_EVAL_TIMELINE)
-                e = launch_eval_timeline(sd + g.stage_off, smask + g.stage_off, g.count, g.n, st, objective,
-                                         swide + 2 * g.stage_off, st, sstatus + g.first, stream);
-            else
-                e = launch_solve_cubic(sd + g.stage_off, g.count, g.n, st, smask + g.stage_off, speak + g.first,
-                                       sbudget + g.first, sstatus + g.first, false, nullptr, nullptr, nullptr,
-                                       base + w.inner, stream);
+            e = launch_solve_cubic(sd + g.stage_off, g.count, g.n, Strides{1, g.pitch}, smask + g.stage_off,
+                                   speak + g.first, sbudget + g.first, sstatus + g.first, false, nullptr, nullptr,
+                                   nullptr, base + w.inner, stream);
             if (e != hipSuccess) return CKPT_ERR_DEVICE;
         }
     }
