@@ -125,6 +125,36 @@ def test_chain_with_a_bad_size_is_reported_alone():
     assert np.array_equal(np_(peak)[[0, 2, 3]], good_peak[[0, 2, 3]])
 
 
+def test_linear_hands_chains_of_several_groups_to_its_later_kernels():
+    """Sizes that are no multiples of a power of two and need more than 30 bits leave the first
+    linear kernel for the 64-bit one, which then finds each listed chain's length and staging
+    from its group; a few chains whose sums pass 2^63 go on to the last kernel and come back with
+    their status.  Groups on both sides of the register-log limit, short and long mixed."""
+    lengths = np.array([3, 40, 300, 17, 40, 258, 1, 40, 255, 300, 17, 64] * 23, dtype=np.int64)
+    d, m, off = inputs.ragged_batch(21, lengths, lo_units=1 << 20, hi_units=1 << 36, unit=1)
+    d_small, _, _ = inputs.ragged_batch(22, lengths)           # every third chain stays in the first kernel
+    for c in range(0, len(lengths), 3):
+        d[off[c]:off[c + 1]] = d_small[off[c]:off[c + 1]]
+    say(f"ragged linear, {len(lengths)} chains, 64-bit sizes in two of three")
+    check_linear(d, off)
+    check_eval(d, m, off)
+    over = d.copy()
+    hit = [5, 40, 101]                                         # chains of 258, 40 and 258 layers: sums beyond 64 bits
+    for c in hit:
+        over[off[c]:off[c + 1]] = (1 << 62) + 12345
+    mask, peak, status = B.ckpt_ragged_solve_linear(to_dev(over), off)
+    torch.cuda.synchronize()
+    want_peak, want_mask = oracle.ragged_solve_dynamic(d, off)
+    st = np_(status)
+    ok = np.ones(len(lengths), dtype=bool)
+    ok[hit] = False
+    assert (st[ok] == 0).all() and (st[hit] == 4).all()        # CKPT_ERR_OVERFLOW
+    assert np.array_equal(np_(peak)[ok], want_peak[ok])
+    got_mask = np_(mask)
+    for c in np.nonzero(ok)[0]:
+        assert np.array_equal(got_mask[off[c]:off[c + 1]], want_mask[off[c]:off[c + 1]]), f"chain {c}"
+
+
 def test_many_distinct_lengths_and_repeated_calls():
     """Every chain a group of its own next to large groups, twice in a row into one workspace: the
     places inside a group may differ between the calls, the results may not."""
