@@ -469,7 +469,8 @@ def time_extras(torch, B, inputs, W, reps=3):
                          "lengths": "15, 24, 152, 257 in turn" + (", sixteen of 1001" if long_every else ""),
                          "instances_per_s": len(lengths) / (t * 1e-3), "hbm_GBs": rbytes / (t * 1e-3) / 1e9,
                          "hbm_frac": rbytes / (t * 1e-3) / 1e9 / HBM_PEAK_GBS,
-                         "note": "includes the host's count of the lengths and one wait on the stream"}
+                         "note": "offsets on the device: the lengths are counted there; includes the call's one "
+                                 "wait on the stream (for the totals that size its launches)"}
             del ws
         del rdd, rmd
     small = min(Bn, 4096)

@@ -257,22 +257,31 @@ int ckpt_solve_quadratic(const int64_t *d, const ckpt_layout *layout, uint8_t *m
  * budget_out and status_out hold one value per chain, as in the equal-length
  * calls, whose results each chain gets exactly (same equations, same canonical
  * sets, same per-chain errors).
- *   offsets_host [in] batch + 1 non-decreasing element offsets in HOST memory
- *       (the caller built the batch and knows them; the library plans its
- *       launches from them).  It is read during the call only.
- *   offsets_dev [in] the same offsets in DEVICE memory, or NULL: the call then
- *       copies offsets_host into the workspace itself (from pageable host
- *       memory that is the slowest part of a call on a large batch).
+ *   offsets_host [in] batch + 1 ascending element offsets in HOST memory (the
+ *       caller built the batch and knows them; the library plans its launches
+ *       from them).  It is read during the call only.
+ *   offsets_dev [in] the same offsets in DEVICE memory, or NULL.  With NULL the
+ *       call counts the lengths on the host and copies offsets_host into the
+ *       workspace itself (from pageable host memory these are the slowest
+ *       steps of a call on a large batch).  With a device copy the lengths are
+ *       counted and checked on the device and offsets_host is not read (it may
+ *       be NULL), except by ckpt_ragged_solve_cubic, which launches length by
+ *       length and always plans on the host.
  *   ws: ckpt_ragged_workspace_bytes(which, offsets_host, batch) bytes, 256-byte
- *       aligned; it receives the table of lengths, the chains' places grouped
- *       by length (handed out on the device: the order inside a group differs
- *       from call to call, the results do not), a copy of the offsets, and
- *       room to run the largest group in the position-major layout.
- * Unlike the other calls these wait once on the stream, for the copy of the
- * table of lengths (and of the offsets) into ws, before they enqueue the
- * kernels: work already on the stream finishes first, and they cannot be
- * captured into a HIP graph.  A bad offset (decreasing, n_c < 1 or beyond the
- * limit) returns CKPT_ERR_SHAPE and launches nothing; batch = 0 does nothing.
+ *       aligned; it receives the counts of the lengths, the table of groups
+ *       (the chains of one length), the chains' places grouped by length
+ *       (handed out on the device: the order inside a group differs from call
+ *       to call, the results do not), a copy of the offsets, room to stage
+ *       every group in the position-major layout and the solver's own
+ *       workspace.
+ * Unlike the other calls these wait once on the stream before they enqueue
+ * their kernels: for the copy of the table of groups (and of the offsets) into
+ * ws, or, with offsets_dev, for the totals of the device's count, which size
+ * the launches that follow.  Work already on the stream finishes first, and the
+ * calls cannot be captured into a HIP graph.  A bad offset (decreasing, negative
+ * or beyond INT64_MAX / 64, n_c < 1 or beyond the limit) returns CKPT_ERR_SHAPE;
+ * found on the host nothing has been launched then, found on the device only
+ * the count, which writes to ws alone.  batch = 0 does nothing.
  * ckpt_ragged_workspace_bytes returns 0 for such input. */
 size_t ckpt_ragged_workspace_bytes(int which, const int64_t *offsets_host, int64_t batch);
 int ckpt_ragged_eval_peak(const int64_t *d, const uint8_t *mask, const int64_t *offsets_host,

@@ -323,8 +323,10 @@ def _ragged_args(d, offsets, mask=None, offsets_dev=None):
 
 
 def _ragged_workspace(which, off_ptr, batch, device, workspace):
-    need = load().ckpt_ragged_workspace_bytes(int(which), off_ptr, batch)
-    if workspace is None or workspace.numel() < need:
+    """The caller's workspace as it is (the library checks its size), else one of the size the
+    library asks for (a pass over the offsets on the host)."""
+    if workspace is None:
+        need = load().ckpt_ragged_workspace_bytes(int(which), off_ptr, batch)
         workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=device)
     return workspace, workspace.numel()
 

@@ -140,6 +140,46 @@ struct RaggedGroupDev {
     int32_t pad;
 };
 
+// The sums over the groups laid out so far (all of them at the end); `bad` is set by the device's
+// count of the lengths when an offset is out of range.
+struct RaggedTotals {
+    int32_t n_groups, bad, max_layers, pad;
+    int64_t chains, waves, tiles, tiles2, staged;
+};
+
+// Elements from one position to the next in a group's staging: rows start on 256 bytes for groups
+// of 32 chains or more, on 64 bytes for smaller ones (a lone long chain is not blown up 32 times).
+__host__ __device__ inline int64_t ragged_pitch(int64_t count)
+{
+    return count >= 32 ? (count + 31) / 32 * 32 : (count + 7) / 8 * 8;
+}
+
+// The descriptor of the group of `many` chains of n layers that follows the groups summed up in
+// t, which it then joins; *tile_first2 receives the number of its first tile among those of the
+// arrays with 2n+2 rows per chain.  The host's plan and the device's are both built with this.
+__host__ __device__ inline RaggedGroupDev ragged_next_group(RaggedTotals &t, int n, int64_t many, int64_t *tile_first2)
+{
+    RaggedGroupDev g;
+    g.n = n;
+    g.count = (int32_t)many;
+    g.first = (int32_t)t.chains;
+    g.wave_first = (int32_t)t.waves;
+    g.tile_first = t.tiles;
+    g.stage_off = t.staged;
+    g.pitch = ragged_pitch(many);
+    g.tiles_x = (int32_t)((many + 63) / 64);
+    g.pad = 0;
+    *tile_first2 = t.tiles2;
+    t.n_groups += 1;
+    t.max_layers = n;
+    t.chains += many;
+    t.waves += (many + 63) / 64;
+    t.tiles += (int64_t)g.tiles_x * ((n + 1 + 63) / 64);
+    t.tiles2 += (int64_t)g.tiles_x * ((2 * n + 2 + 63) / 64);
+    t.staged += ((int64_t)(n + 1) * g.pitch + 31) / 32 * 32;  // the next group starts on 256 bytes
+    return g;
+}
+
 // The group that holds wave `wave`, place `place` or tile `tile` (each exists).
 __device__ inline int ragged_group_of_wave(const RaggedGroupDev *g, int n_groups, int64_t wave)
 {

@@ -17,6 +17,121 @@ namespace {
 constexpr int kTile = 64;         // chains and positions per transposition tile
 constexpr int kTileThreads = 256; // four waves
 
+// ---- the plan made on the device ------------------------------------------------------------
+// When the caller has the offsets in device memory, the lengths are counted here instead of on the
+// host: ragged_count_kernel checks every offset and counts the chains of every length (hist[n]),
+// ragged_layout_kernel turns the counts into the table of groups, exactly as the host would
+// (ragged_next_group), and the host reads back the totals only: how many waves, tiles and bytes of
+// staging the launches that follow need.
+constexpr int kCountThreads = 1024;
+constexpr int kCountLds = 4096;  // lengths below this are first added up per workgroup in LDS
+
+__global__ __launch_bounds__(kCountThreads) void ragged_count_kernel(const int64_t *__restrict__ off, int64_t batch,
+                                                                     int max_layers, uint32_t *__restrict__ hist,
+                                                                     RaggedTotals *__restrict__ totals)
+{
+    __shared__ uint32_t near_count[kCountLds];
+    for (int b = threadIdx.x; b < kCountLds; b += kCountThreads) near_count[b] = 0;
+    __syncthreads();
+    const int64_t c = (int64_t)blockIdx.x * kCountThreads + threadIdx.x;
+    const int lane = threadIdx.x % kWave;
+    constexpr uint64_t kMaxOffset = (uint64_t)(INT64_MAX / 64);
+    bool ok = false;
+    uint32_t n = 0;
+    if (c < batch) {
+        // every offset in 0 .. INT64_MAX / 64 (a negative one reads as huge), so the difference is
+        // exact, and a decreasing pair wraps to a huge length
+        const uint64_t lo = (uint64_t)off[c], hi = (uint64_t)off[c + 1];
+        const uint64_t below = hi - lo - 2;  // n - 1
+        ok = below <= (uint64_t)(max_layers - 1) && hi <= kMaxOffset && lo <= kMaxOffset;
+        n = (uint32_t)below + 1u;
+        if (!ok) totals->bad = 1;  // (every writer writes the same value)
+    }
+    // the lanes of a wave that hold the same length count together
+    uint64_t todo = __builtin_amdgcn_ballot_w64(ok);
+    while (todo) {
+        const int leader = __ffsll((unsigned long long)todo) - 1;
+        const uint32_t nl = (uint32_t)__builtin_amdgcn_readlane((int)n, leader);
+        const uint64_t same = __builtin_amdgcn_ballot_w64(ok && n == nl);
+        if (lane == leader) {
+            const uint32_t many = (uint32_t)__popcll((unsigned long long)same);
+            if (nl < (uint32_t)kCountLds) atomicAdd(near_count + nl, many); else atomicAdd(hist + nl, many);
+        }
+        todo &= ~same;
+    }
+    __syncthreads();
+    for (int b = threadIdx.x; b < kCountLds && b <= max_layers; b += kCountThreads) {
+        const uint32_t many = near_count[b];
+        if (many) atomicAdd(hist + b, many);
+    }
+}
+
+// Exclusive prefix sum of one value per thread over the workgroup (kCountThreads threads);
+// `wave_sum` is LDS for one value per wave.
+__device__ inline int64_t block_exclusive_sum(int64_t v, int64_t *wave_sum)
+{
+    const int lane = threadIdx.x % kWave, wave = threadIdx.x / kWave;
+    int64_t incl = v;
+#pragma unroll
+    for (int s = 1; s < kWave; s <<= 1) {
+        const int64_t up = __shfl_up(incl, s, kWave);
+        if (lane >= s) incl += up;
+    }
+    __syncthreads();  // (the previous call's readers are done with wave_sum)
+    if (lane == kWave - 1) wave_sum[wave] = incl;
+    __syncthreads();
+    int64_t before = 0;
+    for (int k = 0; k < wave; ++k) before += wave_sum[k];
+    return before + incl - v;
+}
+
+// One workgroup: thread t takes the lengths t*span+1 .. (t+1)*span, first adds up what its groups
+// contribute to the totals, then, knowing the totals of the threads before it, writes their
+// descriptors.  The last thread's totals are the call's.
+__global__ __launch_bounds__(kCountThreads) void ragged_layout_kernel(const uint32_t *__restrict__ hist, int max_layers,
+                                                                      RaggedGroupDev *__restrict__ groups,
+                                                                      int64_t *__restrict__ tile_first2,
+                                                                      RaggedTotals *__restrict__ totals)
+{
+    __shared__ int64_t wave_sum[kCountThreads / kWave];
+    __shared__ int longest;
+    if (threadIdx.x == 0) longest = 0;
+    const int span = (max_layers + kCountThreads - 1) / kCountThreads;
+    const int n_lo = (int)threadIdx.x * span + 1, n_hi = min(n_lo + span - 1, max_layers);
+    RaggedTotals mine = {};
+    for (int n = n_lo; n <= n_hi; ++n) {
+        const int64_t many = hist[n];
+        int64_t unused;
+        if (many) (void)ragged_next_group(mine, n, many, &unused);
+    }
+    RaggedTotals t = {};
+    t.n_groups = (int32_t)block_exclusive_sum(mine.n_groups, wave_sum);
+    t.chains = block_exclusive_sum(mine.chains, wave_sum);
+    t.waves = block_exclusive_sum(mine.waves, wave_sum);
+    t.tiles = block_exclusive_sum(mine.tiles, wave_sum);
+    t.tiles2 = block_exclusive_sum(mine.tiles2, wave_sum);
+    t.staged = block_exclusive_sum(mine.staged, wave_sum);
+    for (int n = n_lo; n <= n_hi; ++n) {
+        const int64_t many = hist[n];
+        if (!many) continue;
+        const int at = t.n_groups;
+        int64_t first2;
+        groups[at] = ragged_next_group(t, n, many, &first2);
+        tile_first2[at] = first2;
+    }
+    if (mine.n_groups) atomicMax(&longest, mine.max_layers);
+    __syncthreads();
+    if (threadIdx.x == kCountThreads - 1) {
+        totals->n_groups = t.n_groups;
+        totals->max_layers = longest;
+        totals->chains = t.chains;
+        totals->waves = t.waves;
+        totals->tiles = t.tiles;
+        totals->tiles2 = t.tiles2;
+        totals->staged = t.staged;
+    }
+}
+
 // Hands every chain a place among the chains of its length: perm[first(group) + k] = chain, k
 // taken from a counter per group.  The lanes of a wave that belong to one group take their
 // places together; with few groups (at most kPermLdsGroups) the waves of a workgroup first add
@@ -215,6 +330,30 @@ void scatter_value(const T *stage, const int32_t *perm, int64_t batch, T *dst, h
 
 }  // namespace
 
+int ragged_plan_on_device(const int64_t *offsets_dev, int64_t batch, int max_layers, const RaggedWorkspace &w,
+                          void *ws, hipStream_t stream, RaggedPlan &p)
+{
+    char *base = (char *)ws;
+    RaggedTotals *totals = (RaggedTotals *)(base + w.totals);
+    uint32_t *hist = (uint32_t *)(base + w.hist);
+    static_assert(sizeof(RaggedTotals) % 4 == 0, "cleared as 32-bit words");
+    // the totals and the counts lie behind each other: one fill clears both
+    const int64_t words = (int64_t)((w.hist - w.totals) / 4) + max_layers + 1;
+    hipLaunchKernelGGL(ragged_clear_kernel, dim3((unsigned)((words + 255) / 256)), dim3(256), 0, stream,
+                       (int32_t *)totals, (int)words);
+    hipLaunchKernelGGL(ragged_count_kernel, dim3((unsigned)((batch + kCountThreads - 1) / kCountThreads)),
+                       dim3(kCountThreads), 0, stream, offsets_dev, batch, max_layers, hist, totals);
+    hipLaunchKernelGGL(ragged_layout_kernel, dim3(1), dim3(kCountThreads), 0, stream, hist, max_layers,
+                       (RaggedGroupDev *)(base + w.groups), (int64_t *)(base + w.tiles2), totals);
+    if (hipGetLastError() != hipSuccess) return CKPT_ERR_DEVICE;
+    // the call's one wait: the launches that follow are sized by the totals
+    if (hipMemcpyAsync(&p.t, totals, sizeof(RaggedTotals), hipMemcpyDeviceToHost, stream) != hipSuccess ||
+        hipStreamSynchronize(stream) != hipSuccess)
+        return CKPT_ERR_DEVICE;
+    if (p.t.bad) return CKPT_ERR_SHAPE;
+    return ragged_check_totals(p.t, batch);
+}
+
 int ragged_run(int which, const int64_t *d, const uint8_t *mask_in, const int64_t *offsets_host,
                const int64_t *offsets_dev, int64_t batch, int objective, uint8_t *mask_out, int64_t *peak_out,
                int64_t *budget_out, int64_t *timeline_out, int32_t *status_out, const RaggedPlan &p,
@@ -231,36 +370,38 @@ int ragged_run(int which, const int64_t *d, const uint8_t *mask_in, const int64_
     int64_t *speak = (int64_t *)(base + w.peak), *sbudget = (int64_t *)(base + w.budget);
     uint8_t *smask = (uint8_t *)(base + w.mask);
     int32_t *sstatus = (int32_t *)(base + w.status);
-    const int n_groups = (int)p.groups.size();
-    // The group table lives in host memory that ends with this call (and the caller's offsets may
-    // end with it too): wait until the copies have read them.
-    if (hipMemcpyAsync(base + w.groups, p.groups.data(), p.groups.size() * sizeof(RaggedGroupDev),
-                       hipMemcpyHostToDevice, stream) != hipSuccess ||
-        hipMemcpyAsync(base + w.tiles2, p.tile_first2.data(), p.tile_first2.size() * 8, hipMemcpyHostToDevice,
-                       stream) != hipSuccess)
-        return CKPT_ERR_DEVICE;
-    if (!offsets_dev && hipMemcpyAsync(base + w.off, offsets_host, (size_t)(batch + 1) * 8, hipMemcpyHostToDevice,
-                                       stream) != hipSuccess)
-        return CKPT_ERR_DEVICE;
-    if (hipStreamSynchronize(stream) != hipSuccess) return CKPT_ERR_DEVICE;
+    const int n_groups = p.t.n_groups;
+    if (!p.groups.empty()) {
+        // The host made the plan.  The group table lives in host memory that ends with this call (and
+        // the caller's offsets may end with it too): wait until the copies have read them.
+        if (hipMemcpyAsync(base + w.groups, p.groups.data(), p.groups.size() * sizeof(RaggedGroupDev),
+                           hipMemcpyHostToDevice, stream) != hipSuccess ||
+            hipMemcpyAsync(base + w.tiles2, p.tile_first2.data(), p.tile_first2.size() * 8, hipMemcpyHostToDevice,
+                           stream) != hipSuccess)
+            return CKPT_ERR_DEVICE;
+        if (!offsets_dev && hipMemcpyAsync(base + w.off, offsets_host, (size_t)(batch + 1) * 8,
+                                           hipMemcpyHostToDevice, stream) != hipSuccess)
+            return CKPT_ERR_DEVICE;
+        if (hipStreamSynchronize(stream) != hipSuccess) return CKPT_ERR_DEVICE;
+    }
     hipLaunchKernelGGL(ragged_clear_kernel, dim3((unsigned)((n_groups + 255) / 256)), dim3(256), 0, stream, cursor,
                        n_groups);
     hipLaunchKernelGGL(ragged_perm_kernel, dim3((unsigned)((batch + kPermThreads - 1) / kPermThreads)),
                        dim3(kPermThreads), 0, stream, off, batch, groups, n_groups, cursor, perm);
     // every group's chains into the position-major staging
-    hipLaunchKernelGGL(ragged_gather_kernel<int64_t>, dim3((unsigned)p.tiles), dim3(kTileThreads), 0, stream, d, off, perm,
+    hipLaunchKernelGGL(ragged_gather_kernel<int64_t>, dim3((unsigned)p.t.tiles), dim3(kTileThreads), 0, stream, d, off, perm,
                        groups, tile_first2, n_groups, 1, sd);
     if (eval)
-        hipLaunchKernelGGL(ragged_gather_kernel<uint8_t>, dim3((unsigned)p.tiles), dim3(kTileThreads), 0, stream, mask_in,
+        hipLaunchKernelGGL(ragged_gather_kernel<uint8_t>, dim3((unsigned)p.t.tiles), dim3(kTileThreads), 0, stream, mask_in,
                            off, perm, groups, tile_first2, n_groups, 1, smask);
     hipError_t e = hipSuccess;
     if (which == CKPT_CALL_EVAL_PEAK) {
-        e = launch_eval_peak_ragged(sd, smask, groups, n_groups, p.waves, objective, speak, sstatus, stream);
+        e = launch_eval_peak_ragged(sd, smask, groups, n_groups, p.t.waves, objective, speak, sstatus, stream);
     } else if (which == CKPT_CALL_SOLVE_LINEAR) {
-        e = launch_solve_linear_ragged(sd, groups, n_groups, p.waves, batch, p.max_layers, smask, speak, sstatus,
+        e = launch_solve_linear_ragged(sd, groups, n_groups, p.t.waves, batch, p.t.max_layers, smask, speak, sstatus,
                                        base + w.inner, stream);
     } else if (which == CKPT_CALL_EVAL_TIMELINE) {
-        e = launch_eval_timeline_ragged(sd, smask, groups, n_groups, p.waves, objective, swide, sstatus, stream);
+        e = launch_eval_timeline_ragged(sd, smask, groups, n_groups, p.t.waves, objective, swide, sstatus, stream);
     } else {
         // the cubic solver takes the groups one after the other, each where it is staged (its tables
         // and launches are sized by the group's length)
@@ -273,11 +414,11 @@ int ragged_run(int which, const int64_t *d, const uint8_t *mask_in, const int64_
     }
     if (e != hipSuccess) return CKPT_ERR_DEVICE;
     if (which == CKPT_CALL_EVAL_TIMELINE) {
-        hipLaunchKernelGGL(ragged_scatter_kernel<int64_t>, dim3((unsigned)p.tiles2), dim3(kTileThreads), 0, stream, swide,
+        hipLaunchKernelGGL(ragged_scatter_kernel<int64_t>, dim3((unsigned)p.t.tiles2), dim3(kTileThreads), 0, stream, swide,
                            off, perm, groups, tile_first2, n_groups, 2, timeline_out);
     } else {
         if (!eval)
-            hipLaunchKernelGGL(ragged_scatter_kernel<uint8_t>, dim3((unsigned)p.tiles), dim3(kTileThreads), 0, stream,
+            hipLaunchKernelGGL(ragged_scatter_kernel<uint8_t>, dim3((unsigned)p.t.tiles), dim3(kTileThreads), 0, stream,
                                smask, off, perm, groups, tile_first2, n_groups, 1, mask_out);
         scatter_value(speak, perm, batch, peak_out, stream);
         if (which == CKPT_CALL_SOLVE_CUBIC) scatter_value(sbudget, perm, batch, budget_out, stream);

@@ -7,6 +7,8 @@
 
 namespace ckpt {
 
+int ragged_layer_limit(int which) { return which == CKPT_CALL_SOLVE_CUBIC ? CKPT_CUBIC_MAX_LAYERS : CKPT_MAX_LAYERS; }
+
 int ragged_make_plan(const int64_t *off, int64_t batch, int max_layers, RaggedPlan &p)
 {
     if (batch < 0 || batch > INT32_MAX) return CKPT_ERR_SHAPE;
@@ -22,54 +24,46 @@ int ragged_make_plan(const int64_t *off, int64_t batch, int max_layers, RaggedPl
         ++count[(size_t)(len - 1)];
     }
     if (off[batch] > INT64_MAX / 64) return CKPT_ERR_SHAPE;
-    int64_t first = 0;
     for (int n = 1; n <= max_layers; ++n) {
         const int64_t many = count[(size_t)n];
         if (many == 0) continue;
-        RaggedGroupDev g;
-        g.n = n;
-        g.count = (int32_t)many;
-        g.first = (int32_t)first;
-        g.wave_first = (int32_t)p.waves;
-        g.tile_first = p.tiles;
-        g.stage_off = p.staged;
-        g.pitch = ragged_pitch(many);
-        g.tiles_x = (int32_t)((many + 63) / 64);
-        g.pad = 0;
-        p.tile_first2.push_back(p.tiles2);
-        p.groups.push_back(g);
-        first += many;
-        p.waves += (many + 63) / 64;
-        p.tiles += (int64_t)g.tiles_x * ((n + 1 + 63) / 64);
-        p.tiles2 += (int64_t)g.tiles_x * ((2 * n + 2 + 63) / 64);
-        p.staged += ((int64_t)(n + 1) * g.pitch + 31) / 32 * 32;  // the next group starts on 256 bytes
-        p.max_layers = n;
+        int64_t first2;
+        p.groups.push_back(ragged_next_group(p.t, n, many, &first2));
+        p.tile_first2.push_back(first2);
     }
+    return ragged_check_totals(p.t, batch);
+}
+
+int ragged_check_totals(const RaggedTotals &t, int64_t batch)
+{
     // a padded staging is at most 8 times the sizes themselves (one chain to a group everywhere);
     // launches are 32-bit
-    if (p.staged > INT64_MAX / 64 || p.tiles2 > 0x7fffffffLL || p.waves > 0x7fffffffLL) return CKPT_ERR_SHAPE;
+    if (t.chains != batch || t.staged > INT64_MAX / 64 || t.tiles2 > 0x7fffffffLL || t.waves > 0x7fffffffLL)
+        return CKPT_ERR_SHAPE;
     return CKPT_OK;
 }
 
 RaggedWorkspace ragged_layout(int which, const RaggedPlan &p, int64_t batch)
 {
     size_t inner = 0;
-    if (which == CKPT_CALL_SOLVE_LINEAR) inner = linear_workspace_bytes(batch, p.max_layers);
+    if (which == CKPT_CALL_SOLVE_LINEAR) inner = linear_workspace_bytes(batch, p.t.max_layers);
     if (which == CKPT_CALL_SOLVE_CUBIC)
         for (const RaggedGroupDev &g : p.groups) inner = std::max(inner, cubic_workspace_bytes(g.count, g.n));
-    const bool eval = which == CKPT_CALL_EVAL_PEAK || which == CKPT_CALL_EVAL_TIMELINE;
-    (void)eval;
+    const size_t limit = (size_t)ragged_layer_limit(which);
+    const size_t room = std::min((size_t)batch, limit);  // groups at most
     RaggedWorkspace w;
     size_t at = 0;
     auto take = [&at](size_t bytes) { const size_t here = at; at += align_up(bytes); return here; };
     w.off = take((size_t)(batch + 1) * 8);
     w.perm = take((size_t)batch * 4);
-    w.groups = take(p.groups.size() * sizeof(RaggedGroupDev));
-    w.tiles2 = take(p.groups.size() * 8);
-    w.cursor = take(p.groups.size() * 4);
-    w.d = take((size_t)p.staged * 8);
-    w.mask = take((size_t)p.staged);
-    w.wide = take(which == CKPT_CALL_EVAL_TIMELINE ? (size_t)p.staged * 16 : 0);
+    w.totals = take(sizeof(RaggedTotals));
+    w.hist = take((limit + 1) * 4);  // directly behind the totals: one fill clears both
+    w.groups = take(room * sizeof(RaggedGroupDev));
+    w.tiles2 = take(room * 8);
+    w.cursor = take(room * 4);
+    w.d = take((size_t)p.t.staged * 8);
+    w.mask = take((size_t)p.t.staged);
+    w.wide = take(which == CKPT_CALL_EVAL_TIMELINE ? (size_t)p.t.staged * 16 : 0);
     w.peak = take((size_t)batch * 8);
     w.budget = take(which == CKPT_CALL_SOLVE_CUBIC ? (size_t)batch * 8 : 0);
     w.status = take((size_t)batch * 4);
@@ -81,8 +75,7 @@ RaggedWorkspace ragged_layout(int which, const RaggedPlan &p, int64_t batch)
 size_t ragged_workspace_bytes(int which, const int64_t *offsets_host, int64_t batch)
 {
     RaggedPlan p;
-    const int max_layers = which == CKPT_CALL_SOLVE_CUBIC ? CKPT_CUBIC_MAX_LAYERS : CKPT_MAX_LAYERS;
-    if (ragged_make_plan(offsets_host, batch, max_layers, p) != CKPT_OK || batch == 0) return 0;
+    if (ragged_make_plan(offsets_host, batch, ragged_layer_limit(which), p) != CKPT_OK || batch == 0) return 0;
     return ragged_layout(which, p, batch).total;
 }
 
@@ -91,16 +84,30 @@ int launch_ragged(int which, const int64_t *d, const uint8_t *mask_in, const int
                   int objective, uint8_t *mask_out, int64_t *peak_out, int64_t *budget_out, int64_t *timeline_out,
                   int32_t *status_out, void *ws, size_t ws_bytes, hipStream_t stream)
 {
-    RaggedPlan p;
-    const int max_layers = which == CKPT_CALL_SOLVE_CUBIC ? CKPT_CUBIC_MAX_LAYERS : CKPT_MAX_LAYERS;
-    const int rc = ragged_make_plan(offsets_host, batch, max_layers, p);
-    if (rc != CKPT_OK) return rc;
-    if (batch == 0) return CKPT_OK;
     const bool eval = which == CKPT_CALL_EVAL_PEAK || which == CKPT_CALL_EVAL_TIMELINE;
+    // With the offsets on the device the lengths are counted there (a pass over the host's copy is
+    // the longest step of a call on a large batch otherwise); the cubic solver is launched group
+    // by group and needs the table on the host.
+    const bool on_device = offsets_dev && which != CKPT_CALL_SOLVE_CUBIC;
+    RaggedPlan p;
+    if (!on_device) {
+        const int rc = ragged_make_plan(offsets_host, batch, ragged_layer_limit(which), p);
+        if (rc != CKPT_OK) return rc;
+    } else if (batch < 0 || batch > INT32_MAX) {
+        return CKPT_ERR_SHAPE;
+    }
+    if (batch == 0) return CKPT_OK;
     if (!d || !ws || (eval && !mask_in) || (!eval && !mask_out)) return CKPT_ERR_NULL;
     if (which == CKPT_CALL_EVAL_TIMELINE ? !timeline_out : !peak_out) return CKPT_ERR_NULL;
+    if (((uintptr_t)ws & 255u) != 0) return CKPT_ERR_WORKSPACE;
+    if (on_device) {
+        const RaggedWorkspace tables = ragged_layout(which, p, batch);  // nothing staged yet: the tables only
+        if (ws_bytes < tables.d) return CKPT_ERR_WORKSPACE;
+        const int rc = ragged_plan_on_device(offsets_dev, batch, ragged_layer_limit(which), tables, ws, stream, p);
+        if (rc != CKPT_OK) return rc;
+    }
     const RaggedWorkspace w = ragged_layout(which, p, batch);
-    if (((uintptr_t)ws & 255u) != 0 || ws_bytes < w.total) return CKPT_ERR_WORKSPACE;
+    if (ws_bytes < w.total) return CKPT_ERR_WORKSPACE;
     return ragged_run(which, d, mask_in, offsets_host, offsets_dev, batch, objective, mask_out, peak_out, budget_out, timeline_out,
                       status_out, p, w, ws, stream);
 }

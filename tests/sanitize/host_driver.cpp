@@ -65,13 +65,30 @@ int ragged_run(int, const int64_t *, const uint8_t *, const int64_t *off, const 
         last_n = g.n;
         ++gi;
     }
-    if (seen != batch || waves != plan.waves || tiles != plan.tiles || tiles2 != plan.tiles2 || staged > plan.staged ||
-        last_n != plan.max_layers)
+    if (!plan.groups.empty() &&
+        (seen != batch || waves != plan.t.waves || tiles != plan.t.tiles || tiles2 != plan.t.tiles2 ||
+         staged > plan.t.staged || last_n != plan.t.max_layers || (int)gi != plan.t.n_groups))
         return CKPT_ERR_DEVICE;
-    if (w.total % 256 != 0 || w.inner > w.total || w.groups < w.perm + (size_t)batch * 4 ||
-        w.mask < w.d + (size_t)plan.staged * 8)
+    if (plan.t.chains != batch || plan.t.n_groups < 1 || (int64_t)plan.t.n_groups > batch) return CKPT_ERR_DEVICE;
+    if (w.total % 256 != 0 || w.inner > w.total || w.totals < w.perm + (size_t)batch * 4 ||
+        w.hist != w.totals + 256 || w.cursor + (size_t)plan.t.n_groups * 4 > w.d ||
+        w.mask < w.d + (size_t)plan.t.staged * 8)
         return CKPT_ERR_DEVICE;
     return CKPT_OK;
+}
+
+// the device's count of the lengths: here the host's, with the tables left out as the device
+// leaves them in the workspace
+static int device_plans = 0;
+int ragged_plan_on_device(const int64_t *offsets_dev, int64_t batch, int max_layers, const RaggedWorkspace &w, void *,
+                          hipStream_t, RaggedPlan &plan)
+{
+    ++device_plans;
+    if (w.d != w.mask || w.d % 256 != 0) return CKPT_ERR_DEVICE;  // nothing staged in the layout it is handed
+    const int rc = ragged_make_plan(offsets_dev, batch, max_layers, plan);
+    plan.groups.clear();
+    plan.tile_first2.clear();
+    return rc;
 }
 }  // namespace ckpt
 
@@ -159,6 +176,17 @@ int main()
         CHECK(ckpt_ragged_eval_peak(d, mask, off, nullptr, 5, 1, out, nullptr, big_ws, sizeof(big_ws), nullptr) == CKPT_OK);
         CHECK(ckpt_ragged_eval_timeline(d, mask, off, nullptr, 5, 0, out, nullptr, big_ws, sizeof(big_ws), nullptr) == CKPT_OK);
         CHECK(ckpt::ragged_runs == 3);
+        // with a device copy of the offsets the plan comes from the device side (not for the cubic solver)
+        CHECK(ckpt::device_plans == 0);
+        CHECK(ckpt_ragged_solve_linear(d, nullptr, off, 5, mask, out, nullptr, big_ws, sizeof(big_ws), nullptr) == CKPT_OK);
+        CHECK(ckpt_ragged_eval_timeline(d, mask, off, off, 5, 0, out, nullptr, big_ws, sizeof(big_ws), nullptr) == CKPT_OK);
+        CHECK(ckpt_ragged_eval_peak(d, mask, off, off, 5, 1, out, nullptr, ws, 4096, nullptr) == CKPT_ERR_WORKSPACE);
+        CHECK(ckpt::device_plans == 2 && ckpt::ragged_runs == 5);
+        CHECK(ckpt_ragged_solve_linear(d, off, off, -1, mask, out, nullptr, big_ws, sizeof(big_ws), nullptr) == CKPT_ERR_SHAPE);
+        CHECK(ckpt_ragged_solve_linear(d, off, off, 0, mask, out, nullptr, big_ws, sizeof(big_ws), nullptr) == CKPT_OK);
+        CHECK(ckpt_ragged_solve_linear(nullptr, off, off, 5, mask, out, nullptr, big_ws, sizeof(big_ws), nullptr) == CKPT_ERR_NULL);
+        CHECK(ckpt_ragged_solve_cubic(d, off, off, 5, mask, out, out + 64, nullptr, big_ws, sizeof(big_ws), nullptr) == CKPT_OK);
+        CHECK(ckpt::device_plans == 2 && ckpt::ragged_runs == 6);
         // a large batch of mixed lengths: the plan's counting sort and the sizes it adds up
         const int64_t many = 200000;
         int64_t *offs = (int64_t *)std::malloc((size_t)(many + 1) * sizeof(int64_t));

@@ -119,6 +119,8 @@ def test_ragged_host_checks():
     fake = ctypes.c_void_p(4096)        # never dereferenced: validation fails first
     assert lib.ckpt_ragged_solve_linear(fake, ptr, None, 3, fake, fake, None, fake, 16, None) == 6
     assert lib.ckpt_ragged_solve_linear(fake, ptr, fake, 3, None, fake, None, fake, 1 << 30, None) == 1
-    assert lib.ckpt_ragged_solve_linear(fake, None, fake, 3, fake, fake, None, fake, 1 << 30, None) == 1
+    # offsets in neither place; the cubic solver plans on the host and needs them there
+    assert lib.ckpt_ragged_solve_linear(fake, None, None, 3, fake, fake, None, fake, 1 << 30, None) == 1
+    assert lib.ckpt_ragged_solve_cubic(fake, None, fake, 3, fake, fake, fake, None, fake, 1 << 30, None) == 1
     assert lib.ckpt_ragged_eval_peak(fake, fake, ptr, None, 3, 2, fake, None, fake, 1 << 30, None) == 2
     assert lib.ckpt_ragged_solve_cubic(None, ptr, None, 0, None, None, None, None, None, 0, None) == 0

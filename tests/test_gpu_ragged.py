@@ -172,6 +172,36 @@ def test_many_distinct_lengths_and_repeated_calls():
         assert np.array_equal(np_(peak), want_peak) and np.array_equal(np_(mask), want_mask)
 
 
+def test_offsets_counted_on_the_device_are_checked_there():
+    """With a device copy of the offsets the lengths are counted on the GPU and the host's copy is
+    not read: an offset out of range in the device copy ends the call with CKPT_ERR_SHAPE before
+    any chain is touched, and the next call on the same workspace is as good as ever."""
+    lengths = np.array([15, 3, 24, 15, 70, 1, 300] * 11, dtype=np.int64)
+    d, m, off = inputs.ragged_batch(31, lengths)
+    dd, md = to_dev(d), to_dev(m)
+    need = max(B.load().ckpt_ragged_workspace_bytes(which, off.ctypes.data, len(lengths))
+               for which in (B.CALL_SOLVE_LINEAR, B.CALL_EVAL_PEAK))
+    ws = torch.empty(need, dtype=torch.uint8, device=DEV)
+    for at, value in ((5, off[4]), (9, off[10] - 1), (0, -8), (len(lengths), 1 << 60), (20, off[19] + 70000)):
+        bad = off.copy()
+        bad[at] = value                                        # decreasing, one element, negative, huge, too long
+        say(f"offsets_dev[{at}] = {value}")
+        for call in (lambda: B.ckpt_ragged_solve_linear(dd, off, workspace=ws, offsets_dev=to_dev(bad)),
+                     lambda: B.ckpt_ragged_eval_peak(dd, md, off, B.OBJ_STATIC, workspace=ws, offsets_dev=to_dev(bad))):
+            with pytest.raises(B.CkptError) as err:
+                call()
+            assert err.value.code == 2                         # CKPT_ERR_SHAPE
+        torch.cuda.synchronize()
+    mask, peak, status = B.ckpt_ragged_solve_linear(dd, off, workspace=ws, offsets_dev=to_dev(off))
+    want_peak, want_mask = oracle.ragged_solve_dynamic(d, off)
+    assert (np_(status) == 0).all() and np.array_equal(np_(peak), want_peak) and np.array_equal(np_(mask), want_mask)
+    # a workspace that holds the tables but not the staging is refused after the count
+    small = torch.empty(300 * 1024, dtype=torch.uint8, device=DEV)
+    with pytest.raises(B.CkptError) as err:
+        B.ckpt_ragged_eval_timeline(dd, md, off, B.OBJ_DYNAMIC, workspace=small, offsets_dev=to_dev(off))
+    assert err.value.code == 6                                 # CKPT_ERR_WORKSPACE
+
+
 def test_host_checks_and_the_empty_batch():
     d, m, off = inputs.ragged_batch(16, [4, 5])
     dd = to_dev(d)
