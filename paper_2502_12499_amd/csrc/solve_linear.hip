@@ -191,7 +191,7 @@ __device__ __forceinline__ void linear_ring_wave(const int64_t *__restrict__ d, 
     // (M, GJ) of the three entries under the head, read back after every push so
     // that the steps that follow find them in registers (what lies beyond the
     // crossover entry is never looked at, so it does not matter what they hold there)
-    uint32_t M1 = 0, G1 = 0, M2 = 0, G2 = 0, M3 = 0, G3 = 0;
+    uint32_t M1 = 0, G1 = 0, M2 = 0, G2 = 0, M3 = 0, G3 = 0, M4 = 0, G4 = 0;
     uint32_t Tpt = 0, Jpt = n, Rp = 0;         // crossover entry: T(j), j (only its low byte is kept up), R(i, j)
     uint32_t Jfull = n;                        // its position in full, as of the last chunk check
     uint32_t Mc = kNone, Ac = kNone, Jc = 0, Rc = 0;  // candidate (the entry before pt): M, A, j, R(i, j)
@@ -229,6 +229,7 @@ __device__ __forceinline__ void linear_ring_wave(const int64_t *__restrict__ d, 
                 }
                 Mhd <<= kk; Ghd = scale_gj(Ghd); Tpt <<= kk; Rp <<= kk; Rc <<= kk;
                 M1 <<= kk; G1 = scale_gj(G1); M2 <<= kk; G2 = scale_gj(G2); M3 <<= kk; G3 = scale_gj(G3);
+                M4 <<= kk; G4 = scale_gj(G4);
                 Mc = Mc == kNone ? kNone : Mc << kk;
                 Ac = Ac == kNone ? kNone : Ac << kk;
                 Ti <<= kk; dnext <<= kk; dmax <<= kk;
@@ -374,10 +375,13 @@ __device__ __forceinline__ void linear_ring_wave(const int64_t *__restrict__ d, 
             hd -= p1 ? kStep : 0u;
             hd -= p2 ? kStep : 0u;
             if (__builtin_amdgcn_ballot_w64(p3) != 0) {
-                // more: from the ring, one at a time, down to the crossover entry at the latest.
-                // The lanes concerned go on from the third mirror; the others fail the first test.
-                Mhd = p3 ? M3 : 0u;
-                Ghd = G3;
+                // more: the third mirror goes too, and the lanes concerned go on with the fourth (the
+                // others fail the first test), then from the ring, one at a time, down to the
+                // crossover entry at the latest.
+                Gacc = p3 ? (G3 > Gacc ? G3 : Gacc) : Gacc;
+                hd -= p3 ? kStep : 0u;
+                Mhd = p3 ? M4 : 0u;
+                Ghd = G4;
                 uint32_t ad;
                 uint64_t sv;
                 asm volatile(
@@ -416,6 +420,8 @@ __device__ __forceinline__ void linear_ring_wave(const int64_t *__restrict__ d, 
             M1 = e1[0]; G1 = e1[kGJ];
             M2 = e2[0]; G2 = e2[kGJ];
             M3 = e3[0]; G3 = e3[kGJ];
+            LdsPtr e4 = entry(hd - 4 * kStep);
+            M4 = e4[0]; G4 = e4[kGJ];
         }
         const bool fresh = hd == pt + kStep;  // the new entry is the candidate; R(i', i) starts empty
         Mc = fresh ? Mi : Mc;
