@@ -172,6 +172,19 @@ def test_many_distinct_lengths_and_repeated_calls():
         assert np.array_equal(np_(peak), want_peak) and np.array_equal(np_(mask), want_mask)
 
 
+def test_long_chains_counted_on_the_device():
+    """Lengths on both sides of the limit up to which the device's count adds up per workgroup
+    first, one group of a single chain next to another, and a batch of one chain."""
+    lengths = np.array([4096, 5000, 4095, 1, 7000, 5000, 4096, 2], dtype=np.int64)
+    d, m, off = inputs.ragged_batch(41, lengths)
+    say(f"ragged, lengths {lengths.tolist()}")
+    check_eval(d, m, off)
+    check_linear(d, off)
+    d, m, off = inputs.ragged_batch(42, np.array([9000], dtype=np.int64))
+    check_eval(d, m, off)
+    check_linear(d, off)
+
+
 def test_offsets_counted_on_the_device_are_checked_there():
     """With a device copy of the offsets the lengths are counted on the GPU and the host's copy is
     not read: an offset out of range in the device copy ends the call with CKPT_ERR_SHAPE before
