@@ -28,7 +28,9 @@
 // need nothing else, so that objective reads 9(n+1) bytes and writes 16(n+1)
 // per chain, which is what the method itself has to move.  Algorithm 2's
 // stages all contain the sum of ALL checkpoints, which is only known at the
-// end of the chain, so that objective reads the chain once more beforehand.
+// end of the chain, so that objective passes over the chain once more
+// beforehand; chains of up to 160 layers whose sizes fit 31 bits are left in
+// LDS by that pass, and the walk reads them from there.
 #include "ckpt_internal.h"
 
 namespace ckpt {
@@ -36,18 +38,19 @@ namespace {
 
 constexpr int kBlock = 64;
 constexpr int kChunk = 8;
+// Under Algorithm 2 the chains of up to this many layers are kept in LDS between the two passes
+// (256 bytes per row and wave: 40 KB at most, so that four waves still fit a CU; with fewer the
+// kernel is slower than reading the chain twice: 2.8 ms against 2.0 ms at n = 256).
+constexpr int kLdsRowsMaxLayers = 160;
 
-// The timeline of chain c of a batch laid out by the strides (the lanes of a wave call it together).
-template <int OBJ>
-__device__ __forceinline__ void eval_timeline_chain(const int64_t *__restrict__ d, const uint8_t *__restrict__ mask,
-                                                    int64_t batch, int n, int64_t cstride, int64_t pstride,
-                                                    int64_t *__restrict__ out, int64_t ocstride, int64_t opstride,
-                                                    int32_t *__restrict__ status_out, const int64_t c)
+// The walk up the chain that writes both stages of every row.  ld(r) and lm(r) give the size and
+// the mask byte of row r, 1 <= r <= n (from memory, or from the copy the first pass left in LDS).
+template <int OBJ, class LD, class LM>
+__device__ __forceinline__ void timeline_walk(const LD ld, const LM lm, const int n, const int64_t x0,
+                                              const bool bad_mask, const uint64_t ckpt_all,
+                                              int64_t *__restrict__ op, const int64_t opstride,
+                                              int32_t *__restrict__ status_out, const int64_t c)
 {
-    if (c >= batch) return;
-    const int64_t *dp = d + c * cstride;
-    const uint8_t *mp = mask + c * cstride;
-    int64_t *op = out + c * ocstride;
     const int64_t last = 2 * (int64_t)n + 1;
     // the part of a segment above a row: its largest size (Algorithm 3) or its sum (Algorithm 2).
     // Sums are unsigned so that an invalid chain cannot trip signed overflow.
@@ -55,31 +58,18 @@ __device__ __forceinline__ void eval_timeline_chain(const int64_t *__restrict__ 
         return OBJ == CKPT_OBJ_STATIC ? acc + (uint64_t)x : ((uint64_t)x > acc ? (uint64_t)x : acc);
     };
 
-    const int64_t x0 = dp[0];
-    uint64_t ckpt_all = 0;  // sum of all checkpoints (Algorithm 2 only)
-    if (OBJ == CKPT_OBJ_STATIC) {
-        // both loads of a row are issued whatever the mask says, so that sixteen rows are in flight
-#pragma unroll 16
-        for (int k = 0; k <= n; ++k) {
-            const uint8_t on = mp[(int64_t)k * pstride];
-            const int64_t x = dp[(int64_t)k * pstride];
-            ckpt_all += on ? (uint64_t)x : 0;
-        }
-    }
-
     // rows beyond n re-read row n and are not used
     // the masks of a chunk that has arrived are kept as one bit per row
     int64_t cur_d[kChunk], nxt_d[kChunk];
     uint32_t cur_m = 0, nxt_m = 0;
 #pragma unroll
     for (int u = 0; u < kChunk; ++u) {
-        const int64_t a = (int64_t)min(1 + u, n) * pstride, b = (int64_t)min(1 + kChunk + u, n) * pstride;
-        cur_d[u] = dp[a]; cur_m |= (uint32_t)(mp[a] != 0) << u;
-        nxt_d[u] = dp[b]; nxt_m |= (uint32_t)(mp[b] != 0) << u;
+        const int a = min(1 + u, n), b = min(1 + kChunk + u, n);
+        cur_d[u] = ld(a); cur_m |= (uint32_t)(lm(a) != 0) << u;
+        nxt_d[u] = ld(b); nxt_m |= (uint32_t)(lm(b) != 0) << u;
     }
 
     bool bad_size = x0 <= 0, ovf = false;
-    const bool bad_mask = mp[0] == 0 || mp[(int64_t)n * pstride] == 0;
     uint64_t total = (uint64_t)x0;
     int64_t dmax = x0;
 
@@ -94,8 +84,8 @@ __device__ __forceinline__ void eval_timeline_chain(const int64_t *__restrict__ 
         uint8_t far_m[kChunk];
 #pragma unroll
         for (int u = 0; u < kChunk; ++u) {
-            const int64_t a = (int64_t)min(k0 + 2 * kChunk + u, n) * pstride;
-            far_d[u] = dp[a]; far_m[u] = mp[a];
+            const int a = min(k0 + 2 * kChunk + u, n);
+            far_d[u] = ld(a); far_m[u] = lm(a);
         }
 
         // what lies above the chunk's last row: d from the next chunk's first row up to (not
@@ -128,8 +118,8 @@ __device__ __forceinline__ void eval_timeline_chain(const int64_t *__restrict__ 
                 uint8_t more_m[kChunk];
 #pragma unroll
                 for (int u = 0; u < kChunk; ++u) {
-                    const int64_t a = (int64_t)min(kb + u, n) * pstride;
-                    more_d[u] = dp[a]; more_m[u] = mp[a];
+                    const int a = min(kb + u, n);
+                    more_d[u] = ld(a); more_m[u] = lm(a);
                 }
                 scan(more_d, bits(more_m), kb);
             }
@@ -191,6 +181,54 @@ __device__ __forceinline__ void eval_timeline_chain(const int64_t *__restrict__ 
         for (int64_t t = 0; t <= last; ++t) op[t * opstride] = -1;
 }
 
+// The timeline of chain c of a batch laid out by the strides (the lanes of a wave call it together).
+// LDS_ROWS (Algorithm 2 only; `rows` is LDS for n x 64 words): the pass that adds up the checkpoints
+// leaves row r >= 1 of each lane's chain in rows[r-1][lane] as size | mask << 31, and if every size
+// of every chain of the wave is below 2^31 the walk reads the chain from there instead of from
+// memory a second time.
+template <int OBJ, bool LDS_ROWS>
+__device__ __forceinline__ void eval_timeline_chain(const int64_t *__restrict__ d, const uint8_t *__restrict__ mask,
+                                                    int64_t batch, int n, int64_t cstride, int64_t pstride,
+                                                    int64_t *__restrict__ out, int64_t ocstride, int64_t opstride,
+                                                    int32_t *__restrict__ status_out, const int64_t c, uint32_t *rows)
+{
+    static_assert(!LDS_ROWS || OBJ == CKPT_OBJ_STATIC, "only Algorithm 2 reads the chain twice");
+    if (c >= batch) return;
+    const int64_t *dp = d + c * cstride;
+    const uint8_t *mp = mask + c * cstride;
+    int64_t *op = out + c * ocstride;
+    const int lane = threadIdx.x % kBlock;
+
+    const int64_t x0 = dp[0];
+    uint64_t ckpt_all = 0;  // sum of all checkpoints (Algorithm 2 only)
+    bool narrow = true;
+    if (OBJ == CKPT_OBJ_STATIC) {
+        // both loads of a row are issued whatever the mask says, so that sixteen rows are in flight
+#pragma unroll 16
+        for (int k = 0; k <= n; ++k) {
+            const uint8_t on = mp[(int64_t)k * pstride];
+            const int64_t x = dp[(int64_t)k * pstride];
+            ckpt_all += on ? (uint64_t)x : 0;
+            if (LDS_ROWS && k >= 1) {
+                rows[(k - 1) * kBlock + lane] = (uint32_t)x | (on ? 0x80000000u : 0u);
+                narrow &= ((uint64_t)x >> 31) == 0;
+            }
+        }
+    }
+    const bool bad_mask = mp[0] == 0 || mp[(int64_t)n * pstride] == 0;
+    auto ld_mem = [&](int r) -> int64_t { return dp[(int64_t)r * pstride]; };
+    auto lm_mem = [&](int r) -> uint8_t { return mp[(int64_t)r * pstride]; };
+    if (LDS_ROWS) {
+        if (__builtin_amdgcn_ballot_w64(!narrow) == 0) {
+            auto ld_lds = [&](int r) -> int64_t { return (int64_t)(rows[(r - 1) * kBlock + lane] & 0x7fffffffu); };
+            auto lm_lds = [&](int r) -> uint8_t { return (uint8_t)(rows[(r - 1) * kBlock + lane] >> 31); };
+            timeline_walk<OBJ>(ld_lds, lm_lds, n, x0, bad_mask, ckpt_all, op, opstride, status_out, c);
+            return;
+        }
+    }
+    timeline_walk<OBJ>(ld_mem, lm_mem, n, x0, bad_mask, ckpt_all, op, opstride, status_out, c);
+}
+
 template <int OBJ>
 __global__ __launch_bounds__(kBlock) void eval_timeline_kernel(const int64_t *__restrict__ d,
                                                                const uint8_t *__restrict__ mask, int64_t batch,
@@ -199,7 +237,23 @@ __global__ __launch_bounds__(kBlock) void eval_timeline_kernel(const int64_t *__
                                                                int64_t opstride, int32_t *__restrict__ status_out)
 {
     const int64_t c = (int64_t)xcd_paired_block(blockIdx.x, gridDim.x) * kBlock + threadIdx.x;
-    eval_timeline_chain<OBJ>(d, mask, batch, n, cstride, pstride, out, ocstride, opstride, status_out, c);
+    eval_timeline_chain<OBJ, false>(d, mask, batch, n, cstride, pstride, out, ocstride, opstride, status_out, c,
+                                    nullptr);
+}
+
+// Algorithm 2 for chains short enough that a wave's 64 chains fit in LDS four times per CU (n words
+// per lane, launched with n * 256 bytes of dynamic LDS): the chain is read from memory once.
+extern __shared__ __align__(16) uint32_t timeline_rows[];
+__global__ __launch_bounds__(kBlock) void eval_timeline_static_lds_kernel(const int64_t *__restrict__ d,
+                                                                          const uint8_t *__restrict__ mask,
+                                                                          int64_t batch, int n, int64_t cstride,
+                                                                          int64_t pstride, int64_t *__restrict__ out,
+                                                                          int64_t ocstride, int64_t opstride,
+                                                                          int32_t *__restrict__ status_out)
+{
+    const int64_t c = (int64_t)xcd_paired_block(blockIdx.x, gridDim.x) * kBlock + threadIdx.x;
+    eval_timeline_chain<CKPT_OBJ_STATIC, true>(d, mask, batch, n, cstride, pstride, out, ocstride, opstride, status_out,
+                                               c, timeline_rows);
 }
 
 // Every group of a ragged call in one launch: a wave looks up the group its 64 chains belong to and
@@ -214,8 +268,8 @@ __global__ __launch_bounds__(kBlock) void eval_timeline_ragged_kernel(const int6
 {
     const RaggedGroupDev g = groups[ragged_group_of_wave(groups, n_groups, blockIdx.x)];
     const int64_t c = ((int64_t)blockIdx.x - g.wave_first) * kBlock + threadIdx.x;
-    eval_timeline_chain<OBJ>(d_stage + g.stage_off, mask_stage + g.stage_off, g.count, g.n, 1, g.pitch,
-                             wide_stage + 2 * g.stage_off, 1, g.pitch, status_stage + g.first, c);
+    eval_timeline_chain<OBJ, false>(d_stage + g.stage_off, mask_stage + g.stage_off, g.count, g.n, 1, g.pitch,
+                                    wide_stage + 2 * g.stage_off, 1, g.pitch, status_stage + g.first, c, nullptr);
 }
 
 // Checkpoint sets that do not depend on the sizes: the two ends only, every
@@ -253,7 +307,10 @@ hipError_t launch_eval_timeline(const int64_t *d, const uint8_t *mask, int64_t b
 {
     if (batch == 0) return hipSuccess;
     const unsigned grid = (unsigned)((batch + kBlock - 1) / kBlock);
-    if (objective == CKPT_OBJ_STATIC)
+    if (objective == CKPT_OBJ_STATIC && n <= kLdsRowsMaxLayers)
+        hipLaunchKernelGGL(eval_timeline_static_lds_kernel, dim3(grid), dim3(kBlock), (size_t)n * kBlock * 4, stream, d,
+                           mask, batch, n, st.chain, st.pos, out, out_st.chain, out_st.pos, status_out);
+    else if (objective == CKPT_OBJ_STATIC)
         hipLaunchKernelGGL(eval_timeline_kernel<CKPT_OBJ_STATIC>, dim3(grid), dim3(kBlock), 0, stream, d, mask,
                            batch, n, st.chain, st.pos, out, out_st.chain, out_st.pos, status_out);
     else

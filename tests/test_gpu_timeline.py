@@ -39,6 +39,22 @@ def test_timeline_batches(batch, n):
     check_timeline(inputs.log_uniform_chains(21, n, batch), inputs.bernoulli_masks(21, n, batch))
 
 
+def test_timeline_sizes_on_both_sides_of_31_bits():
+    """Short chains under Algorithm 2 are kept in LDS as 31-bit sizes between the two passes; a wave
+    with a larger size anywhere reads its chains from memory again.  Waves of both kinds, and sizes
+    of exactly 2^31 - 1 and 2^31, at lengths on both sides of the limit for the LDS copy."""
+    for n in (5, 64, 160, 161):
+        batch = 64 * 5 + 17
+        d = inputs.log_uniform_chains(33, n, batch)
+        m = inputs.bernoulli_masks(33, n, batch)
+        d[n // 2, 70] = (1 << 31) - 1          # second wave: still narrow
+        d[n, 130] = 1 << 31                    # third wave: not any more (last row)
+        d[1, 200] = (1 << 40) + 12345          # fourth wave (first row above row 0)
+        d[0, 300] = (1 << 35) + 1              # fifth wave: row 0 never goes through LDS
+        say(f"eval_timeline n={n}: sizes around 2^31")
+        check_timeline(d, m)
+
+
 def test_timeline_fixed_sets():
     say("eval_timeline: VGG-19 with the paper's sets, the extreme sets")
     d = inputs.vgg19_chain()
