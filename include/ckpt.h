@@ -61,7 +61,8 @@ typedef enum {
 
 typedef enum {
     CKPT_OBJ_STATIC = 0,  /* Equation (cost), Section 3.1: all checkpoints + largest segment */
-    CKPT_OBJ_DYNAMIC = 1  /* Equation (memory), Section 4: early release + output-gradient buffer */
+    CKPT_OBJ_DYNAMIC = 1, /* Equation (memory), Section 4: early release + output-gradient buffer */
+    CKPT_OBJ_BOTH = 2     /* ckpt_eval_peak only: both of the above from one pass over the chains */
 } ckpt_objective;
 
 /* Checkpoint sets that do not look at the sizes (ckpt_select_baseline). */
@@ -102,9 +103,13 @@ size_t ckpt_workspace_bytes(int which, const ckpt_layout *layout);
  *   CKPT_OBJ_DYNAMIC: Equation (memory), the model of Algorithm 3 - the
  *       largest, over checkpoints i with previous checkpoint h, of
  *       sum_{c in C, c <= i} d_c + sum_{h<k<i} d_k + max_{h<=k<i} d_k.
+ *   CKPT_OBJ_BOTH   : both (Section 5 compares a set's memory under the two
+ *       models): the chains are read once, peak_out receives 2 * batch values,
+ *       the static peaks first (peak_out[c]), then the dynamic ones
+ *       (peak_out[batch + c]); a chain's status is the same under either.
  * d [in] sizes, mask [in] checkpoint bytes (non-zero = checkpoint), both in
- * `layout`; peak_out [out] `batch` int64; status_out [out] `batch` int32 or
- * NULL. */
+ * `layout`; peak_out [out] `batch` int64 (2 * batch with CKPT_OBJ_BOTH);
+ * status_out [out] `batch` int32 or NULL. */
 int ckpt_eval_peak(const int64_t *d, const uint8_t *mask, const ckpt_layout *layout,
                    int objective, int64_t *peak_out, int32_t *status_out,
                    void *ws, size_t ws_bytes, void *hip_stream);

@@ -19,7 +19,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libckpt_hip.so")
 
 CKPT_OK = 0
-OBJ_STATIC, OBJ_DYNAMIC = 0, 1
+OBJ_STATIC, OBJ_DYNAMIC, OBJ_BOTH = 0, 1, 2
 CALL_EVAL_PEAK, CALL_SOLVE_CUBIC, CALL_SOLVE_LINEAR, CALL_EVAL_TIMELINE = 0, 1, 2, 3
 
 SELECT_ENDS, SELECT_ALL, SELECT_SQRT = 0, 1, 2
@@ -160,10 +160,12 @@ def _check_inputs(d, mask=None):
 
 
 def ckpt_eval_peak(d, mask, objective, chain_major=False, want_status=True):
-    """Peak memory of each chain's checkpoint set.  Returns (peak, status)."""
+    """Peak memory of each chain's checkpoint set.  Returns (peak, status); with OBJ_BOTH peak has
+    shape (2, batch): the static peaks, then the dynamic ones."""
     _check_inputs(d, mask)
     L = layout_of(d, chain_major)
-    peak = torch.empty(L.batch, dtype=torch.int64, device=d.device)
+    shape = (2, L.batch) if int(objective) == OBJ_BOTH else (L.batch,)
+    peak = torch.empty(shape, dtype=torch.int64, device=d.device)
     status = torch.empty(L.batch, dtype=torch.int32, device=d.device) if want_status else None
     rc = load().ckpt_eval_peak(_ptr(d), _ptr(mask), ctypes.byref(L), int(objective), _ptr(peak), _ptr(status),
                                None, 0, _stream())

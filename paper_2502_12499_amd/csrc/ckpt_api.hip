@@ -64,7 +64,8 @@ int ckpt_eval_peak(const int64_t *d, const uint8_t *mask, const ckpt_layout *L, 
     (void)ws_bytes;  // the evaluation keeps all its state in registers
     const int rc = check_layout(L, CKPT_MAX_LAYERS);
     if (rc != CKPT_OK) return rc;
-    if (objective != CKPT_OBJ_STATIC && objective != CKPT_OBJ_DYNAMIC) return CKPT_ERR_SHAPE;
+    if (objective != CKPT_OBJ_STATIC && objective != CKPT_OBJ_DYNAMIC && objective != CKPT_OBJ_BOTH)
+        return CKPT_ERR_SHAPE;
     if (L->batch == 0) return CKPT_OK;
     if (!d || !mask || !peak_out) return CKPT_ERR_NULL;
     return finish(ckpt::launch_eval_peak(d, mask, L->batch, L->n_layers, Strides{L->chain_stride, L->pos_stride},

@@ -13,7 +13,9 @@ namespace {
 
 constexpr int kBlock = 64;
 
-// The evaluation of chain c of a batch laid out by (cstride, pstride).
+// The evaluation of chain c of a batch laid out by (cstride, pstride).  OBJ = CKPT_OBJ_BOTH keeps
+// the running values of both objectives and writes the dynamic peak `batch` values after the
+// static one.
 template <int OBJ>
 __device__ __forceinline__ void eval_peak_chain(const int64_t *__restrict__ d, const uint8_t *__restrict__ mask,
                                        int64_t batch, int n, int64_t cstride, int64_t pstride,
@@ -34,9 +36,12 @@ __device__ __forceinline__ void eval_peak_chain(const int64_t *__restrict__ d, c
 
     int64_t ckpt_sum = x0;  // sum of checkpoints seen so far
     int64_t seg_sum = 0;    // sum of non-checkpoints since the last checkpoint
-    int64_t seg_max = x0;   // max over d_h..d_{k-1}, h the last checkpoint (OBJ 1)
-    int64_t best = 0;       // OBJ 0: largest segment; OBJ 1: largest m(i)
+    int64_t seg_max = x0;   // max over d_h..d_{k-1}, h the last checkpoint (Equation (memory))
+    int64_t best = 0;       // Equation (cost): largest segment, else Equation (memory): largest m(i)
+    int64_t best_dyn = 0;   // the latter when both are wanted
     uint8_t last_mask = 1;
+    constexpr bool kStatic = OBJ == CKPT_OBJ_STATIC || OBJ == CKPT_OBJ_BOTH;
+    constexpr bool kDynamic = OBJ == CKPT_OBJ_DYNAMIC || OBJ == CKPT_OBJ_BOTH;
 
 #pragma unroll 16
     for (int k = 1; k <= n; ++k) {
@@ -49,17 +54,19 @@ __device__ __forceinline__ void eval_peak_chain(const int64_t *__restrict__ d, c
         last_mask = m;
         if (m) {
             ckpt_sum += x;
-            if (OBJ == CKPT_OBJ_STATIC) {
-                best = seg_sum > best ? seg_sum : best;
-            } else {
+            if (kStatic) best = seg_sum > best ? seg_sum : best;
+            if (kDynamic) {
                 const int64_t mi = ckpt_sum + seg_sum + seg_max;
-                best = mi > best ? mi : best;
+                if (OBJ == CKPT_OBJ_BOTH)
+                    best_dyn = mi > best_dyn ? mi : best_dyn;
+                else
+                    best = mi > best ? mi : best;
                 seg_max = x;
             }
             seg_sum = 0;
         } else {
             seg_sum += x;
-            if (OBJ == CKPT_OBJ_DYNAMIC) seg_max = x > seg_max ? x : seg_max;
+            if (kDynamic) seg_max = x > seg_max ? x : seg_max;
         }
     }
     bad_mask |= last_mask == 0;
@@ -70,8 +77,9 @@ __device__ __forceinline__ void eval_peak_chain(const int64_t *__restrict__ d, c
     else if (ovf) status = CKPT_ERR_OVERFLOW;
     else if (bad_mask) status = CKPT_ERR_MASK;
 
-    int64_t peak = (OBJ == CKPT_OBJ_STATIC) ? ckpt_sum + best : best;
+    int64_t peak = kStatic ? ckpt_sum + best : best;
     peak_out[c] = status == CKPT_OK ? peak : -1;
+    if (OBJ == CKPT_OBJ_BOTH) peak_out[batch + c] = status == CKPT_OK ? best_dyn : -1;
     if (status_out) status_out[c] = status;
 }
 
@@ -112,8 +120,11 @@ hipError_t launch_eval_peak(const int64_t *d, const uint8_t *mask, int64_t batch
     if (objective == CKPT_OBJ_STATIC)
         hipLaunchKernelGGL(eval_peak_kernel<CKPT_OBJ_STATIC>, dim3(grid), dim3(kBlock), 0, stream, d, mask,
                            batch, n, st.chain, st.pos, peak_out, status_out);
-    else
+    else if (objective == CKPT_OBJ_DYNAMIC)
         hipLaunchKernelGGL(eval_peak_kernel<CKPT_OBJ_DYNAMIC>, dim3(grid), dim3(kBlock), 0, stream, d, mask,
+                           batch, n, st.chain, st.pos, peak_out, status_out);
+    else
+        hipLaunchKernelGGL(eval_peak_kernel<CKPT_OBJ_BOTH>, dim3(grid), dim3(kBlock), 0, stream, d, mask,
                            batch, n, st.chain, st.pos, peak_out, status_out);
     return hipGetLastError();
 }

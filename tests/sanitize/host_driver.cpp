@@ -121,6 +121,8 @@ int main()
     const ckpt_layout ok = {4, 8, 1, 4};
     CHECK(ckpt_eval_timeline(d, mask, &ok, 1, out, big / 2, big / 2, nullptr, nullptr) == CKPT_ERR_SHAPE);
     CHECK(ckpt_eval_peak(d, mask, &ok, 7, out, nullptr, nullptr, 0, nullptr) == CKPT_ERR_SHAPE);
+    CHECK(ckpt_eval_peak(d, mask, &ok, 3, out, nullptr, nullptr, 0, nullptr) == CKPT_ERR_SHAPE);
+    CHECK(ckpt_eval_timeline(d, mask, &ok, CKPT_OBJ_BOTH, out, 1, 4, nullptr, nullptr) == CKPT_ERR_SHAPE);
     CHECK(ckpt_eval_peak(nullptr, mask, &ok, 0, out, nullptr, nullptr, 0, nullptr) == CKPT_ERR_NULL);
     CHECK(ckpt_solve_linear(d, &ok, mask, out, nullptr, ws, 8, nullptr) == CKPT_ERR_WORKSPACE);
     CHECK(ckpt_solve_linear(d, &ok, mask, out, nullptr, (char *)ws + 8, 1 << 15, nullptr) == CKPT_ERR_WORKSPACE);
@@ -128,6 +130,7 @@ int main()
     CHECK(ckpt::launches == 0);
     // and the calls that are in order reach their launcher exactly once each
     CHECK(ckpt_eval_peak(d, mask, &ok, 1, out, nullptr, nullptr, 0, nullptr) == CKPT_OK);
+    CHECK(ckpt_eval_peak(d, mask, &ok, CKPT_OBJ_BOTH, out, nullptr, nullptr, 0, nullptr) == CKPT_OK);
     CHECK(ckpt_eval_timeline(d, mask, &ok, 0, out, 1, 4, nullptr, nullptr) == CKPT_OK);
     CHECK(ckpt_select_baseline(&ok, 2, mask, nullptr) == CKPT_OK);
     CHECK(ckpt_solve_linear(d, &ok, mask, out, nullptr, ws, 1 << 15, nullptr) == CKPT_OK);
@@ -138,7 +141,7 @@ int main()
     CHECK(ckpt_solve_cubic_costs(d, &ok, mask, out, nullptr, nullptr, out, nullptr, ws, 1 << 15, nullptr) == CKPT_ERR_NULL);
     CHECK(ckpt_solve_cubic_costs(d, &ok, mask, out, nullptr, out, out, nullptr, ws, 1 << 15, nullptr) == CKPT_OK);
     CHECK(ckpt_cubic_costs_len(8) == 64 && ckpt_cubic_costs_len(12) == 128 && ckpt_cubic_costs_len(0) == 0);
-    CHECK(ckpt::launches == 9);
+    CHECK(ckpt::launches == 10);
     CHECK(ckpt_cubic_cells(8191) == ((int64_t)8191 * 8190 / 2 + 1) * 8191 && ckpt_cubic_cells(0) == 0);
     // ragged batches: the grouping by length and the workspace layout are host code (csrc/ragged.hip);
     // only calls that end before any device work are made here
@@ -195,7 +198,7 @@ int main()
         for (int64_t c = 0; c < many; ++c) offs[c + 1] = offs[c] + 2 + (c * 7919) % 300;
         CHECK(ckpt_ragged_workspace_bytes(CKPT_CALL_EVAL_TIMELINE, offs, many) > (size_t)many * 12);
         std::free(offs);
-        CHECK(ckpt::launches == 9);
+        CHECK(ckpt::launches == 10);
     }
     for (int s = -1; s < 10; ++s) CHECK(ckpt_status_string(s) != nullptr);
     std::printf("host_driver ok\n");

@@ -68,7 +68,7 @@ def test_host_detectable_errors_return_without_launching():
     fake = ctypes.c_void_p(4096)  # never dereferenced: every call below fails validation first
     assert lib.ckpt_eval_peak(fake, fake, None, 0, fake, None, None, 0, None) == 1
     assert lib.ckpt_eval_peak(None, fake, ctypes.byref(L), 0, fake, None, None, 0, None) == 1
-    assert lib.ckpt_eval_peak(fake, fake, ctypes.byref(L), 2, fake, None, None, 0, None) == 2
+    assert lib.ckpt_eval_peak(fake, fake, ctypes.byref(L), 3, fake, None, None, 0, None) == 2
     assert lib.ckpt_solve_linear(fake, ctypes.byref(B.Layout(4, 0, 1, 4)), fake, fake, None, fake, 1 << 20, None) == 2
     assert lib.ckpt_solve_linear(fake, ctypes.byref(L), fake, fake, None, None, 0, None) == 1
     assert lib.ckpt_solve_linear(fake, ctypes.byref(L), fake, fake, None, fake, 16, None) == 6      # too small

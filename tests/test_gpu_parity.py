@@ -41,6 +41,15 @@ def check_eval(d, m, chain_major=False):
         want = oracle.batch_peak(dc, mc, obj)
         assert (np_(status) == 0).all()
         assert np.array_equal(np_(peak), want), f"objective {obj}"
+    # both objectives from one pass over the chains
+    if chain_major:
+        peak, status = B.ckpt_eval_peak(to_dev(dc), to_dev(mc), B.OBJ_BOTH, chain_major=True)
+    else:
+        peak, status = B.ckpt_eval_peak(to_dev(d), to_dev(m), B.OBJ_BOTH)
+    torch.cuda.synchronize()
+    assert (np_(status) == 0).all() and peak.shape == (2, d.shape[1])
+    for obj in (B.OBJ_STATIC, B.OBJ_DYNAMIC):
+        assert np.array_equal(np_(peak)[obj], oracle.batch_peak(dc, mc, obj)), f"both objectives, row {obj}"
 
 
 def check_linear(d, chain_major=False):
@@ -143,6 +152,16 @@ def test_eval_peak_data_errors():
         assert np_(status).tolist() == [0, 3, 3, 4, 5, 5]
         assert np_(peak)[1:].tolist() == [-1] * 5
         assert np_(peak)[0] == oracle.batch_peak(inputs.chain_major(d)[:1], inputs.chain_major(m)[:1], obj)[0]
+    peak, status = B.ckpt_eval_peak(to_dev(d), to_dev(m), B.OBJ_BOTH)
+    torch.cuda.synchronize()
+    assert np_(status).tolist() == [0, 3, 3, 4, 5, 5]
+    assert np_(peak)[:, 1:].tolist() == [[-1] * 5] * 2
+    for obj in (0, 1):
+        assert np_(peak)[obj, 0] == oracle.batch_peak(inputs.chain_major(d)[:1], inputs.chain_major(m)[:1], obj)[0]
+    with pytest.raises(B.CkptError):
+        B.ckpt_eval_peak(to_dev(d), to_dev(m), 3)
+    with pytest.raises(B.CkptError):
+        B.ckpt_eval_timeline(to_dev(d), to_dev(m), B.OBJ_BOTH)      # a timeline is of one objective
 
 
 # ---------------------------------------------------------------------------

@@ -28,6 +28,10 @@ def batch():
 
 def test_eval_peak_whole_batch(batch):
     d, m, dt, mt = batch
+    say(f"eval_peak, both objectives in one call (as bench.py times it): all {BATCH} chains")
+    both, status = B.ckpt_eval_peak(dt, mt, B.OBJ_BOTH)
+    both = both.cpu().numpy()
+    assert int(status.abs().sum()) == 0
     for obj in (B.OBJ_STATIC, B.OBJ_DYNAMIC):
         say(f"eval_peak objective {obj}: all {BATCH} chains")
         peak, status = B.ckpt_eval_peak(dt, mt, obj)
@@ -37,6 +41,7 @@ def test_eval_peak_whole_batch(batch):
             sl = slice(c0, c0 + 262144)
             want = oracle.batch_peak(inputs.chain_major(d[:, sl]), inputs.chain_major(m[:, sl]), obj)
             assert np.array_equal(got[sl], want), f"objective {obj}, chains from {c0}"
+            assert np.array_equal(both[obj, sl], want), f"both objectives, row {obj}, chains from {c0}"
 
 
 def test_solve_linear_whole_batch(batch):
