@@ -448,6 +448,13 @@ def time_extras(torch, B, inputs, W, reps=3):
     out[f"solve_cubic_pruned_n{n1}"] = {"ms": t, "instances_per_s": 1.0 / (t * 1e-3), "budgets_run": run,
                                         "budgets": n1 * (n1 - 1) // 2 + 1,
                                         "cells_evaluated_per_s": run * n1 / (t * 1e-3)}
+    # the longest chain the cubic solver takes, sizes as the step's chain
+    d8 = torch.from_numpy(inputs.config5_single(8191)).to(W.d.device)
+    ws8 = torch.empty(B.workspace_bytes(B.CALL_SOLVE_CUBIC, B.layout_of(d8)), dtype=torch.uint8, device=W.d.device)
+    t, _ = timed_ms(torch, lambda: B.ckpt_solve_cubic(d8, workspace=ws8, want_status=False), reps)
+    out["solve_cubic_n8191"] = {"ms": t, "instances_per_s": 1.0 / (t * 1e-3),
+                                "cells_resolved_per_s": B.cubic_cells(8191) / (t * 1e-3)}
+    del d8, ws8
     d4 = torch.from_numpy(inputs.config4()).to(W.d.device)
     n4 = d4.shape[0] - 1
     t, _ = timed_ms(torch, lambda: B.ckpt_solve_quadratic(d4, want_values=False, want_status=False), reps)
