@@ -261,7 +261,8 @@ int ckpt_solve_quadratic(const int64_t *d, const ckpt_layout *layout, uint8_t *m
  * 2 n_c + 2 phases of chain c from element 2 offsets[c] on.  peak_out,
  * budget_out and status_out hold one value per chain, as in the equal-length
  * calls, whose results each chain gets exactly (same equations, same canonical
- * sets, same per-chain errors).
+ * sets, same per-chain errors); ckpt_ragged_eval_peak takes CKPT_OBJ_BOTH as
+ * ckpt_eval_peak does (2 * batch peaks, the static ones first).
  *   offsets_host [in] batch + 1 ascending element offsets in HOST memory (the
  *       caller built the batch and knows them; the library plans its launches
  *       from them).  It is read during the call only.

@@ -334,9 +334,11 @@ def _ragged_workspace(which, off_ptr, batch, device, workspace):
 
 
 def ckpt_ragged_eval_peak(d, mask, offsets, objective, workspace=None, offsets_dev=None):
-    """Peak memory of each chain's set; chain c is d[offsets[c]:offsets[c+1]].  Returns (peak, status)."""
+    """Peak memory of each chain's set; chain c is d[offsets[c]:offsets[c+1]].  Returns (peak, status);
+    with OBJ_BOTH peak has shape (2, batch)."""
     off, off_ptr, batch = _ragged_args(d, offsets, mask, offsets_dev)
-    peak = torch.empty(batch, dtype=torch.int64, device=d.device)
+    shape = (2, batch) if int(objective) == OBJ_BOTH else (batch,)
+    peak = torch.empty(shape, dtype=torch.int64, device=d.device)
     status = torch.empty(batch, dtype=torch.int32, device=d.device)
     ws, ws_bytes = _ragged_workspace(CALL_EVAL_PEAK, off_ptr, batch, d.device, workspace)
     rc = load().ckpt_ragged_eval_peak(_ptr(d), _ptr(mask), off_ptr, _ptr(offsets_dev), batch, int(objective), _ptr(peak), _ptr(status),

@@ -179,7 +179,8 @@ int ckpt_ragged_eval_peak(const int64_t *d, const uint8_t *mask, const int64_t *
                           const int64_t *offsets_dev, int64_t batch, int objective, int64_t *peak_out, int32_t *status_out, void *ws, size_t ws_bytes,
                           void *hip_stream)
 {
-    if (objective != CKPT_OBJ_STATIC && objective != CKPT_OBJ_DYNAMIC) return CKPT_ERR_SHAPE;
+    if (objective != CKPT_OBJ_STATIC && objective != CKPT_OBJ_DYNAMIC && objective != CKPT_OBJ_BOTH)
+        return CKPT_ERR_SHAPE;
     return ckpt::launch_ragged(CKPT_CALL_EVAL_PEAK, d, mask, offsets_host, offsets_dev, batch, objective, nullptr, peak_out,
                                nullptr, nullptr, status_out, ws, ws_bytes, (hipStream_t)hip_stream);
 }

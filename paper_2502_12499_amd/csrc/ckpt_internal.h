@@ -210,8 +210,9 @@ __device__ inline int ragged_group_of_tile(const RaggedGroupDev *g, int n_groups
 }
 
 // All groups of a ragged call in one launch each (the staging arrays hold every group).
+// batch: chains in all groups (with CKPT_OBJ_BOTH peak_stage holds 2 * batch values)
 hipError_t launch_eval_peak_ragged(const int64_t *d_stage, const uint8_t *mask_stage, const RaggedGroupDev *groups,
-                                   int n_groups, int64_t waves, int objective, int64_t *peak_stage,
+                                   int n_groups, int64_t waves, int64_t batch, int objective, int64_t *peak_stage,
                                    int32_t *status_stage, hipStream_t stream);
 hipError_t launch_eval_timeline_ragged(const int64_t *d_stage, const uint8_t *mask_stage,
                                        const RaggedGroupDev *groups, int n_groups, int64_t waves, int objective,

@@ -14,13 +14,13 @@ namespace {
 constexpr int kBlock = 64;
 
 // The evaluation of chain c of a batch laid out by (cstride, pstride).  OBJ = CKPT_OBJ_BOTH keeps
-// the running values of both objectives and writes the dynamic peak `batch` values after the
+// the running values of both objectives and writes the dynamic peak `second` values after the
 // static one.
 template <int OBJ>
 __device__ __forceinline__ void eval_peak_chain(const int64_t *__restrict__ d, const uint8_t *__restrict__ mask,
                                        int64_t batch, int n, int64_t cstride, int64_t pstride,
                                        int64_t *__restrict__ peak_out, int32_t *__restrict__ status_out,
-                                       const int64_t c)
+                                       const int64_t c, const int64_t second)
 {
     if (c >= batch) return;
     const int64_t *dp = d + c * cstride;
@@ -79,7 +79,7 @@ __device__ __forceinline__ void eval_peak_chain(const int64_t *__restrict__ d, c
 
     int64_t peak = kStatic ? ckpt_sum + best : best;
     peak_out[c] = status == CKPT_OK ? peak : -1;
-    if (OBJ == CKPT_OBJ_BOTH) peak_out[batch + c] = status == CKPT_OK ? best_dyn : -1;
+    if (OBJ == CKPT_OBJ_BOTH) peak_out[second + c] = status == CKPT_OK ? best_dyn : -1;
     if (status_out) status_out[c] = status;
 }
 
@@ -92,22 +92,24 @@ __global__ __launch_bounds__(kBlock) void eval_peak_kernel(const int64_t *__rest
                                                            int32_t *__restrict__ status_out)
 {
     const int64_t c = (int64_t)xcd_paired_block(blockIdx.x, gridDim.x) * kBlock + threadIdx.x;
-    eval_peak_chain<OBJ>(d, mask, batch, n, cstride, pstride, peak_out, status_out, c);
+    eval_peak_chain<OBJ>(d, mask, batch, n, cstride, pstride, peak_out, status_out, c, batch);
 }
 
 // Every group of a ragged call in one launch: a wave looks up the group its 64 chains belong to
-// and evaluates them where that group is staged; results go to the chains' places.
+// and evaluates them where that group is staged; results go to the chains' places (with both
+// objectives the dynamic peaks `batch` values, the number of chains of all groups, further on).
 template <int OBJ>
 __global__ __launch_bounds__(kBlock) void eval_peak_ragged_kernel(const int64_t *__restrict__ d_stage,
                                                                   const uint8_t *__restrict__ mask_stage,
                                                                   const RaggedGroupDev *__restrict__ groups,
-                                                                  int n_groups, int64_t *__restrict__ peak_stage,
+                                                                  int n_groups, int64_t batch,
+                                                                  int64_t *__restrict__ peak_stage,
                                                                   int32_t *__restrict__ status_stage)
 {
     const RaggedGroupDev g = groups[ragged_group_of_wave(groups, n_groups, blockIdx.x)];
     const int64_t c = ((int64_t)blockIdx.x - g.wave_first) * kBlock + threadIdx.x;
     eval_peak_chain<OBJ>(d_stage + g.stage_off, mask_stage + g.stage_off, g.count, g.n, 1, g.pitch,
-                         peak_stage + g.first, status_stage + g.first, c);
+                         peak_stage + g.first, status_stage + g.first, c, batch);
 }
 
 }  // namespace
@@ -130,17 +132,20 @@ hipError_t launch_eval_peak(const int64_t *d, const uint8_t *mask, int64_t batch
 }
 
 hipError_t launch_eval_peak_ragged(const int64_t *d_stage, const uint8_t *mask_stage, const RaggedGroupDev *groups,
-                                   int n_groups, int64_t waves, int objective, int64_t *peak_stage,
+                                   int n_groups, int64_t waves, int64_t batch, int objective, int64_t *peak_stage,
                                    int32_t *status_stage, hipStream_t stream)
 {
     if (waves == 0) return hipSuccess;
     static_assert(kBlock == kWave, "a workgroup is one of the groups' waves");
     if (objective == CKPT_OBJ_STATIC)
         hipLaunchKernelGGL(eval_peak_ragged_kernel<CKPT_OBJ_STATIC>, dim3((unsigned)waves), dim3(kBlock), 0, stream,
-                           d_stage, mask_stage, groups, n_groups, peak_stage, status_stage);
-    else
+                           d_stage, mask_stage, groups, n_groups, batch, peak_stage, status_stage);
+    else if (objective == CKPT_OBJ_DYNAMIC)
         hipLaunchKernelGGL(eval_peak_ragged_kernel<CKPT_OBJ_DYNAMIC>, dim3((unsigned)waves), dim3(kBlock), 0, stream,
-                           d_stage, mask_stage, groups, n_groups, peak_stage, status_stage);
+                           d_stage, mask_stage, groups, n_groups, batch, peak_stage, status_stage);
+    else
+        hipLaunchKernelGGL(eval_peak_ragged_kernel<CKPT_OBJ_BOTH>, dim3((unsigned)waves), dim3(kBlock), 0, stream,
+                           d_stage, mask_stage, groups, n_groups, batch, peak_stage, status_stage);
     return hipGetLastError();
 }
 

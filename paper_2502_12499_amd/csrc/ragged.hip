@@ -396,7 +396,7 @@ int ragged_run(int which, const int64_t *d, const uint8_t *mask_in, const int64_
                            off, perm, groups, tile_first2, n_groups, 1, smask);
     hipError_t e = hipSuccess;
     if (which == CKPT_CALL_EVAL_PEAK) {
-        e = launch_eval_peak_ragged(sd, smask, groups, n_groups, p.t.waves, objective, speak, sstatus, stream);
+        e = launch_eval_peak_ragged(sd, smask, groups, n_groups, p.t.waves, batch, objective, speak, sstatus, stream);
     } else if (which == CKPT_CALL_SOLVE_LINEAR) {
         e = launch_solve_linear_ragged(sd, groups, n_groups, p.t.waves, batch, p.t.max_layers, smask, speak, sstatus,
                                        base + w.inner, stream);
@@ -421,6 +421,8 @@ int ragged_run(int which, const int64_t *d, const uint8_t *mask_in, const int64_
             hipLaunchKernelGGL(ragged_scatter_kernel<uint8_t>, dim3((unsigned)p.t.tiles), dim3(kTileThreads), 0, stream,
                                smask, off, perm, groups, tile_first2, n_groups, 1, mask_out);
         scatter_value(speak, perm, batch, peak_out, stream);
+        if (which == CKPT_CALL_EVAL_PEAK && objective == CKPT_OBJ_BOTH)  // the dynamic peaks behind the static ones
+            scatter_value(speak + batch, perm, batch, peak_out + batch, stream);
         if (which == CKPT_CALL_SOLVE_CUBIC) scatter_value(sbudget, perm, batch, budget_out, stream);
     }
     scatter_value(sstatus, perm, batch, status_out, stream);

@@ -45,6 +45,7 @@ int ragged_check_totals(const RaggedTotals &t, int64_t batch)
 
 RaggedWorkspace ragged_layout(int which, const RaggedPlan &p, int64_t batch)
 {
+    // (eval_peak may be asked for both objectives: two peaks per chain)
     size_t inner = 0;
     if (which == CKPT_CALL_SOLVE_LINEAR) inner = linear_workspace_bytes(batch, p.t.max_layers);
     if (which == CKPT_CALL_SOLVE_CUBIC)
@@ -64,7 +65,7 @@ RaggedWorkspace ragged_layout(int which, const RaggedPlan &p, int64_t batch)
     w.d = take((size_t)p.t.staged * 8);
     w.mask = take((size_t)p.t.staged);
     w.wide = take(which == CKPT_CALL_EVAL_TIMELINE ? (size_t)p.t.staged * 16 : 0);
-    w.peak = take((size_t)batch * 8);
+    w.peak = take((size_t)batch * (which == CKPT_CALL_EVAL_PEAK ? 16 : 8));
     w.budget = take(which == CKPT_CALL_SOLVE_CUBIC ? (size_t)batch * 8 : 0);
     w.status = take((size_t)batch * 4);
     w.inner = take(inner);

@@ -122,5 +122,5 @@ def test_ragged_host_checks():
     # offsets in neither place; the cubic solver plans on the host and needs them there
     assert lib.ckpt_ragged_solve_linear(fake, None, None, 3, fake, fake, None, fake, 1 << 30, None) == 1
     assert lib.ckpt_ragged_solve_cubic(fake, None, fake, 3, fake, fake, fake, None, fake, 1 << 30, None) == 1
-    assert lib.ckpt_ragged_eval_peak(fake, fake, ptr, None, 3, 2, fake, None, fake, 1 << 30, None) == 2
+    assert lib.ckpt_ragged_eval_peak(fake, fake, ptr, None, 3, 3, fake, None, fake, 1 << 30, None) == 2
     assert lib.ckpt_ragged_solve_cubic(None, ptr, None, 0, None, None, None, None, None, 0, None) == 0

@@ -34,6 +34,11 @@ def check_eval(d, m, off):
         assert (np_(status) == 0).all() and (np_(status2) == 0).all()
         assert np.array_equal(np_(peak), oracle.ragged_peak(d, m, off, obj)), f"objective {obj}"
         assert np.array_equal(np_(line), oracle.ragged_timeline(d, m, off, obj)), f"objective {obj}"
+    both, status = B.ckpt_ragged_eval_peak(dd, md, off, B.OBJ_BOTH, offsets_dev=off_dev)
+    torch.cuda.synchronize()
+    assert (np_(status) == 0).all() and both.shape == (2, len(off) - 1)
+    for obj in (B.OBJ_STATIC, B.OBJ_DYNAMIC):
+        assert np.array_equal(np_(both)[obj], oracle.ragged_peak(d, m, off, obj)), f"both objectives, row {obj}"
 
 
 def check_linear(d, off):
